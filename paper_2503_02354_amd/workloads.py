@@ -1,0 +1,564 @@
+"""Seeded synthetic CoE workloads: architecture descriptors, expert weight blobs,
+dependency graphs and request images.
+
+This module is pure data generation.  It holds no convolution, routing, regroup
+or cache arithmetic: it only describes expert architectures as flat layer lists,
+draws random numbers from counter-based Philox streams and lays tensors out in
+the canonical weight-blob format that both the HIP library and the CPU oracle
+consume.  It imports neither of them.
+
+CoE structure follows the paper's Section 2.1: a routing rule picks a first
+expert, an expert's output either selects the next expert or is the final
+result, and several upstream experts may share one downstream expert.  The
+paper's own experts (ResNet101 / YOLOv5 on a private circuit-board dataset) are
+not available, so every workload here is a synthetic stand-in of the same
+structure.
+
+Canonical formats
+-----------------
+Layer descriptor: 12 int32 words
+    [op, src, dst, res, k, r, s, stride, pad, act, aux0, aux1]
+    op   1 = CONV      y = act(conv(x) + bias (+ res))         NHWC, weights [K][R][S][C]
+         2 = MAXPOOL   r x s window, stride, pad (padding never wins the max)
+         3 = HEAD      global average pool over H*W, then FC to k logits
+         4 = TOKENS    prepend a class token to the H*W tokens and add a
+                       position embedding; weights cls[C], pos[(H*W+1)][C]
+         5 = LAYERNORM over channels; weights gamma[C], beta[C] (fp32), eps 1e-6
+         6 = ATTENTION src holds [T][3*D] (q | k | v), aux0 = heads; softmax(q k^T / sqrt(dh)) v
+         7 = HEAD_CLS  layer norm of token 0 then FC to k logits
+    src/dst/res are activation buffer ids (0 = the request's input, res -1 = none)
+    act  0 none, 1 ReLU, 2 GELU (erf form)
+Architecture header: dtype (0 fp32, 1 bf16), in_h, in_w, in_c, n_classes.
+Weight blob: tensors in layer order, every tensor at a 256-byte aligned offset.
+    CONV   W[K][R][S][C] in the arch dtype, then bias[K] fp32
+    HEAD   W[k][F] in the arch dtype, then bias[k] fp32
+    TOKENS cls[C] dtype, pos[T][C] dtype
+    LAYERNORM gamma[C] fp32, beta[C] fp32
+    HEAD_CLS gamma[C] fp32, beta[C] fp32, W[k][C] dtype, bias[k] fp32
+"""
+from __future__ import annotations
+
+import dataclasses
+import json
+import math
+import os
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+
+OP_CONV, OP_MAXPOOL, OP_HEAD, OP_TOKENS, OP_LAYERNORM, OP_ATTENTION, OP_HEAD_CLS = 1, 2, 3, 4, 5, 6, 7
+ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
+DT_F32, DT_BF16 = 0, 1
+LAYER_WORDS = 12
+BLOB_ALIGN = 256
+
+
+# ----------------------------------------------------------------------------
+# bf16 quantisation of generated data (input generation only)
+# ----------------------------------------------------------------------------
+def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float32 values to the nearest bfloat16 (ties to even); returns uint16 bit patterns."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    r = u + np.uint32(0x7FFF) + lsb
+    return (r >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(b, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+# ----------------------------------------------------------------------------
+# counter-based random streams
+# ----------------------------------------------------------------------------
+_KIND_WEIGHT, _KIND_INPUT, _KIND_MISC = 1, 2, 3
+
+
+def _stream(seed: int, kind: int, a: int, b: int = 0) -> np.random.Generator:
+    """Philox-4x64 stream keyed by (seed, kind, a, b); streams are independent of each other."""
+    k1 = ((kind & 0xFF) << 56) | ((a & 0xFFFFFFF) << 28) | (b & 0xFFFFFFF)
+    return np.random.Generator(np.random.Philox(key=np.array([seed & (2**64 - 1), k1], dtype=np.uint64)))
+
+
+# ----------------------------------------------------------------------------
+# architecture descriptors
+# ----------------------------------------------------------------------------
+@dataclasses.dataclass
+class Arch:
+    name: str
+    dtype: int
+    in_h: int
+    in_w: int
+    in_c: int
+    n_classes: int
+    layers: np.ndarray  # [n_layers][12] int32
+    # per layer: multiplier applied to the He-normal std of that layer's weights
+    gains: List[float]
+
+    @property
+    def n_layers(self) -> int:
+        return int(self.layers.shape[0])
+
+    @property
+    def elem_bytes(self) -> int:
+        return 2 if self.dtype == DT_BF16 else 4
+
+    @property
+    def input_elems(self) -> int:
+        return self.in_h * self.in_w * self.in_c
+
+
+class _Prog:
+    """Tiny builder that tracks activation shapes per buffer and allocates scratch buffers."""
+
+    def __init__(self, h: int, w: int, c: int, n_scratch: int = 4):
+        self.shape: Dict[int, Tuple[int, int, int]] = {0: (h, w, c)}
+        self.layers: List[List[int]] = []
+        self.gains: List[float] = []
+        self.n_scratch = n_scratch
+
+    def free_buf(self, busy: Sequence[int]) -> int:
+        for b in range(1, self.n_scratch + 1):
+            if b not in busy:
+                return b
+        raise RuntimeError("out of scratch buffers")
+
+    def conv(self, src, dst, k, r, stride, pad, act, res=-1, gain=1.0):
+        h, w, c = self.shape[src]
+        p = (h + 2 * pad - r) // stride + 1
+        q = (w + 2 * pad - r) // stride + 1
+        self.shape[dst] = (p, q, k)
+        self.layers.append([OP_CONV, src, dst, res, k, r, r, stride, pad, act, 0, 0])
+        self.gains.append(gain)
+
+    def maxpool(self, src, dst, r, stride, pad):
+        h, w, c = self.shape[src]
+        p = (h + 2 * pad - r) // stride + 1
+        q = (w + 2 * pad - r) // stride + 1
+        self.shape[dst] = (p, q, c)
+        self.layers.append([OP_MAXPOOL, src, dst, -1, c, r, r, stride, pad, 0, 0, 0])
+        self.gains.append(1.0)
+
+    def head(self, src, n_classes):
+        self.layers.append([OP_HEAD, src, -1, -1, n_classes, 0, 0, 0, 0, 0, 0, 0])
+        self.gains.append(1.0)
+
+    def raw(self, words, gain=1.0):
+        self.layers.append(list(words))
+        self.gains.append(gain)
+
+
+def tiny_cnn(n_classes: int = 4, hw: int = 64, dtype: int = DT_F32) -> Arch:
+    """conv3x3(3->16)-ReLU-conv3x3(16->32)-ReLU-conv3x3(32->64)-ReLU-GAP-FC(64->n_classes), pad 1 stride 1."""
+    p = _Prog(hw, hw, 3)
+    p.conv(0, 1, 16, 3, 1, 1, ACT_RELU)
+    p.conv(1, 2, 32, 3, 1, 1, ACT_RELU)
+    p.conv(2, 1, 64, 3, 1, 1, ACT_RELU)
+    p.head(1, n_classes)
+    return Arch("tiny_cnn", dtype, hw, hw, 3, n_classes, np.array(p.layers, dtype=np.int32), p.gains)
+
+
+RES_BRANCH_GAIN = 0.5  # std multiplier on the last conv of every residual branch
+
+
+def resnet18(n_classes: int, hw: int = 224, dtype: int = DT_BF16, width: int = 64) -> Arch:
+    """ResNet-18-shaped expert: 7x7/2 stem, 3x3/2 max pool, four stages of two basic blocks, GAP, FC.
+
+    Batch norm is folded: every conv is weights + per-channel fp32 bias."""
+    p = _Prog(hw, hw, 3)
+    p.conv(0, 1, width, 7, 2, 3, ACT_RELU)
+    p.maxpool(1, 2, 3, 2, 1)
+    x = 2
+    for stage, ch in enumerate([width, 2 * width, 4 * width, 8 * width]):
+        for blk in range(2):
+            stride = 2 if (stage > 0 and blk == 0) else 1
+            t = p.free_buf([x])
+            p.conv(x, t, ch, 3, stride, 1, ACT_RELU)
+            if stride != 1 or p.shape[x][2] != ch:
+                sc = p.free_buf([x, t])
+                p.conv(x, sc, ch, 1, stride, 0, ACT_NONE)
+            else:
+                sc = x
+            y = p.free_buf([x, t, sc])
+            p.conv(t, y, ch, 3, 1, 1, ACT_RELU, res=sc, gain=RES_BRANCH_GAIN)
+            x = y
+    p.head(x, n_classes)
+    return Arch("resnet18", dtype, hw, hw, 3, n_classes, np.array(p.layers, dtype=np.int32), p.gains)
+
+
+def resnet50(n_classes: int, hw: int = 224, dtype: int = DT_BF16, width: int = 64) -> Arch:
+    """ResNet-50-shaped expert: bottleneck blocks [3,4,6,3], stride on the 3x3 conv of a downsampling block."""
+    p = _Prog(hw, hw, 3)
+    p.conv(0, 1, width, 7, 2, 3, ACT_RELU)
+    p.maxpool(1, 2, 3, 2, 1)
+    x = 2
+    for stage, (mid, nblk) in enumerate(zip([width, 2 * width, 4 * width, 8 * width], [3, 4, 6, 3])):
+        for blk in range(nblk):
+            stride = 2 if (stage > 0 and blk == 0) else 1
+            out = 4 * mid
+            a = p.free_buf([x])
+            p.conv(x, a, mid, 1, 1, 0, ACT_RELU)
+            b = p.free_buf([x, a])
+            p.conv(a, b, mid, 3, stride, 1, ACT_RELU)
+            if stride != 1 or p.shape[x][2] != out:
+                sc = p.free_buf([x, b])
+                p.conv(x, sc, out, 1, stride, 0, ACT_NONE)
+            else:
+                sc = x
+            y = p.free_buf([x, b, sc])
+            p.conv(b, y, out, 1, 1, 0, ACT_RELU, res=sc, gain=RES_BRANCH_GAIN)
+            x = y
+    p.head(x, n_classes)
+    return Arch("resnet50", dtype, hw, hw, 3, n_classes, np.array(p.layers, dtype=np.int32), p.gains)
+
+
+def vit(n_classes: int, hw: int = 224, patch: int = 16, dim: int = 768, depth: int = 12, heads: int = 12,
+        mlp: int = 3072, dtype: int = DT_BF16) -> Arch:
+    """ViT-shaped expert: patch embedding, class token + learned positions, pre-LN blocks, LN + FC on the class token.
+
+    Token tensors are stored as images of height T, width 1, so every linear layer is a 1x1 CONV op."""
+    p = _Prog(hw, hw, 3, n_scratch=5)
+    p.conv(0, 1, dim, patch, patch, 0, ACT_NONE)                    # [hw/patch][hw/patch][dim]
+    gh = hw // patch
+    t = gh * gh + 1
+    p.raw([OP_TOKENS, 1, 2, -1, dim, 0, 0, 0, 0, 0, 0, 0])          # [t][1][dim]
+    p.shape[2] = (t, 1, dim)
+    x = 2
+    for _ in range(depth):
+        n1 = p.free_buf([x])
+        p.raw([OP_LAYERNORM, x, n1, -1, dim, 0, 0, 0, 0, 0, 0, 0]); p.shape[n1] = (t, 1, dim)
+        qkv = p.free_buf([x, n1])
+        p.conv(n1, qkv, 3 * dim, 1, 1, 0, ACT_NONE)
+        at = p.free_buf([x, qkv])
+        p.raw([OP_ATTENTION, qkv, at, -1, dim, 0, 0, 0, 0, 0, heads, 0]); p.shape[at] = (t, 1, dim)
+        x2 = p.free_buf([x, at])
+        p.conv(at, x2, dim, 1, 1, 0, ACT_NONE, res=x)
+        n2 = p.free_buf([x2])
+        p.raw([OP_LAYERNORM, x2, n2, -1, dim, 0, 0, 0, 0, 0, 0, 0]); p.shape[n2] = (t, 1, dim)
+        h = p.free_buf([x2, n2])
+        p.conv(n2, h, mlp, 1, 1, 0, ACT_GELU)
+        x3 = p.free_buf([x2, h])
+        p.conv(h, x3, dim, 1, 1, 0, ACT_NONE, res=x2)
+        x = x3
+    p.raw([OP_HEAD_CLS, x, -1, -1, n_classes, 0, 0, 0, 0, 0, 0, 0])
+    return Arch("vit", dtype, hw, hw, 3, n_classes, np.array(p.layers, dtype=np.int32), p.gains)
+
+
+# ----------------------------------------------------------------------------
+# shape walk and blob layout
+# ----------------------------------------------------------------------------
+@dataclasses.dataclass
+class TensorSpec:
+    layer: int
+    name: str
+    shape: Tuple[int, ...]
+    is_param_dtype: bool   # True: stored in the arch dtype; False: stored as fp32
+    offset: int
+    nbytes: int
+
+
+def _align(x: int, a: int = BLOB_ALIGN) -> int:
+    return (x + a - 1) // a * a
+
+
+def walk(arch: Arch):
+    """Per layer: (src_shape, dst_shape) as (h, w, c); heads have dst_shape None."""
+    shp: Dict[int, Tuple[int, int, int]] = {0: (arch.in_h, arch.in_w, arch.in_c)}
+    out = []
+    for L in arch.layers:
+        op, src, dst, res, k, r, s, stride, pad = [int(v) for v in L[:9]]
+        h, w, c = shp[src]
+        if op in (OP_CONV, OP_MAXPOOL):
+            d = ((h + 2 * pad - r) // stride + 1, (w + 2 * pad - s) // stride + 1, k)
+        elif op == OP_TOKENS:
+            d = (h * w + 1, 1, c)
+        elif op == OP_LAYERNORM:
+            d = (h, w, c)
+        elif op == OP_ATTENTION:
+            d = (h, w, c // 3)
+        else:
+            d = None
+        if d is not None:
+            shp[dst] = d
+        out.append(((h, w, c), d))
+    return out
+
+
+def blob_layout(arch: Arch) -> Tuple[List[TensorSpec], int]:
+    specs: List[TensorSpec] = []
+    off = 0
+    eb = arch.elem_bytes
+
+    def add(layer, name, shape, param_dtype):
+        nonlocal off
+        off = _align(off)
+        nb = int(np.prod(shape)) * (eb if param_dtype else 4)
+        specs.append(TensorSpec(layer, name, tuple(int(v) for v in shape), param_dtype, off, nb))
+        off += nb
+
+    for i, (L, (sshape, dshape)) in enumerate(zip(arch.layers, walk(arch))):
+        op, k, r, s = int(L[0]), int(L[4]), int(L[5]), int(L[6])
+        h, w, c = sshape
+        if op == OP_CONV:
+            add(i, "w", (k, r, s, c), True)
+            add(i, "b", (k,), False)
+        elif op == OP_HEAD:
+            add(i, "w", (k, c), True)
+            add(i, "b", (k,), False)
+        elif op == OP_TOKENS:
+            add(i, "cls", (c,), True)
+            add(i, "pos", (h * w + 1, c), True)
+        elif op == OP_LAYERNORM:
+            add(i, "gamma", (c,), False)
+            add(i, "beta", (c,), False)
+        elif op == OP_HEAD_CLS:
+            add(i, "gamma", (c,), False)
+            add(i, "beta", (c,), False)
+            add(i, "w", (k, c), True)
+            add(i, "b", (k,), False)
+    return specs, _align(off)
+
+
+def arch_macs(arch: Arch) -> int:
+    """Multiply-accumulates of one request through the expert (conv, FC and attention contractions)."""
+    total = 0
+    for L, (sshape, dshape) in zip(arch.layers, walk(arch)):
+        op, k, r, s = int(L[0]), int(L[4]), int(L[5]), int(L[6])
+        h, w, c = sshape
+        if op == OP_CONV:
+            total += dshape[0] * dshape[1] * k * r * s * c
+        elif op in (OP_HEAD, OP_HEAD_CLS):
+            total += k * c
+        elif op == OP_ATTENTION:
+            d = c // 3
+            total += 2 * h * h * d
+    return total
+
+
+# ----------------------------------------------------------------------------
+# expert weights
+# ----------------------------------------------------------------------------
+BIAS_STD = 0.05
+
+
+def make_expert_blob(arch: Arch, seed: int, expert_id: int, head_bias: Optional[np.ndarray] = None) -> np.ndarray:
+    """He-normal weights (std sqrt(2/fan_in) x the layer's gain), biases N(0, BIAS_STD^2), packed into a blob.
+
+    head_bias, when given, replaces the head's bias (calibrated routing offsets).  Returns uint8[nbytes]."""
+    specs, nbytes = blob_layout(arch)
+    blob = np.zeros(nbytes, dtype=np.uint8)
+    for t_idx, sp in enumerate(specs):
+        g = _stream(seed, _KIND_WEIGHT, expert_id, t_idx)
+        n = int(np.prod(sp.shape))
+        op = int(arch.layers[sp.layer][0])
+        if sp.name == "w":
+            fan_in = n // sp.shape[0]
+            if op == OP_CONV:
+                act = int(arch.layers[sp.layer][9])
+                std = math.sqrt((2.0 if act == ACT_RELU or int(arch.layers[sp.layer][3]) >= 0 else 1.0) / fan_in)
+                if arch.name == "vit":
+                    std = math.sqrt(1.0 / fan_in)
+                std *= arch.gains[sp.layer]
+            else:
+                std = math.sqrt(1.0 / fan_in)
+            v = g.standard_normal(n, dtype=np.float32) * np.float32(std)
+        elif sp.name == "b":
+            v = g.standard_normal(n, dtype=np.float32) * np.float32(BIAS_STD)
+            if op in (OP_HEAD, OP_HEAD_CLS) and head_bias is not None:
+                v = np.asarray(head_bias, dtype=np.float32).reshape(n).copy()
+        elif sp.name == "gamma":
+            v = (1.0 + 0.1 * g.standard_normal(n, dtype=np.float32)).astype(np.float32)
+        elif sp.name == "beta":
+            v = (0.1 * g.standard_normal(n, dtype=np.float32)).astype(np.float32)
+        elif sp.name in ("cls", "pos"):
+            v = (0.5 * g.standard_normal(n, dtype=np.float32)).astype(np.float32)
+        else:
+            raise AssertionError(sp.name)
+        if sp.is_param_dtype and arch.dtype == DT_BF16:
+            blob[sp.offset:sp.offset + sp.nbytes] = f32_to_bf16_bits(v).view(np.uint8)
+        else:
+            blob[sp.offset:sp.offset + sp.nbytes] = v.astype(np.float32).view(np.uint8)
+    return blob
+
+
+def blob_tensor(arch: Arch, blob: np.ndarray, layer: int, name: str) -> np.ndarray:
+    """Decode one tensor of a blob to float32 (test helper)."""
+    specs, _ = blob_layout(arch)
+    for sp in specs:
+        if sp.layer == layer and sp.name == name:
+            raw = blob[sp.offset:sp.offset + sp.nbytes]
+            if sp.is_param_dtype and arch.dtype == DT_BF16:
+                return bf16_bits_to_f32(raw.view(np.uint16)).reshape(sp.shape)
+            return raw.view(np.float32).reshape(sp.shape).copy()
+    raise KeyError((layer, name))
+
+
+# ----------------------------------------------------------------------------
+# request inputs
+# ----------------------------------------------------------------------------
+def make_inputs(arch: Arch, seed: int, request_ids: Sequence[int], subseeds: Optional[Sequence[int]] = None) -> np.ndarray:
+    """Images ~ N(0,1), NHWC, one independent Philox stream per (request id, sub-seed).
+
+    Returns uint16 bf16 bit patterns [n][H][W][C] for bf16 architectures, float32 otherwise.  A request whose
+    routing margin is too small for a well-posed argmax is re-drawn by bumping its sub-seed."""
+    n = len(request_ids)
+    elems = arch.input_elems
+    out = np.empty((n, elems), dtype=np.uint16 if arch.dtype == DT_BF16 else np.float32)
+    for i, rid in enumerate(request_ids):
+        ss = 0 if subseeds is None else int(subseeds[i])
+        v = _stream(seed, _KIND_INPUT, int(rid), ss).standard_normal(elems, dtype=np.float32)
+        out[i] = f32_to_bf16_bits(v) if arch.dtype == DT_BF16 else v
+    return out.reshape(n, arch.in_h, arch.in_w, arch.in_c)
+
+
+# ----------------------------------------------------------------------------
+# dependency graphs (CSR successor lists; the argmax over the first n_route classes indexes the list)
+# ----------------------------------------------------------------------------
+@dataclasses.dataclass
+class Graph:
+    n_experts: int
+    succ_off: np.ndarray  # int32 [E+1]
+    succ: np.ndarray      # int32 [nnz], expert id or -1 (= final)
+
+    def successors(self, e: int) -> np.ndarray:
+        return self.succ[self.succ_off[e]:self.succ_off[e + 1]]
+
+
+def graph_from_lists(lists: Sequence[Sequence[int]]) -> Graph:
+    off = np.zeros(len(lists) + 1, dtype=np.int32)
+    for i, l in enumerate(lists):
+        off[i + 1] = off[i] + len(l)
+    succ = np.array([v for l in lists for v in l], dtype=np.int32)
+    return Graph(len(lists), off, succ)
+
+
+def tree_graph(n_experts: int) -> Graph:
+    """Expert 0 routes to experts 1..E-1 (class c -> expert c+1); leaves are final."""
+    return graph_from_lists([list(range(1, n_experts))] + [[] for _ in range(n_experts - 1)])
+
+
+def zipf_probs(n: int, s: float) -> np.ndarray:
+    w = 1.0 / np.arange(1, n + 1, dtype=np.float64) ** s
+    return w / w.sum()
+
+
+# ----------------------------------------------------------------------------
+# whole workloads
+# ----------------------------------------------------------------------------
+@dataclasses.dataclass
+class Workload:
+    name: str
+    seed: int
+    archs: List[Arch]
+    expert_arch: List[int]            # arch index per expert
+    usage_prob: List[float]
+    graph: Graph
+    n_requests: int
+    first_expert: Optional[np.ndarray]  # int32 [n] or None (single root = expert 0)
+    cache_cap_experts: int            # 0 = uncapped
+    arrival_batch: int                # requests per coe_submit
+    head_bias: Dict[int, np.ndarray]  # expert id -> calibrated head bias
+    max_stages: int
+
+    def blob(self, e: int) -> np.ndarray:
+        return make_expert_blob(self.archs[self.expert_arch[e]], self.seed, e, self.head_bias.get(e))
+
+    def inputs(self, request_ids, subseeds=None) -> np.ndarray:
+        return make_inputs(self.archs[0], self.seed, request_ids, subseeds)
+
+    @property
+    def max_classes(self) -> int:
+        return max(a.n_classes for a in self.archs)
+
+
+_CALIB_DIR = os.path.join(os.path.dirname(os.path.abspath(__file__)), "calib")
+
+
+def load_calibration(name: str) -> Dict[int, np.ndarray]:
+    """Head-bias offsets written by the oracle-side calibration script; empty if none was stored."""
+    path = os.path.join(_CALIB_DIR, name + ".json")
+    if not os.path.exists(path):
+        return {}
+    with open(path) as f:
+        d = json.load(f)
+    return {int(k): np.array(v, dtype=np.float32) for k, v in d["head_bias"].items()}
+
+
+def config1(n_requests: int = 256, hw: int = 64, calibrated: bool = True) -> Workload:
+    """Four fp32 tiny-CNN experts, two stages: expert 0's argmax over classes 0-2 routes to experts 1-3."""
+    a = tiny_cnn(4, hw, DT_F32)
+    name = "config1" if hw == 64 else f"config1_hw{hw}"
+    g = graph_from_lists([[1, 2, 3], [], [], []])
+    return Workload(name, 0xC0E1, [a], [0] * 4, [1.0, 1 / 3, 1 / 3, 1 / 3], g, n_requests, None, 0, n_requests,
+                    load_calibration(name) if calibrated else {}, 2)
+
+
+def config2(n_requests: int = 4096, hw: int = 224, n_experts: int = 16, width: int = 64,
+            calibrated: bool = True) -> Workload:
+    """ResNet-18-shaped bf16 experts, one root routing 15 ways (16 logits, the first 15 route), all resident."""
+    a = resnet18(16, hw, DT_BF16, width)
+    name = "config2" if (hw, n_experts, width) == (224, 16, 64) else f"config2_hw{hw}_e{n_experts}_w{width}"
+    g = tree_graph(n_experts)
+    p = [1.0] + [1.0 / (n_experts - 1)] * (n_experts - 1)
+    return Workload(name, 0xC0E2, [a], [0] * n_experts, p, g, n_requests, None, 0, n_requests,
+                    load_calibration(name) if calibrated else {}, 2)
+
+
+def config3(n_requests: int = 16384, hw: int = 224, n_experts: int = 64, width: int = 64, cap: int = 16,
+            arrival_batch: int = 512, calibrated: bool = True) -> Workload:
+    """ResNet-50-shaped bf16 experts, root -> 63 leaves with Zipf(1.1) leaf usage, capped device cache."""
+    a = resnet50(n_experts, hw, DT_BF16, width)
+    name = "config3" if (hw, n_experts, width) == (224, 64, 64) else f"config3_hw{hw}_e{n_experts}_w{width}"
+    g = tree_graph(n_experts)
+    p = [1.0] + list(zipf_probs(n_experts - 1, 1.1))
+    return Workload(name, 0xC0E3, [a], [0] * n_experts, p, g, n_requests, None, cap, arrival_batch,
+                    load_calibration(name) if calibrated else {}, 2)
+
+
+def config4(n_requests: int = 8192, hw: int = 224, tiers: Tuple[int, int, int] = (8, 32, 80), width: int = 64,
+            fan: Tuple[int, int] = (6, 5), calibrated: bool = True) -> Workload:
+    """Three-stage DAG of mixed ResNet-18/50-shaped experts with shared downstream experts and skewed groups.
+
+    Stage-1 expert i routes to `fan[0]` stage-2 experts, stage-2 expert j to `fan[1]` stage-3 experts, chosen
+    from seeded, overlapping windows so several upstream experts share one downstream expert.  Architecture
+    alternates by expert id parity.  first_expert follows a Zipf(1.2) draw over the stage-1 experts."""
+    n1, n2, n3 = tiers
+    e_total = n1 + n2 + n3
+    ncls = max(fan) + 1
+    a18 = resnet18(ncls, hw, DT_BF16, width)
+    a50 = resnet50(ncls, hw, DT_BF16, width)
+    name = "config4" if (hw, tiers, width) == (224, (8, 32, 80), 64) else \
+        f"config4_hw{hw}_t{n1}_{n2}_{n3}_w{width}"
+    seed = 0xC0E4
+    g = _stream(seed, _KIND_MISC, 1)
+    lists: List[List[int]] = []
+    for i in range(n1):
+        start = (i * n2) // n1
+        lists.append([n1 + (start + d * 3 + int(g.integers(0, 3))) % n2 for d in range(fan[0])])
+    for j in range(n2):
+        start = (j * n3) // n2
+        lists.append([n1 + n2 + (start + d * 2 + int(g.integers(0, 2))) % n3 for d in range(fan[1])])
+    for _ in range(n3):
+        lists.append([])
+    graph = graph_from_lists(lists)
+    first = _stream(seed, _KIND_MISC, 2).choice(n1, size=n_requests, p=zipf_probs(n1, 1.2)).astype(np.int32)
+    # usage probability: propagate the first-expert distribution down the DAG with uniform branch choice
+    prob = np.zeros(e_total)
+    prob[:n1] = zipf_probs(n1, 1.2)
+    for e in range(n1 + n2):
+        for s in lists[e]:
+            prob[s] += prob[e] / len(lists[e])
+    return Workload(name, seed, [a18, a50], [e % 2 for e in range(e_total)], list(prob), graph, n_requests, first,
+                    0, n_requests, load_calibration(name) if calibrated else {}, 3)
+
+
+def config5(n_requests: int = 4096, hw: int = 224, n_experts: int = 32, cap: int = 12, dim: int = 768,
+            depth: int = 12, heads: int = 12, mlp: int = 3072, calibrated: bool = True) -> Workload:
+    """ViT-B/16-shaped bf16 experts, root -> 31 leaves with uniform routing, capped device cache."""
+    a = vit(n_experts, hw, 16, dim, depth, heads, mlp, DT_BF16)
+    name = "config5" if (hw, n_experts, dim, depth) == (224, 32, 768, 12) else \
+        f"config5_hw{hw}_e{n_experts}_d{dim}_l{depth}"
+    g = tree_graph(n_experts)
+    p = [1.0] + [1.0 / (n_experts - 1)] * (n_experts - 1)
+    return Workload(name, 0xC0E5, [a], [0] * n_experts, p, g, n_requests, None, cap, n_requests,
+                    load_calibration(name) if calibrated else {}, 2)
