@@ -1,0 +1,194 @@
+/*
+ * coe.h - C ABI of the MI355X (gfx950) library for dependency-routed batched expert inference,
+ * the data-parallel hot path of CoServe-style Collaboration-of-Experts (CoE) serving.
+ *
+ * Model (paper, Section 2.1): a CoE model is a set of experts plus routing rules.  A request first
+ * runs on a preliminary expert; that expert's output either selects the next expert or is the final
+ * result.  Experts of one architecture differ only in their weights (Section 4.5, "profiled only
+ * once"); every expert has a usage probability and a memory footprint (Section 4.5); the memory that
+ * may hold experts on the device is capped (Sections 2.2, 4.3), and a request for an expert that is
+ * not on the device forces an expert switch (Section 4.1, "Online").
+ *
+ * One context drives one GPU.  A context is not thread-safe.  All functions return 0 (COE_OK), a
+ * positive informational code, or a negative error code; coe_last_error() then holds a message.
+ * Nothing throws across this boundary.  Unless a parameter says "device", pointers are host pointers
+ * owned by the caller, read or written during the call only, and may be freed when the call returns.
+ * After COE_EDEVICE (a HIP call failed) the context must be destroyed; after any other error it
+ * stays usable.
+ */
+#ifndef COE_H
+#define COE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define COE_OK 0
+#define COE_DONE 1      /* coe_step: no request is pending */
+#define COE_EINVAL (-1) /* bad argument */
+#define COE_ENOMEM (-2) /* host/device allocation failed, or an expert cannot fit the cache */
+#define COE_ESTATE (-3) /* call order (e.g. submit before the graph is set) */
+#define COE_EGRAPH (-4) /* dependency graph invalid: id out of range, cycle, more routes than classes */
+#define COE_EDEVICE (-5)/* a HIP runtime call failed */
+#define COE_ERANGE (-6) /* a caller buffer or a configured capacity is too small */
+
+typedef struct coe_ctx coe_ctx;
+
+/* ---- architecture descriptor: a flat layer list over numbered activation buffers ---------------------------
+ * Buffer 0 is the request's input image [in_h][in_w][in_c] (NHWC).  Buffers 1..7 are scratch.
+ * Activations are NHWC; a token tensor [T][D] is an image of height T, width 1, D channels.
+ *   op COE_OP_CONV     dst = act(conv(src) + bias (+ res)); cross-correlation, zero padding, k filters r x s
+ *   op COE_OP_MAXPOOL  dst = max over r x s windows of src (padding never wins), k = channels of src
+ *   op COE_OP_HEAD     logits[k] = FC(global average pool of src); ends the program
+ *   op COE_OP_TOKENS   dst = [class token; src tokens] + position embedding
+ *   op COE_OP_LAYERNORM dst = layer norm of src over channels, eps 1e-6
+ *   op COE_OP_ATTENTION src = [T][3D] (q|k|v), aux0 = heads; dst = softmax(q k^T / sqrt(D/heads)) v
+ *   op COE_OP_HEAD_CLS logits[k] = FC(layer norm(token 0 of src)); ends the program
+ * act: 0 none, 1 ReLU, 2 GELU (erf form).  res = -1 for none; res must have dst's shape.
+ * dtype: 0 = fp32 everywhere; 1 = bf16 weights and stored activations, fp32 accumulation, bias, residual add
+ * and activation in fp32, one round-to-nearest-even to bf16 per stored activation, fp32 logits. */
+enum { COE_OP_CONV = 1, COE_OP_MAXPOOL = 2, COE_OP_HEAD = 3, COE_OP_TOKENS = 4, COE_OP_LAYERNORM = 5,
+       COE_OP_ATTENTION = 6, COE_OP_HEAD_CLS = 7 };
+enum { COE_DT_F32 = 0, COE_DT_BF16 = 1 };
+
+typedef struct {
+    int32_t op, src, dst, res, k, r, s, stride, pad, act, aux0, aux1;
+} coe_layer;
+
+typedef struct {
+    int32_t dtype, in_h, in_w, in_c, n_classes, n_layers;
+    const coe_layer* layers; /* [n_layers] */
+} coe_arch_desc;
+
+/* Expert weights ("host_weights" of coe_register_expert) are one blob: the tensors of the layers in order,
+ * each starting at the next multiple of 256 bytes.
+ *   CONV      W[k][r][s][c] in the arch dtype, bias[k] fp32
+ *   HEAD      W[k][c] in the arch dtype, bias[k] fp32
+ *   TOKENS    cls[c], pos[T][c] in the arch dtype
+ *   LAYERNORM gamma[c], beta[c] fp32
+ *   HEAD_CLS  gamma[c], beta[c] fp32, W[k][c] arch dtype, bias[k] fp32
+ * coe_arch_blob_bytes() returns the total (a multiple of 256). */
+
+typedef struct {
+    int32_t device;            /* HIP device ordinal */
+    int32_t max_requests;      /* capacity of the request store (requests submitted and not yet collected) */
+    int32_t max_batch;         /* request splitting: largest batch one expert launch sequence handles (0 = 256);
+                                  paper Section 4.2 "Request splitting" */
+    int32_t max_stages;        /* longest path through the dependency graph that is recorded per request */
+    int32_t cache_cap_experts; /* device expert cache: at most this many resident experts (0 = no limit) */
+    int32_t profile;           /* nonzero: time every kernel class with events (see coe_profile_read) */
+    int64_t cache_cap_bytes;   /* and at most this many bytes of expert weights (0 = no limit) */
+    void* compute_stream;      /* borrowed hipStream_t for kernels, or NULL: the library creates one */
+    void* copy_stream;         /* borrowed hipStream_t for expert switches, or NULL: the library creates one */
+} coe_config;
+
+typedef struct {
+    int32_t n_pending;   /* requests that ran a stage in this step */
+    int32_t n_groups;    /* experts with at least one request */
+    int32_t n_chunks;    /* batches after splitting */
+    int32_t n_hits;      /* groups whose expert was resident */
+    int32_t n_misses;    /* groups that needed an expert switch */
+    int32_t n_evictions; /* experts evicted */
+    int64_t bytes_switched; /* host-to-device bytes of the switches */
+    double host_plan_us; /* host time spent planning (cache policy, splitting) */
+} coe_step_stats;
+
+/* Create / destroy a context.  coe_create fails with COE_EDEVICE when no GPU is usable. */
+int coe_create(const coe_config* cfg, coe_ctx** out);
+void coe_destroy(coe_ctx* ctx);
+const char* coe_last_error(const coe_ctx* ctx); /* valid until the next call on ctx; "" if none */
+
+/* Register an architecture shared by many experts (paper Section 4.5: experts of the same architecture are
+ * profiled once).  All architectures of a context take the same input shape and dtype.  The descriptor is copied.
+ * Errors: COE_EINVAL for a malformed layer list (bad buffer ids, shape mismatch of a residual, unknown op). */
+int coe_register_arch(coe_ctx* ctx, const coe_arch_desc* desc, int32_t* arch_id);
+/* Bytes of a weight blob of that architecture; negative error code on failure. */
+int64_t coe_arch_blob_bytes(const coe_ctx* ctx, int32_t arch_id);
+
+/* Register expert `expert_id` (ids must be dense, 0..E-1, any order).  host_weights is the canonical blob
+ * (nbytes must equal coe_arch_blob_bytes); the library copies it into its own pinned host store, from which
+ * expert switches are served.  usage_prob is the pre-assessed usage probability (paper Section 4.5) used for
+ * the initial cache fill and for eviction. */
+int coe_register_expert(coe_ctx* ctx, int32_t expert_id, int32_t arch_id, const void* host_weights, size_t nbytes,
+                        float usage_prob);
+
+/* Routing rules (paper Sections 2.1, 4.5 "Routing rules"): CSR successor lists.  Expert e routes on the argmax
+ * over its first n_route = succ_off[e+1]-succ_off[e] logits (lowest index wins ties); the request goes to
+ * succ[succ_off[e]+argmax], or is final when that entry is -1 or n_route is 0.  Every stage's expert consumes the
+ * request's original input.  Must be called after all n_experts experts are registered.
+ * Errors: COE_EGRAPH (id out of range, cycle, n_route > classes of e), COE_ESTATE (experts missing). */
+int coe_set_dependency_graph(coe_ctx* ctx, int32_t n_experts, const int32_t* succ_off, const int32_t* succ);
+
+/* Append n requests.  inputs: [n][in_h][in_w][in_c] in the context dtype, a device pointer if on_device != 0,
+ * else a host pointer; copied into the request store (stream-ordered; a device source must stay valid until
+ * coe_sync or coe_collect).  first_expert: [n] host array of preliminary experts, or NULL = expert 0.
+ * *first_request_id (nullable) receives the id of the first request; ids are consecutive.
+ * Errors: COE_ERANGE when the store is full, COE_ESTATE before the graph is set. */
+int coe_submit(coe_ctx* ctx, int32_t n, const void* inputs, int on_device, const int32_t* first_expert,
+               int64_t* first_request_id);
+
+/* Run ONE stage for every pending request: regroup by expert (paper Section 4.2 "Request arranging"), split
+ * groups into batches ("Request splitting"), serve experts from the device cache (hits first; misses are
+ * switched in on the copy stream while earlier groups compute; victims by two-stage eviction, Section 4.3),
+ * run each expert on its batches, and route.  Work is enqueued asynchronously except for one small count
+ * read-back.  Returns COE_DONE when nothing is pending.  stats is nullable. */
+int coe_step(coe_ctx* ctx, coe_step_stats* stats);
+
+/* Wait for all enqueued work. */
+int coe_sync(coe_ctx* ctx);
+
+/* Copy out finished requests not yet collected, in request-id order, at most cap.  logits: [cap][max_classes]
+ * fp32 of the last expert run (zero padded); path: [cap][max_stages] expert ids, -1 padded.  max_classes is the
+ * largest n_classes over registered architectures.  Synchronises.  Any of the three output arrays may be NULL. */
+int coe_collect(coe_ctx* ctx, int32_t cap, int64_t* request_id, float* logits, int32_t* path, int32_t* n_out);
+
+/* Forget all requests (finished or not); experts, graph and cache contents stay. */
+int coe_reset_requests(coe_ctx* ctx);
+
+/* ---- inspection used by tests and the benchmark --------------------------------------------------------------- */
+/* Result of the last step's regroup: cnt[E], off[E+1], perm[n_pending], inv[n_live] (-1 for non-pending).
+ * perm/inv index request slots (request id minus the id of the oldest uncollected-store base).  Nullable outputs. */
+int coe_debug_last_regroup(coe_ctx* ctx, int32_t* n_pending, int32_t* n_live, int32_t* cnt, int32_t* off,
+                           int32_t* perm, int32_t* inv, int32_t perm_cap);
+/* Switch log since creation: flat words {expert, n_victims, victims...} per switch, initial fill included.
+ * Writes at most cap words; *n_words receives the total. */
+int coe_debug_switch_log(coe_ctx* ctx, int32_t cap, int32_t* log, int32_t* n_words);
+/* Which experts are resident: out[E] bytes (0/1). */
+int coe_debug_resident(coe_ctx* ctx, uint8_t* out);
+/* Run one expert on n inputs (device pointer, context dtype) without routing: logits_out [n][n_classes] fp32 (host). */
+int coe_debug_forward(coe_ctx* ctx, int32_t expert_id, int32_t n, const void* device_inputs, float* logits_out);
+/* Stand-alone regroup on a host key vector (uploaded, regrouped on the device, read back): same outputs as above. */
+int coe_debug_regroup(coe_ctx* ctx, int32_t n, const int32_t* cur, int32_t n_experts, int32_t* cnt, int32_t* off,
+                      int32_t* perm, int32_t* inv);
+
+/* Kernel classes timed when cfg.profile != 0. */
+enum { COE_K_REGROUP_INDEX = 0, COE_K_REGROUP_GATHER = 1, COE_K_CONV_MFMA = 2, COE_K_CONV_DIRECT = 3, COE_K_POOL = 4,
+       COE_K_HEAD = 5, COE_K_SWITCH = 6, COE_K_OTHER = 7, COE_K_COUNT = 8 };
+/* Synchronises, then returns and clears the accumulated launches, milliseconds and algorithmic work of a class
+ * (flops for conv classes, bytes for the others). */
+int coe_profile_read(coe_ctx* ctx, int32_t kernel_class, int64_t* launches, double* ms, double* work);
+
+/* ---- host-only pieces (no GPU needed) -------------------------------------------------------------------------- */
+/* Graph check used by coe_set_dependency_graph.  n_classes: [n_experts] or NULL (skip the route-count check). */
+int coe_validate_graph(int32_t n_experts, const int32_t* succ_off, const int32_t* succ, const int32_t* n_classes);
+
+/* The expert-cache policy on its own (paper Section 4.1 initial fill, Section 4.3 two-stage eviction).
+ * coe_policy_stage: has_group[E] marks experts with pending requests; order[E] receives the execution order
+ * (resident first, then missing, each by ascending id), *n_order its length; log receives {expert, n_victims,
+ * victims...} per switch, at most log_cap words; returns the number of words, or COE_ENOMEM / COE_ERANGE. */
+typedef struct coe_policy coe_policy;
+coe_policy* coe_policy_create(int32_t n_experts, const int64_t* nbytes, const float* usage_prob,
+                              const int32_t* succ_off, const int32_t* succ, int32_t cap_experts, int64_t cap_bytes);
+void coe_policy_destroy(coe_policy* p);
+int coe_policy_init_fill(coe_policy* p, int32_t* loaded /*[E]*/);
+int coe_policy_stage(coe_policy* p, const uint8_t* has_group, int32_t* order, int32_t* n_order, int32_t* log,
+                     int32_t log_cap);
+int coe_policy_resident(const coe_policy* p, uint8_t* out /*[E]*/);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* COE_H */

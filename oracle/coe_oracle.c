@@ -534,23 +534,27 @@ int orc_cache_stage(orc_cache* c, const uint8_t* has_group, int32_t* order, int*
         if (!c->resident[e]) {
             if (nl + 2 > log_cap) { free(todo); return -1; }
             int head = nl; log[nl++] = e; log[nl++] = 0;
-            /* stage 1 */
+            /* stage 1: the candidate set is fixed when the miss occurs, then evicted largest first */
+            uint8_t* cand = (uint8_t*)calloc((size_t)E, 1);
+            for (int x = 0; x < E; ++x) {
+                if (!c->resident[x] || todo[x] || has_group[x]) continue;
+                int has_pred = 0, pred_around = 0;
+                for (int p = 0; p < E; ++p)
+                    for (int j = c->succ_off[p]; j < c->succ_off[p + 1]; ++j)
+                        if (c->succ[j] == x) { has_pred = 1; if (c->resident[p] || has_group[p]) pred_around = 1; }
+                cand[x] = (uint8_t)(has_pred && !pred_around);
+            }
             while (!fits(c, e)) {
                 int v = -1;
-                for (int x = 0; x < E; ++x) {
-                    if (!c->resident[x] || todo[x] || has_group[x]) continue;
-                    int has_pred = 0, pred_around = 0;
-                    for (int p = 0; p < E; ++p)
-                        for (int j = c->succ_off[p]; j < c->succ_off[p + 1]; ++j)
-                            if (c->succ[j] == x) { has_pred = 1; if (c->resident[p] || has_group[p]) pred_around = 1; }
-                    if (!has_pred || pred_around) continue;
-                    if (v < 0 || c->bytes[x] > c->bytes[v]) v = x;
-                }
+                for (int x = 0; x < E; ++x)
+                    if (cand[x] && (v < 0 || c->bytes[x] > c->bytes[v])) v = x;
                 if (v < 0) break;
+                cand[v] = 0;
                 c->resident[v] = 0; c->n_res--; c->res_bytes -= c->bytes[v];
-                if (nl >= log_cap) { free(todo); return -1; }
+                if (nl >= log_cap) { free(cand); free(todo); return -1; }
                 log[nl++] = v; log[head + 1]++;
             }
+            free(cand);
             /* stage 2 */
             while (!fits(c, e)) {
                 int v = -1;

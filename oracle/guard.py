@@ -1,0 +1,131 @@
+"""Oracle-side workload preparation (TEST INFRASTRUCTURE ONLY; calls the oracle and the input generators, never the HIP path).
+
+* margin guard: a float argmax is only well posed away from ties, so a request whose oracle top-2 gap at any routing
+  stage is below delta * (largest computed logit magnitude) is re-drawn from its next sub-seed; both sides then see
+  the same re-drawn input.
+* head-bias calibration: random-weight experts on noise images give nearly identical logits for every request, so
+  the routing experts' head biases are offset (from oracle logits only) until the routed classes follow a target
+  distribution.  The offsets are inputs to both sides.
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+from . import oracle as O
+
+# Smallest admissible top-2 gap at a routing stage, as a fraction of the largest |logit - head bias| of that expert
+# (the part of the logit that is computed; the bias is added exactly).  bf16 experts: the HIP path accumulates in fp32
+# in another order than the oracle's fp64, which now and then flips a bf16 rounding of a stored activation; over a
+# 20-50 layer expert that is worth up to ~0.6 % of the computed logit magnitude (measured with an fp32-accumulating
+# copy of the oracle), so gaps below 2 % are not decidable.  fp32 experts: only fp32 summation order differs.
+DELTA_BF16 = 2e-2
+DELTA_F32 = 1e-4
+
+
+def delta_for(wl) -> float:
+    return DELTA_BF16 if wl.archs[0].dtype == 1 else DELTA_F32
+
+
+def routing_margins(wl, blobs, res) -> np.ndarray:
+    """[n][max_stages]: (top1 - top2 over the routed classes) / max_c |logit_c - bias_c| at every routing stage a
+    request went through, -1 elsewhere."""
+    from paper_2503_02354_amd import workloads as W
+    n, S = res["path"].shape
+    out = np.full((n, S), -1.0)
+    bias_cache = {}
+    for r in range(n):
+        for s in range(S):
+            e = int(res["path"][r, s])
+            if e < 0:
+                break
+            k = int(wl.graph.succ_off[e + 1] - wl.graph.succ_off[e])
+            if k == 0:
+                break
+            if e not in bias_cache:
+                a = wl.archs[wl.expert_arch[e]]
+                bias_cache[e] = W.blob_tensor(a, blobs[e], a.n_layers - 1, "b")
+            b = bias_cache[e]
+            lg = res["all_logits"][r, s, :len(b)].astype(np.float64)
+            scale = max(np.abs(lg - b).max(), 1e-30)
+            top = np.sort(lg[:k])[::-1]
+            out[r, s] = (top[0] - top[1]) / scale if k > 1 else 1.0
+    return out
+
+
+def run(wl, blobs, inputs, first_expert=None, threads: int = 0):
+    return O.run_chain(wl.archs, wl.expert_arch, blobs, wl.graph.succ_off, wl.graph.succ, inputs, first_expert,
+                       wl.max_stages, wl.max_classes, threads)
+
+
+def guarded_inputs(wl, blobs, request_ids: Sequence[int], delta: Optional[float] = None, max_rounds: int = 40):
+    """Returns (inputs, subseeds, oracle_result, n_redraws) for the given request ids."""
+    if delta is None:
+        delta = delta_for(wl)
+    ids = np.asarray(list(request_ids), dtype=np.int64)
+    sub = np.zeros(len(ids), np.int32)
+    x = wl.inputs(ids, sub)
+    fe = None if wl.first_expert is None else wl.first_expert[ids]
+    res = run(wl, blobs, x, fe)
+    redraws = 0
+    for _ in range(max_rounds):
+        m = routing_margins(wl, blobs, res)
+        bad = np.nonzero(((m >= 0) & (m < delta)).any(axis=1))[0]
+        if len(bad) == 0:
+            break
+        redraws += len(bad)
+        sub[bad] += 1
+        x[bad] = wl.inputs(ids[bad], sub[bad])
+        r2 = run(wl, blobs, x[bad], None if fe is None else fe[bad])
+        for k in res:
+            res[k][bad] = r2[k]
+    else:
+        raise RuntimeError("margin guard did not converge")
+    return x, sub, res, redraws
+
+
+def calibrate_bias(z: np.ndarray, n_route: int, target: np.ndarray, iters: int = 400, lr: float = 0.5) -> np.ndarray:
+    """z: [n][classes] oracle logits with zero head bias.  Returns a bias [classes] such that argmax over the first
+    n_route classes of z + bias follows `target` (length n_route) as closely as the sample allows."""
+    n, ncls = z.shape
+    zr = z[:, :n_route].astype(np.float64)
+    scale = max(zr.std(axis=0).mean(), 1e-12)
+    b = -zr.mean(axis=0)
+    tgt = np.asarray(target, np.float64)
+    tgt = tgt / tgt.sum()
+    for it in range(iters):
+        freq = np.bincount(np.argmax(zr + b, axis=1), minlength=n_route) / n
+        step = lr * scale * (np.log(tgt + 1e-4) - np.log(freq + 1e-4))
+        b += step * (0.98 ** it)
+    out = np.zeros(ncls, np.float32)
+    out[:n_route] = b.astype(np.float32)
+    return out
+
+
+def calibrate_workload(wl, n_cal: int = 128, targets: Optional[Dict[int, np.ndarray]] = None, cal_seed_offset: int = 1 << 20,
+                       threads: int = 0) -> Dict[int, np.ndarray]:
+    """Head-bias offsets for every routing expert of wl, from oracle logits on n_cal calibration images (request ids
+    offset so they never coincide with workload requests).  targets[e]: routed-class distribution (default uniform).
+    Fills wl.head_bias in place and returns it."""
+    ids = np.arange(cal_seed_offset, cal_seed_offset + n_cal)
+    x = wl.inputs(ids)
+    for e in range(wl.graph.n_experts):
+        k = int(wl.graph.succ_off[e + 1] - wl.graph.succ_off[e])
+        if k <= 1:
+            continue
+        a = wl.archs[wl.expert_arch[e]]
+        zero = np.zeros(a.n_classes, np.float32)
+        wl.head_bias[e] = zero
+        blob = wl.blob(e)
+        z = np.stack([O.forward(a, blob, x[i]) for i in range(n_cal)]) if threads == 1 else _forward_many(a, blob, x, threads)
+        tgt = np.full(k, 1.0 / k) if not targets or e not in targets else targets[e]
+        wl.head_bias[e] = calibrate_bias(z, k, tgt)
+    return wl.head_bias
+
+
+def _forward_many(arch, blob, x, threads):
+    """All calibration images through one expert, in parallel, via the chain runner on a one-expert graph."""
+    so = np.zeros(2, np.int32)
+    r = O.run_chain([arch], [0], [blob], so, np.zeros(1, np.int32), x, None, 1, arch.n_classes, threads)
+    return r["logits"]

@@ -1,0 +1,858 @@
+// Stage driver behind the C ABI: request store, regroup, batch splitting, expert cache with side-stream switches,
+// per-expert batched forward, routing.  Host code only; kernels live in the .hip files.
+#include "../../include/coe.h"
+
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <chrono>
+#include <cstdio>
+#include <cstring>
+#include <memory>
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+#include "policy.h"
+
+namespace {
+
+constexpr int kMaxBufs = 8;
+constexpr size_t kBlobAlign = 256;
+
+size_t align_up(size_t x, size_t a = kBlobAlign) { return (x + a - 1) / a * a; }
+
+struct LayerPlan {
+    coe_layer d;
+    int32_t H, W, C;        // source shape
+    int32_t P, Q, K;        // destination shape (heads: K = classes)
+    size_t off[4];          // byte offsets of this layer's tensors in the blob
+    double macs;            // multiply-accumulates per request
+};
+
+struct ArchPlan {
+    int32_t dtype, in_h, in_w, in_c, n_classes;
+    std::vector<LayerPlan> layers;
+    size_t blob_bytes = 0;
+    size_t buf_elems[kMaxBufs] = {0};   // per request
+    size_t elem() const { return dtype == COE_DT_BF16 ? 2 : 4; }
+    size_t in_bytes() const { return (size_t)in_h * in_w * in_c * elem(); }
+};
+
+struct DevBuf {
+    void* p = nullptr;
+    size_t bytes = 0;
+    hipEvent_t last_use = nullptr;   // recorded on the compute stream after the last kernel that read p
+    bool used = false;
+};
+
+struct Expert {
+    bool registered = false;
+    int32_t arch = -1;
+    float prob = 0.f;
+    void* host = nullptr;            // pinned copy of the blob
+    size_t nbytes = 0;
+    DevBuf* buf = nullptr;           // device copy when resident
+    hipEvent_t loaded = nullptr;     // recorded on the copy stream after the switch
+    bool load_pending = false;       // compute stream has not yet waited for `loaded`
+};
+
+struct ProfClass {
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> spans;
+    double work = 0.0;
+};
+
+}  // namespace
+
+struct coe_ctx {
+    coe_config cfg;
+    std::string err;
+    hipStream_t sc = nullptr, sx = nullptr;
+    bool own_sc = false, own_sx = false;
+
+    std::vector<ArchPlan> archs;
+    std::vector<Expert> experts;
+    bool graph_set = false;
+    int32_t E = 0;
+    std::vector<int32_t> succ_off, succ;
+    int32_t* d_succ = nullptr;
+    std::unique_ptr<coe::Policy> policy;
+    bool filled = false;
+    std::vector<int32_t> switch_log;
+    std::vector<DevBuf*> free_bufs;
+    std::vector<DevBuf*> all_bufs;
+
+    // request store
+    int32_t n_live = 0, n_collected = 0;
+    int64_t id_base = 0;
+    std::vector<uint8_t> collected;
+    void* d_inputs = nullptr;
+    void* d_staged = nullptr;
+    int32_t *d_cur = nullptr, *d_depth = nullptr, *d_path = nullptr;
+    float* d_logits = nullptr;
+    int32_t max_classes = 0;
+    int32_t logits_alloc_classes = 0;
+
+    // regroup
+    int32_t *d_cnt = nullptr, *d_off = nullptr, *d_perm = nullptr, *d_inv = nullptr, *d_blockhist = nullptr;
+    int32_t* h_cnt = nullptr;        // pinned
+    int32_t last_pending = 0, last_live = 0, last_E = 0;
+
+    // activation workspace
+    void* d_buf[kMaxBufs] = {nullptr};
+    size_t buf_bytes[kMaxBufs] = {0};
+
+    // profiling
+    ProfClass prof[COE_K_COUNT];
+    std::vector<hipEvent_t> ev_pool;
+};
+
+namespace {
+
+int fail(coe_ctx* c, int code, const std::string& msg)
+{
+    if (c) c->err = msg;
+    return code;
+}
+
+#define HIPCHK(ctx, call)                                                                          \
+    do {                                                                                           \
+        hipError_t e_ = (call);                                                                    \
+        if (e_ != hipSuccess)                                                                      \
+            return fail(ctx, COE_EDEVICE, std::string(#call) + ": " + hipGetErrorString(e_));      \
+    } while (0)
+
+// ---- profiling spans ---------------------------------------------------------------------------------------------
+struct Span {
+    coe_ctx* c;
+    int cls;
+    hipStream_t s;
+    hipEvent_t e1 = nullptr;
+    Span(coe_ctx* ctx, int kernel_class, double work, hipStream_t stream) : c(ctx), cls(kernel_class), s(stream)
+    {
+        if (!c->cfg.profile) return;
+        hipEvent_t e0 = take();
+        e1 = take();
+        if (!e0 || !e1) { e1 = nullptr; return; }
+        hipEventRecord(e0, s);
+        c->prof[cls].spans.emplace_back(e0, e1);
+        c->prof[cls].work += work;
+    }
+    ~Span()
+    {
+        if (e1) hipEventRecord(e1, s);
+    }
+    hipEvent_t take()
+    {
+        if (!c->ev_pool.empty()) {
+            hipEvent_t e = c->ev_pool.back();
+            c->ev_pool.pop_back();
+            return e;
+        }
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) return nullptr;
+        return e;
+    }
+};
+
+// ---- architecture planning -----------------------------------------------------------------------------------------
+int plan_arch(coe_ctx* c, const coe_arch_desc* d, ArchPlan& a)
+{
+    if (d->dtype != COE_DT_F32 && d->dtype != COE_DT_BF16) return fail(c, COE_EINVAL, "arch: unknown dtype");
+    if (d->in_h <= 0 || d->in_w <= 0 || d->in_c <= 0 || d->n_classes <= 0 || d->n_layers <= 0 || !d->layers)
+        return fail(c, COE_EINVAL, "arch: bad header");
+    a.dtype = d->dtype; a.in_h = d->in_h; a.in_w = d->in_w; a.in_c = d->in_c; a.n_classes = d->n_classes;
+    struct Shape { int32_t h = 0, w = 0, c = 0; bool set = false; } shp[kMaxBufs];
+    shp[0] = {d->in_h, d->in_w, d->in_c, true};
+    size_t off = 0;
+    const size_t eb = a.elem();
+    auto take = [&](size_t n, bool param_dtype) {
+        off = align_up(off);
+        size_t o = off;
+        off += n * (param_dtype ? eb : 4);
+        return o;
+    };
+    for (int32_t i = 0; i < d->n_layers; ++i) {
+        LayerPlan L{};
+        L.d = d->layers[i];
+        const coe_layer& l = L.d;
+        if (l.src < 0 || l.src >= kMaxBufs || !shp[l.src].set) return fail(c, COE_EINVAL, "arch: layer reads an unset buffer");
+        L.H = shp[l.src].h; L.W = shp[l.src].w; L.C = shp[l.src].c;
+        bool is_head = l.op == COE_OP_HEAD || l.op == COE_OP_HEAD_CLS;
+        if (!is_head && (l.dst <= 0 || l.dst >= kMaxBufs || l.dst == l.src))
+            return fail(c, COE_EINVAL, "arch: bad destination buffer");
+        if (is_head && i != d->n_layers - 1) return fail(c, COE_EINVAL, "arch: head must be the last layer");
+        switch (l.op) {
+        case COE_OP_CONV:
+        case COE_OP_MAXPOOL: {
+            if (l.r <= 0 || l.s <= 0 || l.stride <= 0 || l.pad < 0 || l.k <= 0) return fail(c, COE_EINVAL, "arch: bad conv/pool parameters");
+            L.P = (L.H + 2 * l.pad - l.r) / l.stride + 1;
+            L.Q = (L.W + 2 * l.pad - l.s) / l.stride + 1;
+            L.K = l.k;
+            if (L.P <= 0 || L.Q <= 0) return fail(c, COE_EINVAL, "arch: empty output");
+            if (l.op == COE_OP_MAXPOOL) {
+                if (l.k != L.C) return fail(c, COE_EINVAL, "arch: pool must keep channels");
+                if (l.pad >= l.r || l.pad >= l.s) return fail(c, COE_EINVAL, "arch: pool padding must be smaller than the window");
+            } else {
+                L.off[0] = take((size_t)l.k * l.r * l.s * L.C, true);
+                L.off[1] = take((size_t)l.k, false);
+                L.macs = (double)L.P * L.Q * l.k * l.r * l.s * L.C;
+                if (l.res >= 0) {
+                    if (l.res >= kMaxBufs || !shp[l.res].set || l.res == l.dst || shp[l.res].h != L.P || shp[l.res].w != L.Q ||
+                        shp[l.res].c != L.K)
+                        return fail(c, COE_EINVAL, "arch: residual shape mismatch");
+                }
+                if (l.act < 0 || l.act > 2) return fail(c, COE_EINVAL, "arch: unknown activation");
+            }
+            break;
+        }
+        case COE_OP_HEAD:
+            if (l.k != d->n_classes) return fail(c, COE_EINVAL, "arch: head width differs from n_classes");
+            L.K = l.k;
+            L.off[0] = take((size_t)l.k * L.C, true);
+            L.off[1] = take((size_t)l.k, false);
+            L.macs = (double)l.k * L.C;
+            break;
+        case COE_OP_TOKENS:
+            L.P = L.H * L.W + 1; L.Q = 1; L.K = L.C;
+            L.off[0] = take((size_t)L.C, true);
+            L.off[1] = take((size_t)L.P * L.C, true);
+            break;
+        case COE_OP_LAYERNORM:
+            L.P = L.H; L.Q = L.W; L.K = L.C;
+            L.off[0] = take((size_t)L.C, false);
+            L.off[1] = take((size_t)L.C, false);
+            break;
+        case COE_OP_ATTENTION:
+            if (L.C % 3 || l.aux0 <= 0 || (L.C / 3) % l.aux0) return fail(c, COE_EINVAL, "arch: bad attention shape");
+            L.P = L.H; L.Q = L.W; L.K = L.C / 3;
+            L.macs = 2.0 * L.H * L.W * L.H * L.W * (L.C / 3);
+            break;
+        case COE_OP_HEAD_CLS:
+            if (l.k != d->n_classes) return fail(c, COE_EINVAL, "arch: head width differs from n_classes");
+            L.K = l.k;
+            L.off[0] = take((size_t)L.C, false);
+            L.off[1] = take((size_t)L.C, false);
+            L.off[2] = take((size_t)l.k * L.C, true);
+            L.off[3] = take((size_t)l.k, false);
+            L.macs = (double)l.k * L.C;
+            break;
+        default:
+            return fail(c, COE_EINVAL, "arch: unknown op");
+        }
+        if (!is_head) {
+            shp[l.dst] = {L.P, L.Q, L.K, true};
+            a.buf_elems[l.dst] = std::max(a.buf_elems[l.dst], (size_t)L.P * L.Q * L.K);
+        }
+        a.layers.push_back(L);
+    }
+    int last = a.layers.back().d.op;
+    if (last != COE_OP_HEAD && last != COE_OP_HEAD_CLS) return fail(c, COE_EINVAL, "arch: program must end in a head");
+    a.blob_bytes = align_up(off);
+    return COE_OK;
+}
+
+// ---- device memory helpers -----------------------------------------------------------------------------------------
+int ensure_store(coe_ctx* c)
+{
+    if (c->archs.empty()) return fail(c, COE_ESTATE, "no architecture registered");
+    size_t nreq = (size_t)c->cfg.max_requests;
+    if (!c->d_inputs) {
+        size_t ib = c->archs[0].in_bytes();
+        HIPCHK(c, hipMalloc(&c->d_inputs, nreq * ib));
+        HIPCHK(c, hipMalloc(&c->d_staged, nreq * ib));
+    }
+    if (c->logits_alloc_classes < c->max_classes) {
+        if (c->n_live > 0) return fail(c, COE_ESTATE, "architecture with more classes registered while requests are live");
+        if (c->d_logits) HIPCHK(c, hipFree(c->d_logits));
+        HIPCHK(c, hipMalloc((void**)&c->d_logits, nreq * c->max_classes * sizeof(float)));
+        c->logits_alloc_classes = c->max_classes;
+    }
+    return COE_OK;
+}
+
+int ensure_workspace(coe_ctx* c)
+{
+    for (int b = 1; b < kMaxBufs; ++b) {
+        size_t need = 0;
+        for (const ArchPlan& a : c->archs) need = std::max(need, a.buf_elems[b] * a.elem() * (size_t)c->cfg.max_batch);
+        if (need > c->buf_bytes[b]) {
+            HIPCHK(c, hipStreamSynchronize(c->sc));
+            if (c->d_buf[b]) HIPCHK(c, hipFree(c->d_buf[b]));
+            c->d_buf[b] = nullptr;
+            HIPCHK(c, hipMalloc(&c->d_buf[b], need));
+            c->buf_bytes[b] = need;
+        }
+    }
+    return COE_OK;
+}
+
+int acquire_buf(coe_ctx* c, size_t bytes, DevBuf** out)
+{
+    for (size_t i = 0; i < c->free_bufs.size(); ++i)
+        if (c->free_bufs[i]->bytes == bytes) {
+            *out = c->free_bufs[i];
+            c->free_bufs.erase(c->free_bufs.begin() + i);
+            return COE_OK;
+        }
+    // no buffer of that size: give back free buffers of other sizes so the capped footprint holds
+    if (!c->free_bufs.empty()) {
+        HIPCHK(c, hipDeviceSynchronize());
+        for (DevBuf* b : c->free_bufs) {
+            hipFree(b->p);
+            b->p = nullptr;
+            b->bytes = 0;
+        }
+        c->free_bufs.clear();
+    }
+    DevBuf* b = new DevBuf();
+    hipError_t e = hipMalloc(&b->p, bytes);
+    if (e != hipSuccess) {
+        delete b;
+        (void)hipGetLastError();
+        return fail(c, COE_ENOMEM, "device allocation for an expert failed");
+    }
+    b->bytes = bytes;
+    if (hipEventCreateWithFlags(&b->last_use, hipEventDisableTiming) != hipSuccess) {
+        hipFree(b->p);
+        delete b;
+        return fail(c, COE_EDEVICE, "hipEventCreate failed");
+    }
+    c->all_bufs.push_back(b);
+    *out = b;
+    return COE_OK;
+}
+
+void release_expert(coe_ctx* c, int32_t v)
+{
+    Expert& x = c->experts[v];
+    if (x.buf) {
+        c->free_bufs.push_back(x.buf);
+        x.buf = nullptr;
+    }
+    x.load_pending = false;
+}
+
+// Enqueue one expert switch on the copy stream: victims leave, the expert's blob is copied into a device buffer.
+int issue_load(coe_ctx* c, const coe::Switch& sw, coe_step_stats* st)
+{
+    c->switch_log.push_back(sw.expert);
+    c->switch_log.push_back((int32_t)sw.victims.size());
+    for (int32_t v : sw.victims) {
+        c->switch_log.push_back(v);
+        release_expert(c, v);
+    }
+    Expert& x = c->experts[sw.expert];
+    DevBuf* b = nullptr;
+    int rc = acquire_buf(c, x.nbytes, &b);
+    if (rc) return rc;
+    // the buffer may still be read by kernels of its previous owner
+    if (b->used) HIPCHK(c, hipStreamWaitEvent(c->sx, b->last_use, 0));
+    {
+        Span sp(c, COE_K_SWITCH, (double)x.nbytes, c->sx);
+        HIPCHK(c, hipMemcpyAsync(b->p, x.host, x.nbytes, hipMemcpyHostToDevice, c->sx));
+    }
+    HIPCHK(c, hipEventRecord(x.loaded, c->sx));
+    x.buf = b;
+    x.load_pending = true;
+    if (st) {
+        st->n_evictions += (int32_t)sw.victims.size();
+        st->bytes_switched += (int64_t)x.nbytes;
+    }
+    return COE_OK;
+}
+
+// ---- one expert over one batch ---------------------------------------------------------------------------------------
+int run_expert(coe_ctx* c, const Expert& x, const void* weights, const void* input, int32_t n, const coe::k::RouteArgs& route)
+{
+    const ArchPlan& a = c->archs[x.arch];
+    const uint8_t* wb = (const uint8_t*)weights;
+    auto buf = [&](int id) -> void* { return id == 0 ? const_cast<void*>(input) : c->d_buf[id]; };
+    for (const LayerPlan& L : a.layers) {
+        const coe_layer& l = L.d;
+        switch (l.op) {
+        case COE_OP_CONV: {
+            coe::k::ConvShape s{n, L.H, L.W, L.C, L.K, l.r, l.s, l.stride, l.pad, L.P, L.Q, l.act};
+            const void* res = l.res >= 0 ? buf(l.res) : nullptr;
+            double flops = 2.0 * L.macs * n;
+            if (a.dtype == COE_DT_BF16 && coe::k::conv_mfma_supported(s)) {
+                Span sp(c, COE_K_CONV_MFMA, flops, c->sc);
+                HIPCHK(c, coe::k::conv_mfma(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), res, buf(l.dst), s, c->sc));
+            } else {
+                Span sp(c, COE_K_CONV_DIRECT, flops, c->sc);
+                HIPCHK(c, coe::k::conv_direct(a.dtype, buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), res, buf(l.dst), s, c->sc));
+            }
+            break;
+        }
+        case COE_OP_MAXPOOL: {
+            double bytes = (double)n * ((double)L.H * L.W * L.C + (double)L.P * L.Q * L.K) * a.elem();
+            Span sp(c, COE_K_POOL, bytes, c->sc);
+            HIPCHK(c, coe::k::maxpool(a.dtype, buf(l.src), buf(l.dst), n, L.H, L.W, L.C, l.r, l.s, l.stride, l.pad, L.P, L.Q, c->sc));
+            break;
+        }
+        case COE_OP_HEAD: {
+            double bytes = (double)n * L.H * L.W * L.C * a.elem();
+            Span sp(c, COE_K_HEAD, bytes, c->sc);
+            HIPCHK(c, coe::k::head_gap_fc(a.dtype, buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), n, L.H * L.W, L.C, L.K,
+                                          route, c->sc));
+            break;
+        }
+        default:
+            return fail(c, COE_EINVAL, "layer op has no device kernel yet");
+        }
+    }
+    return COE_OK;
+}
+
+int do_init_fill(coe_ctx* c, coe_step_stats* st)
+{
+    if (c->filled) return COE_OK;
+    std::vector<int32_t> loaded = c->policy->init_fill();
+    for (int32_t e : loaded) {
+        coe::Switch sw{e, {}};
+        int rc = issue_load(c, sw, nullptr);
+        if (rc) return rc;
+    }
+    (void)st;
+    c->filled = true;
+    return COE_OK;
+}
+
+}  // namespace
+
+// =====================================================================================================================
+extern "C" {
+
+const char* coe_last_error(const coe_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+int coe_create(const coe_config* cfg, coe_ctx** out)
+{
+    if (!cfg || !out) return COE_EINVAL;
+    *out = nullptr;
+    if (cfg->max_requests <= 0 || cfg->max_stages <= 0 || cfg->max_batch < 0 || cfg->cache_cap_experts < 0 || cfg->cache_cap_bytes < 0)
+        return COE_EINVAL;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || ndev <= 0 || cfg->device < 0 || cfg->device >= ndev) {
+        (void)hipGetLastError();
+        return COE_EDEVICE;
+    }
+    if (hipSetDevice(cfg->device) != hipSuccess) return COE_EDEVICE;
+    coe_ctx* c = new (std::nothrow) coe_ctx();
+    if (!c) return COE_ENOMEM;
+    c->cfg = *cfg;
+    if (c->cfg.max_batch == 0) c->cfg.max_batch = 256;
+    auto bail = [&](int code) { coe_destroy(c); return code; };
+    if (cfg->compute_stream) c->sc = (hipStream_t)cfg->compute_stream;
+    else { if (hipStreamCreateWithFlags(&c->sc, hipStreamNonBlocking) != hipSuccess) return bail(COE_EDEVICE); c->own_sc = true; }
+    if (cfg->copy_stream) c->sx = (hipStream_t)cfg->copy_stream;
+    else { if (hipStreamCreateWithFlags(&c->sx, hipStreamNonBlocking) != hipSuccess) return bail(COE_EDEVICE); c->own_sx = true; }
+    size_t nreq = (size_t)cfg->max_requests;
+    size_t nblocks = (nreq + coe::k::kRegroupTile - 1) / coe::k::kRegroupTile;
+    bool ok = hipMalloc((void**)&c->d_cur, nreq * 4) == hipSuccess && hipMalloc((void**)&c->d_depth, nreq * 4) == hipSuccess &&
+              hipMalloc((void**)&c->d_path, nreq * 4 * (size_t)cfg->max_stages) == hipSuccess &&
+              hipMalloc((void**)&c->d_perm, nreq * 4) == hipSuccess && hipMalloc((void**)&c->d_inv, nreq * 4) == hipSuccess &&
+              hipMalloc((void**)&c->d_cnt, coe::k::kRegroupMaxExperts * 4) == hipSuccess &&
+              hipMalloc((void**)&c->d_off, (coe::k::kRegroupMaxExperts + 1) * 4) == hipSuccess &&
+              hipMalloc((void**)&c->d_blockhist, nblocks * coe::k::kRegroupMaxExperts * 4) == hipSuccess &&
+              hipHostMalloc((void**)&c->h_cnt, coe::k::kRegroupMaxExperts * 4, hipHostMallocDefault) == hipSuccess;
+    if (!ok) return bail(COE_ENOMEM);
+    c->collected.assign(nreq, 0);
+    *out = c;
+    return COE_OK;
+}
+
+void coe_destroy(coe_ctx* c)
+{
+    if (!c) return;
+    (void)hipDeviceSynchronize();
+    for (Expert& x : c->experts) {
+        if (x.host) hipHostFree(x.host);
+        if (x.loaded) hipEventDestroy(x.loaded);
+    }
+    for (DevBuf* b : c->all_bufs) {
+        if (b->p) hipFree(b->p);
+        if (b->last_use) hipEventDestroy(b->last_use);
+        delete b;
+    }
+    for (auto& pc : c->prof)
+        for (auto& s : pc.spans) { hipEventDestroy(s.first); hipEventDestroy(s.second); }
+    for (hipEvent_t e : c->ev_pool) hipEventDestroy(e);
+    void* ptrs[] = {c->d_inputs, c->d_staged, c->d_cur, c->d_depth, c->d_path, c->d_logits, c->d_cnt, c->d_off,
+                    c->d_perm, c->d_inv, c->d_blockhist, c->d_succ};
+    for (void* p : ptrs) if (p) hipFree(p);
+    for (int b = 1; b < kMaxBufs; ++b) if (c->d_buf[b]) hipFree(c->d_buf[b]);
+    if (c->h_cnt) hipHostFree(c->h_cnt);
+    if (c->own_sc && c->sc) hipStreamDestroy(c->sc);
+    if (c->own_sx && c->sx) hipStreamDestroy(c->sx);
+    delete c;
+}
+
+int coe_register_arch(coe_ctx* c, const coe_arch_desc* desc, int32_t* arch_id)
+{
+    if (!c || !desc || !arch_id) return fail(c, COE_EINVAL, "null argument");
+    ArchPlan a;
+    int rc = plan_arch(c, desc, a);
+    if (rc) return rc;
+    if (!c->archs.empty()) {
+        const ArchPlan& f = c->archs[0];
+        if (f.dtype != a.dtype || f.in_h != a.in_h || f.in_w != a.in_w || f.in_c != a.in_c)
+            return fail(c, COE_EINVAL, "all architectures of a context must share input shape and dtype");
+    }
+    c->archs.push_back(std::move(a));
+    c->max_classes = std::max(c->max_classes, desc->n_classes);
+    *arch_id = (int32_t)c->archs.size() - 1;
+    return COE_OK;
+}
+
+int64_t coe_arch_blob_bytes(const coe_ctx* c, int32_t arch_id)
+{
+    if (!c || arch_id < 0 || arch_id >= (int32_t)c->archs.size()) return COE_EINVAL;
+    return (int64_t)c->archs[arch_id].blob_bytes;
+}
+
+int coe_register_expert(coe_ctx* c, int32_t id, int32_t arch_id, const void* w, size_t nbytes, float prob)
+{
+    if (!c || !w) return fail(c, COE_EINVAL, "null argument");
+    if (c->graph_set) return fail(c, COE_ESTATE, "experts must be registered before the dependency graph is set");
+    if (arch_id < 0 || arch_id >= (int32_t)c->archs.size()) return fail(c, COE_EINVAL, "unknown architecture");
+    if (id < 0 || id >= coe::k::kRegroupMaxExperts) return fail(c, COE_EINVAL, "expert id out of range");
+    if (nbytes != c->archs[arch_id].blob_bytes) return fail(c, COE_EINVAL, "weight blob size does not match the architecture");
+    if (!(prob >= 0.f)) return fail(c, COE_EINVAL, "usage probability must be >= 0");
+    if ((size_t)id >= c->experts.size()) c->experts.resize((size_t)id + 1);
+    Expert& x = c->experts[id];
+    if (x.registered) return fail(c, COE_EINVAL, "expert id registered twice");
+    if (hipHostMalloc(&x.host, nbytes, hipHostMallocDefault) != hipSuccess) {
+        (void)hipGetLastError();
+        x.host = nullptr;
+        return fail(c, COE_ENOMEM, "pinned host allocation failed");
+    }
+    std::memcpy(x.host, w, nbytes);
+    HIPCHK(c, hipEventCreateWithFlags(&x.loaded, hipEventDisableTiming));
+    x.registered = true;
+    x.arch = arch_id;
+    x.prob = prob;
+    x.nbytes = nbytes;
+    return COE_OK;
+}
+
+int coe_set_dependency_graph(coe_ctx* c, int32_t n, const int32_t* succ_off, const int32_t* succ)
+{
+    if (!c || !succ_off) return fail(c, COE_EINVAL, "null argument");
+    if (c->graph_set) return fail(c, COE_ESTATE, "dependency graph already set");
+    if (n <= 0 || n != (int32_t)c->experts.size()) return fail(c, COE_ESTATE, "n_experts differs from the registered experts");
+    std::vector<int32_t> ncls(n);
+    for (int32_t e = 0; e < n; ++e) {
+        if (!c->experts[e].registered) return fail(c, COE_ESTATE, "an expert id is missing");
+        ncls[e] = c->archs[c->experts[e].arch].n_classes;
+    }
+    int rc = coe::validate_graph(n, succ_off, succ, ncls.data());
+    if (rc) return fail(c, rc, "dependency graph invalid (id out of range, cycle, or more routes than classes)");
+    // longest path must fit the recorded path length
+    {
+        std::vector<int32_t> depth(n, 0), indeg(n, 0), order;
+        for (int32_t j = 0; j < succ_off[n]; ++j) if (succ[j] >= 0) ++indeg[succ[j]];
+        for (int32_t e = 0; e < n; ++e) if (!indeg[e]) { order.push_back(e); depth[e] = 1; }
+        for (size_t i = 0; i < order.size(); ++i) {
+            int32_t e = order[i];
+            for (int32_t j = succ_off[e]; j < succ_off[e + 1]; ++j) {
+                int32_t s = succ[j];
+                if (s < 0) continue;
+                depth[s] = std::max(depth[s], depth[e] + 1);
+                if (--indeg[s] == 0) order.push_back(s);
+            }
+        }
+        if (*std::max_element(depth.begin(), depth.end()) > c->cfg.max_stages)
+            return fail(c, COE_ERANGE, "dependency graph is deeper than max_stages");
+    }
+    c->succ_off.assign(succ_off, succ_off + n + 1);
+    c->succ.assign(succ, succ + succ_off[n]);
+    size_t nb = std::max<size_t>(1, c->succ.size()) * 4;
+    HIPCHK(c, hipMalloc((void**)&c->d_succ, nb));
+    if (!c->succ.empty()) HIPCHK(c, hipMemcpy(c->d_succ, c->succ.data(), c->succ.size() * 4, hipMemcpyHostToDevice));
+    std::vector<int64_t> bytes(n);
+    std::vector<float> prob(n);
+    for (int32_t e = 0; e < n; ++e) { bytes[e] = (int64_t)c->experts[e].nbytes; prob[e] = c->experts[e].prob; }
+    c->policy.reset(new coe::Policy(n, bytes.data(), prob.data(), c->succ_off.data(), c->succ.data(), c->cfg.cache_cap_experts,
+                                    c->cfg.cache_cap_bytes));
+    c->E = n;
+    c->graph_set = true;
+    return COE_OK;
+}
+
+int coe_submit(coe_ctx* c, int32_t n, const void* inputs, int on_device, const int32_t* first, int64_t* first_id)
+{
+    if (!c || n < 0 || (n > 0 && !inputs)) return fail(c, COE_EINVAL, "bad argument");
+    if (!c->graph_set) return fail(c, COE_ESTATE, "set the dependency graph before submitting");
+    if ((int64_t)c->n_live + n > c->cfg.max_requests) return fail(c, COE_ERANGE, "request store is full");
+    if (first)
+        for (int32_t i = 0; i < n; ++i)
+            if (first[i] < 0 || first[i] >= c->E) return fail(c, COE_EINVAL, "first_expert out of range");
+    int rc = ensure_store(c);
+    if (rc) return rc;
+    if (first_id) *first_id = c->id_base + c->n_live;
+    if (n == 0) return COE_OK;
+    size_t ib = c->archs[0].in_bytes();
+    size_t base = (size_t)c->n_live;
+    HIPCHK(c, hipMemcpyAsync((uint8_t*)c->d_inputs + base * ib, inputs, (size_t)n * ib,
+                             on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, c->sc));
+    std::vector<int32_t> cur(n, 0);
+    if (first) std::copy(first, first + n, cur.begin());
+    HIPCHK(c, hipMemcpyAsync(c->d_cur + base, cur.data(), (size_t)n * 4, hipMemcpyHostToDevice, c->sc));
+    HIPCHK(c, hipMemsetAsync(c->d_depth + base, 0, (size_t)n * 4, c->sc));
+    HIPCHK(c, hipMemsetAsync(c->d_path + base * c->cfg.max_stages, 0xFF, (size_t)n * 4 * c->cfg.max_stages, c->sc));
+    HIPCHK(c, hipMemsetAsync(c->d_logits + base * c->max_classes, 0, (size_t)n * 4 * c->max_classes, c->sc));
+    // `cur` is pageable host memory: the copy above has been staged by the runtime when the call returns only if we wait
+    HIPCHK(c, hipStreamSynchronize(c->sc));
+    std::fill(c->collected.begin() + base, c->collected.begin() + base + n, 0);
+    c->n_live += n;
+    return COE_OK;
+}
+
+int coe_step(coe_ctx* c, coe_step_stats* stats)
+{
+    if (!c) return COE_EINVAL;
+    coe_step_stats st{};
+    if (stats) *stats = st;
+    if (!c->graph_set) return fail(c, COE_ESTATE, "dependency graph not set");
+    if (c->n_live == 0) return COE_DONE;
+    int rc = ensure_workspace(c);
+    if (rc) return rc;
+    rc = do_init_fill(c, &st);
+    if (rc) return rc;
+    const int32_t E = c->E;
+
+    // request arranging, index part
+    {
+        Span sp(c, COE_K_REGROUP_INDEX, (double)c->n_live * 16.0, c->sc);
+        HIPCHK(c, coe::k::regroup_index(c->d_cur, c->n_live, E, c->d_cnt, c->d_off, c->d_perm, c->d_inv, c->d_blockhist, c->sc));
+    }
+    HIPCHK(c, hipMemcpyAsync(c->h_cnt, c->d_cnt, (size_t)E * 4, hipMemcpyDeviceToHost, c->sc));
+    HIPCHK(c, hipStreamSynchronize(c->sc));
+    auto t0 = std::chrono::steady_clock::now();
+    std::vector<int32_t> off(E + 1, 0);
+    std::vector<uint8_t> has_group(E, 0);
+    for (int32_t e = 0; e < E; ++e) {
+        off[e + 1] = off[e] + c->h_cnt[e];
+        has_group[e] = c->h_cnt[e] > 0;
+    }
+    const int32_t n_pending = off[E];
+    c->last_pending = n_pending; c->last_live = c->n_live; c->last_E = E;
+    if (n_pending == 0) return COE_DONE;
+
+    // cache plan: execution order and switches
+    std::vector<int32_t> order;
+    std::vector<coe::Switch> switches;
+    if (!c->policy->plan_stage(has_group.data(), order, switches)) {
+        for (int32_t e = 0; e < E; ++e)
+            if (!c->policy->resident(e)) release_expert(c, e);
+        return fail(c, COE_ENOMEM, "an expert does not fit the device cache");
+    }
+    st.n_pending = n_pending;
+    st.n_groups = (int32_t)order.size();
+    st.n_misses = (int32_t)switches.size();
+    st.n_hits = st.n_groups - st.n_misses;
+    st.host_plan_us = std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
+
+    // request arranging, activation part: inputs into group-contiguous order
+    const size_t ib = c->archs[0].in_bytes();
+    {
+        Span sp(c, COE_K_REGROUP_GATHER, 2.0 * (double)n_pending * (double)ib, c->sc);
+        HIPCHK(c, coe::k::gather_rows(c->d_inputs, c->d_perm, n_pending, ib, c->d_staged, c->sc));
+    }
+
+    std::vector<uint8_t> launched(E, 0);
+    size_t next_load = 0;
+    for (int32_t e : order) {
+        // enqueue every switch whose victims are no longer needed by a group that has not been launched yet;
+        // the copies run on the copy stream while earlier groups compute
+        while (next_load < switches.size()) {
+            const coe::Switch& sw = switches[next_load];
+            bool ready = true;
+            for (int32_t v : sw.victims) ready = ready && !(has_group[v] && !launched[v]);
+            if (!ready) break;
+            rc = issue_load(c, sw, &st);
+            if (rc) return rc;
+            ++next_load;
+        }
+        Expert& x = c->experts[e];
+        if (!x.buf) return fail(c, COE_ESTATE, "internal: expert not loaded at launch time");
+        if (x.load_pending) {
+            HIPCHK(c, hipStreamWaitEvent(c->sc, x.loaded, 0));
+            x.load_pending = false;
+        }
+        const int32_t n_route = c->succ_off[e + 1] - c->succ_off[e];
+        for (int32_t s = off[e]; s < off[e + 1]; s += c->cfg.max_batch) {
+            int32_t cnt = std::min(c->cfg.max_batch, off[e + 1] - s);
+            coe::k::RouteArgs r{c->d_perm + s, e, c->d_succ + c->succ_off[e], n_route, c->d_cur, c->d_depth, c->d_path,
+                                c->cfg.max_stages, c->d_logits, c->max_classes};
+            rc = run_expert(c, x, x.buf->p, (const uint8_t*)c->d_staged + (size_t)s * ib, cnt, r);
+            if (rc) return rc;
+            ++st.n_chunks;
+        }
+        HIPCHK(c, hipEventRecord(x.buf->last_use, c->sc));
+        x.buf->used = true;
+        launched[e] = 1;
+    }
+    if (stats) *stats = st;
+    return COE_OK;
+}
+
+int coe_sync(coe_ctx* c)
+{
+    if (!c) return COE_EINVAL;
+    HIPCHK(c, hipStreamSynchronize(c->sx));
+    HIPCHK(c, hipStreamSynchronize(c->sc));
+    return COE_OK;
+}
+
+int coe_collect(coe_ctx* c, int32_t cap, int64_t* ids, float* logits, int32_t* path, int32_t* n_out)
+{
+    if (!c || cap < 0 || !n_out) return fail(c, COE_EINVAL, "bad argument");
+    *n_out = 0;
+    if (c->n_live == 0) return COE_OK;
+    HIPCHK(c, hipStreamSynchronize(c->sc));
+    const size_t n = (size_t)c->n_live, ms = (size_t)c->cfg.max_stages, mc = (size_t)c->max_classes;
+    std::vector<int32_t> cur(n), hpath(path ? n * ms : 0);
+    std::vector<float> hlog(logits ? n * mc : 0);
+    HIPCHK(c, hipMemcpy(cur.data(), c->d_cur, n * 4, hipMemcpyDeviceToHost));
+    if (path) HIPCHK(c, hipMemcpy(hpath.data(), c->d_path, n * ms * 4, hipMemcpyDeviceToHost));
+    if (logits) HIPCHK(c, hipMemcpy(hlog.data(), c->d_logits, n * mc * 4, hipMemcpyDeviceToHost));
+    int32_t m = 0;
+    for (size_t i = 0; i < n && m < cap; ++i) {
+        if (c->collected[i] || cur[i] >= 0) continue;
+        if (ids) ids[m] = c->id_base + (int64_t)i;
+        if (logits) std::memcpy(logits + (size_t)m * mc, hlog.data() + i * mc, mc * 4);
+        if (path) std::memcpy(path + (size_t)m * ms, hpath.data() + i * ms, ms * 4);
+        c->collected[i] = 1;
+        ++c->n_collected;
+        ++m;
+    }
+    *n_out = m;
+    if (c->n_collected == c->n_live) {   // store drained: start over at slot 0, ids keep counting
+        c->id_base += c->n_live;
+        c->n_live = 0;
+        c->n_collected = 0;
+    }
+    return COE_OK;
+}
+
+int coe_reset_requests(coe_ctx* c)
+{
+    if (!c) return COE_EINVAL;
+    HIPCHK(c, hipStreamSynchronize(c->sc));
+    c->id_base += c->n_live;
+    c->n_live = 0;
+    c->n_collected = 0;
+    return COE_OK;
+}
+
+int coe_debug_last_regroup(coe_ctx* c, int32_t* n_pending, int32_t* n_live, int32_t* cnt, int32_t* off, int32_t* perm,
+                           int32_t* inv, int32_t perm_cap)
+{
+    if (!c) return COE_EINVAL;
+    HIPCHK(c, hipStreamSynchronize(c->sc));
+    if (n_pending) *n_pending = c->last_pending;
+    if (n_live) *n_live = c->last_live;
+    if (c->last_E == 0) return COE_OK;
+    if (cnt) HIPCHK(c, hipMemcpy(cnt, c->d_cnt, (size_t)c->last_E * 4, hipMemcpyDeviceToHost));
+    if (off) HIPCHK(c, hipMemcpy(off, c->d_off, ((size_t)c->last_E + 1) * 4, hipMemcpyDeviceToHost));
+    if (perm) {
+        if (perm_cap < c->last_pending) return fail(c, COE_ERANGE, "perm buffer too small");
+        if (c->last_pending) HIPCHK(c, hipMemcpy(perm, c->d_perm, (size_t)c->last_pending * 4, hipMemcpyDeviceToHost));
+    }
+    if (inv && c->last_live) HIPCHK(c, hipMemcpy(inv, c->d_inv, (size_t)c->last_live * 4, hipMemcpyDeviceToHost));
+    return COE_OK;
+}
+
+int coe_debug_switch_log(coe_ctx* c, int32_t cap, int32_t* log, int32_t* n_words)
+{
+    if (!c || !n_words || cap < 0 || (cap > 0 && !log)) return COE_EINVAL;
+    *n_words = (int32_t)c->switch_log.size();
+    std::copy(c->switch_log.begin(), c->switch_log.begin() + std::min<size_t>(cap, c->switch_log.size()), log);
+    return COE_OK;
+}
+
+int coe_debug_resident(coe_ctx* c, uint8_t* out)
+{
+    if (!c || !out) return COE_EINVAL;
+    for (size_t e = 0; e < c->experts.size(); ++e) out[e] = c->experts[e].buf ? 1 : 0;
+    return COE_OK;
+}
+
+int coe_debug_forward(coe_ctx* c, int32_t e, int32_t n, const void* dev_in, float* logits_out)
+{
+    if (!c || !dev_in || !logits_out || n < 0) return fail(c, COE_EINVAL, "bad argument");
+    if (e < 0 || e >= (int32_t)c->experts.size() || !c->experts[e].registered) return fail(c, COE_EINVAL, "unknown expert");
+    if (n == 0) return COE_OK;
+    int rc = ensure_workspace(c);
+    if (rc) return rc;
+    Expert& x = c->experts[e];
+    const ArchPlan& a = c->archs[x.arch];
+    void* w = nullptr;
+    float* d_log = nullptr;
+    bool temp = false;
+    if (x.buf) {
+        if (x.load_pending) { HIPCHK(c, hipStreamWaitEvent(c->sc, x.loaded, 0)); x.load_pending = false; }
+        w = x.buf->p;
+    } else {
+        HIPCHK(c, hipMalloc(&w, x.nbytes));
+        temp = true;
+        HIPCHK(c, hipMemcpy(w, x.host, x.nbytes, hipMemcpyHostToDevice));
+    }
+    HIPCHK(c, hipMalloc((void**)&d_log, (size_t)n * a.n_classes * 4));
+    const size_t ib = a.in_bytes();
+    for (int32_t s = 0; s < n && rc == COE_OK; s += c->cfg.max_batch) {
+        int32_t cnt = std::min(c->cfg.max_batch, n - s);
+        coe::k::RouteArgs r{nullptr, e, nullptr, 0, nullptr, nullptr, nullptr, 0, d_log + (size_t)s * a.n_classes, a.n_classes};
+        rc = run_expert(c, x, w, (const uint8_t*)dev_in + (size_t)s * ib, cnt, r);
+    }
+    hipError_t he = hipStreamSynchronize(c->sc);
+    if (rc == COE_OK && he == hipSuccess) he = hipMemcpy(logits_out, d_log, (size_t)n * a.n_classes * 4, hipMemcpyDeviceToHost);
+    hipFree(d_log);
+    if (temp) hipFree(w);
+    if (rc) return rc;
+    if (he != hipSuccess) return fail(c, COE_EDEVICE, hipGetErrorString(he));
+    return COE_OK;
+}
+
+int coe_debug_regroup(coe_ctx* c, int32_t n, const int32_t* cur, int32_t E, int32_t* cnt, int32_t* off, int32_t* perm, int32_t* inv)
+{
+    if (!c || n < 0 || (n > 0 && !cur)) return fail(c, COE_EINVAL, "bad argument");
+    if (E <= 0 || E > coe::k::kRegroupMaxExperts) return fail(c, COE_EINVAL, "n_experts out of range");
+    if (n > c->cfg.max_requests) return fail(c, COE_ERANGE, "more keys than max_requests");
+    if (c->n_live > 0) return fail(c, COE_ESTATE, "requests are live");
+    if (n) HIPCHK(c, hipMemcpy(c->d_cur, cur, (size_t)n * 4, hipMemcpyHostToDevice));
+    HIPCHK(c, coe::k::regroup_index(c->d_cur, n, E, c->d_cnt, c->d_off, c->d_perm, c->d_inv, c->d_blockhist, c->sc));
+    HIPCHK(c, hipStreamSynchronize(c->sc));
+    std::vector<int32_t> hoff(E + 1);
+    HIPCHK(c, hipMemcpy(hoff.data(), c->d_off, ((size_t)E + 1) * 4, hipMemcpyDeviceToHost));
+    if (off) std::copy(hoff.begin(), hoff.end(), off);
+    if (cnt) HIPCHK(c, hipMemcpy(cnt, c->d_cnt, (size_t)E * 4, hipMemcpyDeviceToHost));
+    if (perm && hoff[E] > 0) HIPCHK(c, hipMemcpy(perm, c->d_perm, (size_t)hoff[E] * 4, hipMemcpyDeviceToHost));
+    if (inv && n > 0) HIPCHK(c, hipMemcpy(inv, c->d_inv, (size_t)n * 4, hipMemcpyDeviceToHost));
+    return hoff[E];
+}
+
+int coe_profile_read(coe_ctx* c, int32_t cls, int64_t* launches, double* ms, double* work)
+{
+    if (!c || cls < 0 || cls >= COE_K_COUNT) return COE_EINVAL;
+    HIPCHK(c, hipStreamSynchronize(c->sx));
+    HIPCHK(c, hipStreamSynchronize(c->sc));
+    ProfClass& p = c->prof[cls];
+    double total = 0.0;
+    for (auto& s : p.spans) {
+        float t = 0.f;
+        if (hipEventElapsedTime(&t, s.first, s.second) == hipSuccess) total += t;
+        else (void)hipGetLastError();
+        c->ev_pool.push_back(s.first);
+        c->ev_pool.push_back(s.second);
+    }
+    if (launches) *launches = (int64_t)p.spans.size();
+    if (ms) *ms = total;
+    if (work) *work = p.work;
+    p.spans.clear();
+    p.work = 0.0;
+    return COE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,60 @@
+// Launch interface of the gfx950 kernels.  Every function enqueues on `stream` and returns the launch status;
+// shapes are validated by the caller (the stage driver), which owns all buffers.
+#pragma once
+#include <hip/hip_runtime_api.h>
+
+#include <cstddef>
+#include <cstdint>
+
+namespace coe {
+namespace k {
+
+constexpr int kRegroupTile = 256;     // requests per workgroup in the regroup kernels
+constexpr int kRegroupMaxExperts = 2048;
+
+// Routing epilogue arguments.  slot == nullptr: row i writes logits row i and nothing else (plain forward).
+struct RouteArgs {
+    const int32_t* slot;   // [n] request-store slot of each row of this batch (device)
+    int32_t expert;        // expert that ran
+    const int32_t* succ;   // device successor list of that expert
+    int32_t n_route;       // its length (0: every request is final)
+    int32_t* cur;          // [slots] next expert per request, -1 = final
+    int32_t* depth;        // [slots] stages executed so far
+    int32_t* path;         // [slots][max_stages]
+    int32_t max_stages;
+    float* logits;         // [slots or n][logits_stride]
+    int32_t logits_stride;
+};
+
+// Request arranging, index part: per-expert histogram, prefix scan, stable scatter of request indices.
+// cur[n]: expert id in [0,E) = pending, anything else = not pending.  cnt[E], off[E+1], perm[<=n], inv[n].
+// blockhist: scratch of ceil(n/kRegroupTile)*E int32.
+hipError_t regroup_index(const int32_t* cur, int32_t n, int32_t E, int32_t* cnt, int32_t* off, int32_t* perm,
+                         int32_t* inv, int32_t* blockhist, hipStream_t stream);
+
+// Request arranging, activation part: dst row i = src row perm[i]; rows of row_bytes (multiple of 4) bytes.
+hipError_t gather_rows(const void* src, const int32_t* perm, int32_t n_rows, size_t row_bytes, void* dst,
+                       hipStream_t stream);
+
+struct ConvShape {
+    int32_t N, H, W, C, K, R, S, stride, pad, P, Q, act;
+};
+
+// Plain convolution kernel for any shape, fp32 or bf16 storage, fp32 FMA accumulation.
+hipError_t conv_direct(int dtype, const void* x, const void* w, const float* bias, const void* res, void* y,
+                       const ConvShape& s, hipStream_t stream);
+
+// bf16 implicit-GEMM convolution on the matrix cores.  Requires C % 32 == 0 and K % 32 == 0.
+bool conv_mfma_supported(const ConvShape& s);
+hipError_t conv_mfma(const void* x, const void* w, const float* bias, const void* res, void* y, const ConvShape& s,
+                     hipStream_t stream);
+
+hipError_t maxpool(int dtype, const void* x, void* y, int32_t N, int32_t H, int32_t W, int32_t C, int32_t R, int32_t S,
+                   int32_t stride, int32_t pad, int32_t P, int32_t Q, hipStream_t stream);
+
+// Global average pool + FC + argmax routing.  x: [N][HW][C]; w: [ncls][C] in dtype; b: [ncls] fp32.
+hipError_t head_gap_fc(int dtype, const void* x, const void* w, const float* b, int32_t N, int32_t HW, int32_t C,
+                       int32_t ncls, const RouteArgs& r, hipStream_t stream);
+
+}  // namespace k
+}  // namespace coe

@@ -1,0 +1,398 @@
+// gfx950 kernels: request arranging (regroup), plain convolution, max pool, routing head.
+// Wavefronts are 64 lanes wide throughout.
+#include <hip/hip_runtime.h>
+
+#include "kernels.h"
+
+namespace coe {
+namespace k {
+
+namespace {
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// round to nearest even; NaN becomes a quiet NaN
+__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0;
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static __device__ __forceinline__ float load(const float* p) { return *p; }
+    static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
+};
+template <> struct Elem<uint16_t> {
+    static __device__ __forceinline__ float load(const uint16_t* p) { return bf16_to_f32(*p); }
+    static __device__ __forceinline__ void store(uint16_t* p, float v) { *p = f32_to_bf16(v); }
+};
+
+__device__ __forceinline__ float apply_act(float v, int act)
+{
+    if (act == 1) return v > 0.f ? v : 0.f;
+    if (act == 2) return 0.5f * v * (1.f + erff(v * 0.70710678118654752440f));
+    return v;
+}
+
+// -------------------------------------------------------------------------------------------------------------
+// regroup, index part
+// -------------------------------------------------------------------------------------------------------------
+// Pass 1: per-workgroup histogram of the pending requests' expert ids.
+__global__ __launch_bounds__(kRegroupTile) void regroup_count_kernel(const int32_t* __restrict__ cur, int32_t n,
+                                                                     int32_t E, int32_t* __restrict__ blockhist)
+{
+    extern __shared__ int32_t hist[];
+    for (int e = threadIdx.x; e < E; e += kRegroupTile) hist[e] = 0;
+    __syncthreads();
+    int i = blockIdx.x * kRegroupTile + threadIdx.x;
+    if (i < n) {
+        int key = cur[i];
+        if (key >= 0 && key < E) atomicAdd(&hist[key], 1);
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < E; e += kRegroupTile) blockhist[(size_t)blockIdx.x * E + e] = hist[e];
+}
+
+// inclusive prefix sum across one wavefront
+__device__ __forceinline__ int wave_inclusive_scan(int v)
+{
+    int lane = threadIdx.x & (kWave - 1);
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        int t = __shfl_up(v, d, kWave);
+        if (lane >= d) v += t;
+    }
+    return v;
+}
+
+// Pass 2 (one workgroup): column sums of blockhist -> cnt; blockhist becomes the exclusive prefix down each column;
+// exclusive scan of cnt over experts -> off.
+constexpr int kScanThreads = 1024;
+__global__ __launch_bounds__(kScanThreads) void regroup_scan_kernel(int32_t* __restrict__ blockhist, int32_t nblocks,
+                                                                    int32_t E, int32_t* __restrict__ cnt,
+                                                                    int32_t* __restrict__ off)
+{
+    __shared__ int32_t wave_tot[kScanThreads / kWave];
+    __shared__ int32_t carry;
+    if (threadIdx.x == 0) carry = 0;
+    __syncthreads();
+    int lane = threadIdx.x & (kWave - 1), wid = threadIdx.x / kWave;
+    for (int base = 0; base < E; base += kScanThreads) {
+        int e = base + threadIdx.x;
+        int total = 0;
+        if (e < E) {
+            for (int b = 0; b < nblocks; ++b) {
+                int t = blockhist[(size_t)b * E + e];
+                blockhist[(size_t)b * E + e] = total;
+                total += t;
+            }
+            cnt[e] = total;
+        }
+        int incl = wave_inclusive_scan(total);
+        if (lane == kWave - 1) wave_tot[wid] = incl;
+        __syncthreads();
+        if (wid == 0) {
+            int t = lane < kScanThreads / kWave ? wave_tot[lane] : 0;
+            int s = wave_inclusive_scan(t);
+            if (lane < kScanThreads / kWave) wave_tot[lane] = s - t;   // exclusive offset of each wave
+        }
+        __syncthreads();
+        int c = carry;
+        int excl = c + wave_tot[wid] + incl - total;
+        if (e < E) off[e] = excl;
+        __syncthreads();
+        if (threadIdx.x == kScanThreads - 1) carry = excl + total;
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) off[E] = carry;
+}
+
+// Pass 3: stable scatter.  Position of request i = off[key] + (requests with that key in earlier workgroups)
+// + (in earlier wavefronts of this workgroup) + (in lower lanes of this wavefront).
+__global__ __launch_bounds__(kRegroupTile) void regroup_scatter_kernel(const int32_t* __restrict__ cur, int32_t n,
+                                                                       int32_t E, const int32_t* __restrict__ blockhist,
+                                                                       const int32_t* __restrict__ off,
+                                                                       int32_t* __restrict__ perm,
+                                                                       int32_t* __restrict__ inv)
+{
+    extern __shared__ int32_t wcount[];   // [waves][E]
+    constexpr int kWaves = kRegroupTile / kWave;
+    for (int j = threadIdx.x; j < kWaves * E; j += kRegroupTile) wcount[j] = 0;
+    __syncthreads();
+    int i = blockIdx.x * kRegroupTile + threadIdx.x;
+    int lane = threadIdx.x & (kWave - 1), wid = threadIdx.x / kWave;
+    int key = -1;
+    if (i < n) {
+        key = cur[i];
+        if (key < 0 || key >= E) key = -1;
+    }
+    unsigned long long lt_mask = lane == 0 ? 0ull : (~0ull >> (kWave - lane));
+    unsigned long long remaining = __ballot(key >= 0);
+    int rank = 0;
+    while (remaining) {
+        int leader = __ffsll((long long)remaining) - 1;
+        int lk = __shfl(key, leader, kWave);
+        unsigned long long peers = __ballot(key == lk);
+        if (key == lk) {
+            rank = __popcll(peers & lt_mask);
+            if (lane == leader) wcount[wid * E + lk] = __popcll(peers);
+        }
+        remaining &= ~peers;
+    }
+    __syncthreads();
+    if (key >= 0) {
+        int before = 0;
+        for (int w = 0; w < wid; ++w) before += wcount[w * E + key];
+        int pos = off[key] + blockhist[(size_t)blockIdx.x * E + key] + before + rank;
+        perm[pos] = i;
+        inv[i] = pos;
+    } else if (i < n) {
+        inv[i] = -1;
+    }
+}
+
+// -------------------------------------------------------------------------------------------------------------
+// regroup, activation part: coalesced row gather, 16 bytes per lane
+// -------------------------------------------------------------------------------------------------------------
+constexpr int kGatherThreads = 256;
+template <typename V>
+__global__ __launch_bounds__(kGatherThreads) void gather_rows_kernel(const V* __restrict__ src,
+                                                                     const int32_t* __restrict__ perm,
+                                                                     size_t row_vecs, V* __restrict__ dst)
+{
+    int row = blockIdx.x;
+    const V* s = src + (size_t)perm[row] * row_vecs;
+    V* d = dst + (size_t)row * row_vecs;
+    for (size_t j = (size_t)blockIdx.y * kGatherThreads + threadIdx.x; j < row_vecs; j += (size_t)gridDim.y * kGatherThreads)
+        d[j] = s[j];
+}
+
+// -------------------------------------------------------------------------------------------------------------
+// plain convolution: one thread per output element, channels fastest
+// -------------------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void conv_direct_kernel(const T* __restrict__ x, const T* __restrict__ w,
+                                                          const float* __restrict__ bias, const T* __restrict__ res,
+                                                          T* __restrict__ y, ConvShape s)
+{
+    size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    size_t total = (size_t)s.N * s.P * s.Q * s.K;
+    if (idx >= total) return;
+    int k = (int)(idx % s.K);
+    size_t m = idx / s.K;
+    int q = (int)(m % s.Q);
+    int p = (int)((m / s.Q) % s.P);
+    int n = (int)(m / ((size_t)s.Q * s.P));
+    float acc = 0.f;
+    for (int r = 0; r < s.R; ++r) {
+        int ih = p * s.stride - s.pad + r;
+        if (ih < 0 || ih >= s.H) continue;
+        for (int t = 0; t < s.S; ++t) {
+            int iw = q * s.stride - s.pad + t;
+            if (iw < 0 || iw >= s.W) continue;
+            const T* xp = x + (((size_t)n * s.H + ih) * s.W + iw) * s.C;
+            const T* wp = w + (((size_t)k * s.R + r) * s.S + t) * s.C;
+            for (int c = 0; c < s.C; ++c) acc = fmaf(Elem<T>::load(xp + c), Elem<T>::load(wp + c), acc);
+        }
+    }
+    float v = acc + bias[k];
+    if (res) v += Elem<T>::load(res + idx);
+    Elem<T>::store(y + idx, apply_act(v, s.act));
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void maxpool_kernel(const T* __restrict__ x, T* __restrict__ y, int N, int H, int W,
+                                                      int C, int R, int S, int stride, int pad, int P, int Q)
+{
+    size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    size_t total = (size_t)N * P * Q * C;
+    if (idx >= total) return;
+    int c = (int)(idx % C);
+    size_t m = idx / C;
+    int q = (int)(m % Q);
+    int p = (int)((m / Q) % P);
+    int n = (int)(m / ((size_t)Q * P));
+    float best = -INFINITY;
+    for (int r = 0; r < R; ++r) {
+        int ih = p * stride - pad + r;
+        if (ih < 0 || ih >= H) continue;
+        for (int t = 0; t < S; ++t) {
+            int iw = q * stride - pad + t;
+            if (iw < 0 || iw >= W) continue;
+            best = fmaxf(best, Elem<T>::load(x + (((size_t)n * H + ih) * W + iw) * C + c));
+        }
+    }
+    Elem<T>::store(y + idx, best);
+}
+
+// -------------------------------------------------------------------------------------------------------------
+// routing head: global average pool, FC, argmax over the routed classes, successor lookup
+// -------------------------------------------------------------------------------------------------------------
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int d = kWave / 2; d > 0; d >>= 1) v += __shfl_xor(v, d, kWave);
+    return v;
+}
+
+constexpr int kHeadThreads = 256;
+template <typename T>
+__global__ __launch_bounds__(kHeadThreads) void head_gap_fc_kernel(const T* __restrict__ x, const T* __restrict__ w,
+                                                                   const float* __restrict__ b, int HW, int C, int ncls,
+                                                                   RouteArgs r)
+{
+    extern __shared__ float smem[];          // feat[C] | part[groups][C] | logit[ncls]
+    int row = blockIdx.x;
+    const T* xp = x + (size_t)row * HW * C;
+    int groups = C < kHeadThreads ? kHeadThreads / C : 1;      // position groups when there are few channels
+    float* feat = smem;
+    float* part = smem + C;
+    float* logit = part + (size_t)groups * C;
+    // phase 1: per-channel sums, lanes run along channels (contiguous in NHWC)
+    if (groups > 1) {
+        int g = threadIdx.x / C, c = threadIdx.x % C;
+        if (g < groups) {
+            float a = 0.f;
+            for (int i = g; i < HW; i += groups) a += Elem<T>::load(xp + (size_t)i * C + c);
+            part[g * C + c] = a;
+        }
+        __syncthreads();
+        for (int c2 = threadIdx.x; c2 < C; c2 += kHeadThreads) {
+            float a = 0.f;
+            for (int g2 = 0; g2 < groups; ++g2) a += part[g2 * C + c2];
+            feat[c2] = a / (float)HW;
+        }
+    } else {
+        for (int c = threadIdx.x; c < C; c += kHeadThreads) {
+            float a = 0.f;
+            for (int i = 0; i < HW; ++i) a += Elem<T>::load(xp + (size_t)i * C + c);
+            feat[c] = a / (float)HW;
+        }
+    }
+    __syncthreads();
+    // phase 2: one wavefront per class, lanes along the feature dimension, wavefront reduction
+    int lane = threadIdx.x & (kWave - 1), wid = threadIdx.x / kWave;
+    for (int j = wid; j < ncls; j += kHeadThreads / kWave) {
+        float a = 0.f;
+        for (int c = lane; c < C; c += kWave) a = fmaf(feat[c], Elem<T>::load(w + (size_t)j * C + c), a);
+        a = wave_sum(a);
+        if (lane == 0) logit[j] = a + b[j];
+    }
+    __syncthreads();
+    // phase 3: write logits, pick the route
+    int slot = r.slot ? r.slot[row] : row;
+    for (int j = threadIdx.x; j < r.logits_stride; j += kHeadThreads)
+        r.logits[(size_t)slot * r.logits_stride + j] = j < ncls ? logit[j] : 0.f;
+    if (threadIdx.x == 0 && r.cur) {
+        int nxt = -1;
+        if (r.n_route > 0) {
+            int best = 0;
+            for (int j = 1; j < r.n_route; ++j)
+                if (logit[j] > logit[best]) best = j;      // strict: the lowest index wins ties
+            nxt = r.succ[best];
+        }
+        int d = r.depth[slot];
+        if (d < r.max_stages) r.path[(size_t)slot * r.max_stages + d] = r.expert;
+        r.depth[slot] = d + 1;
+        r.cur[slot] = nxt;
+    }
+}
+
+}  // namespace
+
+// -------------------------------------------------------------------------------------------------------------
+// launchers
+// -------------------------------------------------------------------------------------------------------------
+hipError_t regroup_index(const int32_t* cur, int32_t n, int32_t E, int32_t* cnt, int32_t* off, int32_t* perm,
+                         int32_t* inv, int32_t* blockhist, hipStream_t stream)
+{
+    if (n < 0 || E <= 0 || E > kRegroupMaxExperts) return hipErrorInvalidValue;
+    int nblocks = (n + kRegroupTile - 1) / kRegroupTile;
+    if (nblocks > 0)
+        hipLaunchKernelGGL(regroup_count_kernel, dim3(nblocks), dim3(kRegroupTile), sizeof(int32_t) * E, stream, cur, n, E,
+                           blockhist);
+    hipLaunchKernelGGL(regroup_scan_kernel, dim3(1), dim3(kScanThreads), 0, stream, blockhist, nblocks, E, cnt, off);
+    if (nblocks > 0)
+        hipLaunchKernelGGL(regroup_scatter_kernel, dim3(nblocks), dim3(kRegroupTile),
+                           sizeof(int32_t) * E * (kRegroupTile / kWave), stream, cur, n, E, blockhist, off, perm, inv);
+    return hipGetLastError();
+}
+
+hipError_t gather_rows(const void* src, const int32_t* perm, int32_t n_rows, size_t row_bytes, void* dst,
+                       hipStream_t stream)
+{
+    if (n_rows <= 0) return hipSuccess;
+    if (row_bytes % 4) return hipErrorInvalidValue;
+    if (row_bytes % 16 == 0) {
+        size_t vecs = row_bytes / 16;
+        int gy = (int)((vecs + kGatherThreads * 8 - 1) / (kGatherThreads * 8));
+        if (gy < 1) gy = 1;
+        if (gy > 64) gy = 64;
+        hipLaunchKernelGGL(gather_rows_kernel<uint4>, dim3(n_rows, gy), dim3(kGatherThreads), 0, stream,
+                           (const uint4*)src, perm, vecs, (uint4*)dst);
+    } else {
+        size_t vecs = row_bytes / 4;
+        int gy = (int)((vecs + kGatherThreads * 8 - 1) / (kGatherThreads * 8));
+        if (gy < 1) gy = 1;
+        if (gy > 64) gy = 64;
+        hipLaunchKernelGGL(gather_rows_kernel<uint32_t>, dim3(n_rows, gy), dim3(kGatherThreads), 0, stream,
+                           (const uint32_t*)src, perm, vecs, (uint32_t*)dst);
+    }
+    return hipGetLastError();
+}
+
+hipError_t conv_direct(int dtype, const void* x, const void* w, const float* bias, const void* res, void* y,
+                       const ConvShape& s, hipStream_t stream)
+{
+    size_t total = (size_t)s.N * s.P * s.Q * s.K;
+    if (total == 0) return hipSuccess;
+    size_t blocks = (total + 255) / 256;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    if (dtype == 1)
+        hipLaunchKernelGGL(conv_direct_kernel<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, stream, (const uint16_t*)x,
+                           (const uint16_t*)w, bias, (const uint16_t*)res, (uint16_t*)y, s);
+    else
+        hipLaunchKernelGGL(conv_direct_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, stream, (const float*)x,
+                           (const float*)w, bias, (const float*)res, (float*)y, s);
+    return hipGetLastError();
+}
+
+hipError_t maxpool(int dtype, const void* x, void* y, int32_t N, int32_t H, int32_t W, int32_t C, int32_t R, int32_t S,
+                   int32_t stride, int32_t pad, int32_t P, int32_t Q, hipStream_t stream)
+{
+    size_t total = (size_t)N * P * Q * C;
+    if (total == 0) return hipSuccess;
+    size_t blocks = (total + 255) / 256;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    if (dtype == 1)
+        hipLaunchKernelGGL(maxpool_kernel<uint16_t>, dim3((unsigned)blocks), dim3(256), 0, stream, (const uint16_t*)x,
+                           (uint16_t*)y, N, H, W, C, R, S, stride, pad, P, Q);
+    else
+        hipLaunchKernelGGL(maxpool_kernel<float>, dim3((unsigned)blocks), dim3(256), 0, stream, (const float*)x, (float*)y,
+                           N, H, W, C, R, S, stride, pad, P, Q);
+    return hipGetLastError();
+}
+
+hipError_t head_gap_fc(int dtype, const void* x, const void* w, const float* b, int32_t N, int32_t HW, int32_t C,
+                       int32_t ncls, const RouteArgs& r, hipStream_t stream)
+{
+    if (N <= 0) return hipSuccess;
+    int groups = C < kHeadThreads ? kHeadThreads / C : 1;
+    size_t smem = sizeof(float) * ((size_t)C + (size_t)groups * C + (size_t)ncls);
+    if (smem > 60 * 1024) return hipErrorInvalidValue;
+    if (dtype == 1)
+        hipLaunchKernelGGL(head_gap_fc_kernel<uint16_t>, dim3(N), dim3(kHeadThreads), smem, stream, (const uint16_t*)x,
+                           (const uint16_t*)w, b, HW, C, ncls, r);
+    else
+        hipLaunchKernelGGL(head_gap_fc_kernel<float>, dim3(N), dim3(kHeadThreads), smem, stream, (const float*)x,
+                           (const float*)w, b, HW, C, ncls, r);
+    return hipGetLastError();
+}
+
+}  // namespace k
+}  // namespace coe

@@ -1,0 +1,287 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+
+from paper_2503_02354_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2503_02354_amd import binding
+    return binding
+
+
+@pytest.fixture(scope="module")
+def G():
+    from oracle import guard
+    return guard
+
+
+from gpu_util import REL_TOL_BF16, REL_TOL_F32, assert_chain_parity, device_tensor, rel_err, run_chain_gpu  # noqa: E402
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# regroup: bit exact
+# ---------------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,E,mode", [
+    (0, 4, "uniform"), (1, 1, "uniform"), (63, 3, "uniform"), (255, 16, "uniform"), (256, 16, "uniform"),
+    (257, 16, "holes"), (4096, 16, "uniform"), (5000, 64, "zipf"), (8192, 120, "zipf"), (16384, 64, "holes"),
+    (3000, 2048, "uniform"), (4096, 32, "single"), (1000, 7, "none"),
+])
+def test_regroup_bit_exact(B, oracle, n, E, mode):
+    rng = np.random.default_rng(n * 31 + E)
+    if mode == "uniform":
+        cur = rng.integers(0, E, n)
+    elif mode == "holes":
+        cur = rng.integers(-1, E, n); cur[rng.random(n) < 0.3] = -1
+    elif mode == "zipf":
+        cur = rng.choice(E, size=n, p=W.zipf_probs(E, 1.1)); cur[rng.random(n) < 0.1] = -1
+    elif mode == "single":
+        cur = np.full(n, E - 1)
+    else:
+        cur = np.full(n, -1)
+    cur = cur.astype(np.int32)
+    ctx = B.Context(max_requests=max(n, 1))
+    got = ctx.coe_debug_regroup(cur, E)
+    ctx.close()
+    want = oracle.regroup(cur, E)
+    assert got["n_pending"] == want["n_pending"]
+    for k in ("cnt", "off", "perm"):
+        assert np.array_equal(got[k], want[k]), k
+    assert np.array_equal(got["inv"], want["inv"])
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# single-expert forwards
+# ---------------------------------------------------------------------------------------------------------------
+def _forward_case(B, oracle, arch, n, seed, tol, max_batch=0):
+    blob = W.make_expert_blob(arch, seed, 0)
+    x = W.make_inputs(arch, seed, range(n))
+    ctx = B.Context(max_requests=max(n, 1), max_batch=max_batch)
+    aid = ctx.coe_register_arch(arch)
+    assert ctx.coe_arch_blob_bytes(aid) == blob.nbytes == W.blob_layout(arch)[1]
+    ctx.coe_register_expert(0, aid, blob, 1.0)
+    dev = device_tensor(x)
+    got = ctx.coe_debug_forward(0, n, dev.data_ptr())
+    ctx.close()
+    want = np.stack([oracle.forward(arch, blob, x[i]) for i in range(n)])
+    err = rel_err(got, want)
+    assert err.max() <= tol, err.max()
+
+
+def test_forward_tiny_cnn_fp32(B, oracle):
+    _forward_case(B, oracle, W.tiny_cnn(4, 64), 9, 11, REL_TOL_F32, max_batch=4)
+
+
+def test_forward_resnet18_bf16(B, oracle):
+    _forward_case(B, oracle, W.resnet18(16, 64, W.DT_BF16, 32), 7, 12, REL_TOL_BF16, max_batch=3)
+
+
+def test_forward_resnet18_fp32(B, oracle):
+    _forward_case(B, oracle, W.resnet18(10, 48, W.DT_F32, 16), 5, 13, REL_TOL_F32)
+
+
+def test_forward_resnet50_bf16(B, oracle):
+    _forward_case(B, oracle, W.resnet50(12, 64, W.DT_BF16, 32), 5, 14, REL_TOL_BF16)
+
+
+def test_forward_resnet18_bf16_full_width_ragged(B, oracle):
+    # real channel counts (64..512), odd spatial size so tiles end ragged (input 72 -> 36 -> 18, 9, 5, 3)
+    _forward_case(B, oracle, W.resnet18(16, 72, W.DT_BF16, 64), 3, 15, REL_TOL_BF16)
+
+
+def _conv_pair_arch(H, Wd, C, K, R, stride, pad, ncls=8):
+    """conv(RxR, stride) + ReLU, then conv3x3 with the first output as residual + ReLU, then the head: a permuted or
+    misplaced output tile of the first conv changes the second conv's result."""
+    p = W._Prog(H, Wd, C)
+    p.conv(0, 1, K, R, stride, pad, W.ACT_RELU)
+    p.conv(1, 2, K, 3, 1, 1, W.ACT_RELU, res=1, gain=0.5)
+    p.head(2, ncls)
+    return W.Arch("conv_pair", W.DT_BF16, H, Wd, C, ncls, np.array(p.layers, dtype=np.int32), p.gains)
+
+
+@pytest.mark.parametrize("H,Wd,C,K,R,stride,pad,n", [
+    (14, 14, 64, 128, 3, 1, 1, 5),      # 128-wide filter tile, rows end ragged (980 rows)
+    (9, 11, 32, 64, 3, 1, 1, 3),        # 64-wide filter tile, one partial row tile
+    (10, 10, 96, 32, 3, 2, 1, 4),       # 32-wide filter tile, stride 2, C = 3 reduction blocks
+    (16, 12, 64, 256, 1, 1, 0, 6),      # 1x1
+    (15, 15, 128, 128, 1, 2, 0, 3),     # 1x1 stride 2 (shortcut conv)
+    (7, 7, 512, 512, 3, 1, 1, 11),      # late-stage shape: 539 rows, 4 filter tiles, long reduction
+    (56, 56, 64, 64, 3, 1, 1, 2),       # first-stage shape: many row tiles across the XCD remap
+    (5, 5, 32, 96, 5, 1, 2, 2),         # 5x5 window, K = 96 -> 32-wide tiles
+])
+def test_conv_mfma_shapes(B, oracle, H, Wd, C, K, R, stride, pad, n):
+    _forward_case(B, oracle, _conv_pair_arch(H, Wd, C, K, R, stride, pad), n, 100 + H + K, REL_TOL_BF16)
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# whole chains
+# ---------------------------------------------------------------------------------------------------------------
+def test_config1_full_size(B, oracle, G):
+    """Config 1 as specified: 4 fp32 tiny-CNN experts, 256 requests of 3x64x64, expert 0 routes over classes 0-2."""
+    wl = W.config1(calibrated=False)
+    G.calibrate_workload(wl, n_cal=64)
+    blobs = [wl.blob(e) for e in range(4)]
+    x, sub, want, redraws = G.guarded_inputs(wl, blobs, range(wl.n_requests))
+    assert redraws < 26
+    got = run_chain_gpu(B, wl, blobs, x, max_batch=100)
+    assert_chain_parity(got, want, REL_TOL_F32)
+    leaves = np.bincount(want["path"][:, 1], minlength=4)[1:]
+    assert leaves.min() > 20, leaves                                 # calibration spreads the routes
+    # regroup of the second stage equals the oracle's stable regroup of the routed ids
+    assert [s[1].n_groups for s in got["stats"][:2]] == [1, 3]
+
+
+def _config2_small(n=96, hw=64, E=6, width=32):
+    return W.config2(n, hw=hw, n_experts=E, width=width, calibrated=False)
+
+
+def test_config2_small_chain(B, oracle, G):
+    wl = _config2_small()
+    G.calibrate_workload(wl, n_cal=48)
+    blobs = [wl.blob(e) for e in range(wl.graph.n_experts)]
+    x, sub, want, redraws = G.guarded_inputs(wl, blobs, range(wl.n_requests))
+    got = run_chain_gpu(B, wl, blobs, x, max_batch=20)
+    assert_chain_parity(got, want, REL_TOL_BF16)
+    assert len(set(want["path"][:, 1].tolist())) >= 3
+    # schedule independence on the GPU: other batch size, arrival in pieces, host inputs: identical routes and logits
+    got2 = run_chain_gpu(B, wl, blobs, x, max_batch=7, arrival=25, on_device=False)
+    assert np.array_equal(got2["path"], got["path"])
+    assert rel_err(got2["logits"], got["logits"]).max() <= 1e-6
+
+
+def test_regroup_inside_step_matches_oracle(B, oracle, G):
+    wl = _config2_small(n=80)
+    G.calibrate_workload(wl, n_cal=48)
+    blobs = [wl.blob(e) for e in range(wl.graph.n_experts)]
+    x, sub, want, _ = G.guarded_inputs(wl, blobs, range(80))
+    ctx = B.Context(max_requests=80, max_stages=2, max_batch=16)
+    B.setup_workload(ctx, wl, blobs)
+    dev = device_tensor(x)
+    ctx.coe_submit(80, dev.data_ptr(), True)
+    ctx.coe_step()
+    r1 = ctx.coe_debug_last_regroup(80)
+    assert r1["perm"].tolist() == list(range(80)) and r1["cnt"][0] == 80           # single root: identity
+    ctx.coe_step()
+    r2 = ctx.coe_debug_last_regroup(80)
+    ref = oracle.regroup(want["path"][:, 1], wl.graph.n_experts)
+    for k in ("cnt", "off", "perm", "inv"):
+        assert np.array_equal(r2[k], ref[k]), k
+    rc, _ = ctx.coe_step()
+    assert rc == B.COE_DONE
+    ctx.close()
+
+
+def test_capped_cache_switches_match_policy_and_results_do_not_change(B, oracle, G):
+    """Config-3 structure at small scale: Zipf leaves, capped cache, requests arriving in batches."""
+    wl = W.config3(120, hw=64, n_experts=10, width=16, cap=4, arrival_batch=30, calibrated=False)
+    G.calibrate_workload(wl, n_cal=64, targets={0: W.zipf_probs(9, 1.1)})
+    blobs = [wl.blob(e) for e in range(10)]
+    x, sub, want, _ = G.guarded_inputs(wl, blobs, range(120))
+    got = run_chain_gpu(B, wl, blobs, x, max_batch=16, arrival=30)
+    assert_chain_parity(got, want, REL_TOL_BF16)
+    # replay the oracle's cache simulator over the same per-step group sets
+    nbytes = [blobs[e].nbytes for e in range(10)]
+    sim = oracle.CacheSim(nbytes, wl.usage_prob, wl.graph.succ_off, wl.graph.succ, cap_experts=4)
+    log = [(e, []) for e in sim.init_fill()]
+    pend = {}                                                       # request -> expert it waits for
+    nxt = 0
+    for rc, st in got["stats"]:
+        if nxt < 120:
+            for r in range(nxt, nxt + 30):
+                pend[r] = 0
+            nxt += 30
+        if not pend:
+            break
+        hg = np.zeros(10, np.uint8); hg[list(set(pend.values()))] = 1
+        order, sw = sim.stage(hg)
+        log += sw
+        assert st.n_groups == len(order) and st.n_misses == len(sw)
+        new = {}
+        for r, e in pend.items():
+            stage = want["path"][r].tolist().index(e)
+            if stage + 1 < want["path"].shape[1] and want["path"][r, stage + 1] >= 0:
+                new[r] = int(want["path"][r, stage + 1])
+        pend = new
+    assert got["switch_log"] == log
+    assert len(log) > 6                                             # the cap really forces switches
+    # uncapped and cap=2 (every group a switch) give the same routes and logits
+    for cap in (0, 2):
+        g2 = run_chain_gpu(B, wl, blobs, x, max_batch=16, arrival=30, cap_experts=cap)
+        assert np.array_equal(g2["path"], got["path"])
+        assert rel_err(g2["logits"], got["logits"]).max() <= 1e-6
+
+
+def test_config4_small_dag(B, oracle, G):
+    """Three-stage DAG, two architectures, shared downstream experts, skewed first experts."""
+    wl = W.config4(150, hw=64, tiers=(3, 6, 9), width=16, fan=(3, 2), calibrated=False)
+    G.calibrate_workload(wl, n_cal=32)
+    E = wl.graph.n_experts
+    blobs = [wl.blob(e) for e in range(E)]
+    x, sub, want, _ = G.guarded_inputs(wl, blobs, range(150))
+    got = run_chain_gpu(B, wl, blobs, x, wl.first_expert, max_batch=32)
+    assert_chain_parity(got, want, REL_TOL_BF16)
+    assert np.all(got["path"][:, 2] >= 0)
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# error paths and degenerate inputs (forced from the host; no kernel misbehaves)
+# ---------------------------------------------------------------------------------------------------------------
+def test_error_codes_and_empty_inputs(B):
+    wl = W.config1(8, hw=16, calibrated=False)
+    blobs = [wl.blob(e) for e in range(4)]
+    ctx = B.Context(max_requests=8, max_stages=2)
+    with pytest.raises(B.CoEError) as ei:
+        ctx.coe_submit(1, np.zeros((1, 16, 16, 3), np.float32), False)
+    assert ei.value.code == B.COE_ESTATE                             # graph not set
+    aid = ctx.coe_register_arch(wl.archs[0])
+    with pytest.raises(B.CoEError) as ei:
+        ctx.coe_register_expert(0, aid, blobs[0][:-256], 1.0)
+    assert ei.value.code == B.COE_EINVAL                             # wrong blob size
+    for e in range(4):
+        ctx.coe_register_expert(e, aid, blobs[e], 0.5)
+    with pytest.raises(B.CoEError) as ei:
+        ctx.coe_register_expert(1, aid, blobs[1], 0.5)
+    assert ei.value.code == B.COE_EINVAL                             # twice
+    bad = W.graph_from_lists([[1, 2, 3, 1, 2], [], [], []])          # 5 routes > 4 classes
+    with pytest.raises(B.CoEError) as ei:
+        ctx.coe_set_dependency_graph(bad.succ_off, bad.succ)
+    assert ei.value.code == B.COE_EGRAPH
+    deep = W.graph_from_lists([[1], [2], [3], []])                   # depth 4 > max_stages 2
+    with pytest.raises(B.CoEError) as ei:
+        ctx.coe_set_dependency_graph(deep.succ_off, deep.succ)
+    assert ei.value.code == B.COE_ERANGE
+    ctx.coe_set_dependency_graph(wl.graph.succ_off, wl.graph.succ)
+    rc, _ = ctx.coe_step()
+    assert rc == B.COE_DONE                                          # nothing submitted
+    assert ctx.coe_submit(0, None, False) == 0                       # empty submit is fine
+    ids, logits, path = ctx.coe_collect(8)
+    assert len(ids) == 0
+    with pytest.raises(B.CoEError) as ei:
+        ctx.coe_submit(9, np.zeros((9, 16, 16, 3), np.float32), False)
+    assert ei.value.code == B.COE_ERANGE                             # store full
+    with pytest.raises(B.CoEError) as ei:
+        ctx.coe_submit(1, np.zeros((1, 16, 16, 3), np.float32), False, np.array([7], np.int32))
+    assert ei.value.code == B.COE_EINVAL                             # unknown first expert
+    # the context is still usable
+    x = wl.inputs(range(3))
+    assert ctx.coe_submit(3, x, False) == 0
+    while ctx.coe_step()[0] != B.COE_DONE:
+        pass
+    ids, logits, path = ctx.coe_collect(8)
+    assert ids.tolist() == [0, 1, 2] and np.all(path[:, 0] == 0)
+    # ids keep counting after the store drained
+    assert ctx.coe_submit(2, x[:2], False) == 3
+    ctx.close()
+    # an expert larger than the cache cap cannot run
+    ctx = B.Context(max_requests=8, max_stages=2, cache_cap_bytes=1000)
+    B.setup_workload(ctx, wl, blobs)
+    ctx.coe_submit(2, x[:2], False)
+    with pytest.raises(B.CoEError) as ei:
+        ctx.coe_step()
+    assert ei.value.code == B.COE_ENOMEM
+    ctx.close()

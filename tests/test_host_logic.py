@@ -1,0 +1,110 @@
+"""Host-side logic of the library that needs no GPU: exported symbols, graph validation, cache policy vs the oracle."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2503_02354_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2503_02354_amd import build
+    if build.needs_build():
+        build.build()
+    from paper_2503_02354_amd import binding
+    return binding
+
+
+def test_library_exports_every_declared_symbol(B):
+    hdr = open(os.path.join(ROOT, "include", "coe.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(coe_[a-z_0-9]+)\s*\(", hdr))
+    assert declared, "no declarations found"
+    assert declared == set(B.EXPORTS)
+    L = C.CDLL(B.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(L, name), name
+
+
+def test_validate_graph(B):
+    g = W.tree_graph(4)
+    assert B.coe_validate_graph(4, g.succ_off, g.succ, [3, 1, 1, 1]) == B.COE_OK
+    assert B.coe_validate_graph(4, g.succ_off, g.succ, [2, 1, 1, 1]) == B.COE_EGRAPH        # more routes than classes
+    bad = W.graph_from_lists([[1], [2], [0]])                                                # cycle
+    assert B.coe_validate_graph(3, bad.succ_off, bad.succ) == B.COE_EGRAPH
+    self_loop = W.graph_from_lists([[0]])
+    assert B.coe_validate_graph(1, self_loop.succ_off, self_loop.succ) == B.COE_EGRAPH
+    oob = W.graph_from_lists([[1, 5], []])
+    assert B.coe_validate_graph(2, oob.succ_off, oob.succ) == B.COE_EGRAPH
+    final = W.graph_from_lists([[1, -1], [-1]])
+    assert B.coe_validate_graph(2, final.succ_off, final.succ) == B.COE_OK
+    dag = W.config4(8, hw=32, tiers=(3, 5, 7), width=8, fan=(3, 2), calibrated=False).graph    # shared downstream experts
+    assert B.coe_validate_graph(dag.n_experts, dag.succ_off, dag.succ) == B.COE_OK
+    assert B.coe_validate_graph(0, g.succ_off, g.succ) == B.COE_EINVAL
+
+
+def test_create_without_gpu_fails_loudly(B):
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(B.CoEError) as ei:
+        B.Context(max_requests=4)
+    assert ei.value.code == B.COE_EDEVICE
+
+
+def _compare_policy(B, oracle, nbytes, prob, graph, cap_experts, cap_bytes, stages):
+    sim = oracle.CacheSim(nbytes, prob, graph.succ_off, graph.succ, cap_experts, cap_bytes)
+    pol = B.Policy(nbytes, prob, graph.succ_off, graph.succ, cap_experts, cap_bytes)
+    assert sim.init_fill() == pol.init_fill()
+    for hg in stages:
+        try:
+            want = sim.stage(hg)
+        except MemoryError:
+            with pytest.raises(MemoryError):
+                pol.stage(hg)
+            return
+        got = pol.stage(hg)
+        assert got == want
+        assert np.array_equal(sim.resident(), pol.resident())
+
+
+def test_policy_matches_oracle_on_hand_cases(B, oracle):
+    g = W.graph_from_lists([[2, 3], [4], [], [], [], []])
+    _compare_policy(B, oracle, [50, 10, 20, 40, 30, 60], [0.0, 0.0, 0.9, 0.8, 0.7, 0.6], g, 0, 150,
+                    [[0, 1, 0, 0, 0, 0], [1, 0, 0, 0, 0, 0]])
+    g = W.graph_from_lists([[1], [2], [], [], []])
+    _compare_policy(B, oracle, [100, 10, 50, 10, 30], [0.0, 0.9, 0.8, 0.1, 0.05], g, 0, 70, [[0, 0, 0, 0, 1]])
+    g = W.tree_graph(4)
+    _compare_policy(B, oracle, [10] * 4, [1.0, 0.5, 0.3, 0.2], g, 2, 0, [[0, 1, 1, 1], [1, 0, 0, 0], [0, 1, 0, 1]])
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_policy_matches_oracle_random(B, oracle, seed):
+    rng = np.random.default_rng(seed)
+    wl = W.config4(8, hw=32, tiers=(4, 8, 12), width=8, fan=(3, 2), calibrated=False)
+    E = wl.graph.n_experts
+    nbytes = rng.integers(5, 30, E) if seed % 2 else np.full(E, 10)
+    prob = np.round(np.asarray(wl.usage_prob), 2) if seed % 3 == 0 else wl.usage_prob      # rounded: exercises ties
+    stages = [(rng.random(E) < rng.choice([0.1, 0.3, 0.6])).astype(np.uint8) for _ in range(40)]
+    _compare_policy(B, oracle, nbytes, prob, wl.graph, 0 if seed % 2 else 6, 110 if seed % 2 else 0, stages)
+
+
+def test_policy_zipf_tree_keeps_hot_experts(B, oracle):
+    # config-3 structure at small scale: root + Zipf leaves, cap 5: after many stages the hottest leaves stay resident
+    wl = W.config3(64, hw=32, n_experts=12, width=8, cap=5, arrival_batch=16, calibrated=False)
+    E = 12
+    nbytes = [100] * E
+    rng = np.random.default_rng(0)
+    p = np.asarray(wl.usage_prob[1:])
+    stages = []
+    for _ in range(30):
+        hg = np.zeros(E, np.uint8); hg[0] = 1
+        leaves = rng.choice(np.arange(1, E), size=6, p=p / p.sum())
+        hg[leaves] = 1
+        stages.append(hg)
+    _compare_policy(B, oracle, nbytes, wl.usage_prob, wl.graph, 5, 0, stages)

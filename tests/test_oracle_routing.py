@@ -206,6 +206,17 @@ def test_cache_stage1_order_descending_bytes(oracle):
     assert sim.resident().tolist() == [True, False, True, False, True, False]
 
 
+def test_cache_stage1_candidates_fixed_at_the_miss(oracle):
+    # chain 0 -> 1 -> 2 plus independent 3, 4.  Resident {1, 2, 3}; 0 absent.  The dependents-without-predecessor set is
+    # taken when the miss occurs ("sorted ... and evicted sequentially"): evicting 1 does not add 2 to it.
+    g = W.graph_from_lists([[1], [2], [], [], []])
+    sim = oracle.CacheSim([100, 10, 50, 10, 30], [0.0, 0.9, 0.8, 0.1, 0.05], g.succ_off, g.succ, cap_bytes=70)
+    assert sim.init_fill() == [1, 2, 3]
+    order, sw = sim.stage([False, False, False, False, True])
+    # stage 1: {1} (10 bytes) -> 60 + 30 > 70; stage 2 ascending probability: 3 (0.1) -> 50 + 30 > 70; 2 (0.8) -> fits
+    assert sw == [(4, [1, 3, 2])]
+
+
 def test_cache_never_evicts_waiting_group_and_reports_no_fit(oracle):
     g = W.tree_graph(4)
     sim = oracle.CacheSim([10] * 4, [1.0, 0.5, 0.3, 0.2], g.succ_off, g.succ, cap_experts=2)
