@@ -404,10 +404,20 @@ def make_inputs(arch: Arch, seed: int, request_ids: Sequence[int], subseeds: Opt
     n = len(request_ids)
     elems = arch.input_elems
     out = np.empty((n, elems), dtype=np.uint16 if arch.dtype == DT_BF16 else np.float32)
-    for i, rid in enumerate(request_ids):
+    ids = [int(r) for r in request_ids]
+
+    def draw(i):
         ss = 0 if subseeds is None else int(subseeds[i])
-        v = _stream(seed, _KIND_INPUT, int(rid), ss).standard_normal(elems, dtype=np.float32)
+        v = _stream(seed, _KIND_INPUT, ids[i], ss).standard_normal(elems, dtype=np.float32)
         out[i] = f32_to_bf16_bits(v) if arch.dtype == DT_BF16 else v
+
+    if n * elems > (1 << 24):      # large batches: numpy releases the GIL inside the generator
+        from concurrent.futures import ThreadPoolExecutor
+        with ThreadPoolExecutor(max_workers=min(16, os.cpu_count() or 1)) as ex:
+            list(ex.map(draw, range(n)))
+    else:
+        for i in range(n):
+            draw(i)
     return out.reshape(n, arch.in_h, arch.in_w, arch.in_c)
 
 
