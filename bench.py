@@ -77,7 +77,7 @@ def main():
     for _ in range(args.warmup):
         path = one_step()
     ctx.coe_sync()
-    for k in range(B.K_OTHER + 1):
+    for k in range(len(B.KERNEL_CLASS_NAMES)):
         ctx.coe_profile_read(k)            # drop warm-up spans
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -104,13 +104,13 @@ def main():
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                     "traffic": None, "launches": p["launches"], "avg_launch_us": round(p["ms"] * 1e3 / p["launches"], 2)}
     other = {}
-    for name in ("regroup_gather", "switch", "pool", "conv_direct", "head", "regroup_index"):
+    for name in ("regroup_gather", "switch", "pool", "conv_stem", "conv_direct", "head", "regroup_index"):
         if name in prof:
             p = prof[name]
             entry = {"ms_per_step": round(p["ms"] / args.steps, 3), "launches_per_step": p["launches"] // max(args.steps, 1)}
             if name in ("regroup_gather", "pool", "switch"):
                 entry["GB/s"] = round(p["work"] / (p["ms"] * 1e-3) / 1e9, 1) if p["ms"] > 0 else None
-            if name == "conv_direct":
+            if name in ("conv_direct", "conv_stem"):
                 entry["TFLOP/s"] = round(p["work"] / (p["ms"] * 1e-3) / 1e12, 2)
             other[name] = entry
 

@@ -166,7 +166,7 @@ int coe_debug_regroup(coe_ctx* ctx, int32_t n, const int32_t* cur, int32_t n_exp
 
 /* Kernel classes timed when cfg.profile != 0. */
 enum { COE_K_REGROUP_INDEX = 0, COE_K_REGROUP_GATHER = 1, COE_K_CONV_MFMA = 2, COE_K_CONV_DIRECT = 3, COE_K_POOL = 4,
-       COE_K_HEAD = 5, COE_K_SWITCH = 6, COE_K_OTHER = 7, COE_K_COUNT = 8 };
+       COE_K_HEAD = 5, COE_K_SWITCH = 6, COE_K_CONV_STEM = 7, COE_K_COUNT = 8 };
 /* Synchronises, then returns and clears the accumulated launches, milliseconds and algorithmic work of a class
  * (flops for conv classes, bytes for the others). */
 int coe_profile_read(coe_ctx* ctx, int32_t kernel_class, int64_t* launches, double* ms, double* work);

@@ -378,6 +378,9 @@ int run_expert(coe_ctx* c, const Expert& x, const void* weights, const void* inp
             if (a.dtype == COE_DT_BF16 && coe::k::conv_mfma_supported(s)) {
                 Span sp(c, COE_K_CONV_MFMA, flops, c->sc);
                 HIPCHK(c, coe::k::conv_mfma(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), res, buf(l.dst), s, c->sc));
+            } else if (a.dtype == COE_DT_BF16 && coe::k::conv_smallc_supported(s, res != nullptr)) {
+                Span sp(c, COE_K_CONV_STEM, flops, c->sc);
+                HIPCHK(c, coe::k::conv_smallc(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), buf(l.dst), s, c->sc));
             } else {
                 Span sp(c, COE_K_CONV_DIRECT, flops, c->sc);
                 HIPCHK(c, coe::k::conv_direct(a.dtype, buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), res, buf(l.dst), s, c->sc));

@@ -49,6 +49,11 @@ bool conv_mfma_supported(const ConvShape& s);
 hipError_t conv_mfma(const void* x, const void* w, const float* bias, const void* res, void* y, const ConvShape& s,
                      hipStream_t stream);
 
+// bf16 convolution with few input channels (C not a multiple of 32, e.g. the C=3 stem) on the matrix cores.
+// Requires K in {32, 64}, stride*C even, no residual.
+bool conv_smallc_supported(const ConvShape& s, bool has_res);
+hipError_t conv_smallc(const void* x, const void* w, const float* bias, void* y, const ConvShape& s, hipStream_t stream);
+
 hipError_t maxpool(int dtype, const void* x, void* y, int32_t N, int32_t H, int32_t W, int32_t C, int32_t R, int32_t S,
                    int32_t stride, int32_t pad, int32_t P, int32_t Q, hipStream_t stream);
 

@@ -230,6 +230,45 @@ __global__ __launch_bounds__(256) void maxpool_kernel(const T* __restrict__ x, T
     Elem<T>::store(y + idx, best);
 }
 
+// bf16 max pool, 8 channels (16 bytes) per lane.  bf16 order equals the order of the fp32 values, so the max is taken
+// on the widened values and the winning pattern is stored unchanged.
+__global__ __launch_bounds__(256) void maxpool_bf16x8_kernel(const uint4* __restrict__ x, uint4* __restrict__ y, int N, int H,
+                                                             int W, int C8, int R, int S, int stride, int pad, int P, int Q)
+{
+    size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    size_t total = (size_t)N * P * Q * C8;
+    if (idx >= total) return;
+    int c8 = (int)(idx % C8);
+    size_t m = idx / C8;
+    int q = (int)(m % Q);
+    int p = (int)((m / Q) % P);
+    int n = (int)(m / ((size_t)Q * P));
+    float best[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) best[i] = -INFINITY;
+    for (int r = 0; r < R; ++r) {
+        int ih = p * stride - pad + r;
+        if (ih < 0 || ih >= H) continue;
+        for (int t = 0; t < S; ++t) {
+            int iw = q * stride - pad + t;
+            if (iw < 0 || iw >= W) continue;
+            uint4 v = x[(((size_t)n * H + ih) * W + iw) * C8 + c8];
+            uint32_t wds[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                best[2 * i] = fmaxf(best[2 * i], __uint_as_float(wds[i] << 16));
+                best[2 * i + 1] = fmaxf(best[2 * i + 1], __uint_as_float(wds[i] & 0xFFFF0000u));
+            }
+        }
+    }
+    uint4 o;
+    o.x = (__float_as_uint(best[0]) >> 16) | (__float_as_uint(best[1]) & 0xFFFF0000u);
+    o.y = (__float_as_uint(best[2]) >> 16) | (__float_as_uint(best[3]) & 0xFFFF0000u);
+    o.z = (__float_as_uint(best[4]) >> 16) | (__float_as_uint(best[5]) & 0xFFFF0000u);
+    o.w = (__float_as_uint(best[6]) >> 16) | (__float_as_uint(best[7]) & 0xFFFF0000u);
+    y[idx] = o;
+}
+
 // -------------------------------------------------------------------------------------------------------------
 // routing head: global average pool, FC, argmax over the routed classes, successor lookup
 // -------------------------------------------------------------------------------------------------------------
@@ -367,6 +406,13 @@ hipError_t maxpool(int dtype, const void* x, void* y, int32_t N, int32_t H, int3
 {
     size_t total = (size_t)N * P * Q * C;
     if (total == 0) return hipSuccess;
+    if (dtype == 1 && C % 8 == 0) {
+        size_t blocks8 = (total / 8 + 255) / 256;
+        if (blocks8 > 0x7FFFFFFFull) return hipErrorInvalidValue;
+        hipLaunchKernelGGL(maxpool_bf16x8_kernel, dim3((unsigned)blocks8), dim3(256), 0, stream, (const uint4*)x, (uint4*)y, N,
+                           H, W, C / 8, R, S, stride, pad, P, Q);
+        return hipGetLastError();
+    }
     size_t blocks = (total + 255) / 256;
     if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
     if (dtype == 1)

@@ -118,6 +118,17 @@ def test_conv_mfma_shapes(B, oracle, H, Wd, C, K, R, stride, pad, n):
     _forward_case(B, oracle, _conv_pair_arch(H, Wd, C, K, R, stride, pad), n, 100 + H + K, REL_TOL_BF16)
 
 
+@pytest.mark.parametrize("H,Wd,C,K,R,stride,pad,n", [
+    (37, 45, 3, 64, 7, 2, 3, 3),        # stem shape at an odd size: ragged 16x16 tiles on both axes
+    (224, 224, 3, 64, 7, 2, 3, 2),      # the real stem: 7x7 tiles per image, several tiles per workgroup
+    (30, 30, 4, 32, 3, 1, 1, 2),        # C=4, stride 1, 32 filters
+    (20, 33, 6, 64, 5, 1, 2, 2),        # C=6: 30-element window rows -> 4 chunks per row
+    (64, 64, 3, 32, 7, 2, 3, 40),       # many images: the tile loop wraps around the grid
+])
+def test_conv_small_channel_shapes(B, oracle, H, Wd, C, K, R, stride, pad, n):
+    _forward_case(B, oracle, _conv_pair_arch(H, Wd, C, K, R, stride, pad), n, 200 + H + K, REL_TOL_BF16)
+
+
 # ---------------------------------------------------------------------------------------------------------------
 # whole chains
 # ---------------------------------------------------------------------------------------------------------------
