@@ -160,6 +160,12 @@ int coe_debug_switch_log(coe_ctx* ctx, int32_t cap, int32_t* log, int32_t* n_wor
 int coe_debug_resident(coe_ctx* ctx, uint8_t* out);
 /* Run one expert on n inputs (device pointer, context dtype) without routing: logits_out [n][n_classes] fp32 (host). */
 int coe_debug_forward(coe_ctx* ctx, int32_t expert_id, int32_t n, const void* device_inputs, float* logits_out);
+/* One convolution layer with the library's kernel selection, on host tensors (uploaded, run `repeat` times, read back):
+ * x [n][h][w][c], w [k][r][s][c] (canonical order), bias [k] fp32, res [n][p][q][k] or NULL, y [n][p][q][k]; x, w, res,
+ * y in `dtype`.  *kernel_class (nullable) receives the COE_K_* class that ran.  Timed under cfg.profile like any launch. */
+int coe_debug_conv(coe_ctx* ctx, int32_t dtype, const void* x, const void* w, const float* bias, const void* res, void* y,
+                   int32_t n, int32_t h, int32_t wd, int32_t c, int32_t k, int32_t r, int32_t s, int32_t stride,
+                   int32_t pad, int32_t act, int32_t repeat, int32_t* kernel_class);
 /* Stand-alone regroup on a host key vector (uploaded, regrouped on the device, read back): same outputs as above. */
 int coe_debug_regroup(coe_ctx* ctx, int32_t n, const int32_t* cur, int32_t n_experts, int32_t* cnt, int32_t* off,
                       int32_t* perm, int32_t* inv);

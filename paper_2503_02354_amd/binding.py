@@ -22,7 +22,7 @@ KERNEL_CLASS_NAMES = ["regroup_index", "regroup_gather", "conv_mfma", "conv_dire
 EXPORTS = [
     "coe_create", "coe_destroy", "coe_last_error", "coe_register_arch", "coe_arch_blob_bytes", "coe_register_expert",
     "coe_set_dependency_graph", "coe_submit", "coe_step", "coe_sync", "coe_collect", "coe_reset_requests",
-    "coe_debug_last_regroup", "coe_debug_switch_log", "coe_debug_resident", "coe_debug_forward", "coe_debug_regroup",
+    "coe_debug_last_regroup", "coe_debug_switch_log", "coe_debug_resident", "coe_debug_forward", "coe_debug_regroup", "coe_debug_conv",
     "coe_profile_read", "coe_validate_graph", "coe_policy_create", "coe_policy_destroy", "coe_policy_init_fill",
     "coe_policy_stage", "coe_policy_resident",
 ]
@@ -72,6 +72,7 @@ def _load():
     L.coe_debug_resident.argtypes = [vp, vp]
     L.coe_debug_forward.argtypes = [vp, i32, i32, vp, vp]
     L.coe_debug_regroup.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp]
+    L.coe_debug_conv.argtypes = [vp, i32, vp, vp, vp, vp, vp] + [i32] * 11 + [C.POINTER(i32)]
     L.coe_profile_read.argtypes = [vp, i32, C.POINTER(i64), C.POINTER(C.c_double), C.POINTER(C.c_double)]
     L.coe_validate_graph.argtypes = [i32, vp, vp, vp]
     L.coe_policy_create.argtypes = [i32, vp, vp, vp, vp, i32, i64]; L.coe_policy_create.restype = vp
@@ -273,6 +274,21 @@ class Context:
         perm = np.full(max(n, 1), -1, np.int32); inv = np.full(max(n, 1), -1, np.int32)
         m = self._chk(lib.coe_debug_regroup(self._h, n, _ptr(cur), n_experts, _ptr(cnt), _ptr(off), _ptr(perm), _ptr(inv)))
         return dict(n_pending=m, cnt=cnt, off=off, perm=perm[:m], inv=inv[:n])
+
+    def coe_debug_conv(self, dtype: int, x: np.ndarray, w: np.ndarray, bias: np.ndarray, res: Optional[np.ndarray], stride: int,
+                       pad: int, act: int, repeat: int = 1):
+        """x [n][h][w][c], w [k][r][s][c] (uint16 bf16 bits or float32), bias float32 -> (y, kernel class)."""
+        x = np.ascontiguousarray(x); w = np.ascontiguousarray(w); bias = np.ascontiguousarray(bias, np.float32)
+        n, h, wd, c = x.shape; k, r, s, c2 = w.shape
+        assert c2 == c and x.dtype == w.dtype
+        p = (h + 2 * pad - r) // stride + 1; q = (wd + 2 * pad - s) // stride + 1
+        y = np.zeros((n, p, q, k), x.dtype)
+        if res is not None:
+            res = np.ascontiguousarray(res); assert res.shape == y.shape and res.dtype == x.dtype
+        cls = C.c_int32(-1)
+        self._chk(lib.coe_debug_conv(self._h, dtype, _ptr(x), _ptr(w), _ptr(bias), _ptr(res), _ptr(y), n, h, wd, c, k, r, s, stride,
+                                     pad, act, repeat, C.byref(cls)))
+        return y, cls.value
 
     def coe_profile_read(self, kernel_class: int):
         n = C.c_int64(0); ms = C.c_double(0); work = C.c_double(0)

@@ -28,6 +28,7 @@ struct LayerPlan {
     int32_t P, Q, K;        // destination shape (heads: K = classes)
     size_t off[4];          // byte offsets of this layer's tensors in the blob
     double macs;            // multiply-accumulates per request
+    bool packed = false;    // conv filters are stored in matrix-core fragment order (device and pinned copies)
 };
 
 struct ArchPlan {
@@ -197,6 +198,10 @@ int plan_arch(coe_ctx* c, const coe_arch_desc* d, ArchPlan& a)
                 L.off[0] = take((size_t)l.k * l.r * l.s * L.C, true);
                 L.off[1] = take((size_t)l.k, false);
                 L.macs = (double)L.P * L.Q * l.k * l.r * l.s * L.C;
+                {
+                    coe::k::ConvShape cs{1, L.H, L.W, L.C, l.k, l.r, l.s, l.stride, l.pad, L.P, L.Q, l.act};
+                    L.packed = d->dtype == COE_DT_BF16 && coe::k::conv_mfma_supported(cs);
+                }
                 if (l.res >= 0) {
                     if (l.res >= kMaxBufs || !shp[l.res].set || l.res == l.dst || shp[l.res].h != L.P || shp[l.res].w != L.Q ||
                         shp[l.res].c != L.K)
@@ -375,7 +380,7 @@ int run_expert(coe_ctx* c, const Expert& x, const void* weights, const void* inp
             coe::k::ConvShape s{n, L.H, L.W, L.C, L.K, l.r, l.s, l.stride, l.pad, L.P, L.Q, l.act};
             const void* res = l.res >= 0 ? buf(l.res) : nullptr;
             double flops = 2.0 * L.macs * n;
-            if (a.dtype == COE_DT_BF16 && coe::k::conv_mfma_supported(s)) {
+            if (L.packed) {
                 Span sp(c, COE_K_CONV_MFMA, flops, c->sc);
                 HIPCHK(c, coe::k::conv_mfma(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), res, buf(l.dst), s, c->sc));
             } else if (a.dtype == COE_DT_BF16 && coe::k::conv_smallc_supported(s, res != nullptr)) {
@@ -530,6 +535,19 @@ int coe_register_expert(coe_ctx* c, int32_t id, int32_t arch_id, const void* w, 
         return fail(c, COE_ENOMEM, "pinned host allocation failed");
     }
     std::memcpy(x.host, w, nbytes);
+    // filters of the layers that run on the matrix cores are kept in fragment order from here on
+    {
+        std::vector<uint16_t> tmp;
+        for (const LayerPlan& L : c->archs[arch_id].layers) {
+            if (!L.packed) continue;
+            const int red = L.d.r * L.d.s * L.C;
+            const size_t n = (size_t)L.K * red;
+            tmp.resize(n);
+            uint16_t* t = (uint16_t*)((uint8_t*)x.host + L.off[0]);
+            coe::k::pack_filters_mfma(t, tmp.data(), L.K, red);
+            std::memcpy(t, tmp.data(), n * sizeof(uint16_t));
+        }
+    }
     HIPCHK(c, hipEventCreateWithFlags(&x.loaded, hipEventDisableTiming));
     x.registered = true;
     x.arch = arch_id;
@@ -834,6 +852,55 @@ int coe_debug_regroup(coe_ctx* c, int32_t n, const int32_t* cur, int32_t E, int3
     if (perm && hoff[E] > 0) HIPCHK(c, hipMemcpy(perm, c->d_perm, (size_t)hoff[E] * 4, hipMemcpyDeviceToHost));
     if (inv && n > 0) HIPCHK(c, hipMemcpy(inv, c->d_inv, (size_t)n * 4, hipMemcpyDeviceToHost));
     return hoff[E];
+}
+
+int coe_debug_conv(coe_ctx* c, int32_t dtype, const void* x, const void* w, const float* bias, const void* res, void* y,
+                   int32_t n, int32_t h, int32_t wd, int32_t ch, int32_t k, int32_t r, int32_t s, int32_t stride, int32_t pad,
+                   int32_t act, int32_t repeat, int32_t* kernel_class)
+{
+    if (!c || !x || !w || !bias || !y) return fail(c, COE_EINVAL, "null argument");
+    if ((dtype != COE_DT_F32 && dtype != COE_DT_BF16) || n <= 0 || h <= 0 || wd <= 0 || ch <= 0 || k <= 0 || r <= 0 || s <= 0 ||
+        stride <= 0 || pad < 0 || act < 0 || act > 2 || repeat <= 0)
+        return fail(c, COE_EINVAL, "bad convolution parameters");
+    const int P = (h + 2 * pad - r) / stride + 1, Q = (wd + 2 * pad - s) / stride + 1;
+    if (P <= 0 || Q <= 0) return fail(c, COE_EINVAL, "empty output");
+    const size_t eb = dtype == COE_DT_BF16 ? 2 : 4;
+    const size_t nx = (size_t)n * h * wd * ch, nw = (size_t)k * r * s * ch, ny = (size_t)n * P * Q * k;
+    void *dx = nullptr, *dw = nullptr, *dres = nullptr, *dy = nullptr;
+    float* db = nullptr;
+    coe::k::ConvShape cs{n, h, wd, ch, k, r, s, stride, pad, P, Q, act};
+    const bool mfma = dtype == COE_DT_BF16 && coe::k::conv_mfma_supported(cs);
+    const bool smallc = !mfma && dtype == COE_DT_BF16 && coe::k::conv_smallc_supported(cs, res != nullptr);
+    const int cls = mfma ? COE_K_CONV_MFMA : smallc ? COE_K_CONV_STEM : COE_K_CONV_DIRECT;
+    if (kernel_class) *kernel_class = cls;
+    hipError_t he = hipSuccess;
+    auto ok = [&](hipError_t e) { if (he == hipSuccess) he = e; return he == hipSuccess; };
+    std::vector<uint16_t> packed;
+    const void* wsrc = w;
+    if (mfma) {
+        packed.resize(nw);
+        coe::k::pack_filters_mfma((const uint16_t*)w, packed.data(), k, r * s * ch);
+        wsrc = packed.data();
+    }
+    if (ok(hipMalloc(&dx, nx * eb)) && ok(hipMalloc(&dw, nw * eb)) && ok(hipMalloc((void**)&db, (size_t)k * 4)) &&
+        ok(hipMalloc(&dy, ny * eb)) && (!res || ok(hipMalloc(&dres, ny * eb))) &&
+        ok(hipMemcpy(dx, x, nx * eb, hipMemcpyHostToDevice)) && ok(hipMemcpy(dw, wsrc, nw * eb, hipMemcpyHostToDevice)) &&
+        ok(hipMemcpy(db, bias, (size_t)k * 4, hipMemcpyHostToDevice)) &&
+        (!res || ok(hipMemcpy(dres, res, ny * eb, hipMemcpyHostToDevice)))) {
+        const double flops = 2.0 * (double)ny * r * s * ch;
+        for (int it = 0; it < repeat && he == hipSuccess; ++it) {
+            Span sp(c, cls, flops, c->sc);
+            if (mfma) ok(coe::k::conv_mfma(dx, dw, db, dres, dy, cs, c->sc));
+            else if (smallc) ok(coe::k::conv_smallc(dx, dw, db, dy, cs, c->sc));
+            else ok(coe::k::conv_direct(dtype, dx, dw, db, dres, dy, cs, c->sc));
+        }
+        ok(hipStreamSynchronize(c->sc));
+        ok(hipMemcpy(y, dy, ny * eb, hipMemcpyDeviceToHost));
+    }
+    void* ptrs[] = {dx, dw, db, dres, dy};
+    for (void* p : ptrs) if (p) (void)hipFree(p);
+    if (he != hipSuccess) return fail(c, COE_EDEVICE, hipGetErrorString(he));
+    return COE_OK;
 }
 
 int coe_profile_read(coe_ctx* c, int32_t cls, int64_t* launches, double* ms, double* work)

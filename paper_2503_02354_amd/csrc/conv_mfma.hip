@@ -1,12 +1,23 @@
 // bf16 implicit-GEMM convolution on the gfx950 matrix cores.
 //
 // GEMM view: out[m][k] = sum_{r,s,c} x[n][p*stride-pad+r][q*stride-pad+s][c] * w[k][r][s][c], m = (n,p,q) flattened.
-// NHWC activations and [K][R][S][C] weights make the reduction index contiguous in c for both operands, so a
-// reduction step is one (r,s) position and a run of 32 channels: 64 bytes per output pixel and per filter.
-// A workgroup (4 wavefronts of 64) owns a BM x BN output tile; every step stages a BM x 32 activation slab and a
-// BN x 32 weight slab in LDS (two stages, global loads of step i+1 in flight while step i runs on the matrix
-// cores), and each wavefront feeds v_mfma_f32_32x32x16_bf16 from LDS with 16-byte reads.
-// Epilogue in fp32: + bias (+ residual), activation, one round-to-nearest-even to bf16.
+// NHWC activations make the reduction index contiguous in c, so a reduction step is one (r,s) position and a run
+// of BK channels.  A workgroup (4 wavefronts of 64) owns a BM x BN output tile.
+//   * Loads run kDepth steps ahead: each step's activation slab (BM x BK) and filter slab (BN x BK) travel
+//     global -> registers (kDepth register stages) -> LDS (two stages) -> matrix-core operands.  Every step issues
+//     the same loads unconditionally, so the wait before a register stage is moved to LDS can leave the younger
+//     stages in flight.
+//   * A wave64 vector instruction occupies a SIMD for 4 cycles and a step has only 16 matrix-core instructions per
+//     wavefront, so per-step address arithmetic is kept to a few instructions per load: activations are fetched with
+//     buffer loads whose out-of-range offsets return zero (the zero padding of the convolution and the rows past
+//     the end of the tile cost one select of the offset), the position inside the window is a scalar offset shared
+//     by all lanes, and which window positions fall inside the image is a per-row bit mask computed once.
+//   * Activation rows are padded by 16 bytes in LDS so the 16-byte operand reads are bank-conflict free.
+//   * Filters are repacked once, when an expert is registered, into matrix-core fragment order (pack_filters_mfma),
+//     so a filter slab is contiguous in memory and in LDS and an operand read is one linear 1 KiB access.
+//   * v_mfma_f32_32x32x16_bf16 is issued with the filter fragment as the first operand, so a lane ends up holding 4
+//     consecutive output channels of one pixel per accumulator quad: the epilogue stores 8 bytes at a time.
+// Epilogue in fp32: + bias (+ residual), activation, one round-to-nearest-even to bf16 (v_cvt_pk_bf16_f32).
 #include <hip/hip_runtime.h>
 
 #include "kernels.h"
@@ -17,31 +28,38 @@ namespace k {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int kThreads = 256;
-constexpr int kBK = 32;              // reduction elements per step
-constexpr int kLdsStride = 40;       // elements per LDS row: 64 data bytes + 16 pad bytes -> conflict-free 16-byte reads
+constexpr int kPad = 8;              // elements of padding per LDS activation row (16 bytes)
 constexpr int kXcds = 8;
+constexpr int kDepth = 3;            // register stages = how many steps ahead the global loads run
+constexpr uint32_t kOutOfRange = 0x80000000u;   // buffer offset beyond any tensor: the load returns zeros
 
-__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
-__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+__device__ __forceinline__ float bf16_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0;
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    f32x2 f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));   // round to nearest even
 }
 __device__ __forceinline__ float act_fn(float v, int act)
 {
     if (act == 1) return v > 0.f ? v : 0.f;
-    if (act == 2) return 0.5f * v * (1.f + erff(v * 0.70710678118654752440f));
+    if (act == 2) return 0.5f * v * erfcf(-v * 0.70710678118654752440f);
     return v;
 }
+// raw buffer descriptor over [p, p + bytes): offsets at or beyond `bytes` read as zero
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes)
+{
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(p), 0, (int)bytes, 0x00020000);
+}
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N>
 __global__ __launch_bounds__(kThreads) void conv_igemm_bf16_kernel(const uint16_t* __restrict__ x,
-                                                                    const uint16_t* __restrict__ w,
+                                                                    const uint16_t* __restrict__ wp,
                                                                     const float* __restrict__ bias,
                                                                     const uint16_t* __restrict__ res,
                                                                     uint16_t* __restrict__ y, ConvShape s, int M,
@@ -51,12 +69,19 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_bf16_kernel(const uint16_
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int MB = WM / 32, NB = WN / 32;
     static_assert(MB >= 1 && NB >= 1, "wave tile");
-    constexpr int A_CHUNKS = BM * 4, B_CHUNKS = BN * 4;          // 16-byte chunks per slab
-    constexpr int A_LOADS = (A_CHUNKS + kThreads - 1) / kThreads;
+    constexpr int CH = BK / 8;                       // 16-byte chunks per activation slab row
+    constexpr int ROWS_PER_PASS = kThreads / CH;
+    constexpr int A_LOADS = BM / ROWS_PER_PASS;
+    constexpr int KS = BK / 16;                      // matrix-core steps per slab
+    constexpr int A_STRIDE = BK + kPad;
+    constexpr int A_STAGE = BM * A_STRIDE;           // elements
+    constexpr int B_STAGE = BN * BK;                 // elements, fragment order: [BN/32][KS][64 lanes][8]
+    constexpr int B_CHUNKS = B_STAGE / 8;
     constexpr int B_LOADS = (B_CHUNKS + kThreads - 1) / kThreads;
-    constexpr int STAGE = (BM + BN) * kLdsStride;                // elements
+    constexpr int B_PER_BLOCK = KS * 64;             // chunks per 32-filter block and step
+    constexpr int STAGE = A_STAGE + B_STAGE;
 
-    __shared__ __attribute__((aligned(16))) uint16_t lds[2 * STAGE];
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // 2 * STAGE elements
 
     // XCD-aware tile order: consecutive workgroup ids land on different XCDs, so give each XCD a contiguous range
     // of tiles (filter tiles fastest) and the slabs shared by neighbouring tiles stay in one XCD's L2.
@@ -72,65 +97,88 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_bf16_kernel(const uint16_
 
     const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
     const int wm = wid / WAVES_N, wn = wid % WAVES_N;
-    const int chunk = tid & 3;               // which 16-byte piece of the 64-byte run
-    const int row0 = tid >> 2;               // 0..63
+    const int chunk = tid % CH;
+    const int row0 = tid / CH;
 
-    // per-thread description of the activation rows it fetches
-    const int PQ = s.P * s.Q;
-    int a_ih0[A_LOADS], a_iw0[A_LOADS];
-    size_t a_base[A_LOADS];
-    bool a_ok[A_LOADS];
+    const int cblocks = s.C / BK;
+    const int RS = s.R * s.S;
+    const int nsteps = RS * cblocks;
+    const int ks16_total = nsteps * KS;               // 16-channel steps per filter
+
+    const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(x, (uint32_t)s.N * (uint32_t)(s.H * s.W * s.C) * 2u);
+    const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(wp, (uint32_t)s.K * (uint32_t)(RS * s.C) * 2u);
+
+    // Per activation row this thread fetches: byte offset of window position (0,0), channel 0 (+ its 16-byte chunk),
+    // and a mask with bit r*S+s set when that window position lies inside the image.  Rows past M have mask 0.
+    int32_t a_off[A_LOADS];
+    uint64_t a_mask[A_LOADS];
+    {
+        const int PQ = s.P * s.Q;
 #pragma unroll
-    for (int j = 0; j < A_LOADS; ++j) {
-        int row = row0 + 64 * j;
-        int m = m0 + row;
-        a_ok[j] = (row < BM) && (m < M);
-        int mm = a_ok[j] ? m : 0;
-        int n = mm / PQ, pq = mm % PQ;
-        int p = pq / s.Q, q = pq % s.Q;
-        a_ih0[j] = p * s.stride - s.pad;
-        a_iw0[j] = q * s.stride - s.pad;
-        a_base[j] = (size_t)n * s.H * s.W * s.C;
+        for (int j = 0; j < A_LOADS; ++j) {
+            int m = m0 + row0 + ROWS_PER_PASS * j;
+            bool ok = m < M;
+            int mm = ok ? m : 0;
+            int n = mm / PQ, pq = mm % PQ;
+            int p = pq / s.Q, q = pq % s.Q;
+            int ih0 = p * s.stride - s.pad, iw0 = q * s.stride - s.pad;
+            a_off[j] = ((n * s.H + ih0) * s.W + iw0) * s.C * 2 + chunk * 16;
+            uint64_t mask = 0;
+            for (int rr = 0; rr < s.R; ++rr)
+                for (int tt = 0; tt < s.S; ++tt)
+                    if (ok && (unsigned)(ih0 + rr) < (unsigned)s.H && (unsigned)(iw0 + tt) < (unsigned)s.W)
+                        mask |= 1ull << (rr * s.S + tt);
+            a_mask[j] = mask;
+        }
     }
-    const size_t w_row = (size_t)s.R * s.S * s.C;   // elements per filter
-
-    const int cblocks = s.C / kBK;
-    const int nsteps = s.R * s.S * cblocks;
-
-    uint4 a_reg[A_LOADS], b_reg[B_LOADS];
-    int r = 0, t = 0, cb = 0;                       // position of the step being fetched
-
-    auto fetch = [&]() {
+    // filter slab: chunk c of a step lives at block (c / B_PER_BLOCK), offset (c % B_PER_BLOCK) inside the step's
+    // KS fragments of that block; LDS keeps the same linear order
+    uint32_t b_off[B_LOADS];
 #pragma unroll
-        for (int j = 0; j < A_LOADS; ++j) {
-            int ih = a_ih0[j] + r, iw = a_iw0[j] + t;
-            bool ok = a_ok[j] && (unsigned)ih < (unsigned)s.H && (unsigned)iw < (unsigned)s.W;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (ok) v = *(const uint4*)(x + a_base[j] + ((size_t)ih * s.W + iw) * s.C + cb * kBK + chunk * 8);
-            a_reg[j] = v;
-        }
-#pragma unroll
-        for (int j = 0; j < B_LOADS; ++j) {
-            int row = row0 + 64 * j;
-            uint4 v = make_uint4(0, 0, 0, 0);
-            if (row < BN) v = *(const uint4*)(w + (size_t)(n0 + row) * w_row + ((size_t)r * s.S + t) * s.C + cb * kBK + chunk * 8);
-            b_reg[j] = v;
-        }
-        if (++cb == cblocks) { cb = 0; if (++t == s.S) { t = 0; ++r; } }
+    for (int j = 0; j < B_LOADS; ++j) {
+        int c = tid + kThreads * j;
+        b_off[j] = c < B_CHUNKS
+                       ? (uint32_t)((((n0 / 32 + c / B_PER_BLOCK) * ks16_total) * 512 + (c % B_PER_BLOCK) * 8) * 2)
+                       : kOutOfRange;
+    }
+
+    // One register stage: the loads of one reduction step while they are in flight.
+    struct RegStage {
+        u32x4 a[A_LOADS];
+        u32x4 b[B_LOADS];
     };
-    auto stash = [&](int stage) {
-        uint16_t* a_lds = lds + stage * STAGE;
-        uint16_t* b_lds = a_lds + BM * kLdsStride;
+    RegStage st0, st1, st2;
+    static_assert(kDepth == 3, "three named register stages");
+    int r = 0, t = 0, cb = 0, f_step = 0;             // (r, s, channel block) and index of the step being fetched
+
+    auto fetch = [&](RegStage& st) {
+        const int rs = r * s.S + t;
+        const int32_t win = ((r * s.W + t) * s.C + cb * BK) * 2;      // scalar: same for every lane
 #pragma unroll
         for (int j = 0; j < A_LOADS; ++j) {
-            int row = row0 + 64 * j;
-            if (row < BM) *(uint4*)(a_lds + row * kLdsStride + chunk * 8) = a_reg[j];
+            uint32_t off = ((a_mask[j] >> rs) & 1ull) ? (uint32_t)(a_off[j] + win) : kOutOfRange;
+            st.a[j] = __builtin_amdgcn_raw_buffer_load_b128(x_rsrc, off, 0, 0);
         }
+        const uint32_t wstep = (uint32_t)f_step * (KS * 512 * 2);     // scalar
 #pragma unroll
-        for (int j = 0; j < B_LOADS; ++j) {
-            int row = row0 + 64 * j;
-            if (row < BN) *(uint4*)(b_lds + row * kLdsStride + chunk * 8) = b_reg[j];
+        for (int j = 0; j < B_LOADS; ++j) st.b[j] = __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, b_off[j], wstep, 0);
+        // advance; past the last step the fetch position stays put, so a fetch issued beyond the end re-reads the
+        // last step (never used) and every step issues the same number of loads
+        if (f_step + 1 < nsteps) {
+            ++f_step;
+            if (++cb == cblocks) { cb = 0; if (++t == s.S) { t = 0; ++r; } }
         }
+    };
+    uint16_t* const a_dst = lds + row0 * A_STRIDE + chunk * 8;
+    uint16_t* const b_dst = lds + A_STAGE + tid * 8;
+    auto stash = [&](int stage, const RegStage& st) {
+#pragma unroll
+        for (int j = 0; j < A_LOADS; ++j)
+            *(u32x4*)(a_dst + stage * STAGE + ROWS_PER_PASS * j * A_STRIDE) = st.a[j];
+#pragma unroll
+        for (int j = 0; j < B_LOADS; ++j)
+            if (B_CHUNKS % kThreads == 0 || tid + kThreads * j < B_CHUNKS)
+                *(u32x4*)(b_dst + stage * STAGE + kThreads * j * 8) = st.b[j];
     };
 
     f32x16 acc[MB][NB];
@@ -141,86 +189,157 @@ __global__ __launch_bounds__(kThreads) void conv_igemm_bf16_kernel(const uint16_
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    fetch();
-    stash(0);
-    __syncthreads();
-
-    const int frag_row = lane & 31;          // row (A) / filter (B) inside a 32-wide block
+    const int frag_row = lane & 31;          // pixel row inside a 32-row block
     const int frag_k = (lane >> 5) * 8;      // which 8 of the 16 reduction elements this lane supplies
 
-    for (int step = 0; step < nsteps; ++step) {
-        const bool more = step + 1 < nsteps;
-        if (more) fetch();
-        const uint16_t* a_lds = lds + (step & 1) * STAGE;
-        const uint16_t* b_lds = a_lds + BM * kLdsStride;
+    // Operand fragments are read one matrix-core step ahead of their use, so the LDS latency of step ks+1 hides behind
+    // the matrix-core work of step ks.
+    const uint16_t* const a_src = lds + (wm * WM + frag_row) * A_STRIDE + frag_k;
+    const uint16_t* const b_src = lds + A_STAGE + (wn * NB) * (KS * 512) + lane * 8;
+    auto compute = [&](int stage) {
+        const uint16_t* a_lds = a_src + stage * STAGE;
+        const uint16_t* b_lds = b_src + stage * STAGE;
+        bf16x8 af[2][MB], bfr[2][NB];
 #pragma unroll
-        for (int ks = 0; ks < kBK / 16; ++ks) {
-            bf16x8 af[MB], bfr[NB];
+        for (int i = 0; i < MB; ++i) af[0][i] = *(const bf16x8*)(a_lds + i * 32 * A_STRIDE);
 #pragma unroll
-            for (int i = 0; i < MB; ++i)
-                af[i] = *(const bf16x8*)(a_lds + (wm * WM + i * 32 + frag_row) * kLdsStride + ks * 16 + frag_k);
+        for (int j = 0; j < NB; ++j) bfr[0][j] = *(const bf16x8*)(b_lds + (j * KS) * 512);
 #pragma unroll
-            for (int j = 0; j < NB; ++j)
-                bfr[j] = *(const bf16x8*)(b_lds + (wn * WN + j * 32 + frag_row) * kLdsStride + ks * 16 + frag_k);
+        for (int ks = 0; ks < KS; ++ks) {
+            if (ks + 1 < KS) {
+#pragma unroll
+                for (int i = 0; i < MB; ++i)
+                    af[(ks + 1) & 1][i] = *(const bf16x8*)(a_lds + i * 32 * A_STRIDE + (ks + 1) * 16);
+#pragma unroll
+                for (int j = 0; j < NB; ++j)
+                    bfr[(ks + 1) & 1][j] = *(const bf16x8*)(b_lds + (j * KS + ks + 1) * 512);
+            }
 #pragma unroll
             for (int i = 0; i < MB; ++i)
 #pragma unroll
                 for (int j = 0; j < NB; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks & 1][j], af[ks & 1][i], acc[i][j], 0, 0, 0);
         }
-        if (more) stash((step + 1) & 1);
+    };
+
+    // prologue: three steps in flight, the first one staged
+    fetch(st0);
+    fetch(st1);
+    fetch(st2);
+    stash(0, st0);
+    __syncthreads();
+
+    // Step u: the register stage that held step u is free -> refill it with step u + 3; compute step u from LDS
+    // stage u & 1; move step u + 1 (loads issued two steps ago) from its register stage to the other LDS stage.
+    // Fetch and staging are unconditional (past the end they move data nobody reads): the number of loads in flight
+    // at every wait is then a compile-time constant and the wait can leave the younger two stages outstanding.
+    auto step = [&](int u, RegStage& refill, const RegStage& next) {
+        fetch(refill);
+        if (u < nsteps) compute(u & 1);
+        stash((u + 1) & 1, next);
         __syncthreads();
+    };
+    for (int u0 = 0; u0 < nsteps; u0 += kDepth) {
+        step(u0, st0, st1);
+        step(u0 + 1, st1, st2);
+        step(u0 + 2, st2, st0);
     }
 
-    // epilogue.  Accumulator element v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32 of the 32x32 block.
-    const int col_in = lane & 31, row_hi = (lane >> 5) * 4;
+    // Epilogue.  With the filter fragment as the first operand, accumulator element v of lane l belongs to pixel l%32
+    // and filter 8*(v/4) + 4*(l/32) + v%4 of the 32x32 block: a quad of v is 4 consecutive channels of one pixel.
+    const int f_hi = (lane >> 5) * 4;
 #pragma unroll
-    for (int j = 0; j < NB; ++j) {
-        const int col = n0 + wn * WN + j * 32 + col_in;
-        const float bv = bias[col];
+    for (int i = 0; i < MB; ++i) {
+        const int m = m0 + wm * WM + i * 32 + frag_row;
+        if (m >= M) continue;
+        const size_t orow = (size_t)m * s.K;
 #pragma unroll
-        for (int i = 0; i < MB; ++i) {
+        for (int j = 0; j < NB; ++j) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                int row = wm * WM + i * 32 + 8 * (v >> 2) + row_hi + (v & 3);
-                int m = m0 + row;
-                if (m < M) {
-                    size_t o = (size_t)m * s.K + col;
-                    float val = acc[i][j][v] + bv;
-                    if (res) val += bf16_to_f32(res[o]);
-                    y[o] = f32_to_bf16(act_fn(val, s.act));
+            for (int g = 0; g < 4; ++g) {
+                const int n = n0 + wn * WN + j * 32 + 8 * g + f_hi;
+                const float4 bv = *(const float4*)(bias + n);
+                float v0 = acc[i][j][4 * g + 0] + bv.x, v1 = acc[i][j][4 * g + 1] + bv.y;
+                float v2 = acc[i][j][4 * g + 2] + bv.z, v3 = acc[i][j][4 * g + 3] + bv.w;
+                if (res) {
+                    uint2 rv = *(const uint2*)(res + orow + n);
+                    v0 += bf16_to_f32(rv.x & 0xFFFFu); v1 += bf16_to_f32(rv.x >> 16);
+                    v2 += bf16_to_f32(rv.y & 0xFFFFu); v3 += bf16_to_f32(rv.y >> 16);
                 }
+                uint2 o;
+                o.x = pack_bf16(act_fn(v0, s.act), act_fn(v1, s.act));
+                o.y = pack_bf16(act_fn(v2, s.act), act_fn(v3, s.act));
+                *(uint2*)(y + orow + n) = o;
             }
         }
     }
 }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
-hipError_t launch(const void* x, const void* w, const float* bias, const void* res, void* y, const ConvShape& s,
+template <int BM, int BN, int BK, int WAVES_M, int WAVES_N>
+hipError_t launch(const void* x, const void* wp, const float* bias, const void* res, void* y, const ConvShape& s,
                   hipStream_t stream)
 {
     long long M = (long long)s.N * s.P * s.Q;
-    if (M <= 0) return hipSuccess;
-    if (M > 0x7FFFFFFFll - BM) return hipErrorInvalidValue;
     int tiles_m = (int)((M + BM - 1) / BM), tiles_n = s.K / BN;
     long long total = (long long)tiles_m * tiles_n;
     if (total > 0x7FFFFFFFll) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((conv_igemm_bf16_kernel<BM, BN, WAVES_M, WAVES_N>), dim3((unsigned)total), dim3(kThreads), 0, stream,
-                       (const uint16_t*)x, (const uint16_t*)w, bias, (const uint16_t*)res, (uint16_t*)y, s, (int)M, tiles_n);
+    constexpr size_t kLdsBytes = 2 * (size_t)(BM * (BK + kPad) + BN * BK) * sizeof(uint16_t);
+    static bool configured = false;
+    if (!configured) {   // more than the default 64 KiB of LDS per workgroup needs an explicit opt-in
+        hipError_t e = hipFuncSetAttribute((const void*)conv_igemm_bf16_kernel<BM, BN, BK, WAVES_M, WAVES_N>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL((conv_igemm_bf16_kernel<BM, BN, BK, WAVES_M, WAVES_N>), dim3((unsigned)total), dim3(kThreads), kLdsBytes,
+                       stream, (const uint16_t*)x, (const uint16_t*)wp, bias, (const uint16_t*)res, (uint16_t*)y, s, (int)M,
+                       tiles_n);
     return hipGetLastError();
+}
+
+template <int BK>
+hipError_t pick_tile(const void* x, const void* wp, const float* bias, const void* res, void* y, const ConvShape& s,
+                     hipStream_t stream)
+{
+    if (s.K % 128 == 0) return launch<128, 128, BK, 2, 2>(x, wp, bias, res, y, s, stream);
+    if (s.K % 64 == 0) return launch<128, 64, BK, 2, 2>(x, wp, bias, res, y, s, stream);
+    return launch<128, 32, BK, 4, 1>(x, wp, bias, res, y, s, stream);
 }
 
 }  // namespace
 
-bool conv_mfma_supported(const ConvShape& s) { return s.C % kBK == 0 && s.K % 32 == 0 && s.C > 0 && s.K > 0; }
+bool conv_mfma_supported(const ConvShape& s)
+{
+    return s.C > 0 && s.K > 0 && s.C % 32 == 0 && s.K % 32 == 0 && s.R * s.S <= 64;
+}
 
-hipError_t conv_mfma(const void* x, const void* w, const float* bias, const void* res, void* y, const ConvShape& s,
+void pack_filters_mfma(const uint16_t* w, uint16_t* out, int K, int red)
+{
+    // out[((nb * red/16 + ks) * 64 + lane) * 8 + i] = w[nb*32 + lane%32][ks*16 + (lane/32)*8 + i]
+    const int ks_total = red / 16;
+    for (int nb = 0; nb < K / 32; ++nb)
+        for (int ks = 0; ks < ks_total; ++ks)
+            for (int lane = 0; lane < 64; ++lane) {
+                const uint16_t* src = w + (size_t)(nb * 32 + lane % 32) * red + ks * 16 + (lane / 32) * 8;
+                uint16_t* dst = out + (((size_t)nb * ks_total + ks) * 64 + lane) * 8;
+                for (int i = 0; i < 8; ++i) dst[i] = src[i];
+            }
+}
+
+hipError_t conv_mfma(const void* x, const void* wp, const float* bias, const void* res, void* y, const ConvShape& s,
                      hipStream_t stream)
 {
     if (!conv_mfma_supported(s)) return hipErrorInvalidValue;
-    if (s.K % 128 == 0) return launch<128, 128, 2, 2>(x, w, bias, res, y, s, stream);
-    if (s.K % 64 == 0) return launch<256, 64, 4, 1>(x, w, bias, res, y, s, stream);
-    return launch<256, 32, 4, 1>(x, w, bias, res, y, s, stream);
+    long long M = (long long)s.N * s.P * s.Q;
+    if (M <= 0) return hipSuccess;
+    // 31-bit byte offsets inside the kernel (buffer offsets; bit 31 marks "out of range")
+    if ((long long)s.N * s.H * s.W * s.C * 2 >= 0x7FFFFFFFll || (long long)s.K * s.R * s.S * s.C * 2 >= 0x7FFFFFFFll ||
+        M >= 0x7FFFFFFFll - 256)
+        return hipErrorInvalidValue;
+#ifndef COE_FORCE_BK32
+    if (s.C % 64 == 0) return pick_tile<64>(x, wp, bias, res, y, s, stream);
+#endif
+    return pick_tile<32>(x, wp, bias, res, y, s, stream);
 }
 
 }  // namespace k

@@ -31,7 +31,7 @@ __device__ __forceinline__ uint16_t f32_to_bf16(float f)
 __device__ __forceinline__ float act_fn(float v, int act)
 {
     if (act == 1) return v > 0.f ? v : 0.f;
-    if (act == 2) return 0.5f * v * (1.f + erff(v * 0.70710678118654752440f));
+    if (act == 2) return 0.5f * v * erfcf(-v * 0.70710678118654752440f);
     return v;
 }
 

@@ -44,8 +44,11 @@ struct ConvShape {
 hipError_t conv_direct(int dtype, const void* x, const void* w, const float* bias, const void* res, void* y,
                        const ConvShape& s, hipStream_t stream);
 
-// bf16 implicit-GEMM convolution on the matrix cores.  Requires C % 32 == 0 and K % 32 == 0.
+// bf16 implicit-GEMM convolution on the matrix cores.  Requires C % 32 == 0 and K % 32 == 0 (N is not looked at).
+// The filters must have been repacked with pack_filters_mfma (host): w is [K][red] with red = R*S*C, out has the
+// same number of elements, ordered so that a wavefront reads a 32-filter x 16-element operand as 1 KiB contiguous.
 bool conv_mfma_supported(const ConvShape& s);
+void pack_filters_mfma(const uint16_t* w, uint16_t* out, int K, int red);
 hipError_t conv_mfma(const void* x, const void* w, const float* bias, const void* res, void* y, const ConvShape& s,
                      hipStream_t stream);
 

@@ -35,7 +35,7 @@ template <> struct Elem<uint16_t> {
 __device__ __forceinline__ float apply_act(float v, int act)
 {
     if (act == 1) return v > 0.f ? v : 0.f;
-    if (act == 2) return 0.5f * v * (1.f + erff(v * 0.70710678118654752440f));
+    if (act == 2) return 0.5f * v * erfcf(-v * 0.70710678118654752440f);
     return v;
 }
 

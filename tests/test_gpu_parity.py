@@ -296,3 +296,38 @@ def test_error_codes_and_empty_inputs(B):
         ctx.coe_step()
     assert ei.value.code == B.COE_ENOMEM
     ctx.close()
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# convolution kernels element by element (appended: the full output tensor, not only pooled logits)
+# ---------------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("n,H,Wd,C,K,R,stride,pad,use_res,act", [
+    (3, 14, 14, 64, 128, 3, 1, 1, True, 1),       # MFMA, 128-wide tiles, residual
+    (2, 20, 17, 64, 64, 3, 1, 1, False, 1),       # MFMA, 64-wide tiles, ragged rows
+    (5, 9, 9, 32, 96, 3, 2, 1, True, 0),          # MFMA, 32-channel steps, stride 2, no activation
+    (40, 8, 8, 128, 256, 1, 1, 0, False, 2),      # MFMA 1x1 with GELU, 2560 rows
+    (2, 33, 29, 3, 64, 7, 2, 3, False, 1),        # stem kernel
+    (2, 12, 12, 16, 24, 3, 1, 1, True, 1),        # plain kernel (bf16)
+])
+def test_conv_elementwise_bf16(B, oracle, n, H, Wd, C, K, R, stride, pad, use_res, act):
+    rng = np.random.default_rng(n * 1000 + H * 10 + K)
+    q = lambda a: W.f32_to_bf16_bits(a.astype(np.float32))
+    xb = q(rng.standard_normal((n, H, Wd, C))).reshape(n, H, Wd, C)
+    wb = q(rng.standard_normal((K, R, R, C)) * np.sqrt(2.0 / (R * R * C))).reshape(K, R, R, C)
+    bias = (0.1 * rng.standard_normal(K)).astype(np.float32)
+    P = (H + 2 * pad - R) // stride + 1; Q = (Wd + 2 * pad - R) // stride + 1
+    rb = q(rng.standard_normal((n, P, Q, K))).reshape(n, P, Q, K) if use_res else None
+    ctx = B.Context(max_requests=1)
+    got, cls = ctx.coe_debug_conv(1, xb, wb, bias, rb, stride, pad, act)
+    ctx.close()
+    xf, wf = W.bf16_bits_to_f32(xb).reshape(xb.shape), W.bf16_bits_to_f32(wb).reshape(wb.shape)
+    rf = None if rb is None else W.bf16_bits_to_f32(rb).reshape(rb.shape)
+    want = np.stack([oracle.conv2d(xf[i], wf, bias, None if rf is None else rf[i], stride, pad, act, 1) for i in range(n)])
+    g = W.bf16_bits_to_f32(got).reshape(got.shape)
+    # both sides round the same fp32-epilogue value to bf16; fp32 vs fp64 accumulation may flip a rounding now and then
+    # (one bf16 ulp), and where the terms cancel to almost nothing the fp32 accumulation error itself (terms are O(1),
+    # up to ~1e3 of them: ~1e-5 absolute) is all that is left
+    ulp = np.maximum(np.abs(want) * 2.0 ** -7, 1e-5)
+    worst = np.unravel_index(np.argmax(np.abs(g - want) / ulp), g.shape)
+    assert np.all(np.abs(g - want) <= ulp), (worst, float(g[worst]), float(want[worst]), int(np.sum(np.abs(g - want) > ulp)))
+    assert np.mean(g == want) > 0.995
