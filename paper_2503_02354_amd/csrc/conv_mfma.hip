@@ -2,7 +2,7 @@
 //
 // GEMM view: out[m][k] = sum_{r,s,c} x[n][p*stride-pad+r][q*stride-pad+s][c] * w[k][r][s][c], m = (n,p,q) flattened.
 // NHWC activations make the reduction index contiguous in c, so a reduction step is one (r,s) position and a run
-// of BK channels.  A workgroup (4 wavefronts of 64) owns a BM x BN output tile.
+// of BK channels.  A workgroup (4 or 8 wavefronts of 64) owns a BM x BN output tile.
 //   * Loads run kDepth steps ahead: each step's activation slab (BM x BK) and filter slab (BN x BK) travel
 //     global -> registers (kDepth register stages) -> LDS (two stages) -> matrix-core operands.  Every step issues
 //     the same loads unconditionally, so the wait before a register stage is moved to LDS can leave the younger
@@ -33,7 +33,6 @@ typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kThreads = 256;
 constexpr int kPad = 8;              // elements of padding per LDS activation row (16 bytes)
 constexpr int kXcds = 8;
 constexpr int kDepth = 3;            // register stages = how many steps ahead the global loads run
@@ -58,14 +57,15 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint3
 }
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N>
-__global__ __launch_bounds__(kThreads) void conv_igemm_bf16_kernel(const uint16_t* __restrict__ x,
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_bf16_kernel(const uint16_t* __restrict__ x,
                                                                     const uint16_t* __restrict__ wp,
                                                                     const float* __restrict__ bias,
                                                                     const uint16_t* __restrict__ res,
                                                                     uint16_t* __restrict__ y, ConvShape s, int M,
                                                                     int tiles_n)
 {
-    static_assert(WAVES_M * WAVES_N == 4, "four wavefronts per workgroup");
+    constexpr int kThreads = 64 * WAVES_M * WAVES_N;
+    static_assert(kThreads == 256 || kThreads == 512, "four or eight wavefronts per workgroup");
     constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
     constexpr int MB = WM / 32, NB = WN / 32;
     static_assert(MB >= 1 && NB >= 1, "wave tile");
@@ -284,6 +284,7 @@ hipError_t launch(const void* x, const void* wp, const float* bias, const void* 
     long long total = (long long)tiles_m * tiles_n;
     if (total > 0x7FFFFFFFll) return hipErrorInvalidValue;
     constexpr size_t kLdsBytes = 2 * (size_t)(BM * (BK + kPad) + BN * BK) * sizeof(uint16_t);
+    constexpr int kThreads = 64 * WAVES_M * WAVES_N;
     static bool configured = false;
     if (!configured) {   // more than the default 64 KiB of LDS per workgroup needs an explicit opt-in
         hipError_t e = hipFuncSetAttribute((const void*)conv_igemm_bf16_kernel<BM, BN, BK, WAVES_M, WAVES_N>,
@@ -336,9 +337,8 @@ hipError_t conv_mfma(const void* x, const void* wp, const float* bias, const voi
     if ((long long)s.N * s.H * s.W * s.C * 2 >= 0x7FFFFFFFll || (long long)s.K * s.R * s.S * s.C * 2 >= 0x7FFFFFFFll ||
         M >= 0x7FFFFFFFll - 256)
         return hipErrorInvalidValue;
-#ifndef COE_FORCE_BK32
-    if (s.C % 64 == 0) return pick_tile<64>(x, wp, bias, res, y, s, stream);
-#endif
+    // 32-channel steps everywhere: measured equal or better than 64-channel steps on every ResNet layer shape
+    // (smaller register stages -> three workgroups per compute unit instead of two)
     return pick_tile<32>(x, wp, bias, res, y, s, stream);
 }
 
