@@ -33,7 +33,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--requests", type=int, default=4096)
     ap.add_argument("--max-batch", type=int, default=512)
-    ap.add_argument("--cpu-sample", type=int, default=96, help="requests the oracle is timed on (0 = skip)")
+    ap.add_argument("--cpu-sample", type=int, default=384, help="requests the oracle is timed on (0 = skip)")
     ap.add_argument("--no-profile", action="store_true", help="do not time kernel classes with events")
     args = ap.parse_args()
     if args.gpus != 1:
