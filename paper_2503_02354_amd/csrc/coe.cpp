@@ -29,6 +29,8 @@ struct LayerPlan {
     size_t off[4];          // byte offsets of this layer's tensors in the blob
     double macs;            // multiply-accumulates per request
     bool packed = false;    // conv filters are stored in matrix-core fragment order (device and pinned copies)
+    bool fuse_pool = false; // conv: the max pool that follows runs inside the conv kernel, which writes the pool's dst
+    bool fused_away = false;// pool: done by the preceding conv kernel
 };
 
 struct ArchPlan {
@@ -253,6 +255,23 @@ int plan_arch(coe_ctx* c, const coe_arch_desc* d, ArchPlan& a)
     }
     int last = a.layers.back().d.op;
     if (last != COE_OP_HEAD && last != COE_OP_HEAD_CLS) return fail(c, COE_EINVAL, "arch: program must end in a head");
+    // few-channel conv followed by a 3x3/2 pad-1 max pool of its output, which nobody else reads: one fused kernel
+    for (size_t i = 0; i + 1 < a.layers.size(); ++i) {
+        LayerPlan& cv = a.layers[i];
+        LayerPlan& pl = a.layers[i + 1];
+        if (a.dtype != COE_DT_BF16 || cv.d.op != COE_OP_CONV || cv.packed || cv.d.res >= 0 || pl.d.op != COE_OP_MAXPOOL) continue;
+        if (pl.d.src != cv.d.dst || pl.d.r != 3 || pl.d.s != 3 || pl.d.stride != 2 || pl.d.pad != 1) continue;
+        coe::k::ConvShape cs{1, cv.H, cv.W, cv.C, cv.K, cv.d.r, cv.d.s, cv.d.stride, cv.d.pad, cv.P, cv.Q, cv.d.act};
+        if (!coe::k::conv_smallc_supported(cs, false, true)) continue;
+        bool read_later = false;
+        for (size_t j = i + 2; j < a.layers.size(); ++j) {
+            if (a.layers[j].d.src == cv.d.dst || a.layers[j].d.res == cv.d.dst) { read_later = true; break; }
+            if (a.layers[j].d.dst == cv.d.dst) break;       // overwritten before anyone reads it
+        }
+        if (read_later) continue;
+        cv.fuse_pool = true;
+        pl.fused_away = true;
+    }
     a.blob_bytes = align_up(off);
     return COE_OK;
 }
@@ -383,9 +402,13 @@ int run_expert(coe_ctx* c, const Expert& x, const void* weights, const void* inp
             if (L.packed) {
                 Span sp(c, COE_K_CONV_MFMA, flops, c->sc);
                 HIPCHK(c, coe::k::conv_mfma(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), res, buf(l.dst), s, c->sc));
-            } else if (a.dtype == COE_DT_BF16 && coe::k::conv_smallc_supported(s, res != nullptr)) {
+            } else if (L.fuse_pool) {
+                const LayerPlan& pool = *(&L + 1);
                 Span sp(c, COE_K_CONV_STEM, flops, c->sc);
-                HIPCHK(c, coe::k::conv_smallc(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), buf(l.dst), s, c->sc));
+                HIPCHK(c, coe::k::conv_smallc(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), buf(pool.d.dst), s, true, c->sc));
+            } else if (a.dtype == COE_DT_BF16 && coe::k::conv_smallc_supported(s, res != nullptr, false)) {
+                Span sp(c, COE_K_CONV_STEM, flops, c->sc);
+                HIPCHK(c, coe::k::conv_smallc(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), buf(l.dst), s, false, c->sc));
             } else {
                 Span sp(c, COE_K_CONV_DIRECT, flops, c->sc);
                 HIPCHK(c, coe::k::conv_direct(a.dtype, buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), res, buf(l.dst), s, c->sc));
@@ -393,6 +416,7 @@ int run_expert(coe_ctx* c, const Expert& x, const void* weights, const void* inp
             break;
         }
         case COE_OP_MAXPOOL: {
+            if (L.fused_away) break;
             double bytes = (double)n * ((double)L.H * L.W * L.C + (double)L.P * L.Q * L.K) * a.elem();
             Span sp(c, COE_K_POOL, bytes, c->sc);
             HIPCHK(c, coe::k::maxpool(a.dtype, buf(l.src), buf(l.dst), n, L.H, L.W, L.C, l.r, l.s, l.stride, l.pad, L.P, L.Q, c->sc));
@@ -870,7 +894,7 @@ int coe_debug_conv(coe_ctx* c, int32_t dtype, const void* x, const void* w, cons
     float* db = nullptr;
     coe::k::ConvShape cs{n, h, wd, ch, k, r, s, stride, pad, P, Q, act};
     const bool mfma = dtype == COE_DT_BF16 && coe::k::conv_mfma_supported(cs);
-    const bool smallc = !mfma && dtype == COE_DT_BF16 && coe::k::conv_smallc_supported(cs, res != nullptr);
+    const bool smallc = !mfma && dtype == COE_DT_BF16 && coe::k::conv_smallc_supported(cs, res != nullptr, false);
     const int cls = mfma ? COE_K_CONV_MFMA : smallc ? COE_K_CONV_STEM : COE_K_CONV_DIRECT;
     if (kernel_class) *kernel_class = cls;
     hipError_t he = hipSuccess;
@@ -891,7 +915,7 @@ int coe_debug_conv(coe_ctx* c, int32_t dtype, const void* x, const void* w, cons
         for (int it = 0; it < repeat && he == hipSuccess; ++it) {
             Span sp(c, cls, flops, c->sc);
             if (mfma) ok(coe::k::conv_mfma(dx, dw, db, dres, dy, cs, c->sc));
-            else if (smallc) ok(coe::k::conv_smallc(dx, dw, db, dy, cs, c->sc));
+            else if (smallc) ok(coe::k::conv_smallc(dx, dw, db, dy, cs, false, c->sc));
             else ok(coe::k::conv_direct(dtype, dx, dw, db, dres, dy, cs, c->sc));
         }
         ok(hipStreamSynchronize(c->sc));

@@ -1,11 +1,19 @@
-// bf16 convolution for few input channels (the 7x7/2, C=3 stem) on the gfx950 matrix cores.
+// bf16 convolution for few input channels (the 7x7/2, C=3 stem) on the gfx950 matrix cores, optionally fused with
+// the 3x3/2 max pool that follows it.
 //
 // With C=3 the reduction run that is contiguous in memory is one window row: S*C elements (21 for 7x7x3).  A workgroup
-// stages the input patch of a 16x16 output tile in LDS once, and every lane builds its matrix-core operand straight
-// from that patch: the reduction is cut into 8-element chunks (ceil(S*C/8) per window row, zero weights where a chunk
-// overhangs the row), and one v_mfma_f32_32x32x16_bf16 consumes two chunks (lanes 0-31 one, lanes 32-63 the next).
+// stages the input patch of a 16x16 tile of conv outputs in LDS once, and every lane builds its matrix-core operand
+// straight from that patch: the reduction is cut into 8-element chunks (ceil(S*C/8) per window row, zero weights where a
+// chunk overhangs the row), and one v_mfma_f32_32x32x16_bf16 consumes two chunks (lanes 0-31 one, lanes 32-63 the next).
 // The filters are repacked into the same chunk order in LDS once per workgroup, which then loops over many tiles.
+// The patch is fetched row by row with 2-byte buffer loads through a per-row descriptor, so both image edges and
+// rows outside the image read as zero without any per-element bounds arithmetic.
 // Epilogue in fp32: + bias, activation, one round-to-nearest-even to bf16.
+//
+// Fused pool: the stem output is 1.6 MB per 224x224 image and the pool reads it straight back to keep a quarter of
+// it.  In the fused form a 16x16 conv tile starts at (14t-1, 14u-1), its rounded outputs go to LDS, and the workgroup
+// writes the 7x7 pooled pixels whose 3x3 windows lie inside the tile.  Rounding is monotonic, so the max of the rounded
+// values equals what a separate pool kernel would produce from the stored conv output.
 #include <hip/hip_runtime.h>
 
 #include "kernels.h"
@@ -16,17 +24,21 @@ namespace k {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kThreads = 256;
-constexpr int kTile = 16;     // output tile is kTile x kTile pixels = 256 GEMM rows, 64 per wavefront
+constexpr int kTile = 16;        // conv-output tile is kTile x kTile pixels = 256 GEMM rows, 64 per wavefront
+constexpr int kPoolTile = 7;     // pooled pixels per tile side in the fused form (3x3/2 windows inside 16 rows)
+constexpr int kOutPad = 8;       // elements of padding per LDS row of the conv-output tile
+constexpr int kMaxRowsPerWave = 12;   // patch rows one wavefront fetches (patch_rows <= 48)
+constexpr int kMaxColsPerLane = 3;    // patch columns one lane fetches per row (patch_cols <= 192)
 
-__device__ __forceinline__ uint16_t f32_to_bf16(float f)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0;
-    u += 0x7FFFu + ((u >> 16) & 1u);
-    return (uint16_t)(u >> 16);
+    f32x2 f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2));   // round to nearest even
 }
 __device__ __forceinline__ float act_fn(float v, int act)
 {
@@ -42,22 +54,28 @@ struct StemGeom {
     int cpr;                      // 8-element chunks per window row
     int ksteps;                   // matrix-core steps = ceil(R*cpr / 2)
     int wstride;                  // elements per LDS filter row
+    int PP, PQ;                   // pooled output size (fused form)
 };
 
-template <int NB>
+template <int NB, bool POOL>
 __global__ __launch_bounds__(kThreads) void conv_smallc_bf16_kernel(const uint16_t* __restrict__ x,
                                                                      const uint16_t* __restrict__ w,
                                                                      const float* __restrict__ bias,
                                                                      uint16_t* __restrict__ y, ConvShape s, StemGeom g)
 {
+    constexpr int K = 32 * NB;
+    constexpr int OUT_STRIDE = K + kOutPad;
     extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
-    uint16_t* wpack = smem;                               // [32*NB][wstride]
-    uint16_t* patch = smem + 32 * NB * g.wstride;         // [patch_rows][patch_stride]
-    const int tid = threadIdx.x, lane = tid & 63, wid = tid >> 6;
+    uint16_t* wpack = smem;                               // [K][wstride]
+    uint16_t* patch = smem + K * g.wstride;               // [patch_rows][patch_stride]
+    uint16_t* otile = patch + g.patch_rows * g.patch_stride;   // [256][OUT_STRIDE], fused form only (16-byte aligned)
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wid = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int SC = s.S * s.C;
+    const int WC = s.W * s.C;
 
     // filters into chunk order; zero where a chunk overhangs its window row or the step count is padded
-    for (int idx = tid; idx < 32 * NB * g.ksteps * 16; idx += kThreads) {
+    for (int idx = tid; idx < K * g.ksteps * 16; idx += kThreads) {
         int kk = idx / (g.ksteps * 16), e = idx % (g.ksteps * 16);
         int chunk = e >> 3, i = e & 7;
         int r = chunk / g.cpr, sc = (chunk % g.cpr) * 8 + i;
@@ -69,21 +87,50 @@ __global__ __launch_bounds__(kThreads) void conv_smallc_bf16_kernel(const uint16
     __syncthreads();
 
     const int half = lane >> 5, l32 = lane & 31;
+    const int tile_step = POOL ? 2 * kPoolTile : kTile;   // conv rows/cols between tile origins
+    const int tile_org = POOL ? -1 : 0;
+
+    // The patch of the NEXT tile is fetched into registers while the current tile is computed: patch rows round-robin
+    // over wavefronts, lanes along the row; offsets outside [0, W*C) and rows outside the image read as zero.
+    uint16_t pre[kMaxRowsPerWave][kMaxColsPerLane];
+    auto prefetch = [&](int tile) {
+        const int n = tile / (g.tiles_p * g.tiles_q);
+        const int tp = (tile / g.tiles_q) % g.tiles_p, tq = tile % g.tiles_q;
+        const int ih_base = (tp * tile_step + tile_org) * s.stride - s.pad;
+        const int g_base = ((tq * tile_step + tile_org) * s.stride - s.pad) * s.C;   // may be negative
+#pragma unroll
+        for (int i = 0; i < kMaxRowsPerWave; ++i) {
+            const int pr = wid + i * (kThreads / 64);
+            const int ih = ih_base + pr;
+            const bool row_ok = pr < g.patch_rows && (unsigned)ih < (unsigned)s.H;
+            const uint16_t* rowp = x + ((size_t)n * s.H + (row_ok ? ih : 0)) * WC;
+            __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(rowp), 0, row_ok ? WC * 2 : 0,
+                                                                          0x00020000);
+#pragma unroll
+            for (int j = 0; j < kMaxColsPerLane; ++j)
+                pre[i][j] = __builtin_amdgcn_raw_buffer_load_b16(rs, (g_base + lane + 64 * j) * 2, 0, 0);
+        }
+    };
+    auto commit = [&]() {
+#pragma unroll
+        for (int i = 0; i < kMaxRowsPerWave; ++i) {
+            const int pr = wid + i * (kThreads / 64);
+            if (pr < g.patch_rows) {
+#pragma unroll
+                for (int j = 0; j < kMaxColsPerLane; ++j)
+                    if (lane + 64 * j < g.patch_cols) patch[pr * g.patch_stride + lane + 64 * j] = pre[i][j];
+            }
+        }
+    };
+
+    if ((int)blockIdx.x < g.total_tiles) prefetch(blockIdx.x);
     for (int tile = blockIdx.x; tile < g.total_tiles; tile += gridDim.x) {
         const int n = tile / (g.tiles_p * g.tiles_q);
         const int tp = (tile / g.tiles_q) % g.tiles_p, tq = tile % g.tiles_q;
-        const int p0 = tp * kTile, q0 = tq * kTile;
-        const int ih_base = p0 * s.stride - s.pad;
-        const int g_base = (q0 * s.stride - s.pad) * s.C;         // element offset inside an input row, may be negative
-        const int WC = s.W * s.C;
-        for (int idx = tid; idx < g.patch_rows * g.patch_cols; idx += kThreads) {
-            int pr = idx / g.patch_cols, ce = idx % g.patch_cols;
-            int ih = ih_base + pr, ge = g_base + ce;
-            uint16_t v = 0;
-            if ((unsigned)ih < (unsigned)s.H && ge >= 0 && ge < WC) v = x[((size_t)n * s.H + ih) * WC + ge];
-            patch[pr * g.patch_stride + ce] = v;
-        }
+        const int p0 = tp * tile_step + tile_org, q0 = tq * tile_step + tile_org;     // conv-output origin of the tile
+        commit();
         __syncthreads();
+        if (tile + (int)gridDim.x < g.total_tiles) prefetch(tile + gridDim.x);
 
         f32x16 acc[2][NB];
 #pragma unroll
@@ -114,33 +161,73 @@ __global__ __launch_bounds__(kThreads) void conv_smallc_bf16_kernel(const uint16
 #pragma unroll
             for (int jn = 0; jn < NB; ++jn)
                 bfr[jn] = *(const bf16x8*)(wpack + (jn * 32 + l32) * g.wstride + chunk * 8);
+            // filter fragment first: a lane then holds 4 consecutive output channels of one pixel per accumulator quad
 #pragma unroll
             for (int i = 0; i < 2; ++i)
 #pragma unroll
                 for (int jn = 0; jn < NB; ++jn)
-                    acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i], bfr[jn], acc[i][jn], 0, 0, 0);
+                    acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[jn], af[i], acc[i][jn], 0, 0, 0);
         }
 
-        // accumulator element v of lane l: row 8*(v/4) + 4*(l/32) + v%4, column l%32 of the 32x32 block
+        // accumulator element v of lane l: pixel l%32 of the 32-pixel block, filter 8*(v/4) + 4*(l/32) + v%4
 #pragma unroll
-        for (int jn = 0; jn < NB; ++jn) {
-            const int col = jn * 32 + l32;
-            const float bv = bias[col];
+        for (int i = 0; i < 2; ++i) {
+            const int ml = wid * 64 + i * 32 + l32;
+            const int p = p0 + ml / kTile, q = q0 + ml % kTile;
+            const bool inside = (unsigned)p < (unsigned)s.P && (unsigned)q < (unsigned)s.Q;
 #pragma unroll
-            for (int i = 0; i < 2; ++i)
+            for (int jn = 0; jn < NB; ++jn)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    int ml = wid * 64 + i * 32 + 8 * (v >> 2) + half * 4 + (v & 3);
-                    int p = p0 + ml / kTile, q = q0 + ml % kTile;
-                    if (p < s.P && q < s.Q)
-                        y[(((size_t)n * s.P + p) * s.Q + q) * s.K + col] = f32_to_bf16(act_fn(acc[i][jn][v] + bv, s.act));
+                for (int gq = 0; gq < 4; ++gq) {
+                    const int ch = jn * 32 + 8 * gq + half * 4;
+                    const float4 bv = *(const float4*)(bias + ch);
+                    uint2 o;
+                    o.x = pack_bf16(act_fn(acc[i][jn][4 * gq + 0] + bv.x, s.act), act_fn(acc[i][jn][4 * gq + 1] + bv.y, s.act));
+                    o.y = pack_bf16(act_fn(acc[i][jn][4 * gq + 2] + bv.z, s.act), act_fn(acc[i][jn][4 * gq + 3] + bv.w, s.act));
+                    if (POOL) {
+                        if (!inside) o = make_uint2(0xFF80FF80u, 0xFF80FF80u);      // -inf: never wins the max
+                        *(uint2*)(otile + ml * OUT_STRIDE + ch) = o;
+                    } else if (inside) {
+                        *(uint2*)(y + (((size_t)n * s.P + p) * s.Q + q) * K + ch) = o;
+                    }
                 }
         }
-        __syncthreads();      // the patch is rewritten by the next tile
+        if (POOL) {
+            __syncthreads();
+            // 7x7 pooled pixels x K/8 channel groups; window of pooled (a, b) = tile rows 2a..2a+2, cols 2b..2b+2
+            for (int item = tid; item < kPoolTile * kPoolTile * (K / 8); item += kThreads) {
+                const int c8 = item % (K / 8), pix = item / (K / 8);
+                const int a = pix / kPoolTile, b = pix % kPoolTile;
+                const int pi = tp * kPoolTile + a, pj = tq * kPoolTile + b;
+                if (pi >= g.PP || pj >= g.PQ) continue;
+                float best[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) best[e] = -INFINITY;
+#pragma unroll
+                for (int dr = 0; dr < 3; ++dr)
+#pragma unroll
+                    for (int dc = 0; dc < 3; ++dc) {
+                        const uint4 v = *(const uint4*)(otile + ((2 * a + dr) * kTile + 2 * b + dc) * OUT_STRIDE + c8 * 8);
+                        const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            best[2 * e] = fmaxf(best[2 * e], __uint_as_float(wds[e] << 16));
+                            best[2 * e + 1] = fmaxf(best[2 * e + 1], __uint_as_float(wds[e] & 0xFFFF0000u));
+                        }
+                    }
+                uint4 o;
+                o.x = (__float_as_uint(best[0]) >> 16) | (__float_as_uint(best[1]) & 0xFFFF0000u);
+                o.y = (__float_as_uint(best[2]) >> 16) | (__float_as_uint(best[3]) & 0xFFFF0000u);
+                o.z = (__float_as_uint(best[4]) >> 16) | (__float_as_uint(best[5]) & 0xFFFF0000u);
+                o.w = (__float_as_uint(best[6]) >> 16) | (__float_as_uint(best[7]) & 0xFFFF0000u);
+                *(uint4*)(y + (((size_t)n * g.PP + pi) * g.PQ + pj) * K + c8 * 8) = o;
+            }
+        }
+        __syncthreads();      // patch (and the conv-output tile) are rewritten by the next tile
     }
 }
 
-bool geometry(const ConvShape& s, StemGeom& g, size_t& smem)
+bool geometry(const ConvShape& s, bool pool, StemGeom& g, size_t& smem)
 {
     if (s.K != 32 && s.K != 64) return false;
     if (s.C <= 0 || s.C % 32 == 0) return false;
@@ -153,39 +240,63 @@ bool geometry(const ConvShape& s, StemGeom& g, size_t& smem)
     g.patch_cols = ((kTile - 1) * s.stride + s.S) * s.C;
     int furthest = (kTile - 1) * s.stride * s.C + g.cpr * 8;       // one past the last element any chunk read touches
     int ps = g.patch_cols > furthest ? g.patch_cols : furthest;
-    g.patch_stride = (ps + 1) / 2 * 2 + 2;
-    g.tiles_p = (s.P + kTile - 1) / kTile;
-    g.tiles_q = (s.Q + kTile - 1) / kTile;
+    g.patch_stride = (ps + 7) / 8 * 8 + 8;                         // multiple of 8: the regions after it stay 16-byte aligned
+    if ((long long)s.W * s.C * 2 >= 0x7FFFFFFFll) return false;
+    if (g.patch_rows > kMaxRowsPerWave * (kThreads / 64) || g.patch_cols > kMaxColsPerLane * 64) return false;
+    g.PP = (s.P + 2 - 3) / 2 + 1;
+    g.PQ = (s.Q + 2 - 3) / 2 + 1;
+    if (pool) {
+        if (s.P < 2 || s.Q < 2) return false;
+        g.tiles_p = (g.PP + kPoolTile - 1) / kPoolTile;
+        g.tiles_q = (g.PQ + kPoolTile - 1) / kPoolTile;
+    } else {
+        g.tiles_p = (s.P + kTile - 1) / kTile;
+        g.tiles_q = (s.Q + kTile - 1) / kTile;
+    }
     long long total = (long long)s.N * g.tiles_p * g.tiles_q;
     if (total > 0x7FFFFFFFll) return false;
     g.total_tiles = (int)total;
-    smem = sizeof(uint16_t) * ((size_t)s.K * g.wstride + (size_t)g.patch_rows * g.patch_stride);
-    return smem <= 64 * 1024;
+    smem = sizeof(uint16_t) * ((size_t)s.K * g.wstride + (size_t)g.patch_rows * g.patch_stride +
+                               (pool ? (size_t)kTile * kTile * (s.K + kOutPad) : 0));
+    return smem <= 96 * 1024;
+}
+
+template <int NB, bool POOL>
+hipError_t launch(const void* x, const void* w, const float* bias, void* y, const ConvShape& s, const StemGeom& g, size_t smem,
+                  hipStream_t stream)
+{
+    static bool configured = false;
+    if (!configured) {   // more than the default 64 KiB of LDS per workgroup needs an explicit opt-in
+        hipError_t e = hipFuncSetAttribute((const void*)conv_smallc_bf16_kernel<NB, POOL>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    int grid = g.total_tiles < 1024 ? g.total_tiles : 1024;
+    hipLaunchKernelGGL((conv_smallc_bf16_kernel<NB, POOL>), dim3(grid), dim3(kThreads), smem, stream, (const uint16_t*)x,
+                       (const uint16_t*)w, bias, (uint16_t*)y, s, g);
+    return hipGetLastError();
 }
 
 }  // namespace
 
-bool conv_smallc_supported(const ConvShape& s, bool has_res)
+bool conv_smallc_supported(const ConvShape& s, bool has_res, bool fused_pool)
 {
     StemGeom g;
     size_t smem;
-    return !has_res && geometry(s, g, smem);
+    return !has_res && geometry(s, fused_pool, g, smem);
 }
 
-hipError_t conv_smallc(const void* x, const void* w, const float* bias, void* y, const ConvShape& s, hipStream_t stream)
+hipError_t conv_smallc(const void* x, const void* w, const float* bias, void* y, const ConvShape& s, bool fused_pool,
+                       hipStream_t stream)
 {
     StemGeom g;
     size_t smem = 0;
-    if (!geometry(s, g, smem)) return hipErrorInvalidValue;
+    if (!geometry(s, fused_pool, g, smem)) return hipErrorInvalidValue;
     if (g.total_tiles == 0) return hipSuccess;
-    int grid = g.total_tiles < 1024 ? g.total_tiles : 1024;
     if (s.K == 64)
-        hipLaunchKernelGGL(conv_smallc_bf16_kernel<2>, dim3(grid), dim3(kThreads), smem, stream, (const uint16_t*)x,
-                           (const uint16_t*)w, bias, (uint16_t*)y, s, g);
-    else
-        hipLaunchKernelGGL(conv_smallc_bf16_kernel<1>, dim3(grid), dim3(kThreads), smem, stream, (const uint16_t*)x,
-                           (const uint16_t*)w, bias, (uint16_t*)y, s, g);
-    return hipGetLastError();
+        return fused_pool ? launch<2, true>(x, w, bias, y, s, g, smem, stream) : launch<2, false>(x, w, bias, y, s, g, smem, stream);
+    return fused_pool ? launch<1, true>(x, w, bias, y, s, g, smem, stream) : launch<1, false>(x, w, bias, y, s, g, smem, stream);
 }
 
 }  // namespace k
