@@ -59,8 +59,10 @@ def run(wl, blobs, inputs, first_expert=None, threads: int = 0):
                        wl.max_stages, wl.max_classes, threads)
 
 
-def guarded_inputs(wl, blobs, request_ids: Sequence[int], delta: Optional[float] = None, max_rounds: int = 40):
-    """Returns (inputs, subseeds, oracle_result, n_redraws) for the given request ids."""
+def guarded_inputs(wl, blobs, request_ids: Sequence[int], delta: Optional[float] = None, max_rounds: int = 8):
+    """Returns (inputs, subseeds, oracle_result, n_redraws) for the given request ids.  oracle_result["ambiguous"] marks
+    the requests that still have a routing gap below delta after max_rounds re-draws (many-way routing over nearly
+    identical logits): for those the admissible outcomes are enumerated with admissible_outcomes()."""
     if delta is None:
         delta = delta_for(wl)
     ids = np.asarray(list(request_ids), dtype=np.int64)
@@ -69,10 +71,11 @@ def guarded_inputs(wl, blobs, request_ids: Sequence[int], delta: Optional[float]
     fe = None if wl.first_expert is None else wl.first_expert[ids]
     res = run(wl, blobs, x, fe)
     redraws = 0
-    for _ in range(max_rounds):
+    bad = np.zeros(0, dtype=np.int64)
+    for rnd in range(max_rounds + 1):
         m = routing_margins(wl, blobs, res)
         bad = np.nonzero(((m >= 0) & (m < delta)).any(axis=1))[0]
-        if len(bad) == 0:
+        if len(bad) == 0 or rnd == max_rounds:
             break
         redraws += len(bad)
         sub[bad] += 1
@@ -80,9 +83,69 @@ def guarded_inputs(wl, blobs, request_ids: Sequence[int], delta: Optional[float]
         r2 = run(wl, blobs, x[bad], None if fe is None else fe[bad])
         for k in res:
             res[k][bad] = r2[k]
-    else:
-        raise RuntimeError("margin guard did not converge")
+    amb = np.zeros(len(ids), bool)
+    amb[bad] = True
+    res["ambiguous"] = amb
     return x, sub, res, redraws
+
+
+def evaluate_pairs(wl, blobs, xs: np.ndarray, experts: Sequence[int], threads: int = 0) -> np.ndarray:
+    """Oracle logits of expert experts[i] on input xs[i], all pairs in parallel (a graph without routes makes the
+    chain runner evaluate exactly the first expert of every request)."""
+    E = wl.graph.n_experts
+    r = O.run_chain(wl.archs, wl.expert_arch, blobs, np.zeros(E + 1, np.int32), np.zeros(1, np.int32), xs,
+                    np.asarray(experts, np.int32), 1, wl.max_classes, threads)
+    return r["logits"]
+
+
+def admissible_outcomes_batch(wl, blobs, xs: np.ndarray, first_experts: Sequence[int], delta: Optional[float] = None):
+    """For every request: every outcome that is correct up to the routing tolerance.  At each routing stage every class
+    whose logit is within delta * (largest computed logit magnitude) of the maximum may be taken.  Returns one list per
+    request of (path [max_stages] int32, final logits [max_classes] float32), in no particular order."""
+    from paper_2503_02354_amd import workloads as W
+    if delta is None:
+        delta = delta_for(wl)
+    n = len(xs)
+    done = [[] for _ in range(n)]
+    frontier = [(i, int(first_experts[i]), []) for i in range(n)]        # (request, expert to run, path so far)
+    bias_cache = {}
+    while frontier:
+        lg_all = evaluate_pairs(wl, blobs, xs[[f[0] for f in frontier]], [f[1] for f in frontier])
+        nxt_frontier = []
+        for (i, e, path), lg in zip(frontier, lg_all):
+            path = path + [e]
+            succ = wl.graph.successors(e)
+            k = len(succ)
+            if k == 0:
+                done[i].append((path, lg)); continue
+            if e not in bias_cache:
+                a = wl.archs[wl.expert_arch[e]]
+                bias_cache[e] = W.blob_tensor(a, blobs[e], a.n_layers - 1, "b")
+            b = bias_cache[e]
+            scale = max(float(np.abs(lg[:len(b)].astype(np.float64) - b).max()), 1e-30)
+            order = np.argsort(-lg[:k], kind="stable")
+            for c in order:
+                if lg[order[0]] - lg[c] > delta * scale:
+                    break
+                nxt = int(succ[c])
+                if nxt == -1:
+                    done[i].append((path, lg))
+                else:
+                    nxt_frontier.append((i, nxt, path))
+        frontier = nxt_frontier
+    out = []
+    for i in range(n):
+        res = []
+        for path, lg in done[i]:
+            p = np.full(wl.max_stages, -1, np.int32); p[:len(path)] = path
+            res.append((p, np.asarray(lg, np.float32)))
+        out.append(res)
+    return out
+
+
+def admissible_outcomes(wl, blobs, x_r: np.ndarray, first_expert: int = 0, delta: Optional[float] = None):
+    """Single-request form of admissible_outcomes_batch."""
+    return admissible_outcomes_batch(wl, blobs, x_r[None], [first_expert], delta)[0]
 
 
 def calibrate_bias(z: np.ndarray, n_route: int, target: np.ndarray, iters: int = 400, lr: float = 0.5) -> np.ndarray:

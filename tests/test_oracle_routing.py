@@ -253,3 +253,39 @@ def test_cache_invariants_random(oracle):
         assert [e for e, _ in sw] == [e for e in order if not before[e]]          # one load per missing group, no more
         n_hit = int(before[hg].sum())
         assert all(before[e] for e in order[:n_hit])                              # hits run first
+
+
+# ---------------------------------------------------------------------------------------------
+# margin guard: admissible outcomes at near-ties
+# ---------------------------------------------------------------------------------------------
+def test_admissible_outcomes_planted(oracle):
+    from oracle import guard as G
+    a = _head_only_arch(4)
+    # expert 0: logits = (m0, m1, m2, 0) route over 3 classes to experts 1, 2, final
+    e0 = _planted_blob(a, [[1, 0, 0], [0, 1, 0], [0, 0, 1], [0, 0, 0]], [0, 0, 0, 0])
+    e1 = _planted_blob(a, [[0, 0, 0]] * 4, [1, 2, 3, 4])
+    e2 = _planted_blob(a, [[0, 0, 0]] * 4, [5, 6, 7, 8])
+    g = W.graph_from_lists([[1, 2, -1], [], []])
+    wl = W.Workload("planted", 0, [a], [0, 0, 0], [1, .5, .5], g, 1, None, 0, 1, {}, 2)
+    blobs = [e0, e1, e2]
+
+    def img(m):
+        return np.broadcast_to(np.array(m, np.float32), (2, 2, 3)).copy()
+
+    # clear winner: class 0 by a wide gap -> one outcome, the oracle's
+    out = G.admissible_outcomes(wl, blobs, img([10, 1, 2]), 0, delta=2e-2)
+    assert [p.tolist() for p, _ in out] == [[0, 1]] and out[0][1].tolist() == [1, 2, 3, 4]
+    # classes 0 and 1 within 1 % of the largest logit magnitude (10): both routes admissible, best first
+    out = G.admissible_outcomes(wl, blobs, img([10, 9.95, 2]), 0, delta=2e-2)
+    assert [p.tolist() for p, _ in out] == [[0, 1], [0, 2]] and out[1][1].tolist() == [5, 6, 7, 8]
+    # a final (-1) route within the tolerance: stopping at expert 0 is admissible too
+    out = G.admissible_outcomes(wl, blobs, img([10, 2, 9.9]), 0, delta=2e-2)
+    assert sorted(p.tolist() for p, _ in out) == [[0, -1], [0, 1]]
+    stop = [lg for p, lg in out if p.tolist() == [0, -1]][0]
+    np.testing.assert_allclose(stop, [10, 2, 9.9, 0], rtol=1e-6)
+    # guarded_inputs marks what it could not resolve instead of failing
+    wl2 = W.config2(6, hw=32, n_experts=4, width=8, calibrated=False)
+    wl2.head_bias[0] = np.zeros(16, np.float32)
+    b2 = [wl2.blob(e) for e in range(4)]
+    x, sub, res, redraws = G.guarded_inputs(wl2, b2, range(6), delta=10.0, max_rounds=1)    # absurd delta: nothing passes
+    assert res["ambiguous"].all() and redraws == 6 and sub.tolist() == [1] * 6
