@@ -124,3 +124,32 @@ def test_config3_full_size(B, oracle):
     assert 0.15 < leaves.max() / wl.n_requests < 0.40 and (leaves > 0).sum() >= 40, leaves
     print(f"config3 full size: {len(sample)} sampled, max rel err {err:.2e}, {redraws} re-draws, "
           f"{len(log) - 16} switches, top leaves {np.sort(leaves)[::-1][:6].tolist()}")
+
+
+def test_config4_full_size(B, oracle):
+    """Three-stage DAG of 120 mixed ResNet-18/50-shaped experts, shared downstream experts, skewed group sizes,
+    8192 requests, everything resident."""
+    wl = W.config4()
+    assert wl.head_bias, "calibration file missing"
+    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=24, max_batch=512, seed=4)
+    stats = [st for rc, st in got["stats"] if rc == B.COE_OK]
+    assert len(stats) == 3 and all(st.n_pending == wl.n_requests for st in stats)
+    assert np.all(got["path"][:, 2] >= 0)
+    # regroup at every stage = stable sort of that stage's expert ids, all 8192 requests, bit exact
+    ctx = B.Context(max_requests=wl.n_requests)
+    sizes = []
+    for stage in range(3):
+        keys = got["path"][:, stage].astype(np.int32)
+        dev = ctx.coe_debug_regroup(keys, wl.graph.n_experts)
+        ref = oracle.regroup(keys, wl.graph.n_experts)
+        for k in ("cnt", "off", "perm", "inv"):
+            assert np.array_equal(dev[k], ref[k]), (stage, k)
+        assert stats[stage].n_groups == int((ref["cnt"] > 0).sum())
+        sizes.append(ref["cnt"][ref["cnt"] > 0])
+    ctx.close()
+    # chunks: every group cut into ceil(size / max_batch) batches
+    assert [st.n_chunks for st in stats] == [int(np.sum(-(-s // 512))) for s in sizes]
+    allsz = np.concatenate(sizes)
+    print(f"config4 full size: {len(sample)} sampled, max rel err {err:.2e}, {redraws} re-draws, groups per stage "
+          f"{[len(s) for s in sizes]}, sizes min {allsz.min()} median {int(np.median(allsz))} max {allsz.max()}")
+    assert allsz.max() >= 1000 and (allsz <= 64).sum() >= 5        # skew: a few huge groups, several small ones
