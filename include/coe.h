@@ -160,6 +160,10 @@ int coe_debug_switch_log(coe_ctx* ctx, int32_t cap, int32_t* log, int32_t* n_wor
 int coe_debug_resident(coe_ctx* ctx, uint8_t* out);
 /* Run one expert on n inputs (device pointer, context dtype) without routing: logits_out [n][n_classes] fp32 (host). */
 int coe_debug_forward(coe_ctx* ctx, int32_t expert_id, int32_t n, const void* device_inputs, float* logits_out);
+/* Run the first `layer + 1` layers of an expert on n <= max_batch inputs (device pointer) and copy that layer's output
+ * tensor [n][p][q][k] (context dtype) to `out` (host, out_bytes must match).  Heads and fused layers have none. */
+int coe_debug_layer_output(coe_ctx* ctx, int32_t expert_id, int32_t n, const void* device_inputs, int32_t layer, void* out,
+                           size_t out_bytes);
 /* One convolution layer with the library's kernel selection, on host tensors (uploaded, run `repeat` times, read back):
  * x [n][h][w][c], w [k][r][s][c] (canonical order), bias [k] fp32, res [n][p][q][k] or NULL, y [n][p][q][k]; x, w, res,
  * y in `dtype`.  *kernel_class (nullable) receives the COE_K_* class that ran.  Timed under cfg.profile like any launch. */
@@ -172,9 +176,9 @@ int coe_debug_regroup(coe_ctx* ctx, int32_t n, const int32_t* cur, int32_t n_exp
 
 /* Kernel classes timed when cfg.profile != 0. */
 enum { COE_K_REGROUP_INDEX = 0, COE_K_REGROUP_GATHER = 1, COE_K_CONV_MFMA = 2, COE_K_CONV_DIRECT = 3, COE_K_POOL = 4,
-       COE_K_HEAD = 5, COE_K_SWITCH = 6, COE_K_CONV_STEM = 7, COE_K_COUNT = 8 };
+       COE_K_HEAD = 5, COE_K_SWITCH = 6, COE_K_CONV_STEM = 7, COE_K_ATTENTION = 8, COE_K_TOKEN_OPS = 9, COE_K_COUNT = 10 };
 /* Synchronises, then returns and clears the accumulated launches, milliseconds and algorithmic work of a class
- * (flops for conv classes, bytes for the others). */
+ * (flops for the conv and attention classes, bytes for the others). */
 int coe_profile_read(coe_ctx* ctx, int32_t kernel_class, int64_t* launches, double* ms, double* work);
 
 /* ---- host-only pieces (no GPU needed) -------------------------------------------------------------------------- */

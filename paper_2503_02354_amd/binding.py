@@ -17,12 +17,12 @@ LIB_PATH = os.path.join(_HERE, "libcoe.so")
 COE_OK, COE_DONE = 0, 1
 COE_EINVAL, COE_ENOMEM, COE_ESTATE, COE_EGRAPH, COE_EDEVICE, COE_ERANGE = -1, -2, -3, -4, -5, -6
 K_REGROUP_INDEX, K_REGROUP_GATHER, K_CONV_MFMA, K_CONV_DIRECT, K_POOL, K_HEAD, K_SWITCH, K_CONV_STEM = range(8)
-KERNEL_CLASS_NAMES = ["regroup_index", "regroup_gather", "conv_mfma", "conv_direct", "pool", "head", "switch", "conv_stem"]
+KERNEL_CLASS_NAMES = ["regroup_index", "regroup_gather", "conv_mfma", "conv_direct", "pool", "head", "switch", "conv_stem", "attention", "token_ops"]
 
 EXPORTS = [
     "coe_create", "coe_destroy", "coe_last_error", "coe_register_arch", "coe_arch_blob_bytes", "coe_register_expert",
     "coe_set_dependency_graph", "coe_submit", "coe_step", "coe_sync", "coe_collect", "coe_reset_requests",
-    "coe_debug_last_regroup", "coe_debug_switch_log", "coe_debug_resident", "coe_debug_forward", "coe_debug_regroup", "coe_debug_conv",
+    "coe_debug_last_regroup", "coe_debug_switch_log", "coe_debug_resident", "coe_debug_forward", "coe_debug_layer_output", "coe_debug_regroup", "coe_debug_conv",
     "coe_profile_read", "coe_validate_graph", "coe_policy_create", "coe_policy_destroy", "coe_policy_init_fill",
     "coe_policy_stage", "coe_policy_resident",
 ]
@@ -71,6 +71,7 @@ def _load():
     L.coe_debug_switch_log.argtypes = [vp, i32, vp, C.POINTER(i32)]
     L.coe_debug_resident.argtypes = [vp, vp]
     L.coe_debug_forward.argtypes = [vp, i32, i32, vp, vp]
+    L.coe_debug_layer_output.argtypes = [vp, i32, i32, vp, i32, vp, C.c_size_t]
     L.coe_debug_regroup.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp]
     L.coe_debug_conv.argtypes = [vp, i32, vp, vp, vp, vp, vp] + [i32] * 11 + [C.POINTER(i32)]
     L.coe_profile_read.argtypes = [vp, i32, C.POINTER(i64), C.POINTER(C.c_double), C.POINTER(C.c_double)]
@@ -266,6 +267,12 @@ class Context:
         ncls = self._arch_classes[self._expert_arch[expert_id]]
         out = np.zeros((n, ncls), np.float32)
         self._chk(lib.coe_debug_forward(self._h, expert_id, n, C.c_void_p(int(device_inputs)), _ptr(out)))
+        return out
+
+    def coe_debug_layer_output(self, expert_id: int, n: int, device_inputs: int, layer: int, shape, dtype) -> np.ndarray:
+        """Output tensor of one layer, shape (n, p, q, k), dtype np.uint16 (bf16 bits) or np.float32."""
+        out = np.zeros(shape, dtype)
+        self._chk(lib.coe_debug_layer_output(self._h, expert_id, n, C.c_void_p(int(device_inputs)), layer, _ptr(out), out.nbytes))
         return out
 
     def coe_debug_regroup(self, cur: np.ndarray, n_experts: int):

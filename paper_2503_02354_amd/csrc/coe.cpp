@@ -31,6 +31,7 @@ struct LayerPlan {
     bool packed = false;    // conv filters are stored in matrix-core fragment order (device and pinned copies)
     bool fuse_pool = false; // conv: the max pool that follows runs inside the conv kernel, which writes the pool's dst
     bool fused_away = false;// pool: done by the preceding conv kernel
+    bool patchify = false;  // conv with stride == window and no padding: patches are gathered into GEMM rows, then a 1x1 conv
 };
 
 struct ArchPlan {
@@ -38,6 +39,7 @@ struct ArchPlan {
     std::vector<LayerPlan> layers;
     size_t blob_bytes = 0;
     size_t buf_elems[kMaxBufs] = {0};   // per request
+    size_t patch_elems = 0;             // per request: rows of the largest patch-gathered conv
     size_t elem() const { return dtype == COE_DT_BF16 ? 2 : 4; }
     size_t in_bytes() const { return (size_t)in_h * in_w * in_c * elem(); }
 };
@@ -104,6 +106,8 @@ struct coe_ctx {
     // activation workspace
     void* d_buf[kMaxBufs] = {nullptr};
     size_t buf_bytes[kMaxBufs] = {0};
+    void* d_patch = nullptr;         // GEMM rows of patch-gathered convolutions
+    size_t patch_bytes = 0;
 
     // profiling
     ProfClass prof[COE_K_COUNT];
@@ -203,6 +207,16 @@ int plan_arch(coe_ctx* c, const coe_arch_desc* d, ArchPlan& a)
                 {
                     coe::k::ConvShape cs{1, L.H, L.W, L.C, l.k, l.r, l.s, l.stride, l.pad, L.P, L.Q, l.act};
                     L.packed = d->dtype == COE_DT_BF16 && coe::k::conv_mfma_supported(cs);
+                    // non-overlapping windows of a few-channel image (patch embedding): a GEMM over gathered patches
+                    const int red = l.r * l.s * L.C;
+                    if (!L.packed && d->dtype == COE_DT_BF16 && l.stride == l.r && l.stride == l.s && l.pad == 0 && l.r > 1 &&
+                        L.H % l.r == 0 && L.W % l.s == 0 && (l.s * L.C * 2) % 16 == 0 && l.res < 0) {
+                        coe::k::ConvShape gs{1, L.P, L.Q, red, l.k, 1, 1, 1, 0, L.P, L.Q, l.act};
+                        if (coe::k::conv_mfma_supported(gs)) {
+                            L.packed = L.patchify = true;
+                            a.patch_elems = std::max(a.patch_elems, (size_t)L.P * L.Q * red);
+                        }
+                    }
                 }
                 if (l.res >= 0) {
                     if (l.res >= kMaxBufs || !shp[l.res].set || l.res == l.dst || shp[l.res].h != L.P || shp[l.res].w != L.Q ||
@@ -221,11 +235,14 @@ int plan_arch(coe_ctx* c, const coe_arch_desc* d, ArchPlan& a)
             L.macs = (double)l.k * L.C;
             break;
         case COE_OP_TOKENS:
+            if (d->dtype != COE_DT_BF16 || L.C % 8) return fail(c, COE_EINVAL, "arch: token ops need bf16 and channels % 8 == 0");
             L.P = L.H * L.W + 1; L.Q = 1; L.K = L.C;
             L.off[0] = take((size_t)L.C, true);
             L.off[1] = take((size_t)L.P * L.C, true);
             break;
         case COE_OP_LAYERNORM:
+            if (d->dtype != COE_DT_BF16 || L.C % 2 || L.C > 2048)
+                return fail(c, COE_EINVAL, "arch: layer norm needs bf16 and an even channel count <= 2048");
             L.P = L.H; L.Q = L.W; L.K = L.C;
             L.off[0] = take((size_t)L.C, false);
             L.off[1] = take((size_t)L.C, false);
@@ -233,10 +250,13 @@ int plan_arch(coe_ctx* c, const coe_arch_desc* d, ArchPlan& a)
         case COE_OP_ATTENTION:
             if (L.C % 3 || l.aux0 <= 0 || (L.C / 3) % l.aux0) return fail(c, COE_EINVAL, "arch: bad attention shape");
             L.P = L.H; L.Q = L.W; L.K = L.C / 3;
+            if (d->dtype != COE_DT_BF16 || !coe::k::attention_supported(L.H * L.W, L.C / 3, l.aux0))
+                return fail(c, COE_EINVAL, "arch: attention needs bf16, head width 64 and at most 224 tokens");
             L.macs = 2.0 * L.H * L.W * L.H * L.W * (L.C / 3);
             break;
         case COE_OP_HEAD_CLS:
             if (l.k != d->n_classes) return fail(c, COE_EINVAL, "arch: head width differs from n_classes");
+            if (d->dtype != COE_DT_BF16) return fail(c, COE_EINVAL, "arch: class-token head needs bf16");
             L.K = l.k;
             L.off[0] = take((size_t)L.C, false);
             L.off[1] = take((size_t)L.C, false);
@@ -307,6 +327,15 @@ int ensure_workspace(coe_ctx* c)
             HIPCHK(c, hipMalloc(&c->d_buf[b], need));
             c->buf_bytes[b] = need;
         }
+    }
+    size_t need = 0;
+    for (const ArchPlan& a : c->archs) need = std::max(need, a.patch_elems * a.elem() * (size_t)c->cfg.max_batch);
+    if (need > c->patch_bytes) {
+        HIPCHK(c, hipStreamSynchronize(c->sc));
+        if (c->d_patch) HIPCHK(c, hipFree(c->d_patch));
+        c->d_patch = nullptr;
+        HIPCHK(c, hipMalloc(&c->d_patch, need));
+        c->patch_bytes = need;
     }
     return COE_OK;
 }
@@ -387,19 +416,31 @@ int issue_load(coe_ctx* c, const coe::Switch& sw, coe_step_stats* st)
 }
 
 // ---- one expert over one batch ---------------------------------------------------------------------------------------
-int run_expert(coe_ctx* c, const Expert& x, const void* weights, const void* input, int32_t n, const coe::k::RouteArgs& route)
+int run_expert(coe_ctx* c, const Expert& x, const void* weights, const void* input, int32_t n, const coe::k::RouteArgs& route,
+               int32_t last_layer = -1)
 {
+    int32_t li = -1;
     const ArchPlan& a = c->archs[x.arch];
     const uint8_t* wb = (const uint8_t*)weights;
     auto buf = [&](int id) -> void* { return id == 0 ? const_cast<void*>(input) : c->d_buf[id]; };
     for (const LayerPlan& L : a.layers) {
         const coe_layer& l = L.d;
+        if (last_layer >= 0 && ++li > last_layer) break;
         switch (l.op) {
         case COE_OP_CONV: {
             coe::k::ConvShape s{n, L.H, L.W, L.C, L.K, l.r, l.s, l.stride, l.pad, L.P, L.Q, l.act};
             const void* res = l.res >= 0 ? buf(l.res) : nullptr;
             double flops = 2.0 * L.macs * n;
-            if (L.packed) {
+            if (L.patchify) {
+                {
+                    double bytes = 2.0 * n * (double)L.H * L.W * L.C * a.elem();
+                    Span sp(c, COE_K_TOKEN_OPS, bytes, c->sc);
+                    HIPCHK(c, coe::k::patchify(buf(l.src), c->d_patch, n, L.H, L.W, L.C, l.r, l.s, c->sc));
+                }
+                coe::k::ConvShape g{n, L.P, L.Q, l.r * l.s * L.C, L.K, 1, 1, 1, 0, L.P, L.Q, l.act};
+                Span sp(c, COE_K_CONV_MFMA, flops, c->sc);
+                HIPCHK(c, coe::k::conv_mfma(c->d_patch, wb + L.off[0], (const float*)(wb + L.off[1]), nullptr, buf(l.dst), g, c->sc));
+            } else if (L.packed) {
                 Span sp(c, COE_K_CONV_MFMA, flops, c->sc);
                 HIPCHK(c, coe::k::conv_mfma(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), res, buf(l.dst), s, c->sc));
             } else if (L.fuse_pool) {
@@ -429,8 +470,33 @@ int run_expert(coe_ctx* c, const Expert& x, const void* weights, const void* inp
                                           route, c->sc));
             break;
         }
+        case COE_OP_TOKENS: {
+            double bytes = (double)n * ((double)L.H * L.W + L.P) * L.C * a.elem();
+            Span sp(c, COE_K_TOKEN_OPS, bytes, c->sc);
+            HIPCHK(c, coe::k::tokens(buf(l.src), wb + L.off[0], wb + L.off[1], buf(l.dst), n, L.P, L.C, c->sc));
+            break;
+        }
+        case COE_OP_LAYERNORM: {
+            double bytes = 2.0 * n * (double)L.H * L.W * L.C * a.elem();
+            Span sp(c, COE_K_TOKEN_OPS, bytes, c->sc);
+            HIPCHK(c, coe::k::layernorm(buf(l.src), (const float*)(wb + L.off[0]), (const float*)(wb + L.off[1]), buf(l.dst),
+                                        (int64_t)n * L.H * L.W, L.C, c->sc));
+            break;
+        }
+        case COE_OP_ATTENTION: {
+            Span sp(c, COE_K_ATTENTION, 2.0 * L.macs * n, c->sc);
+            HIPCHK(c, coe::k::attention(buf(l.src), buf(l.dst), n, L.H * L.W, L.K, l.aux0, c->sc));
+            break;
+        }
+        case COE_OP_HEAD_CLS: {
+            double bytes = (double)n * L.C * a.elem();
+            Span sp(c, COE_K_HEAD, bytes, c->sc);
+            HIPCHK(c, coe::k::head_cls(buf(l.src), (const float*)(wb + L.off[0]), (const float*)(wb + L.off[1]), wb + L.off[2],
+                                       (const float*)(wb + L.off[3]), n, L.H * L.W, L.C, L.K, route, c->sc));
+            break;
+        }
         default:
-            return fail(c, COE_EINVAL, "layer op has no device kernel yet");
+            return fail(c, COE_EINVAL, "unknown layer op");
         }
     }
     return COE_OK;
@@ -513,6 +579,7 @@ void coe_destroy(coe_ctx* c)
                     c->d_perm, c->d_inv, c->d_blockhist, c->d_succ};
     for (void* p : ptrs) if (p) hipFree(p);
     for (int b = 1; b < kMaxBufs; ++b) if (c->d_buf[b]) hipFree(c->d_buf[b]);
+    if (c->d_patch) hipFree(c->d_patch);
     if (c->h_cnt) hipHostFree(c->h_cnt);
     if (c->own_sc && c->sc) hipStreamDestroy(c->sc);
     if (c->own_sx && c->sx) hipStreamDestroy(c->sx);
@@ -855,6 +922,35 @@ int coe_debug_forward(coe_ctx* c, int32_t e, int32_t n, const void* dev_in, floa
     if (rc == COE_OK && he == hipSuccess) he = hipMemcpy(logits_out, d_log, (size_t)n * a.n_classes * 4, hipMemcpyDeviceToHost);
     hipFree(d_log);
     if (temp) hipFree(w);
+    if (rc) return rc;
+    if (he != hipSuccess) return fail(c, COE_EDEVICE, hipGetErrorString(he));
+    return COE_OK;
+}
+
+int coe_debug_layer_output(coe_ctx* c, int32_t e, int32_t n, const void* dev_in, int32_t layer, void* out, size_t out_bytes)
+{
+    if (!c || !dev_in || !out || n <= 0) return fail(c, COE_EINVAL, "bad argument");
+    if (e < 0 || e >= (int32_t)c->experts.size() || !c->experts[e].registered) return fail(c, COE_EINVAL, "unknown expert");
+    if (n > c->cfg.max_batch) return fail(c, COE_ERANGE, "more inputs than max_batch");
+    Expert& x = c->experts[e];
+    const ArchPlan& a = c->archs[x.arch];
+    if (layer < 0 || layer >= (int32_t)a.layers.size() - 1) return fail(c, COE_EINVAL, "layer index out of range (heads have no output tensor)");
+    const LayerPlan& L = a.layers[layer];
+    if (L.fuse_pool || L.fused_away) return fail(c, COE_EINVAL, "layer is fused with its neighbour");
+    const size_t bytes = (size_t)n * L.P * L.Q * L.K * a.elem();
+    if (out_bytes != bytes) return fail(c, COE_EINVAL, "output size does not match the layer");
+    int rc = ensure_workspace(c);
+    if (rc) return rc;
+    void* w = nullptr;
+    HIPCHK(c, hipMalloc(&w, x.nbytes));
+    hipError_t he = hipMemcpy(w, x.host, x.nbytes, hipMemcpyHostToDevice);
+    if (he == hipSuccess) {
+        coe::k::RouteArgs r{};
+        rc = run_expert(c, x, w, dev_in, n, r, layer);
+        he = hipStreamSynchronize(c->sc);
+        if (rc == COE_OK && he == hipSuccess) he = hipMemcpy(out, c->d_buf[L.d.dst], bytes, hipMemcpyDeviceToHost);
+    }
+    hipFree(w);
     if (rc) return rc;
     if (he != hipSuccess) return fail(c, COE_EDEVICE, hipGetErrorString(he));
     return COE_OK;

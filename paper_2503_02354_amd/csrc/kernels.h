@@ -66,5 +66,20 @@ hipError_t maxpool(int dtype, const void* x, void* y, int32_t N, int32_t H, int3
 hipError_t head_gap_fc(int dtype, const void* x, const void* w, const float* b, int32_t N, int32_t HW, int32_t C,
                        int32_t ncls, const RouteArgs& r, hipStream_t stream);
 
+// ---- transformer-shaped experts (bf16 only) --------------------------------------------------------------------
+// Patches of a non-overlapping convolution (stride == window, no padding) as GEMM rows:
+// x [N][H][W][C] -> out [N * (H/R) * (W/S)][R*S*C].  S*C*2 bytes must be a multiple of 16.
+hipError_t patchify(const void* x, void* out, int32_t N, int32_t H, int32_t W, int32_t C, int32_t R, int32_t S, hipStream_t stream);
+// out[n][0] = cls + pos[0]; out[n][1+i] = x[n][i] + pos[1+i]; T = tokens of out; D % 8 == 0.
+hipError_t tokens(const void* x, const void* cls, const void* pos, void* out, int32_t N, int32_t T, int32_t D, hipStream_t stream);
+// layer norm over D channels of `rows` tokens, eps 1e-6, D even and <= 2048.
+hipError_t layernorm(const void* x, const float* gamma, const float* beta, void* y, int64_t rows, int32_t D, hipStream_t stream);
+// qkv [N][T][3D] (q | k | v) -> out [N][T][D]; head width must be 64, T <= 224.
+bool attention_supported(int32_t T, int32_t D, int32_t heads);
+hipError_t attention(const void* qkv, void* out, int32_t N, int32_t T, int32_t D, int32_t heads, hipStream_t stream);
+// logits = FC(layer norm(token 0 of x [N][T][D])), then routing like head_gap_fc.
+hipError_t head_cls(const void* x, const float* gamma, const float* beta, const void* w, const float* b, int32_t N, int32_t T,
+                    int32_t D, int32_t ncls, const RouteArgs& r, hipStream_t stream);
+
 }  // namespace k
 }  // namespace coe

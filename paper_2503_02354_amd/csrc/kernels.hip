@@ -280,6 +280,29 @@ __device__ __forceinline__ float wave_sum(float v)
 }
 
 constexpr int kHeadThreads = 256;
+
+// logits of one request are in LDS: write them out, take the argmax over the routed classes (lowest index wins
+// ties), look the successor up, append the expert to the request's path
+__device__ __forceinline__ void route_tail(const float* logit, int ncls, int row, const RouteArgs& r)
+{
+    int slot = r.slot ? r.slot[row] : row;
+    for (int j = threadIdx.x; j < r.logits_stride; j += kHeadThreads)
+        r.logits[(size_t)slot * r.logits_stride + j] = j < ncls ? logit[j] : 0.f;
+    if (threadIdx.x == 0 && r.cur) {
+        int nxt = -1;
+        if (r.n_route > 0) {
+            int best = 0;
+            for (int j = 1; j < r.n_route; ++j)
+                if (logit[j] > logit[best]) best = j;      // strict: the lowest index wins ties
+            nxt = r.succ[best];
+        }
+        int d = r.depth[slot];
+        if (d < r.max_stages) r.path[(size_t)slot * r.max_stages + d] = r.expert;
+        r.depth[slot] = d + 1;
+        r.cur[slot] = nxt;
+    }
+}
+
 template <typename T>
 __global__ __launch_bounds__(kHeadThreads) void head_gap_fc_kernel(const T* __restrict__ x, const T* __restrict__ w,
                                                                    const float* __restrict__ b, int HW, int C, int ncls,
@@ -324,22 +347,44 @@ __global__ __launch_bounds__(kHeadThreads) void head_gap_fc_kernel(const T* __re
     }
     __syncthreads();
     // phase 3: write logits, pick the route
-    int slot = r.slot ? r.slot[row] : row;
-    for (int j = threadIdx.x; j < r.logits_stride; j += kHeadThreads)
-        r.logits[(size_t)slot * r.logits_stride + j] = j < ncls ? logit[j] : 0.f;
-    if (threadIdx.x == 0 && r.cur) {
-        int nxt = -1;
-        if (r.n_route > 0) {
-            int best = 0;
-            for (int j = 1; j < r.n_route; ++j)
-                if (logit[j] > logit[best]) best = j;      // strict: the lowest index wins ties
-            nxt = r.succ[best];
-        }
-        int d = r.depth[slot];
-        if (d < r.max_stages) r.path[(size_t)slot * r.max_stages + d] = r.expert;
-        r.depth[slot] = d + 1;
-        r.cur[slot] = nxt;
+    route_tail(logit, ncls, row, r);
+}
+
+// class-token head: layer norm of token 0 (rounded to bf16 like every stored activation), FC, routing
+__global__ __launch_bounds__(kHeadThreads) void head_cls_kernel(const uint16_t* __restrict__ x, const float* __restrict__ gamma,
+                                                                const float* __restrict__ beta, const uint16_t* __restrict__ w,
+                                                                const float* __restrict__ b, int T, int D, int ncls, RouteArgs r)
+{
+    extern __shared__ float smem[];          // feat[D] | red[8] | logit[ncls]
+    float* feat = smem;
+    float* red = smem + D;
+    float* logit = red + 8;
+    const int row = blockIdx.x;
+    const uint16_t* xp = x + (size_t)row * T * D;     // token 0
+    const int lane = threadIdx.x & (kWave - 1), wid = threadIdx.x / kWave;
+    float sum = 0.f;
+    for (int c = threadIdx.x; c < D; c += kHeadThreads) { float v = bf16_to_f32(xp[c]); feat[c] = v; sum += v; }
+    sum = wave_sum(sum);
+    if (lane == 0) red[wid] = sum;
+    __syncthreads();
+    const float mean = (red[0] + red[1] + red[2] + red[3]) / (float)D;
+    float sq = 0.f;
+    for (int c = threadIdx.x; c < D; c += kHeadThreads) { float d = feat[c] - mean; sq += d * d; }
+    sq = wave_sum(sq);
+    if (lane == 0) red[4 + wid] = sq;
+    __syncthreads();
+    const float rstd = rsqrtf((red[4] + red[5] + red[6] + red[7]) / (float)D + 1e-6f);
+    for (int c = threadIdx.x; c < D; c += kHeadThreads)
+        feat[c] = bf16_to_f32(f32_to_bf16((feat[c] - mean) * rstd * gamma[c] + beta[c]));
+    __syncthreads();
+    for (int j = wid; j < ncls; j += kHeadThreads / kWave) {
+        float a = 0.f;
+        for (int c = lane; c < D; c += kWave) a = fmaf(feat[c], bf16_to_f32(w[(size_t)j * D + c]), a);
+        a = wave_sum(a);
+        if (lane == 0) logit[j] = a + b[j];
     }
+    __syncthreads();
+    route_tail(logit, ncls, row, r);
 }
 
 }  // namespace
@@ -437,6 +482,17 @@ hipError_t head_gap_fc(int dtype, const void* x, const void* w, const float* b, 
     else
         hipLaunchKernelGGL(head_gap_fc_kernel<float>, dim3(N), dim3(kHeadThreads), smem, stream, (const float*)x,
                            (const float*)w, b, HW, C, ncls, r);
+    return hipGetLastError();
+}
+
+hipError_t head_cls(const void* x, const float* gamma, const float* beta, const void* w, const float* b, int32_t N, int32_t T,
+                    int32_t D, int32_t ncls, const RouteArgs& r, hipStream_t stream)
+{
+    if (N <= 0) return hipSuccess;
+    size_t smem = sizeof(float) * ((size_t)D + 8 + (size_t)ncls);
+    if (smem > 60 * 1024) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(head_cls_kernel, dim3(N), dim3(kHeadThreads), smem, stream, (const uint16_t*)x, gamma, beta,
+                       (const uint16_t*)w, b, T, D, ncls, r);
     return hipGetLastError();
 }
 

@@ -331,3 +331,99 @@ def test_conv_elementwise_bf16(B, oracle, n, H, Wd, C, K, R, stride, pad, use_re
     worst = np.unravel_index(np.argmax(np.abs(g - want) / ulp), g.shape)
     assert np.all(np.abs(g - want) <= ulp), (worst, float(g[worst]), float(want[worst]), int(np.sum(np.abs(g - want) > ulp)))
     assert np.mean(g == want) > 0.995
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# transformer-shaped experts: each token op element by element, then whole forwards
+# ---------------------------------------------------------------------------------------------------------------
+def _token_op_arch(T, C, words, out_c, ncls=4):
+    """One token op on the raw input [T][1][C], then a pooled head so the program is complete."""
+    p = W._Prog(T, 1, C)
+    p.raw([words[0], 0, 1, -1] + list(words[1:]))
+    p.shape[1] = (T if words[0] != W.OP_TOKENS else T + 1, 1, out_c)
+    p.head(1, ncls)
+    return W.Arch("token_op", W.DT_BF16, T, 1, C, ncls, np.array(p.layers, dtype=np.int32), p.gains)
+
+
+def _layer0(B, arch, blob, x, shape):
+    n = x.shape[0]
+    ctx = B.Context(max_requests=n, max_batch=n)
+    aid = ctx.coe_register_arch(arch)
+    ctx.coe_register_expert(0, aid, blob, 1.0)
+    dev = device_tensor(x)
+    got = ctx.coe_debug_layer_output(0, n, dev.data_ptr(), 0, (n,) + shape, np.uint16)
+    ctx.close()
+    return W.bf16_bits_to_f32(got).reshape(got.shape)
+
+
+def _assert_bf16_close(g, want, floor):
+    """Both sides round an fp32 (GPU) / fp64 (oracle) value to bf16: equal except for rounding flips of one ulp."""
+    ulp = np.maximum(np.abs(want) * 2.0 ** -7, floor)
+    bad = np.abs(g - want) > ulp
+    worst = np.unravel_index(np.argmax(np.abs(g - want) / ulp), g.shape)
+    assert not bad.any(), (worst, float(g[worst]), float(want[worst]), int(bad.sum()))
+
+
+@pytest.mark.parametrize("T,D,heads,n", [(197, 128, 2, 3), (32, 64, 1, 2), (50, 192, 3, 2), (224, 64, 1, 1), (1, 64, 1, 2)])
+def test_attention_elementwise(B, oracle, T, D, heads, n):
+    arch = _token_op_arch(T, 3 * D, [W.OP_ATTENTION, D, 0, 0, 0, 0, 0, heads, 0], D)
+    blob = W.make_expert_blob(arch, 31, 0)
+    x = W.make_inputs(arch, 31, range(n)).reshape(n, T, 3 * D)
+    g = _layer0(B, arch, blob, x, (T, 1, D)).reshape(n, T, D)
+    xf = W.bf16_bits_to_f32(x).reshape(n, T, 3 * D)
+    want = np.stack([oracle.attention(xf[i], heads, 1) for i in range(n)])
+    # weights are bf16(e) on both sides; expf vs exp may flip a weight's rounding: 2^-9 relative on one term
+    _assert_bf16_close(g, want, 2e-3)
+    assert np.mean(g == want) > 0.98
+
+
+@pytest.mark.parametrize("T,D,n", [(197, 768, 2), (5, 66, 3), (64, 2048, 1)])
+def test_layernorm_elementwise(B, oracle, T, D, n):
+    arch = _token_op_arch(T, D, [W.OP_LAYERNORM, D, 0, 0, 0, 0, 0, 0, 0], D)
+    blob = W.make_expert_blob(arch, 32, 0)
+    x = W.make_inputs(arch, 32, range(n)).reshape(n, T, D)
+    g = _layer0(B, arch, blob, x, (T, 1, D)).reshape(n, T, D)
+    xf = W.bf16_bits_to_f32(x).reshape(n, T, D)
+    gamma, beta = W.blob_tensor(arch, blob, 0, "gamma"), W.blob_tensor(arch, blob, 0, "beta")
+    want = np.stack([oracle.layernorm(xf[i], gamma, beta, 1) for i in range(n)])
+    _assert_bf16_close(g, want, 1e-5)
+    assert np.mean(g == want) > 0.995
+
+
+def test_tokens_elementwise(B, oracle):
+    T0, D, n = 49, 72, 3
+    arch = _token_op_arch(T0, D, [W.OP_TOKENS, D, 0, 0, 0, 0, 0, 0, 0], D)
+    blob = W.make_expert_blob(arch, 33, 0)
+    x = W.make_inputs(arch, 33, range(n)).reshape(n, T0, D)
+    g = _layer0(B, arch, blob, x, (T0 + 1, 1, D)).reshape(n, T0 + 1, D)
+    xf = W.bf16_bits_to_f32(x).reshape(n, T0, D)
+    cls, pos = W.blob_tensor(arch, blob, 0, "cls"), W.blob_tensor(arch, blob, 0, "pos")
+    want = np.stack([oracle.tokens(xf[i], cls, pos, 1) for i in range(n)])
+    assert np.array_equal(g, want)          # one exact fp32 add, one rounding: no room for a difference
+
+
+def test_patch_embedding_elementwise(B, oracle):
+    # 16x16 patches of a 3-channel image as one GEMM over gathered rows (red = 768), ragged last tile (3*4*4 = 48 rows)
+    hw, patch, K, n = 64, 16, 96, 3
+    p = W._Prog(hw, hw, 3)
+    p.conv(0, 1, K, patch, patch, 0, W.ACT_NONE)
+    p.head(1, 4)
+    arch = W.Arch("patch", W.DT_BF16, hw, hw, 3, 4, np.array(p.layers, dtype=np.int32), p.gains)
+    blob = W.make_expert_blob(arch, 34, 0)
+    x = W.make_inputs(arch, 34, range(n)).reshape(n, hw, hw, 3)
+    g = _layer0(B, arch, blob, x, (hw // patch, hw // patch, K))
+    xf = W.bf16_bits_to_f32(x).reshape(n, hw, hw, 3)
+    w, b = W.blob_tensor(arch, blob, 0, "w"), W.blob_tensor(arch, blob, 0, "b")
+    want = np.stack([oracle.conv2d(xf[i], w, b, None, patch, 0, 0, 1) for i in range(n)])
+    _assert_bf16_close(g, want, 1e-5)
+    assert np.mean(g == want) > 0.995
+
+
+def test_forward_vit_small_bf16(B, oracle):
+    # 4 blocks, 2 heads of 64, 17 tokens: every op of the transformer program once through the library's dispatch
+    _forward_case(B, oracle, W.vit(6, 32, 8, 128, 4, 2, 256, W.DT_BF16), 5, 35, REL_TOL_BF16, max_batch=3)
+
+
+def test_forward_vit_base_shape_bf16(B, oracle):
+    # ViT-B/16 geometry (197 tokens: ragged 32-key blocks; 12 heads; red 768) with 2 blocks to keep the oracle quick
+    _forward_case(B, oracle, W.vit(8, 224, 16, 768, 2, 12, 3072, W.DT_BF16), 3, 36, REL_TOL_BF16)

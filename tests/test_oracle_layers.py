@@ -282,7 +282,31 @@ def _np_forward_f64(arch, blob, x):
                 y = y + bufs[res]
             if act == 1:
                 y = np.maximum(y, 0)
+            elif act == 2:
+                y = 0.5 * y * (1.0 + np.vectorize(math.erf)(y / math.sqrt(2.0)))
             bufs[dst] = y
+        elif op == W.OP_TOKENS:
+            t = bufs[src].reshape(-1, bufs[src].shape[2])
+            t = np.concatenate([W.blob_tensor(arch, blob, li, "cls")[None].astype(np.float64), t], 0)
+            bufs[dst] = (t + W.blob_tensor(arch, blob, li, "pos"))[:, None, :]
+        elif op == W.OP_LAYERNORM:
+            t = bufs[src]
+            mu = t.mean(-1, keepdims=True); var = ((t - mu) ** 2).mean(-1, keepdims=True)
+            bufs[dst] = (t - mu) / np.sqrt(var + 1e-6) * W.blob_tensor(arch, blob, li, "gamma") + W.blob_tensor(arch, blob, li, "beta")
+        elif op == W.OP_ATTENTION:
+            t = bufs[src][:, 0, :]; T, D3 = t.shape; D = D3 // 3; heads = int(L[10]); dh = D // heads
+            y = np.empty((T, D))
+            for h in range(heads):
+                q = t[:, h * dh:(h + 1) * dh]; kk = t[:, D + h * dh:D + (h + 1) * dh]; v = t[:, 2 * D + h * dh:2 * D + (h + 1) * dh]
+                sc = q @ kk.T / math.sqrt(dh)
+                pr = np.exp(sc - sc.max(1, keepdims=True)); pr /= pr.sum(1, keepdims=True)
+                y[:, h * dh:(h + 1) * dh] = pr @ v
+            bufs[dst] = y[:, None, :]
+        elif op == W.OP_HEAD_CLS:
+            t = bufs[src][0, 0]
+            mu = t.mean(); var = ((t - mu) ** 2).mean()
+            nrm = (t - mu) / math.sqrt(var + 1e-6) * W.blob_tensor(arch, blob, li, "gamma") + W.blob_tensor(arch, blob, li, "beta")
+            return W.blob_tensor(arch, blob, li, "w").astype(np.float64) @ nrm + W.blob_tensor(arch, blob, li, "b")
         elif op == W.OP_MAXPOOL:
             xin = bufs[src]; H, Wd, C = xin.shape
             xp = np.full((H + 2 * pad, Wd + 2 * pad, C), -np.inf); xp[pad:pad + H, pad:pad + Wd] = xin
@@ -321,6 +345,24 @@ def test_forward_resnet50_fp32_matches_numpy(oracle):
     blob = W.make_expert_blob(a, 8, 3)
     x = W.make_inputs(a, 8, [2])[0]
     np.testing.assert_allclose(oracle.forward(a, blob, x), _np_forward_f64(a, blob, x), rtol=1e-4, atol=1e-5)
+
+
+def test_forward_vit_fp32_matches_numpy(oracle):
+    # small ViT-shaped expert (4x4 patches of 8x8, dim 32, 2 blocks, 2 heads): wiring of tokens, pre-LN blocks,
+    # attention, GELU MLP, residuals, class-token head and blob offsets against the independent walk
+    a = W.vit(5, hw=32, patch=8, dim=32, depth=2, heads=2, mlp=64, dtype=W.DT_F32)
+    blob = W.make_expert_blob(a, 21, 0)
+    x = W.make_inputs(a, 21, [3])[0]
+    np.testing.assert_allclose(oracle.forward(a, blob, x), _np_forward_f64(a, blob, x), rtol=1e-4, atol=1e-5)
+
+
+def test_forward_vit_bf16_close_to_unrounded(oracle):
+    a = W.vit(5, hw=32, patch=8, dim=32, depth=2, heads=2, mlp=64, dtype=W.DT_BF16)
+    blob = W.make_expert_blob(a, 21, 0)
+    xb = W.make_inputs(a, 21, [3])[0]
+    got = oracle.forward(a, blob, xb)
+    want = _np_forward_f64(a, blob, W.bf16_bits_to_f32(xb).reshape(xb.shape))
+    assert np.max(np.abs(got - want)) / np.max(np.abs(want)) < 3e-2
 
 
 def test_forward_bf16_close_to_unrounded(oracle):
