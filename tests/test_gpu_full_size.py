@@ -2,6 +2,8 @@
 request at these sizes, so: a seeded sample of requests (margin-guarded, re-drawn where needed) is compared with the
 oracle one by one; every request is checked through properties that hold at any size (valid path through the graph,
 regroup = stable sort of the routed ids, identical results when the sampled requests run alone)."""
+from concurrent.futures import ThreadPoolExecutor
+
 import numpy as np
 import pytest
 
@@ -34,7 +36,8 @@ def _sampled_case(B, oracle, wl, n_sample, max_batch, arrival=None, seed=1):
     from oracle import guard as G
     n = wl.n_requests
     E = wl.graph.n_experts
-    blobs = [wl.blob(e) for e in range(E)]
+    with ThreadPoolExecutor(8) as ex:
+        blobs = list(ex.map(wl.blob, range(E)))
     rng = np.random.default_rng(seed)
     sample = np.sort(rng.choice(n, size=n_sample, replace=False))
     print(f"{wl.name}: blobs ready", flush=True)
@@ -153,3 +156,24 @@ def test_config4_full_size(B, oracle):
     print(f"config4 full size: {len(sample)} sampled, max rel err {err:.2e}, {redraws} re-draws, groups per stage "
           f"{[len(s) for s in sizes]}, sizes min {allsz.min()} median {int(np.median(allsz))} max {allsz.max()}")
     assert allsz.max() >= 1000 and (allsz <= 64).sum() >= 5        # skew: a few huge groups, several small ones
+
+
+def test_config5_full_size(B, oracle):
+    """32 ViT-B/16-shaped bf16 experts (172 MB each), root -> 31 leaves routed uniformly, cache capped at 12 experts,
+    4096 requests: the 3.4 GB/stage of expert switches overlap the forwards of the groups already resident."""
+    wl = W.config5()
+    assert wl.head_bias, "calibration file missing"
+    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=16, max_batch=512, seed=5)
+    stats = [st for rc, st in got["stats"] if rc == B.COE_OK]
+    assert len(stats) == 2 and all(st.n_pending == wl.n_requests for st in stats)
+    log = got["switch_log"]
+    assert [e for e, v in log[:12]] == list(range(12)) and all(v == [] for e, v in log[:12])   # initial fill
+    assert len(log) == 12 + sum(st.n_misses for st in stats)
+    resident = _replay_switch_log(log, 32, 12)
+    assert 0 in resident and all(0 not in v for e, v in log)
+    leaves = np.bincount(got["path"][:, 1], minlength=32)[1:]
+    assert leaves.min() > 40 and leaves.max() < 300, leaves              # calibration spreads the 31 routes
+    assert stats[1].n_groups == 31 and stats[1].n_misses == 31 - 11      # 11 leaves were resident after the fill
+    assert sum(st.bytes_switched for st in stats) == sum(st.n_misses for st in stats) * W.blob_layout(wl.archs[0])[1]
+    print(f"config5 full size: {len(sample)} sampled, max rel err {err:.2e}, {redraws} re-draws, "
+          f"{len(log) - 12} switches, leaves min {leaves.min()} max {leaves.max()}")
