@@ -298,6 +298,446 @@ hipError_t launch(const void* x, const void* wp, const float* bias, const void* 
     return hipGetLastError();
 }
 
+
+// ---------------------------------------------------------------------------------------------------------------
+// Direct-to-LDS kernel.  Both operands of a reduction step are DMA'd from global memory straight into LDS (buffer
+// loads with the LDS bit: lane i of a load lands at base + 16 i, one instruction fills 1 KiB).  No register staging
+// and no LDS store instructions (an LDS store instruction moves 64 bytes per clock, half the read rate, and the
+// staging registers cost occupancy).
+//   * Filters: one load = one fragment of the repacked filter tensor, read back linearly.
+//   * Activations: one load = 16 pixel rows x 64 bytes (a 32-channel run), four adjacent lanes per row so the global
+//     access stays 64 bytes contiguous.  Inside the 1 KiB block the 16-byte chunk c of row r sits in slot
+//     4 r + (c ^ f(r)), f(r) = ((r >> 1) & 3) ^ (r >> 3): the later operand read (lane = pixel row, fixed chunk) then
+//     touches every LDS bank equally, whether the hardware resolves conflicts per 8 or per 16 lanes.  The lane that
+//     fills slot i simply fetches the chunk that belongs there.
+// Three LDS stages, loads two steps ahead, one barrier per step:
+//     wait until this wave's loads of step u have landed | barrier | issue loads of step u+2 into the stage that
+//     step u-1 was computed from (every wave is past that, it is behind the barrier) | compute step u.
+// ---------------------------------------------------------------------------------------------------------------
+typedef __attribute__((address_space(3))) void lds_void;
+
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    // s_waitcnt with only the vector-memory counter armed (expcnt and lgkmcnt fields at their maxima)
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv_igemm_dma_kernel(const uint16_t* __restrict__ x,
+                                                                   const uint16_t* __restrict__ wp,
+                                                                   const float* __restrict__ bias,
+                                                                   const uint16_t* __restrict__ res,
+                                                                   uint16_t* __restrict__ y, ConvShape s, int M,
+                                                                   int tiles_n)
+{
+#if defined(__HIP_DEVICE_COMPILE__)      // the host pass only needs the launch stub (LDS address-space casts do not exist there)
+    constexpr int BK = 32, KS = 2, kStages = 3;
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int MB = WM / 32, NB = WN / 32;
+    constexpr int FA = BM / 16, FB = BN / 32 * KS;           // 1 KiB blocks per step: 16-row activation blocks, filter fragments
+    static_assert(FA % NW == 0 && FB % NW == 0, "every wave issues the same number of loads");
+    constexpr int A_PER_WAVE = FA / NW, B_PER_WAVE = FB / NW;
+    constexpr int LOADS = A_PER_WAVE + B_PER_WAVE;
+    constexpr int FRAG = 512;                                 // elements per 1 KiB block
+    constexpr int STAGE = (FA + FB) * FRAG;                   // elements
+
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // kStages * STAGE elements
+
+    int tile;
+    {
+        int L = blockIdx.x, total = gridDim.x;
+        int xcd = L % kXcds, slot = L / kXcds;
+        int base = total / kXcds, rem = total % kXcds;
+        tile = xcd * base + (xcd < rem ? xcd : rem) + slot;
+    }
+    const int tile_n = tile % tiles_n, tile_m = tile / tiles_n;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int tid = threadIdx.x, lane = tid & 63, wid = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wid / WAVES_N, wn = wid % WAVES_N;
+
+    const int cblocks = s.C / BK;
+    const int RS = s.R * s.S;
+    const int nsteps = RS * cblocks;
+    const int ks16_total = nsteps * KS;
+
+    const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(x, (uint32_t)s.N * (uint32_t)(s.H * s.W * s.C) * 2u);
+    const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(wp, (uint32_t)s.K * (uint32_t)(RS * s.C) * 2u);
+
+    // rows this lane fetches: block (wid * A_PER_WAVE + j), row lane / 4 of the block; which 16-byte chunk of the
+    // 32-channel run follows from the slot the lane fills
+    auto swz = [](int r16) { return ((r16 >> 1) & 3) ^ (r16 >> 3); };
+    int32_t a_off[A_PER_WAVE];
+    uint64_t a_mask[A_PER_WAVE];
+    {
+        const int PQ = s.P * s.Q;
+        const int chunk = (lane & 3) ^ swz(lane >> 2);
+#pragma unroll
+        for (int j = 0; j < A_PER_WAVE; ++j) {
+            int m = m0 + (wid * A_PER_WAVE + j) * 16 + (lane >> 2);
+            bool ok = m < M;
+            int mm = ok ? m : 0;
+            int n = mm / PQ, pq = mm % PQ;
+            int p = pq / s.Q, q = pq % s.Q;
+            int ih0 = p * s.stride - s.pad, iw0 = q * s.stride - s.pad;
+            a_off[j] = ((n * s.H + ih0) * s.W + iw0) * s.C * 2 + chunk * 16;
+            uint64_t mask = 0;
+            for (int rr = 0; rr < s.R; ++rr)
+                for (int tt = 0; tt < s.S; ++tt)
+                    if (ok && (unsigned)(ih0 + rr) < (unsigned)s.H && (unsigned)(iw0 + tt) < (unsigned)s.W)
+                        mask |= 1ull << (rr * s.S + tt);
+            a_mask[j] = mask;
+        }
+    }
+    // filter fragments of this wave: (wid * B_PER_WAVE + j) = nb * KS + ks
+    uint32_t b_off[B_PER_WAVE];
+#pragma unroll
+    for (int j = 0; j < B_PER_WAVE; ++j) {
+        int fb = wid * B_PER_WAVE + j;
+        b_off[j] = (uint32_t)((((n0 / 32 + fb / KS) * ks16_total + fb % KS) * FRAG + lane * 8) * 2);
+    }
+
+    int r = 0, t = 0, cb = 0, f_step = 0;
+    auto issue = [&](int stage) {
+        uint16_t* const st = lds + stage * STAGE;
+        const int rs = r * s.S + t;
+        const int32_t win = ((r * s.W + t) * s.C + cb * BK) * 2;
+#pragma unroll
+        for (int j = 0; j < A_PER_WAVE; ++j) {
+            uint32_t off = ((a_mask[j] >> rs) & 1ull) ? (uint32_t)(a_off[j] + win) : kOutOfRange;
+            // (the immediate offset of such a load would also shift the LDS destination: keep it 0)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rsrc, (lds_void*)(st + (wid * A_PER_WAVE + j) * FRAG), 16, off, 0, 0, 0);
+        }
+        const uint32_t wstep = (uint32_t)f_step * (KS * FRAG * 2);
+#pragma unroll
+        for (int j = 0; j < B_PER_WAVE; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rsrc, (lds_void*)(st + (FA + wid * B_PER_WAVE + j) * FRAG), 16, b_off[j],
+                                                     wstep, 0, 0);
+        if (f_step + 1 < nsteps) {
+            ++f_step;
+            if (++cb == cblocks) { cb = 0; if (++t == s.S) { t = 0; ++r; } }
+        }
+    };
+
+    f32x16 acc[MB][NB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // operand read: pixel row lane % 32 of a 32-row block, chunk 2 ks + lane / 32 -> element offset inside the
+    // two 1 KiB blocks; the chunk of ks = 1 is the one of ks = 0 with bit 1 flipped (32 bytes = 16 elements)
+    static_assert(KS == 2, "two 16-channel halves per step");
+    const int rd_row = lane & 31;
+    const int rd0 = (rd_row >> 4) * FRAG + ((rd_row & 15) * 4 + ((lane >> 5) ^ swz(rd_row & 15))) * 8;
+    auto compute = [&](int stage) {
+        const uint16_t* a_lds = lds + stage * STAGE + (wm * MB * 2) * FRAG;
+        const uint16_t* b_lds = lds + stage * STAGE + (FA + wn * NB * KS) * FRAG + lane * 8;
+        bf16x8 af[KS][MB], bfr[KS][NB];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+            for (int i = 0; i < MB; ++i) af[ks][i] = *(const bf16x8*)(a_lds + i * 2 * FRAG + (rd0 ^ (ks * 16)));
+#pragma unroll
+            for (int j = 0; j < NB; ++j) bfr[ks][j] = *(const bf16x8*)(b_lds + (j * KS + ks) * FRAG);
+        }
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int i = 0; i < MB; ++i)
+#pragma unroll
+                for (int j = 0; j < NB; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks][j], af[ks][i], acc[i][j], 0, 0, 0);
+    };
+
+    issue(0);
+    issue(1);
+    int stage_c = 0, stage_l = 2;
+    for (int u = 0; u < nsteps; ++u) {
+        wait_vmcnt<LOADS>();                 // step u has landed; step u + 1 may still be in flight
+        __builtin_amdgcn_s_barrier();
+        issue(stage_l);
+        compute(stage_c);
+        stage_c = stage_c == kStages - 1 ? 0 : stage_c + 1;
+        stage_l = stage_l == kStages - 1 ? 0 : stage_l + 1;
+    }
+    wait_vmcnt<0>();
+
+    const int frag_row = lane & 31;
+    const int f_hi = (lane >> 5) * 4;
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+        const int m = m0 + wm * WM + i * 32 + frag_row;
+        if (m >= M) continue;
+        const size_t orow = (size_t)m * s.K;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = n0 + wn * WN + j * 32 + 8 * g + f_hi;
+                const float4 bv = *(const float4*)(bias + n);
+                float v0 = acc[i][j][4 * g + 0] + bv.x, v1 = acc[i][j][4 * g + 1] + bv.y;
+                float v2 = acc[i][j][4 * g + 2] + bv.z, v3 = acc[i][j][4 * g + 3] + bv.w;
+                if (res) {
+                    uint2 rv = *(const uint2*)(res + orow + n);
+                    v0 += bf16_to_f32(rv.x & 0xFFFFu); v1 += bf16_to_f32(rv.x >> 16);
+                    v2 += bf16_to_f32(rv.y & 0xFFFFu); v3 += bf16_to_f32(rv.y >> 16);
+                }
+                uint2 o;
+                o.x = pack_bf16(act_fn(v0, s.act), act_fn(v1, s.act));
+                o.y = pack_bf16(act_fn(v2, s.act), act_fn(v3, s.act));
+                *(uint2*)(y + orow + n) = o;
+            }
+        }
+    }
+#endif
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+hipError_t launch_dma(const void* x, const void* wp, const float* bias, const void* res, void* y, const ConvShape& s,
+                      hipStream_t stream)
+{
+    long long M = (long long)s.N * s.P * s.Q;
+    int tiles_m = (int)((M + BM - 1) / BM), tiles_n = s.K / BN;
+    long long total = (long long)tiles_m * tiles_n;
+    if (total > 0x7FFFFFFFll) return hipErrorInvalidValue;
+    constexpr size_t kLdsBytes = 3 * (size_t)(BM + BN) * 32 * sizeof(uint16_t);
+    constexpr int kThreads = 64 * WAVES_M * WAVES_N;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute((const void*)conv_igemm_dma_kernel<BM, BN, WAVES_M, WAVES_N>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL((conv_igemm_dma_kernel<BM, BN, WAVES_M, WAVES_N>), dim3((unsigned)total), dim3(kThreads), kLdsBytes, stream,
+                       (const uint16_t*)x, (const uint16_t*)wp, bias, (const uint16_t*)res, (uint16_t*)y, s, (int)M, tiles_n);
+    return hipGetLastError();
+}
+
+
+// ---------------------------------------------------------------------------------------------------------------
+// 3x3, stride 1, pad 1: the activation slab is loaded ONCE per 32-channel block and shared by the nine window
+// positions.  Output pixels are numbered m = (n, p, q) flattened and, with "same" padding, input pixel (n, h, w) has
+// the same number; window position (r, s) of output pixel m reads input pixel m + (r-1) W + (s-1) whenever that
+// position is inside the image.  A tile of BM consecutive output pixels therefore needs the BM + 2W + 2 consecutive
+// input pixels starting at m0 - W - 1: they are DMA'd into LDS as 16-row blocks (same swizzle as above) while the
+// previous channel block is being computed, one block per wave and step.  Window positions outside the image are
+// redirected to a 64-byte row of zeros; every lane keeps its nine LDS addresses per 32-row block in registers, so the
+// inner loop has no address arithmetic beyond adding the slab buffer's base.  Filters: as above, three stages.
+// ---------------------------------------------------------------------------------------------------------------
+constexpr int kSlabMaxW = 56;
+
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+__global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_slab_kernel(const uint16_t* __restrict__ x,
+                                                                    const uint16_t* __restrict__ wp,
+                                                                    const float* __restrict__ bias,
+                                                                    const uint16_t* __restrict__ res,
+                                                                    uint16_t* __restrict__ y, ConvShape s, int M,
+                                                                    int tiles_n)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    constexpr int BK = 32, KS = 2, kTaps = 9;
+    constexpr int NW = WAVES_M * WAVES_N;
+    constexpr int WM = BM / WAVES_M, WN = BN / WAVES_N;
+    constexpr int MB = WM / 32, NB = WN / 32;
+    constexpr int FRAG = 512;                                             // elements per 1 KiB block
+    constexpr int SB_CAP = (BM + 2 * kSlabMaxW + 2 + 15) / 16;            // slab blocks per channel block (capacity)
+    static_assert(SB_CAP <= 8 * NW, "the slab must be complete one step before it is used");
+    constexpr int SLAB = SB_CAP * FRAG + 64;                              // + the row of zeros (32 elements) + padding
+    constexpr int ZERO_OFF = SB_CAP * FRAG;                               // elements, inside either slab buffer
+    constexpr int FB = BN / 32 * KS;
+    static_assert(FB % NW == 0, "every wave issues the same number of loads");
+    constexpr int B_PER_WAVE = FB / NW;
+    constexpr int B_STAGE = FB * FRAG;
+    constexpr int SPARE = 2 * SLAB;                                       // 1 KiB that absorbs the padding loads
+    constexpr int B_BASE = SPARE + FRAG;
+
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // 2 slabs | spare block | 3 filter stages
+
+    int tile;
+    {
+        int L = blockIdx.x, total = gridDim.x;
+        int xcd = L % kXcds, slot = L / kXcds;
+        int base = total / kXcds, rem = total % kXcds;
+        tile = xcd * base + (xcd < rem ? xcd : rem) + slot;
+    }
+    const int tile_n = tile % tiles_n, tile_m = tile / tiles_n;
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int tid = threadIdx.x, lane = tid & 63, wid = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wid / WAVES_N, wn = wid % WAVES_N;
+    const int W = s.W, H = s.H;
+    const int cblocks = s.C / BK;
+    const int ks16_total = kTaps * cblocks * KS;
+    const int total_px = s.N * H * W;
+    const int slab_rows = BM + 2 * W + 2;
+
+    const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(x, (uint32_t)total_px * (uint32_t)s.C * 2u);
+    const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(wp, (uint32_t)s.K * (uint32_t)(kTaps * s.C) * 2u);
+
+    auto swz = [](int r16) { return ((r16 >> 1) & 3) ^ (r16 >> 3); };
+
+    // the rows of zeros
+    if (tid < 8) {
+        *(u32x4*)(lds + ZERO_OFF + (tid & 3) * 8 + (tid >> 2) * SLAB) = u32x4{0u, 0u, 0u, 0u};
+    }
+    __syncthreads();
+
+    // operand addresses (elements, relative to a slab buffer) of this lane's pixel rows for the nine positions
+    int32_t a_addr[MB][kTaps];
+    {
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            const int ml = wm * WM + i * 32 + (lane & 31);
+            const int m = m0 + ml;
+            const bool ok = m < M;
+            const int mm = ok ? m : 0;
+            const int pq = mm % (H * W);
+            const int p = pq / W, q = pq % W;
+#pragma unroll
+            for (int rr = 0; rr < 3; ++rr)
+#pragma unroll
+                for (int tt = 0; tt < 3; ++tt) {
+                    const bool in = ok && (unsigned)(p + rr - 1) < (unsigned)H && (unsigned)(q + tt - 1) < (unsigned)W;
+                    const int rho = ml + (W + 1) + (rr - 1) * W + (tt - 1);
+                    const int r16 = rho & 15;
+                    const int a = (rho >> 4) * FRAG + (r16 * 4 + ((lane >> 5) ^ swz(r16))) * 8;
+                    a_addr[i][rr * 3 + tt] = in ? a : ZERO_OFF + (lane >> 5) * 8;
+                }
+        }
+    }
+    // slab loader: row lane / 4 of a block, chunk chosen by the slot this lane fills
+    const int ld_row = lane >> 2;
+    const int ld_chunk = (lane & 3) ^ swz(ld_row);
+    const int g_base = m0 - (W + 1) + ld_row;                 // input pixel of slab row ld_row
+    auto issue_slab = [&](int cb, int tap, int parity) {
+        const int sb = tap * NW + wid;                        // wave-uniform
+        const int rho = sb * 16 + ld_row;
+        const int g = g_base + sb * 16;
+        const bool ok = sb < SB_CAP && cb < cblocks && rho < slab_rows && (unsigned)g < (unsigned)total_px;
+        const uint32_t off = ok ? (uint32_t)((g * s.C + cb * BK + ld_chunk * 8) * 2) : kOutOfRange;
+        uint16_t* dst = sb < SB_CAP ? lds + parity * SLAB + sb * FRAG : lds + SPARE;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(x_rsrc, (lds_void*)dst, 16, off, 0, 0, 0);
+    };
+    uint32_t b_off[B_PER_WAVE];
+#pragma unroll
+    for (int j = 0; j < B_PER_WAVE; ++j) {
+        int fb = wid * B_PER_WAVE + j;
+        b_off[j] = (uint32_t)((((n0 / 32 + fb / KS) * ks16_total + fb % KS) * FRAG + lane * 8) * 2);
+    }
+    auto issue_b = [&](int cb, int tap, int stage) {
+        if (cb >= cblocks) { cb = cblocks - 1; tap = kTaps - 1; }          // past the end: re-read the last step
+        const uint32_t wstep = (uint32_t)((tap * cblocks + cb) * KS) * (FRAG * 2);
+#pragma unroll
+        for (int j = 0; j < B_PER_WAVE; ++j)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(w_rsrc, (lds_void*)(lds + B_BASE + stage * B_STAGE + (wid * B_PER_WAVE + j) * FRAG),
+                                                     16, b_off[j], wstep, 0, 0);
+    };
+
+    f32x16 acc[MB][NB];
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
+
+    // prologue: the whole first slab, then filters of steps 0 and 1 with one padding load between them so that the
+    // order of outstanding loads is the steady-state one (slab piece, filters, slab piece, filters)
+#pragma unroll
+    for (int t = 0; t < (SB_CAP + NW - 1) / NW; ++t) issue_slab(0, t, 0);
+    issue_b(0, 0, 0);
+    issue_slab(cblocks, 8, 0);                                              // lands in the spare block
+    issue_b(0, 1, 1);
+
+    for (int cb = 0; cb < cblocks; ++cb) {
+        const uint16_t* slab = lds + (cb & 1) * SLAB;
+#pragma unroll
+        for (int tap = 0; tap < kTaps; ++tap) {
+            wait_vmcnt<1 + B_PER_WAVE>();       // everything up to this step's filters has landed
+            __builtin_amdgcn_s_barrier();
+            issue_slab(cb + 1, tap, (cb + 1) & 1);
+            issue_b(tap + 2 < kTaps ? cb : cb + 1, (tap + 2) % kTaps, (tap + 2) % 3);
+            const uint16_t* b_lds = lds + B_BASE + (tap % 3) * B_STAGE + (wn * NB * KS) * FRAG + lane * 8;
+            bf16x8 af[KS][MB], bfr[KS][NB];
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+                for (int i = 0; i < MB; ++i) af[ks][i] = *(const bf16x8*)(slab + (a_addr[i][tap] ^ (ks * 16)));
+#pragma unroll
+                for (int j = 0; j < NB; ++j) bfr[ks][j] = *(const bf16x8*)(b_lds + (j * KS + ks) * FRAG);
+            }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int i = 0; i < MB; ++i)
+#pragma unroll
+                    for (int j = 0; j < NB; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks][j], af[ks][i], acc[i][j], 0, 0, 0);
+        }
+    }
+    wait_vmcnt<0>();
+
+    const int frag_row = lane & 31;
+    const int f_hi = (lane >> 5) * 4;
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+        const int m = m0 + wm * WM + i * 32 + frag_row;
+        if (m >= M) continue;
+        const size_t orow = (size_t)m * s.K;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int n = n0 + wn * WN + j * 32 + 8 * g + f_hi;
+                const float4 bv = *(const float4*)(bias + n);
+                float v0 = acc[i][j][4 * g + 0] + bv.x, v1 = acc[i][j][4 * g + 1] + bv.y;
+                float v2 = acc[i][j][4 * g + 2] + bv.z, v3 = acc[i][j][4 * g + 3] + bv.w;
+                if (res) {
+                    uint2 rv = *(const uint2*)(res + orow + n);
+                    v0 += bf16_to_f32(rv.x & 0xFFFFu); v1 += bf16_to_f32(rv.x >> 16);
+                    v2 += bf16_to_f32(rv.y & 0xFFFFu); v3 += bf16_to_f32(rv.y >> 16);
+                }
+                uint2 o;
+                o.x = pack_bf16(act_fn(v0, s.act), act_fn(v1, s.act));
+                o.y = pack_bf16(act_fn(v2, s.act), act_fn(v3, s.act));
+                *(uint2*)(y + orow + n) = o;
+            }
+        }
+    }
+#endif
+}
+
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+hipError_t launch_slab(const void* x, const void* wp, const float* bias, const void* res, void* y, const ConvShape& s,
+                       hipStream_t stream)
+{
+    long long M = (long long)s.N * s.P * s.Q;
+    int tiles_m = (int)((M + BM - 1) / BM), tiles_n = s.K / BN;
+    long long total = (long long)tiles_m * tiles_n;
+    if (total > 0x7FFFFFFFll) return hipErrorInvalidValue;
+    constexpr int kSbCap = (BM + 2 * kSlabMaxW + 2 + 15) / 16;
+    constexpr size_t kLdsBytes = (2 * (size_t)(kSbCap * 512 + 64) + 512 + 3 * (size_t)BN * 32) * sizeof(uint16_t);
+    constexpr int kThreads = 64 * WAVES_M * WAVES_N;
+    static bool configured = false;
+    if (!configured) {
+        hipError_t e = hipFuncSetAttribute((const void*)conv3x3_slab_kernel<BM, BN, WAVES_M, WAVES_N>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
+        if (e != hipSuccess) return e;
+        configured = true;
+    }
+    hipLaunchKernelGGL((conv3x3_slab_kernel<BM, BN, WAVES_M, WAVES_N>), dim3((unsigned)total), dim3(kThreads), kLdsBytes, stream,
+                       (const uint16_t*)x, (const uint16_t*)wp, bias, (const uint16_t*)res, (uint16_t*)y, s, (int)M, tiles_n);
+    return hipGetLastError();
+}
+
+bool slab_supported(const ConvShape& s)
+{
+    return s.R == 3 && s.S == 3 && s.stride == 1 && s.pad == 1 && s.W <= kSlabMaxW && s.C % 32 == 0 && s.K % 64 == 0;
+}
+
 template <int BK>
 hipError_t pick_tile(const void* x, const void* wp, const float* bias, const void* res, void* y, const ConvShape& s,
                      hipStream_t stream)
@@ -339,6 +779,22 @@ hipError_t conv_mfma(const void* x, const void* wp, const float* bias, const voi
         return hipErrorInvalidValue;
     // 32-channel steps everywhere: measured equal or better than 64-channel steps on every ResNet layer shape
     // (smaller register stages -> three workgroups per compute unit instead of two)
+#ifndef SLAB_TILE
+#define SLAB_TILE 1
+#endif
+    if (slab_supported(s)) {
+#if SLAB_TILE == 1
+        if (s.K % 128 == 0) return launch_slab<256, 128, 2, 2>(x, wp, bias, res, y, s, stream);
+        return launch_slab<256, 64, 4, 1>(x, wp, bias, res, y, s, stream);
+#elif SLAB_TILE == 2
+        if (s.K % 128 == 0) return launch_slab<128, 128, 2, 2>(x, wp, bias, res, y, s, stream);
+        return launch_slab<128, 64, 4, 1>(x, wp, bias, res, y, s, stream);
+#endif
+    }
+    // 128-row tiles: three workgroups per compute unit; measured ahead of 256-row tiles on the ResNet layer shapes
+    if (s.K % 128 == 0) return launch_dma<128, 128, 2, 2>(x, wp, bias, res, y, s, stream);
+    if (s.K % 64 == 0) return launch_dma<128, 64, 2, 2>(x, wp, bias, res, y, s, stream);
+    // filter counts that are not a multiple of 64: the register-staged kernel
     return pick_tile<32>(x, wp, bias, res, y, s, stream);
 }
 
