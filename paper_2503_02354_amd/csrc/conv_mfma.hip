@@ -316,6 +316,53 @@ hipError_t launch(const void* x, const void* wp, const float* bias, const void* 
 // ---------------------------------------------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) void lds_void;
 
+// Epilogue of the direct-to-LDS kernels: + bias (+ residual), activation, round to bf16 in the accumulator layout (a
+// lane holds 4 consecutive channels of one pixel per accumulator quad), then through a wave-private LDS buffer of
+// 32 rows so that the global stores are 16 bytes per lane and cover whole rows of the wave tile (full cache lines
+// instead of 8-byte pieces of 32 different lines per instruction).
+template <int MB, int NB>
+__device__ __forceinline__ void store_tile_via_lds(f32x16 (&acc)[MB][NB], uint16_t* stage, const float* __restrict__ bias,
+                                                   const uint16_t* __restrict__ res, uint16_t* __restrict__ y, int m_wave,
+                                                   int n_wave, int M, int K, int act, int lane)
+{
+    constexpr int WN = NB * 32, ROW = WN + 8;             // elements; 16 bytes of padding per staged row
+    constexpr int CPR = WN / 8;                            // 16-byte chunks per row
+    const int frag_row = lane & 31, f_hi = (lane >> 5) * 4;
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+        const int m = m_wave + i * 32 + frag_row;
+        const size_t orow = (size_t)(m < M ? m : 0) * K;
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int nl = j * 32 + 8 * g + f_hi;
+                const float4 bv = *(const float4*)(bias + n_wave + nl);
+                float v0 = acc[i][j][4 * g + 0] + bv.x, v1 = acc[i][j][4 * g + 1] + bv.y;
+                float v2 = acc[i][j][4 * g + 2] + bv.z, v3 = acc[i][j][4 * g + 3] + bv.w;
+                if (res && m < M) {
+                    uint2 rv = *(const uint2*)(res + orow + n_wave + nl);
+                    v0 += bf16_to_f32(rv.x & 0xFFFFu); v1 += bf16_to_f32(rv.x >> 16);
+                    v2 += bf16_to_f32(rv.y & 0xFFFFu); v3 += bf16_to_f32(rv.y >> 16);
+                }
+                uint2 o;
+                o.x = pack_bf16(act_fn(v0, act), act_fn(v1, act));
+                o.y = pack_bf16(act_fn(v2, act), act_fn(v3, act));
+                *(uint2*)(stage + frag_row * ROW + nl) = o;
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < 32 * CPR / 64; ++t) {
+            const int idx = lane + 64 * t;
+            const int row = idx / CPR, ch = idx % CPR;
+            const int mo = m_wave + i * 32 + row;
+            const u32x4 v = *(const u32x4*)(stage + row * ROW + ch * 8);
+            if (mo < M) *(u32x4*)(y + (size_t)mo * K + n_wave + ch * 8) = v;
+        }
+    }
+}
+
+
 template <int N> __device__ __forceinline__ void wait_vmcnt()
 {
     // s_waitcnt with only the vector-memory counter armed (expcnt and lgkmcnt fields at their maxima)
@@ -465,33 +512,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv_igemm_dma_kern
     }
     wait_vmcnt<0>();
 
-    const int frag_row = lane & 31;
-    const int f_hi = (lane >> 5) * 4;
-#pragma unroll
-    for (int i = 0; i < MB; ++i) {
-        const int m = m0 + wm * WM + i * 32 + frag_row;
-        if (m >= M) continue;
-        const size_t orow = (size_t)m * s.K;
-#pragma unroll
-        for (int j = 0; j < NB; ++j) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n = n0 + wn * WN + j * 32 + 8 * g + f_hi;
-                const float4 bv = *(const float4*)(bias + n);
-                float v0 = acc[i][j][4 * g + 0] + bv.x, v1 = acc[i][j][4 * g + 1] + bv.y;
-                float v2 = acc[i][j][4 * g + 2] + bv.z, v3 = acc[i][j][4 * g + 3] + bv.w;
-                if (res) {
-                    uint2 rv = *(const uint2*)(res + orow + n);
-                    v0 += bf16_to_f32(rv.x & 0xFFFFu); v1 += bf16_to_f32(rv.x >> 16);
-                    v2 += bf16_to_f32(rv.y & 0xFFFFu); v3 += bf16_to_f32(rv.y >> 16);
-                }
-                uint2 o;
-                o.x = pack_bf16(act_fn(v0, s.act), act_fn(v1, s.act));
-                o.y = pack_bf16(act_fn(v2, s.act), act_fn(v3, s.act));
-                *(uint2*)(y + orow + n) = o;
-            }
-        }
-    }
+    __builtin_amdgcn_s_barrier();        // every wave is done with the operand stages: LDS is free for the epilogue
+    store_tile_via_lds<MB, NB>(acc, lds + wid * (32 * (WN + 8)), bias, res, y, m0 + wm * WM, n0 + wn * WN, M, s.K, s.act, lane);
 #endif
 }
 
@@ -680,33 +702,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_slab_kernel
     }
     wait_vmcnt<0>();
 
-    const int frag_row = lane & 31;
-    const int f_hi = (lane >> 5) * 4;
-#pragma unroll
-    for (int i = 0; i < MB; ++i) {
-        const int m = m0 + wm * WM + i * 32 + frag_row;
-        if (m >= M) continue;
-        const size_t orow = (size_t)m * s.K;
-#pragma unroll
-        for (int j = 0; j < NB; ++j) {
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int n = n0 + wn * WN + j * 32 + 8 * g + f_hi;
-                const float4 bv = *(const float4*)(bias + n);
-                float v0 = acc[i][j][4 * g + 0] + bv.x, v1 = acc[i][j][4 * g + 1] + bv.y;
-                float v2 = acc[i][j][4 * g + 2] + bv.z, v3 = acc[i][j][4 * g + 3] + bv.w;
-                if (res) {
-                    uint2 rv = *(const uint2*)(res + orow + n);
-                    v0 += bf16_to_f32(rv.x & 0xFFFFu); v1 += bf16_to_f32(rv.x >> 16);
-                    v2 += bf16_to_f32(rv.y & 0xFFFFu); v3 += bf16_to_f32(rv.y >> 16);
-                }
-                uint2 o;
-                o.x = pack_bf16(act_fn(v0, s.act), act_fn(v1, s.act));
-                o.y = pack_bf16(act_fn(v2, s.act), act_fn(v3, s.act));
-                *(uint2*)(y + orow + n) = o;
-            }
-        }
-    }
+    __builtin_amdgcn_s_barrier();        // every wave is done with the operand stages: LDS is free for the epilogue
+    store_tile_via_lds<MB, NB>(acc, lds + wid * (32 * (WN + 8)), bias, res, y, m0 + wm * WM, n0 + wn * WN, M, s.K, s.act, lane);
 #endif
 }
 
