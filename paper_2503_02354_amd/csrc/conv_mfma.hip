@@ -319,7 +319,8 @@ typedef __attribute__((address_space(3))) void lds_void;
 // Epilogue of the direct-to-LDS kernels: + bias (+ residual), activation, round to bf16 in the accumulator layout (a
 // lane holds 4 consecutive channels of one pixel per accumulator quad), then through a wave-private LDS buffer of
 // 32 rows so that the global stores are 16 bytes per lane and cover whole rows of the wave tile (full cache lines
-// instead of 8-byte pieces of 32 different lines per instruction).
+// instead of 8-byte pieces of 32 different lines per instruction).  LDS operations of one wave execute in program
+// order, so the wave-private buffer needs no barrier between its writes and reads.
 template <int MB, int NB>
 __device__ __forceinline__ void store_tile_via_lds(f32x16 (&acc)[MB][NB], uint16_t* stage, const float* __restrict__ bias,
                                                    const uint16_t* __restrict__ res, uint16_t* __restrict__ y, int m_wave,
@@ -327,32 +328,52 @@ __device__ __forceinline__ void store_tile_via_lds(f32x16 (&acc)[MB][NB], uint16
 {
     constexpr int WN = NB * 32, ROW = WN + 8;             // elements; 16 bytes of padding per staged row
     constexpr int CPR = WN / 8;                            // 16-byte chunks per row
+    constexpr int T = 32 * CPR / 64;                       // chunks per lane and 32-row block
     const int frag_row = lane & 31, f_hi = (lane >> 5) * 4;
+    // the residual takes the same road in the other direction: row-contiguous 16-byte loads (all issued up front),
+    // staged in LDS, picked up in the accumulator layout
+    u32x4 rres[MB][T];
+    if (res) {
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const int idx = lane + 64 * t;
+                const int mo = m_wave + i * 32 + idx / CPR;
+                rres[i][t] = mo < M ? *(const u32x4*)(res + (size_t)mo * K + n_wave + (idx % CPR) * 8) : u32x4{0u, 0u, 0u, 0u};
+            }
+    }
 #pragma unroll
     for (int i = 0; i < MB; ++i) {
-        const int m = m_wave + i * 32 + frag_row;
-        const size_t orow = (size_t)(m < M ? m : 0) * K;
+        if (res) {
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const int idx = lane + 64 * t;
+                *(u32x4*)(stage + (idx / CPR) * ROW + (idx % CPR) * 8) = rres[i][t];
+            }
+        }
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int nl = j * 32 + 8 * g + f_hi;
+                uint2* cell = (uint2*)(stage + frag_row * ROW + nl);
                 const float4 bv = *(const float4*)(bias + n_wave + nl);
                 float v0 = acc[i][j][4 * g + 0] + bv.x, v1 = acc[i][j][4 * g + 1] + bv.y;
                 float v2 = acc[i][j][4 * g + 2] + bv.z, v3 = acc[i][j][4 * g + 3] + bv.w;
-                if (res && m < M) {
-                    uint2 rv = *(const uint2*)(res + orow + n_wave + nl);
+                if (res) {
+                    const uint2 rv = *cell;
                     v0 += bf16_to_f32(rv.x & 0xFFFFu); v1 += bf16_to_f32(rv.x >> 16);
                     v2 += bf16_to_f32(rv.y & 0xFFFFu); v3 += bf16_to_f32(rv.y >> 16);
                 }
                 uint2 o;
                 o.x = pack_bf16(act_fn(v0, act), act_fn(v1, act));
                 o.y = pack_bf16(act_fn(v2, act), act_fn(v3, act));
-                *(uint2*)(stage + frag_row * ROW + nl) = o;
+                *cell = o;
             }
         }
 #pragma unroll
-        for (int t = 0; t < 32 * CPR / 64; ++t) {
+        for (int t = 0; t < T; ++t) {
             const int idx = lane + 64 * t;
             const int row = idx / CPR, ch = idx % CPR;
             const int mo = m_wave + i * 32 + row;
@@ -361,7 +382,6 @@ __device__ __forceinline__ void store_tile_via_lds(f32x16 (&acc)[MB][NB], uint16
         }
     }
 }
-
 
 template <int N> __device__ __forceinline__ void wait_vmcnt()
 {
