@@ -35,6 +35,9 @@ def main():
     ap.add_argument("--max-batch", type=int, default=512)
     ap.add_argument("--cpu-sample", type=int, default=384, help="requests the oracle is timed on (0 = skip)")
     ap.add_argument("--no-profile", action="store_true", help="do not time kernel classes with events")
+    ap.add_argument("--profile-every", type=int, default=7,
+                    help="time every k-th launch of each kernel class (an event pair costs a pipeline bubble; 7 is coprime "
+                         "to the launches per forward, so every layer shape is sampled)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py runs on exactly one GPU: this build has no multi-GPU path (--gpus 1 only)", file=sys.stderr)
@@ -55,7 +58,7 @@ def main():
     x = wl.inputs(range(n))
     t_gen = time.time() - t0
 
-    ctx = B.Context(max_requests=n, max_stages=wl.max_stages, max_batch=args.max_batch, profile=not args.no_profile)
+    ctx = B.Context(max_requests=n, max_stages=wl.max_stages, max_batch=args.max_batch, profile=0 if args.no_profile else args.profile_every)
     B.setup_workload(ctx, wl, blobs)
     dev = torch.from_numpy(x.view(np.int16)).cuda()
     torch.cuda.synchronize()
@@ -79,6 +82,7 @@ def main():
     ctx.coe_sync()
     for k in range(len(B.KERNEL_CLASS_NAMES)):
         ctx.coe_profile_read(k)            # drop warm-up spans
+        ctx.coe_profile_issued(k)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(args.steps):
@@ -93,8 +97,9 @@ def main():
     if not args.no_profile:
         for k, name in enumerate(B.KERNEL_CLASS_NAMES):
             launches, ms, work = ctx.coe_profile_read(k)
+            issued = ctx.coe_profile_issued(k)
             if launches:
-                prof[name] = {"launches": launches, "ms": round(ms, 3), "work": work}
+                prof[name] = {"launches": launches, "ms": round(ms, 3), "work": work, "issued": issued}
     flops_per_step = 2.0 * sum(W.arch_macs(wl.archs[wl.expert_arch[0]]) for _ in range(wl.max_stages)) * n
     roofline = None
     if "conv_mfma" in prof:
@@ -102,12 +107,15 @@ def main():
         achieved = p["work"] / (p["ms"] * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": "conv_igemm_bf16_kernel", "achieved": round(achieved, 2),
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "traffic": None, "launches": p["launches"], "avg_launch_us": round(p["ms"] * 1e3 / p["launches"], 2)}
+                    "traffic": None, "launches_timed": p["launches"], "launches": p["issued"],
+                    "avg_launch_us": round(p["ms"] * 1e3 / p["launches"], 2)}
     other = {}
     for name in ("regroup_gather", "switch", "pool", "conv_stem", "conv_direct", "head", "regroup_index"):
         if name in prof:
             p = prof[name]
-            entry = {"ms_per_step": round(p["ms"] / args.steps, 3), "launches_per_step": p["launches"] // max(args.steps, 1)}
+            # timed launches are every k-th of the class: scale their mean to all launches
+            entry = {"ms_per_step": round(p["ms"] / p["launches"] * p["issued"] / args.steps, 3),
+                     "launches_per_step": p["issued"] // max(args.steps, 1)}
             if name in ("regroup_gather", "pool", "switch"):
                 entry["GB/s"] = round(p["work"] / (p["ms"] * 1e-3) / 1e9, 1) if p["ms"] > 0 else None
             if name in ("conv_direct", "conv_stem"):

@@ -79,7 +79,8 @@ typedef struct {
                                   paper Section 4.2 "Request splitting" */
     int32_t max_stages;        /* longest path through the dependency graph that is recorded per request */
     int32_t cache_cap_experts; /* device expert cache: at most this many resident experts (0 = no limit) */
-    int32_t profile;           /* nonzero: time every kernel class with events (see coe_profile_read) */
+    int32_t profile;           /* k > 0: time every k-th launch of each kernel class with events (1 = all; see
+                                * coe_profile_read); 0: no events */
     int64_t cache_cap_bytes;   /* and at most this many bytes of expert weights (0 = no limit) */
     void* compute_stream;      /* borrowed hipStream_t for kernels, or NULL: the library creates one */
     void* copy_stream;         /* borrowed hipStream_t for expert switches, or NULL: the library creates one */
@@ -177,9 +178,11 @@ int coe_debug_regroup(coe_ctx* ctx, int32_t n, const int32_t* cur, int32_t n_exp
 /* Kernel classes timed when cfg.profile != 0. */
 enum { COE_K_REGROUP_INDEX = 0, COE_K_REGROUP_GATHER = 1, COE_K_CONV_MFMA = 2, COE_K_CONV_DIRECT = 3, COE_K_POOL = 4,
        COE_K_HEAD = 5, COE_K_SWITCH = 6, COE_K_CONV_STEM = 7, COE_K_ATTENTION = 8, COE_K_TOKEN_OPS = 9, COE_K_COUNT = 10 };
-/* Synchronises, then returns and clears the accumulated launches, milliseconds and algorithmic work of a class
+/* Synchronises, then returns and clears the accumulated TIMED launches, their milliseconds and algorithmic work of a class
  * (flops for the conv and attention classes, bytes for the others). */
 int coe_profile_read(coe_ctx* ctx, int32_t kernel_class, int64_t* launches, double* ms, double* work);
+/* Returns and clears the number of launches of a class since the last call, timed or not (cfg.profile != 0). */
+int coe_profile_issued(coe_ctx* ctx, int32_t kernel_class, int64_t* issued);
 
 /* ---- host-only pieces (no GPU needed) -------------------------------------------------------------------------- */
 /* Graph check used by coe_set_dependency_graph.  n_classes: [n_experts] or NULL (skip the route-count check). */

@@ -23,7 +23,7 @@ EXPORTS = [
     "coe_create", "coe_destroy", "coe_last_error", "coe_register_arch", "coe_arch_blob_bytes", "coe_register_expert",
     "coe_set_dependency_graph", "coe_submit", "coe_step", "coe_sync", "coe_collect", "coe_reset_requests",
     "coe_debug_last_regroup", "coe_debug_switch_log", "coe_debug_resident", "coe_debug_forward", "coe_debug_layer_output", "coe_debug_regroup", "coe_debug_conv",
-    "coe_profile_read", "coe_validate_graph", "coe_policy_create", "coe_policy_destroy", "coe_policy_init_fill",
+    "coe_profile_read", "coe_profile_issued", "coe_validate_graph", "coe_policy_create", "coe_policy_destroy", "coe_policy_init_fill",
     "coe_policy_stage", "coe_policy_resident",
 ]
 
@@ -75,6 +75,7 @@ def _load():
     L.coe_debug_regroup.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp]
     L.coe_debug_conv.argtypes = [vp, i32, vp, vp, vp, vp, vp] + [i32] * 11 + [C.POINTER(i32)]
     L.coe_profile_read.argtypes = [vp, i32, C.POINTER(i64), C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    L.coe_profile_issued.argtypes = [vp, i32, C.POINTER(i64)]
     L.coe_validate_graph.argtypes = [i32, vp, vp, vp]
     L.coe_policy_create.argtypes = [i32, vp, vp, vp, vp, i32, i64]; L.coe_policy_create.restype = vp
     L.coe_policy_destroy.argtypes = [vp]; L.coe_policy_destroy.restype = None
@@ -163,7 +164,7 @@ class Context:
     def __init__(self, max_requests: int, max_stages: int = 2, max_batch: int = 0, cache_cap_experts: int = 0,
                  cache_cap_bytes: int = 0, device: int = 0, profile: bool = False, compute_stream: int = 0,
                  copy_stream: int = 0):
-        cfg = coe_config(device, max_requests, max_batch, max_stages, cache_cap_experts, 1 if profile else 0, cache_cap_bytes,
+        cfg = coe_config(device, max_requests, max_batch, max_stages, cache_cap_experts, int(profile), cache_cap_bytes,
                          compute_stream or None, copy_stream or None)
         h = C.c_void_p()
         rc = lib.coe_create(C.byref(cfg), C.byref(h))
@@ -301,6 +302,11 @@ class Context:
         n = C.c_int64(0); ms = C.c_double(0); work = C.c_double(0)
         self._chk(lib.coe_profile_read(self._h, kernel_class, C.byref(n), C.byref(ms), C.byref(work)))
         return n.value, ms.value, work.value
+
+    def coe_profile_issued(self, kernel_class: int) -> int:
+        n = C.c_int64(0)
+        self._chk(lib.coe_profile_issued(self._h, kernel_class, C.byref(n)))
+        return n.value
 
 
 def setup_workload(ctx: Context, wl, blobs: Optional[Sequence[np.ndarray]] = None):

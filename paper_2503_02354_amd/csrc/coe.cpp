@@ -63,8 +63,9 @@ struct Expert {
 };
 
 struct ProfClass {
-    std::vector<std::pair<hipEvent_t, hipEvent_t>> spans;
-    double work = 0.0;
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> spans;   // the timed launches
+    double work = 0.0;                                       // their algorithmic work
+    int64_t issued = 0;                                      // all launches of the class, timed or not
 };
 
 }  // namespace
@@ -138,6 +139,9 @@ struct Span {
     Span(coe_ctx* ctx, int kernel_class, double work, hipStream_t stream) : c(ctx), cls(kernel_class), s(stream)
     {
         if (!c->cfg.profile) return;
+        // cfg.profile = k > 1 times every k-th launch of a class: an event pair costs a few microseconds of
+        // pipeline bubble, which adds up over hundreds of launches per step
+        if (c->prof[cls].issued++ % c->cfg.profile) return;
         hipEvent_t e0 = take();
         e1 = take();
         if (!e0 || !e1) { e1 = nullptr; return; }
@@ -1042,6 +1046,14 @@ int coe_profile_read(coe_ctx* c, int32_t cls, int64_t* launches, double* ms, dou
     if (work) *work = p.work;
     p.spans.clear();
     p.work = 0.0;
+    return COE_OK;
+}
+
+int coe_profile_issued(coe_ctx* c, int32_t cls, int64_t* issued)
+{
+    if (!c || !issued || cls < 0 || cls >= COE_K_COUNT) return COE_EINVAL;
+    *issued = c->prof[cls].issued;
+    c->prof[cls].issued = 0;
     return COE_OK;
 }
 

@@ -27,6 +27,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kThreads = 256;
 constexpr int kTile = 16;        // conv-output tile is kTile x kTile pixels = 256 GEMM rows, 64 per wavefront
@@ -146,11 +147,13 @@ __global__ __launch_bounds__(kThreads) void conv_smallc_bf16_kernel(const uint16
             int ml = wid * 64 + i * 32 + l32;
             a_off[i] = (ml / kTile) * s.stride * g.patch_stride + (ml % kTile) * s.stride * s.C;
         }
+        int kr = half / g.cpr, kpart = half % g.cpr;              // window row and chunk inside it of this lane's chunk
         for (int j = 0; j < g.ksteps; ++j) {
-            int chunk = 2 * j + half;
-            int r = chunk / g.cpr, part = chunk % g.cpr;
-            if (r >= s.R) { r = s.R - 1; }                         // padded step: filters are zero, any finite data will do
-            const int koff = r * g.patch_stride + part * 8;
+            const int chunk = 2 * j + half;
+            const int r = kr < s.R ? kr : s.R - 1;                 // padded step: filters are zero, any finite data will do
+            const int koff = r * g.patch_stride + kpart * 8;
+            kpart += 2;                                            // next step: two chunks on, without a division
+            while (kpart >= g.cpr) { kpart -= g.cpr; ++kr; }
             bf16x8 af[2], bfr[NB];
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
@@ -185,7 +188,8 @@ __global__ __launch_bounds__(kThreads) void conv_smallc_bf16_kernel(const uint16
                     o.x = pack_bf16(act_fn(acc[i][jn][4 * gq + 0] + bv.x, s.act), act_fn(acc[i][jn][4 * gq + 1] + bv.y, s.act));
                     o.y = pack_bf16(act_fn(acc[i][jn][4 * gq + 2] + bv.z, s.act), act_fn(acc[i][jn][4 * gq + 3] + bv.w, s.act));
                     if (POOL) {
-                        if (!inside) o = make_uint2(0xFF80FF80u, 0xFF80FF80u);      // -inf: never wins the max
+                        // outside the conv output: -inf (or 0 after ReLU, see the pool below) never wins the max
+                        if (!inside) o = s.act == 1 ? make_uint2(0u, 0u) : make_uint2(0xFF80FF80u, 0xFF80FF80u);
                         *(uint2*)(otile + ml * OUT_STRIDE + ch) = o;
                     } else if (inside) {
                         *(uint2*)(y + (((size_t)n * s.P + p) * s.Q + q) * K + ch) = o;
@@ -200,6 +204,27 @@ __global__ __launch_bounds__(kThreads) void conv_smallc_bf16_kernel(const uint16
                 const int a = pix / kPoolTile, b = pix % kPoolTile;
                 const int pi = tp * kPoolTile + a, pj = tq * kPoolTile + b;
                 if (pi >= g.PP || pj >= g.PQ) continue;
+                if (s.act == 1) {
+                    // after ReLU every value is >= +0, and non-negative bf16 order like their bit patterns: the max is
+                    // a packed 16-bit integer max, two channels per instruction (tile pixels outside the conv output
+                    // hold 0 here, which never beats a real value)
+                    u16x2 m[4] = {u16x2{0, 0}, u16x2{0, 0}, u16x2{0, 0}, u16x2{0, 0}};
+#pragma unroll
+                    for (int dr = 0; dr < 3; ++dr)
+#pragma unroll
+                        for (int dc = 0; dc < 3; ++dc) {
+                            const uint4 v = *(const uint4*)(otile + ((2 * a + dr) * kTile + 2 * b + dc) * OUT_STRIDE + c8 * 8);
+                            m[0] = __builtin_elementwise_max(m[0], __builtin_bit_cast(u16x2, v.x));
+                            m[1] = __builtin_elementwise_max(m[1], __builtin_bit_cast(u16x2, v.y));
+                            m[2] = __builtin_elementwise_max(m[2], __builtin_bit_cast(u16x2, v.z));
+                            m[3] = __builtin_elementwise_max(m[3], __builtin_bit_cast(u16x2, v.w));
+                        }
+                    uint4 o;
+                    o.x = __builtin_bit_cast(uint32_t, m[0]); o.y = __builtin_bit_cast(uint32_t, m[1]);
+                    o.z = __builtin_bit_cast(uint32_t, m[2]); o.w = __builtin_bit_cast(uint32_t, m[3]);
+                    *(uint4*)(y + (((size_t)n * g.PP + pi) * g.PQ + pj) * K + c8 * 8) = o;
+                    continue;
+                }
                 float best[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) best[e] = -INFINITY;
