@@ -101,16 +101,21 @@ def main():
             if launches:
                 prof[name] = {"launches": launches, "ms": round(ms, 3), "work": work, "issued": issued}
     flops_per_step = 2.0 * sum(W.arch_macs(wl.archs[wl.expert_arch[0]]) for _ in range(wl.max_stages)) * n
+    # the matrix-core convolution classes; the roofline object is for the one that takes the most time
+    mfma_kernels = {"conv_slab": "conv3x3_slab_kernel", "conv_mfma": "conv_igemm_dma_kernel"}
+    est_ms = {name: prof[name]["ms"] / prof[name]["launches"] * prof[name]["issued"] for name in mfma_kernels if name in prof}
     roofline = None
-    if "conv_mfma" in prof:
-        p = prof["conv_mfma"]
+    if est_ms:
+        dom = max(est_ms, key=est_ms.get)
+        p = prof[dom]
         achieved = p["work"] / (p["ms"] * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": "conv_igemm_bf16_kernel", "achieved": round(achieved, 2),
+        roofline = {"bound": "mfma", "kernel": mfma_kernels[dom], "achieved": round(achieved, 2),
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                     "traffic": None, "launches_timed": p["launches"], "launches": p["issued"],
-                    "avg_launch_us": round(p["ms"] * 1e3 / p["launches"], 2)}
+                    "avg_launch_us": round(p["ms"] * 1e3 / p["launches"], 2),
+                    "share_of_step": round(est_ms[dom] / args.steps / ms_per_step, 3)}
     other = {}
-    for name in ("regroup_gather", "switch", "pool", "conv_stem", "conv_direct", "head", "regroup_index"):
+    for name in ("conv_slab", "conv_mfma", "regroup_gather", "switch", "pool", "conv_stem", "conv_direct", "head", "regroup_index"):
         if name in prof:
             p = prof[name]
             # timed launches are every k-th of the class: scale their mean to all launches
@@ -118,7 +123,7 @@ def main():
                      "launches_per_step": p["issued"] // max(args.steps, 1)}
             if name in ("regroup_gather", "pool", "switch"):
                 entry["GB/s"] = round(p["work"] / (p["ms"] * 1e-3) / 1e9, 1) if p["ms"] > 0 else None
-            if name in ("conv_direct", "conv_stem"):
+            if name in ("conv_direct", "conv_stem", "conv_slab", "conv_mfma"):
                 entry["TFLOP/s"] = round(p["work"] / (p["ms"] * 1e-3) / 1e12, 2)
             other[name] = entry
 

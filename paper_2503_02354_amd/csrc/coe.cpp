@@ -445,7 +445,7 @@ int run_expert(coe_ctx* c, const Expert& x, const void* weights, const void* inp
                 Span sp(c, COE_K_CONV_MFMA, flops, c->sc);
                 HIPCHK(c, coe::k::conv_mfma(c->d_patch, wb + L.off[0], (const float*)(wb + L.off[1]), nullptr, buf(l.dst), g, c->sc));
             } else if (L.packed) {
-                Span sp(c, COE_K_CONV_MFMA, flops, c->sc);
+                Span sp(c, coe::k::conv_mfma_uses_slab(s) ? COE_K_CONV_SLAB : COE_K_CONV_MFMA, flops, c->sc);
                 HIPCHK(c, coe::k::conv_mfma(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), res, buf(l.dst), s, c->sc));
             } else if (L.fuse_pool) {
                 const LayerPlan& pool = *(&L + 1);
@@ -995,7 +995,8 @@ int coe_debug_conv(coe_ctx* c, int32_t dtype, const void* x, const void* w, cons
     coe::k::ConvShape cs{n, h, wd, ch, k, r, s, stride, pad, P, Q, act};
     const bool mfma = dtype == COE_DT_BF16 && coe::k::conv_mfma_supported(cs);
     const bool smallc = !mfma && dtype == COE_DT_BF16 && coe::k::conv_smallc_supported(cs, res != nullptr, false);
-    const int cls = mfma ? COE_K_CONV_MFMA : smallc ? COE_K_CONV_STEM : COE_K_CONV_DIRECT;
+    const int cls = mfma ? (coe::k::conv_mfma_uses_slab(cs) ? COE_K_CONV_SLAB : COE_K_CONV_MFMA)
+                         : smallc ? COE_K_CONV_STEM : COE_K_CONV_DIRECT;
     if (kernel_class) *kernel_class = cls;
     hipError_t he = hipSuccess;
     auto ok = [&](hipError_t e) { if (he == hipSuccess) he = e; return he == hipSuccess; };

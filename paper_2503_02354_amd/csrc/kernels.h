@@ -48,6 +48,8 @@ hipError_t conv_direct(int dtype, const void* x, const void* w, const float* bia
 // The filters must have been repacked with pack_filters_mfma (host): w is [K][red] with red = R*S*C, out has the
 // same number of elements, ordered so that a wavefront reads a 32-filter x 16-element operand as 1 KiB contiguous.
 bool conv_mfma_supported(const ConvShape& s);
+// true when conv_mfma runs this shape with the 3x3 kernel that keeps the activation slab in LDS for all nine positions
+bool conv_mfma_uses_slab(const ConvShape& s);
 void pack_filters_mfma(const uint16_t* w, uint16_t* out, int K, int red);
 hipError_t conv_mfma(const void* x, const void* w, const float* bias, const void* res, void* y, const ConvShape& s,
                      hipStream_t stream);
