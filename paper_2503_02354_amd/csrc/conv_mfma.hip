@@ -20,6 +20,8 @@
 // Epilogue in fp32: + bias (+ residual), activation, one round-to-nearest-even to bf16 (v_cvt_pk_bf16_f32).
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace coe {
@@ -49,6 +51,14 @@ __device__ __forceinline__ float act_fn(float v, int act)
     if (act == 1) return v > 0.f ? v : 0.f;
     if (act == 2) return 0.5f * v * erfcf(-v * 0.70710678118654752440f);
     return v;
+}
+// The activation is a launch parameter, but an epilogue that tests it per element compiles into hundreds of
+// branches: dispatch ONCE per wave to a body specialised for the activation.
+template <typename F> __device__ __forceinline__ void with_activation(int act, F&& body)
+{
+    if (act == 1) body(std::integral_constant<int, 1>{});
+    else if (act == 2) body(std::integral_constant<int, 2>{});
+    else body(std::integral_constant<int, 0>{});
 }
 // raw buffer descriptor over [p, p + bytes): offsets at or beyond `bytes` read as zero
 __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* p, uint32_t bytes)
@@ -248,6 +258,8 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_bf16_kernel
     // Epilogue.  With the filter fragment as the first operand, accumulator element v of lane l belongs to pixel l%32
     // and filter 8*(v/4) + 4*(l/32) + v%4 of the 32x32 block: a quad of v is 4 consecutive channels of one pixel.
     const int f_hi = (lane >> 5) * 4;
+    with_activation(s.act, [&](auto act_c) {
+    constexpr int ACT = decltype(act_c)::value;
 #pragma unroll
     for (int i = 0; i < MB; ++i) {
         const int m = m0 + wm * WM + i * 32 + frag_row;
@@ -267,12 +279,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N) void conv_igemm_bf16_kernel
                     v2 += bf16_to_f32(rv.y & 0xFFFFu); v3 += bf16_to_f32(rv.y >> 16);
                 }
                 uint2 o;
-                o.x = pack_bf16(act_fn(v0, s.act), act_fn(v1, s.act));
-                o.y = pack_bf16(act_fn(v2, s.act), act_fn(v3, s.act));
+                o.x = pack_bf16(act_fn(v0, ACT), act_fn(v1, ACT));
+                o.y = pack_bf16(act_fn(v2, ACT), act_fn(v3, ACT));
                 *(uint2*)(y + orow + n) = o;
             }
         }
     }
+    });
 }
 
 template <int BM, int BN, int BK, int WAVES_M, int WAVES_N>
@@ -321,10 +334,10 @@ typedef __attribute__((address_space(3))) void lds_void;
 // 32 rows so that the global stores are 16 bytes per lane and cover whole rows of the wave tile (full cache lines
 // instead of 8-byte pieces of 32 different lines per instruction).  LDS operations of one wave execute in program
 // order, so the wave-private buffer needs no barrier between its writes and reads.
-template <int MB, int NB>
-__device__ __forceinline__ void store_tile_via_lds(f32x16 (&acc)[MB][NB], uint16_t* stage, const float* __restrict__ bias,
+template <int MB, int NB, int ACT, bool RES>
+__device__ __forceinline__ void store_tile_via_lds_act(f32x16 (&acc)[MB][NB], uint16_t* stage, const float* __restrict__ bias,
                                                    const uint16_t* __restrict__ res, uint16_t* __restrict__ y, int m_wave,
-                                                   int n_wave, int M, int K, int act, int lane)
+                                                   int n_wave, int M, int K, int lane)
 {
     constexpr int WN = NB * 32, ROW = WN + 8;             // elements; 16 bytes of padding per staged row
     constexpr int CPR = WN / 8;                            // 16-byte chunks per row
@@ -333,7 +346,7 @@ __device__ __forceinline__ void store_tile_via_lds(f32x16 (&acc)[MB][NB], uint16
     // the residual takes the same road in the other direction: row-contiguous 16-byte loads (all issued up front),
     // staged in LDS, picked up in the accumulator layout
     u32x4 rres[MB][T];
-    if (res) {
+    if (RES) {
 #pragma unroll
         for (int i = 0; i < MB; ++i)
 #pragma unroll
@@ -345,7 +358,7 @@ __device__ __forceinline__ void store_tile_via_lds(f32x16 (&acc)[MB][NB], uint16
     }
 #pragma unroll
     for (int i = 0; i < MB; ++i) {
-        if (res) {
+        if (RES) {
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 const int idx = lane + 64 * t;
@@ -361,14 +374,14 @@ __device__ __forceinline__ void store_tile_via_lds(f32x16 (&acc)[MB][NB], uint16
                 const float4 bv = *(const float4*)(bias + n_wave + nl);
                 float v0 = acc[i][j][4 * g + 0] + bv.x, v1 = acc[i][j][4 * g + 1] + bv.y;
                 float v2 = acc[i][j][4 * g + 2] + bv.z, v3 = acc[i][j][4 * g + 3] + bv.w;
-                if (res) {
+                if (RES) {
                     const uint2 rv = *cell;
                     v0 += bf16_to_f32(rv.x & 0xFFFFu); v1 += bf16_to_f32(rv.x >> 16);
                     v2 += bf16_to_f32(rv.y & 0xFFFFu); v3 += bf16_to_f32(rv.y >> 16);
                 }
                 uint2 o;
-                o.x = pack_bf16(act_fn(v0, act), act_fn(v1, act));
-                o.y = pack_bf16(act_fn(v2, act), act_fn(v3, act));
+                o.x = pack_bf16(act_fn(v0, ACT), act_fn(v1, ACT));
+                o.y = pack_bf16(act_fn(v2, ACT), act_fn(v3, ACT));
                 *cell = o;
             }
         }
@@ -381,6 +394,17 @@ __device__ __forceinline__ void store_tile_via_lds(f32x16 (&acc)[MB][NB], uint16
             if (mo < M) *(u32x4*)(y + (size_t)mo * K + n_wave + ch * 8) = v;
         }
     }
+}
+
+template <int MB, int NB>
+__device__ __forceinline__ void store_tile_via_lds(f32x16 (&acc)[MB][NB], uint16_t* stage, const float* __restrict__ bias,
+                                                   const uint16_t* __restrict__ res, uint16_t* __restrict__ y, int m_wave,
+                                                   int n_wave, int M, int K, int act, int lane)
+{
+    with_activation(act, [&](auto a) {
+        if (res) store_tile_via_lds_act<MB, NB, decltype(a)::value, true>(acc, stage, bias, res, y, m_wave, n_wave, M, K, lane);
+        else store_tile_via_lds_act<MB, NB, decltype(a)::value, false>(acc, stage, bias, res, y, m_wave, n_wave, M, K, lane);
+    });
 }
 
 template <int N> __device__ __forceinline__ void wait_vmcnt()

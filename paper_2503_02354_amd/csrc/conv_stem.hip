@@ -16,6 +16,8 @@
 // values equals what a separate pool kernel would produce from the stored conv output.
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace coe {
@@ -47,6 +49,12 @@ __device__ __forceinline__ float act_fn(float v, int act)
     if (act == 2) return 0.5f * v * erfcf(-v * 0.70710678118654752440f);
     return v;
 }
+template <typename F> __device__ __forceinline__ void with_activation(int act, F&& body)
+{
+    if (act == 1) body(std::integral_constant<int, 1>{});
+    else if (act == 2) body(std::integral_constant<int, 2>{});
+    else body(std::integral_constant<int, 0>{});
+}
 
 struct StemGeom {
     int tiles_p, tiles_q, total_tiles;
@@ -59,7 +67,7 @@ struct StemGeom {
 };
 
 template <int NB, bool POOL>
-__global__ __launch_bounds__(kThreads) void conv_smallc_bf16_kernel(const uint16_t* __restrict__ x,
+__global__ __launch_bounds__(kThreads, 2) void conv_smallc_bf16_kernel(const uint16_t* __restrict__ x,
                                                                      const uint16_t* __restrict__ w,
                                                                      const float* __restrict__ bias,
                                                                      uint16_t* __restrict__ y, ConvShape s, StemGeom g)
@@ -172,6 +180,9 @@ __global__ __launch_bounds__(kThreads) void conv_smallc_bf16_kernel(const uint16
                     acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[jn], af[i], acc[i][jn], 0, 0, 0);
         }
 
+        // (dispatched once on the activation: a per-element test compiles into hundreds of branches)
+        with_activation(s.act, [&](auto act_c) {
+        constexpr int ACT = decltype(act_c)::value;
         // accumulator element v of lane l: pixel l%32 of the 32-pixel block, filter 8*(v/4) + 4*(l/32) + v%4
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
@@ -185,17 +196,18 @@ __global__ __launch_bounds__(kThreads) void conv_smallc_bf16_kernel(const uint16
                     const int ch = jn * 32 + 8 * gq + half * 4;
                     const float4 bv = *(const float4*)(bias + ch);
                     uint2 o;
-                    o.x = pack_bf16(act_fn(acc[i][jn][4 * gq + 0] + bv.x, s.act), act_fn(acc[i][jn][4 * gq + 1] + bv.y, s.act));
-                    o.y = pack_bf16(act_fn(acc[i][jn][4 * gq + 2] + bv.z, s.act), act_fn(acc[i][jn][4 * gq + 3] + bv.w, s.act));
+                    o.x = pack_bf16(act_fn(acc[i][jn][4 * gq + 0] + bv.x, ACT), act_fn(acc[i][jn][4 * gq + 1] + bv.y, ACT));
+                    o.y = pack_bf16(act_fn(acc[i][jn][4 * gq + 2] + bv.z, ACT), act_fn(acc[i][jn][4 * gq + 3] + bv.w, ACT));
                     if (POOL) {
                         // outside the conv output: -inf (or 0 after ReLU, see the pool below) never wins the max
-                        if (!inside) o = s.act == 1 ? make_uint2(0u, 0u) : make_uint2(0xFF80FF80u, 0xFF80FF80u);
+                        if (!inside) o = ACT == 1 ? make_uint2(0u, 0u) : make_uint2(0xFF80FF80u, 0xFF80FF80u);
                         *(uint2*)(otile + ml * OUT_STRIDE + ch) = o;
                     } else if (inside) {
                         *(uint2*)(y + (((size_t)n * s.P + p) * s.Q + q) * K + ch) = o;
                     }
                 }
         }
+        });
         if (POOL) {
             __syncthreads();
             // 7x7 pooled pixels x K/8 channel groups; window of pooled (a, b) = tile rows 2a..2a+2, cols 2b..2b+2
