@@ -36,7 +36,7 @@ constexpr int kTile = 16;        // conv-output tile is kTile x kTile pixels = 2
 constexpr int kPoolTile = 7;     // pooled pixels per tile side in the fused form (3x3/2 windows inside 16 rows)
 constexpr int kOutPad = 8;       // elements of padding per LDS row of the conv-output tile
 constexpr int kMaxRowsPerWave = 12;   // patch rows one wavefront fetches (patch_rows <= 48)
-constexpr int kMaxColsPerLane = 3;    // patch columns one lane fetches per row (patch_cols <= 192)
+constexpr int kMaxDwordsPerLane = 1;  // aligned dwords one lane fetches per patch row (patch_cols + 1 <= 128 elements)
 
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 {
@@ -100,13 +100,20 @@ __global__ __launch_bounds__(kThreads, 2) void conv_smallc_bf16_kernel(const uin
     const int tile_org = POOL ? -1 : 0;
 
     // The patch of the NEXT tile is fetched into registers while the current tile is computed: patch rows round-robin
-    // over wavefronts, lanes along the row; offsets outside [0, W*C) and rows outside the image read as zero.
-    uint16_t pre[kMaxRowsPerWave][kMaxColsPerLane];
+    // over wavefronts, lanes along the row, one aligned dword (two elements) per lane and load.  A patch row starts at
+    // element g_base of its image row, which may be odd: the loads start at the even element below it and the staging
+    // step shifts by one element where needed (neighbour lane's dword + one v_alignbit), so that the LDS copy starts
+    // exactly at g_base and the operand reads stay 4-byte aligned.  Dwords outside [0, W*C) and rows outside the
+    // image read as zero through the row's buffer descriptor (W*C is even, so no dword straddles the row's end).
+    uint32_t pre[kMaxRowsPerWave][kMaxDwordsPerLane];
+    int pre_shift = 0;
     auto prefetch = [&](int tile) {
         const int n = tile / (g.tiles_p * g.tiles_q);
         const int tp = (tile / g.tiles_q) % g.tiles_p, tq = tile % g.tiles_q;
         const int ih_base = (tp * tile_step + tile_org) * s.stride - s.pad;
         const int g_base = ((tq * tile_step + tile_org) * s.stride - s.pad) * s.C;   // may be negative
+        const int e0 = g_base & ~1;                                                  // even element at or below g_base
+        pre_shift = g_base - e0;
 #pragma unroll
         for (int i = 0; i < kMaxRowsPerWave; ++i) {
             const int pr = wid + i * (kThreads / 64);
@@ -116,8 +123,8 @@ __global__ __launch_bounds__(kThreads, 2) void conv_smallc_bf16_kernel(const uin
             __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(rowp), 0, row_ok ? WC * 2 : 0,
                                                                           0x00020000);
 #pragma unroll
-            for (int j = 0; j < kMaxColsPerLane; ++j)
-                pre[i][j] = __builtin_amdgcn_raw_buffer_load_b16(rs, (g_base + lane + 64 * j) * 2, 0, 0);
+            for (int j = 0; j < kMaxDwordsPerLane; ++j)
+                pre[i][j] = __builtin_amdgcn_raw_buffer_load_b32(rs, (e0 + 2 * (lane + 64 * j)) * 2, 0, 0);
         }
     };
     auto commit = [&]() {
@@ -126,8 +133,21 @@ __global__ __launch_bounds__(kThreads, 2) void conv_smallc_bf16_kernel(const uin
             const int pr = wid + i * (kThreads / 64);
             if (pr < g.patch_rows) {
 #pragma unroll
-                for (int j = 0; j < kMaxColsPerLane; ++j)
-                    if (lane + 64 * j < g.patch_cols) patch[pr * g.patch_stride + lane + 64 * j] = pre[i][j];
+                for (int j = 0; j < kMaxDwordsPerLane; ++j) {
+                    uint32_t v = pre[i][j];
+                    if (pre_shift) {
+                        // the dword one position further along the row: the next lane's, or lane 0's of the next load
+                        uint32_t nb = __shfl_down(v, 1);
+                        if (j + 1 < kMaxDwordsPerLane) {
+                            const uint32_t first_of_next = __builtin_amdgcn_readfirstlane(pre[i][j + 1 < kMaxDwordsPerLane ? j + 1 : j]);
+                            if (lane == 63) nb = first_of_next;
+                        }
+                        v = __builtin_amdgcn_alignbit(nb, v, 16);
+                    }
+                    const int col = 2 * (lane + 64 * j);
+                    if (col + 1 >= g.patch_cols) v &= 0xFFFFu;            // nothing beyond the patch reaches LDS
+                    if (col < g.patch_cols) *(uint32_t*)(patch + pr * g.patch_stride + col) = v;
+                }
             }
         }
     };
@@ -279,7 +299,8 @@ bool geometry(const ConvShape& s, bool pool, StemGeom& g, size_t& smem)
     int ps = g.patch_cols > furthest ? g.patch_cols : furthest;
     g.patch_stride = (ps + 7) / 8 * 8 + 8;                         // multiple of 8: the regions after it stay 16-byte aligned
     if ((long long)s.W * s.C * 2 >= 0x7FFFFFFFll) return false;
-    if (g.patch_rows > kMaxRowsPerWave * (kThreads / 64) || g.patch_cols > kMaxColsPerLane * 64) return false;
+    if (g.patch_rows > kMaxRowsPerWave * (kThreads / 64) || g.patch_cols + 1 > kMaxDwordsPerLane * 128) return false;
+    if ((s.W * s.C) % 2) return false;                             // aligned dwords must not straddle the end of an image row
     g.PP = (s.P + 2 - 3) / 2 + 1;
     g.PQ = (s.Q + 2 - 3) / 2 + 1;
     if (pool) {

@@ -119,7 +119,8 @@ def test_conv_mfma_shapes(B, oracle, H, Wd, C, K, R, stride, pad, n):
 
 
 @pytest.mark.parametrize("H,Wd,C,K,R,stride,pad,n", [
-    (37, 45, 3, 64, 7, 2, 3, 3),        # stem shape at an odd size: ragged 16x16 tiles on both axes
+    (37, 46, 3, 64, 7, 2, 3, 3),        # stem shape at an odd size: ragged 16x16 tiles on both axes
+    (37, 45, 3, 64, 7, 2, 3, 3),        # odd row length in elements: the stem kernel declines, the plain kernel runs
     (224, 224, 3, 64, 7, 2, 3, 2),      # the real stem: 7x7 tiles per image, several tiles per workgroup
     (30, 30, 4, 32, 3, 1, 1, 2),        # C=4, stride 1, 32 filters
     (20, 33, 6, 64, 5, 1, 2, 2),        # C=6: 30-element window rows -> 4 chunks per row
@@ -306,7 +307,7 @@ def test_error_codes_and_empty_inputs(B):
     (2, 20, 17, 64, 64, 3, 1, 1, False, 1),       # MFMA, 64-wide tiles, ragged rows
     (5, 9, 9, 32, 96, 3, 2, 1, True, 0),          # MFMA, 32-channel steps, stride 2, no activation
     (40, 8, 8, 128, 256, 1, 1, 0, False, 2),      # MFMA 1x1 with GELU, 2560 rows
-    (2, 33, 29, 3, 64, 7, 2, 3, False, 1),        # stem kernel
+    (2, 33, 30, 3, 64, 7, 2, 3, False, 1),        # stem kernel
     (2, 12, 12, 16, 24, 3, 1, 1, True, 1),        # plain kernel (bf16)
 ])
 def test_conv_elementwise_bf16(B, oracle, n, H, Wd, C, K, R, stride, pad, use_res, act):
