@@ -726,8 +726,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_slab_kernel
     issue_slab(cblocks, 8, 0);                                              // lands in the spare block
     issue_b(0, 1, 1);
 
+    // Activation operands of position tap+1 are read while position tap is multiplied: the slab does not change
+    // inside a channel block, so only the filter operands have to wait for the step's barrier.  (With 128-row wave
+    // tiles there are no registers left for that; there the reads of the second 16-channel half are slipped between
+    // the matrix-core instructions of the first.)
+    constexpr bool kAhead = MB <= 2;
     for (int cb = 0; cb < cblocks; ++cb) {
         const uint16_t* slab = lds + (cb & 1) * SLAB;
+        bf16x8 af[2][KS][MB];               // [tap parity]
 #pragma unroll
         for (int tap = 0; tap < kTaps; ++tap) {
             wait_vmcnt<1 + B_PER_WAVE>();       // everything up to this step's filters has landed
@@ -735,13 +741,23 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_slab_kernel
             issue_slab(cb + 1, tap, (cb + 1) & 1);
             issue_b(tap + 2 < kTaps ? cb : cb + 1, (tap + 2) % kTaps, (tap + 2) % 3);
             const uint16_t* b_lds = lds + B_BASE + (tap % 3) * B_STAGE + (wn * NB * KS) * FRAG + lane * 8;
-            bf16x8 af[KS][MB], bfr[KS][NB];
+            bf16x8 bfr[KS][NB];
+            if (!kAhead || tap == 0) {
 #pragma unroll
-            for (int ks = 0; ks < KS; ++ks) {
+                for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
-                for (int i = 0; i < MB; ++i) af[ks][i] = *(const bf16x8*)(slab + (a_addr[i][tap] ^ (ks * 16)));
+                    for (int i = 0; i < MB; ++i) af[tap & 1][ks][i] = *(const bf16x8*)(slab + (a_addr[i][tap] ^ (ks * 16)));
+            }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
 #pragma unroll
                 for (int j = 0; j < NB; ++j) bfr[ks][j] = *(const bf16x8*)(b_lds + (j * KS + ks) * FRAG);
+            if (kAhead && tap + 1 < kTaps) {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                    for (int i = 0; i < MB; ++i)
+                        af[(tap + 1) & 1][ks][i] = *(const bf16x8*)(slab + (a_addr[i][tap + 1] ^ (ks * 16)));
             }
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks)
@@ -749,7 +765,34 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_slab_kernel
                 for (int i = 0; i < MB; ++i)
 #pragma unroll
                     for (int j = 0; j < NB; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks][j], af[ks][i], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[ks][j], af[tap & 1][ks][i], acc[i][j], 0, 0, 0);
+            // issue order inside the step (0x100 = LDS read, 0x008 = matrix core)
+            if (kAhead) {
+                // this step's operands first (filters; at position 0 also the activations), then the matrix-core
+                // instructions with the next position's activation reads slipped in between
+                if (tap == 0) __builtin_amdgcn_sched_group_barrier(0x100, KS * NB + KS * MB, 0);
+                else __builtin_amdgcn_sched_group_barrier(0x100, KS * NB, 0);
+                if (tap + 1 < kTaps) {
+#pragma unroll
+                    for (int t = 0; t < KS * MB; ++t) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x008, KS * MB * NB - KS * MB, 0);
+                } else {
+                    __builtin_amdgcn_sched_group_barrier(0x008, KS * MB * NB, 0);
+                }
+            } else {
+                // the operands of the first 16-channel half, then matrix-core instructions with the reads of the second
+                // half slipped in between them
+                __builtin_amdgcn_sched_group_barrier(0x100, MB + NB, 0);
+#pragma unroll
+                for (int t = 0; t < MB + NB; ++t) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, KS * MB * NB - (MB + NB), 0);
+            }
         }
     }
     wait_vmcnt<0>();
