@@ -413,6 +413,15 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
+// The wait in front of a step's barrier.  Besides the wave's own loads of the step (all but the newest N vector-memory
+// operations) it also drains the wave's LDS reads: the compiler is free to sink the last matrix-core instructions of a
+// step below the barrier, and with them the wait for their operand reads, so a wave could pass the barrier with reads of
+// the previous step still queued while another wave's DMA of a later step already targets the same LDS stage.
+template <int N> __device__ __forceinline__ void wait_before_barrier()
+{
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (7 << 4) | (0 << 8));
+}
+
 template <int BM, int BN, int WAVES_M, int WAVES_N>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv_igemm_dma_kernel(const uint16_t* __restrict__ x,
                                                                    const uint16_t* __restrict__ wp,
@@ -547,15 +556,14 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv_igemm_dma_kern
     issue(1);
     int stage_c = 0, stage_l = 2;
     for (int u = 0; u < nsteps; ++u) {
-        wait_vmcnt<LOADS>();                 // step u has landed; step u + 1 may still be in flight
+        wait_before_barrier<LOADS>();        // step u has landed; step u + 1 may still be in flight
         __builtin_amdgcn_s_barrier();
         issue(stage_l);
         compute(stage_c);
         stage_c = stage_c == kStages - 1 ? 0 : stage_c + 1;
         stage_l = stage_l == kStages - 1 ? 0 : stage_l + 1;
     }
-    wait_vmcnt<0>();
-
+    wait_before_barrier<0>();
     __builtin_amdgcn_s_barrier();        // every wave is done with the operand stages: LDS is free for the epilogue
     store_tile_via_lds<MB, NB>(acc, lds + wid * (32 * (WN + 8)), bias, res, y, m0 + wm * WM, n0 + wn * WN, M, s.K, s.act, lane);
 #endif
@@ -736,7 +744,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_slab_kernel
         bf16x8 af[2][KS][MB];               // [tap parity]
 #pragma unroll
         for (int tap = 0; tap < kTaps; ++tap) {
-            wait_vmcnt<1 + B_PER_WAVE>();       // everything up to this step's filters has landed
+            wait_before_barrier<1 + B_PER_WAVE>();      // everything up to this step's filters has landed
             __builtin_amdgcn_s_barrier();
             issue_slab(cb + 1, tap, (cb + 1) & 1);
             issue_b(tap + 2 < kTaps ? cb : cb + 1, (tap + 2) % kTaps, (tap + 2) % 3);
@@ -795,8 +803,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_slab_kernel
             }
         }
     }
-    wait_vmcnt<0>();
-
+    wait_before_barrier<0>();
     __builtin_amdgcn_s_barrier();        // every wave is done with the operand stages: LDS is free for the epilogue
     store_tile_via_lds<MB, NB>(acc, lds + wid * (32 * (WN + 8)), bias, res, y, m0 + wm * WM, n0 + wn * WN, M, s.K, s.act, lane);
 #endif

@@ -428,3 +428,26 @@ def test_forward_vit_small_bf16(B, oracle):
 def test_forward_vit_base_shape_bf16(B, oracle):
     # ViT-B/16 geometry (197 tokens: ragged 32-key blocks; 12 heads; red 768) with 2 blocks to keep the oracle quick
     _forward_case(B, oracle, W.vit(8, 224, 16, 768, 2, 12, 3072, W.DT_BF16), 3, 36, REL_TOL_BF16)
+
+
+def test_forward_is_deterministic_and_batch_independent(B):
+    """Full-width ResNet-18 at 224x224, 512 requests (thousands of tiles per conv launch, every kernel at its bench
+    shape): repeated runs give the same bits, and a request's logits do not depend on how many requests run with it.
+    Guards the LDS hand-over between pipeline stages of the conv kernels (a stale or early-overwritten operand stage
+    shows up as a handful of wrong tiles per run)."""
+    import torch
+    arch = W.resnet18(16, 224, W.DT_BF16, 64)
+    blob = W.make_expert_blob(arch, 77, 0)
+    n = 512
+    x = W.make_inputs(arch, 77, range(n))
+    ctx = B.Context(max_requests=n, max_batch=n)
+    aid = ctx.coe_register_arch(arch)
+    ctx.coe_register_expert(0, aid, blob, 1.0)
+    dev = device_tensor(x)
+    runs = [ctx.coe_debug_forward(0, n, dev.data_ptr()) for _ in range(4)]
+    small = ctx.coe_debug_forward(0, 48, dev.data_ptr())
+    ctx.close()
+    assert np.isfinite(runs[0]).all()
+    for r in runs[1:]:
+        assert np.array_equal(r, runs[0])
+    assert np.array_equal(small, runs[0][:48])
