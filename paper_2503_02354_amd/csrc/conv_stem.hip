@@ -71,7 +71,9 @@ struct StemGeom {
     int PP, PQ;                   // pooled output size (fused form)
 };
 
-template <int NB, bool POOL>
+// CPR_, R_: chunks per window row and window rows when known at compile time (the 7x7x3 stem: 3, 7), else 0: the
+// reduction loop is then unrolled with constant offsets instead of running a counted loop with a carried (row, chunk).
+template <int NB, bool POOL, int CPR_, int R_>
 __global__ __launch_bounds__(kThreads, 4) void conv_smallc_bf16_kernel(const uint16_t* __restrict__ x,
                                                                      const uint16_t* __restrict__ w,
                                                                      const float* __restrict__ bias,
@@ -180,13 +182,7 @@ __global__ __launch_bounds__(kThreads, 4) void conv_smallc_bf16_kernel(const uin
             int ml = wid * kRowsPerWave + i * 32 + l32;
             a_off[i] = (ml / kTile) * s.stride * g.patch_stride + (ml % kTile) * s.stride * s.C;
         }
-        int kr = half / g.cpr, kpart = half % g.cpr;              // window row and chunk inside it of this lane's chunk
-        for (int j = 0; j < g.ksteps; ++j) {
-            const int chunk = 2 * j + half;
-            const int r = kr < s.R ? kr : s.R - 1;                 // padded step: filters are zero, any finite data will do
-            const int koff = r * g.patch_stride + kpart * 8;
-            kpart += 2;                                            // next step: two chunks on, without a division
-            while (kpart >= g.cpr) { kpart -= g.cpr; ++kr; }
+        auto kstep = [&](int koff, int chunk) {
             bf16x8 af[kMB], bfr[NB];
 #pragma unroll
             for (int i = 0; i < kMB; ++i) {
@@ -203,6 +199,26 @@ __global__ __launch_bounds__(kThreads, 4) void conv_smallc_bf16_kernel(const uin
 #pragma unroll
                 for (int jn = 0; jn < NB; ++jn)
                     acc[i][jn] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[jn], af[i], acc[i][jn], 0, 0, 0);
+        };
+        if constexpr (CPR_ > 0) {
+            constexpr int KSTEPS = (R_ * CPR_ + 1) / 2;
+#pragma unroll
+            for (int j = 0; j < KSTEPS; ++j) {
+                // chunk 2j (lanes 0-31) and 2j+1 (lanes 32-63): window row and chunk inside it are constants; a padded
+                // last chunk reads the last window row again (its filters are zero, any finite data will do)
+                const int c0 = 2 * j, c1 = 2 * j + 1;
+                const int r0 = c0 / CPR_ < R_ ? c0 / CPR_ : R_ - 1, r1 = c1 / CPR_ < R_ ? c1 / CPR_ : R_ - 1;
+                const int off0 = r0 * g.patch_stride + (c0 % CPR_) * 8, off1 = r1 * g.patch_stride + (c1 % CPR_) * 8;
+                kstep(half ? off1 : off0, 2 * j + half);
+            }
+        } else {
+            int kr = half / g.cpr, kpart = half % g.cpr;          // window row and chunk inside it of this lane's chunk
+            for (int j = 0; j < g.ksteps; ++j) {
+                const int r = kr < s.R ? kr : s.R - 1;             // padded step: filters are zero, any finite data will do
+                kstep(r * g.patch_stride + kpart * 8, 2 * j + half);
+                kpart += 2;                                        // next step: two chunks on, without a division
+                while (kpart >= g.cpr) { kpart -= g.cpr; ++kr; }
+            }
         }
 
         // (dispatched once on the activation: a per-element test compiles into hundreds of branches)
@@ -324,19 +340,19 @@ bool geometry(const ConvShape& s, bool pool, StemGeom& g, size_t& smem)
     return smem <= 96 * 1024;
 }
 
-template <int NB, bool POOL>
+template <int NB, bool POOL, int CPR_, int R_>
 hipError_t launch(const void* x, const void* w, const float* bias, void* y, const ConvShape& s, const StemGeom& g, size_t smem,
                   hipStream_t stream)
 {
     static bool configured = false;
     if (!configured) {   // more than the default 64 KiB of LDS per workgroup needs an explicit opt-in
-        hipError_t e = hipFuncSetAttribute((const void*)conv_smallc_bf16_kernel<NB, POOL>,
+        hipError_t e = hipFuncSetAttribute((const void*)conv_smallc_bf16_kernel<NB, POOL, CPR_, R_>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 96 * 1024);
         if (e != hipSuccess) return e;
         configured = true;
     }
     int grid = g.total_tiles < 1024 ? g.total_tiles : 1024;
-    hipLaunchKernelGGL((conv_smallc_bf16_kernel<NB, POOL>), dim3(grid), dim3(kThreads), smem, stream, (const uint16_t*)x,
+    hipLaunchKernelGGL((conv_smallc_bf16_kernel<NB, POOL, CPR_, R_>), dim3(grid), dim3(kThreads), smem, stream, (const uint16_t*)x,
                        (const uint16_t*)w, bias, (uint16_t*)y, s, g);
     return hipGetLastError();
 }
@@ -357,9 +373,14 @@ hipError_t conv_smallc(const void* x, const void* w, const float* bias, void* y,
     size_t smem = 0;
     if (!geometry(s, fused_pool, g, smem)) return hipErrorInvalidValue;
     if (g.total_tiles == 0) return hipSuccess;
-    if (s.K == 64)
-        return fused_pool ? launch<2, true>(x, w, bias, y, s, g, smem, stream) : launch<2, false>(x, w, bias, y, s, g, smem, stream);
-    return fused_pool ? launch<1, true>(x, w, bias, y, s, g, smem, stream) : launch<1, false>(x, w, bias, y, s, g, smem, stream);
+    if (s.K == 64) {
+        if (fused_pool && g.cpr == 3 && s.R == 7)         // the ResNet stem: reduction loop unrolled with constant offsets
+            return launch<2, true, 3, 7>(x, w, bias, y, s, g, smem, stream);
+        return fused_pool ? launch<2, true, 0, 0>(x, w, bias, y, s, g, smem, stream)
+                          : launch<2, false, 0, 0>(x, w, bias, y, s, g, smem, stream);
+    }
+    return fused_pool ? launch<1, true, 0, 0>(x, w, bias, y, s, g, smem, stream)
+                      : launch<1, false, 0, 0>(x, w, bias, y, s, g, smem, stream);
 }
 
 }  // namespace k
