@@ -110,8 +110,7 @@ __global__ __launch_bounds__(kThreads, 4) void conv_smallc_bf16_kernel(const uin
     // over wavefronts, lanes along the row, one aligned dword (two elements) per lane and load.  A patch row starts at
     // element g_base of its image row, which may be odd: the loads start at the even element below it and the staging
     // step shifts by one element where needed (neighbour lane's dword + one v_alignbit), so that the LDS copy starts
-    // exactly at g_base and the operand reads stay 4-byte aligned.  Dwords outside [0, W*C) and rows outside the
-    // image read as zero through the row's buffer descriptor (W*C is even, so no dword straddles the row's end).
+    // exactly at g_base and the operand reads stay 4-byte aligned.  W*C is even, so no dword straddles a row's end.
     uint32_t pre[kMaxRowsPerWave][kMaxDwordsPerLane];
     int pre_shift = 0;
     auto prefetch = [&](int tile) {
@@ -121,17 +120,21 @@ __global__ __launch_bounds__(kThreads, 4) void conv_smallc_bf16_kernel(const uin
         const int g_base = ((tq * tile_step + tile_org) * s.stride - s.pad) * s.C;   // may be negative
         const int e0 = g_base & ~1;                                                  // even element at or below g_base
         pre_shift = g_base - e0;
+        // one descriptor per image; a dword outside its row (left or right of the image) or in a row outside the image
+        // gets an offset beyond the descriptor's range and reads as zero
+        const __amdgpu_buffer_rsrc_t rs =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(x + (size_t)n * s.H * WC), 0, s.H * WC * 2, 0x00020000);
 #pragma unroll
-        for (int i = 0; i < kMaxRowsPerWave; ++i) {
-            const int pr = wid + i * (kThreads / 64);
-            const int ih = ih_base + pr;
-            const bool row_ok = pr < g.patch_rows && (unsigned)ih < (unsigned)s.H;
-            const uint16_t* rowp = x + ((size_t)n * s.H + (row_ok ? ih : 0)) * WC;
-            __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(rowp), 0, row_ok ? WC * 2 : 0,
-                                                                          0x00020000);
+        for (int j = 0; j < kMaxDwordsPerLane; ++j) {
+            const int e = e0 + 2 * (lane + 64 * j);
+            const bool col_ok = (unsigned)e < (unsigned)WC;                          // WC is even: e + 1 < WC as well
 #pragma unroll
-            for (int j = 0; j < kMaxDwordsPerLane; ++j)
-                pre[i][j] = __builtin_amdgcn_raw_buffer_load_b32(rs, (e0 + 2 * (lane + 64 * j)) * 2, 0, 0);
+            for (int i = 0; i < kMaxRowsPerWave; ++i) {
+                const int pr = wid + i * (kThreads / 64);
+                const int ih = ih_base + pr;
+                const bool ok = col_ok && pr < g.patch_rows && (unsigned)ih < (unsigned)s.H;
+                pre[i][j] = __builtin_amdgcn_raw_buffer_load_b32(rs, ok ? (ih * WC + e) * 2 : (int)0x80000000, 0, 0);
+            }
         }
     };
     auto commit = [&]() {
@@ -319,7 +322,7 @@ bool geometry(const ConvShape& s, bool pool, StemGeom& g, size_t& smem)
     int furthest = (kTile - 1) * s.stride * s.C + g.cpr * 8;       // one past the last element any chunk read touches
     int ps = g.patch_cols > furthest ? g.patch_cols : furthest;
     g.patch_stride = (ps + 7) / 8 * 8 + 8;                         // multiple of 8: the regions after it stay 16-byte aligned
-    if ((long long)s.W * s.C * 2 >= 0x7FFFFFFFll) return false;
+    if ((long long)s.H * s.W * s.C * 2 >= 0x7FFFFFFFll) return false;    // byte offsets inside one image are 31-bit
     if (g.patch_rows > kMaxRowsPerWave * (kThreads / 64) || g.patch_cols + 1 > kMaxDwordsPerLane * 128) return false;
     if ((s.W * s.C) % 2) return false;                             // aligned dwords must not straddle the end of an image row
     g.PP = (s.P + 2 - 3) / 2 + 1;
