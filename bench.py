@@ -23,6 +23,25 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
+# HBM bytes per launch of conv3x3_slab_kernel on this workload, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
+# scaled by what the same counters read for the gather kernel's plain copy (profiles/conv3x3_slab_config2_hbm_counters.md).
+# Tied to the kernel source it was measured on: any edit of that file makes bench.py report null again.
+SLAB_TRAFFIC_BYTES_PER_LAUNCH = 205.0e6
+SLAB_TRAFFIC_SOURCE = ("paper_2503_02354_amd/csrc/conv_mfma.hip",
+                       "9bf5e6deb126dc94d616c46622d0565927fe578785cec6f5f54b027b684a7ded")
+
+
+def measured_traffic(kernel: str):
+    if kernel != "conv3x3_slab_kernel":
+        return None
+    import hashlib
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), SLAB_TRAFFIC_SOURCE[0])
+    try:
+        with open(path, "rb") as f:
+            same = hashlib.sha256(f.read()).hexdigest() == SLAB_TRAFFIC_SOURCE[1]
+    except OSError:
+        same = False
+    return SLAB_TRAFFIC_BYTES_PER_LAUNCH if same else None
 PEAK_HBM_GBS = 8000.0
 
 
@@ -111,7 +130,8 @@ def main():
         achieved = p["work"] / (p["ms"] * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": mfma_kernels[dom], "achieved": round(achieved, 2),
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "traffic": None, "launches_timed": p["launches"], "launches": p["issued"],
+                    "traffic": measured_traffic(mfma_kernels[dom]), "traffic_unit": "HBM bytes per launch",
+                    "launches_timed": p["launches"], "launches": p["issued"],
                     "avg_launch_us": round(p["ms"] * 1e3 / p["launches"], 2),
                     "share_of_step": round(est_ms[dom] / args.steps / ms_per_step, 3)}
     other = {}
