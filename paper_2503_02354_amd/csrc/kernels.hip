@@ -303,6 +303,12 @@ __device__ __forceinline__ void route_tail(const float* logit, int ncls, int row
     }
 }
 
+// 16-byte loads in the pooling phase: bf16 tensors whose channel count is a multiple of 8 with C/8 dividing the block
+template <typename T> __host__ __device__ inline bool head_vector_path(int C)
+{
+    return sizeof(T) == 2 && C >= 64 && C % 8 == 0 && kHeadThreads % (C / 8) == 0;
+}
+
 template <typename T>
 __global__ __launch_bounds__(kHeadThreads) void head_gap_fc_kernel(const T* __restrict__ x, const T* __restrict__ w,
                                                                    const float* __restrict__ b, int HW, int C, int ncls,
@@ -312,11 +318,35 @@ __global__ __launch_bounds__(kHeadThreads) void head_gap_fc_kernel(const T* __re
     int row = blockIdx.x;
     const T* xp = x + (size_t)row * HW * C;
     int groups = C < kHeadThreads ? kHeadThreads / C : 1;      // position groups when there are few channels
+    if (head_vector_path<T>(C)) groups = kHeadThreads / (C / 8);
     float* feat = smem;
     float* part = smem + C;
     float* logit = part + (size_t)groups * C;
     // phase 1: per-channel sums, lanes run along channels (contiguous in NHWC)
-    if (groups > 1) {
+    if (head_vector_path<T>(C)) {
+        // bf16, C a multiple of 8 with C/8 dividing the block: 16-byte loads, 8 channels per thread, the positions
+        // dealt round-robin to 256 / (C/8) thread groups whose partial sums meet in LDS
+        const int cpb = C / 8, G = kHeadThreads / cpb;
+        const int chunk = threadIdx.x % cpb, pg = threadIdx.x / cpb;
+        float a8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int i = pg; i < HW; i += G) {
+            const uint4 v = *(const uint4*)((const uint16_t*)xp + (size_t)i * C + chunk * 8);
+            const uint32_t wds[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                a8[2 * e] += __uint_as_float(wds[e] << 16);
+                a8[2 * e + 1] += __uint_as_float(wds[e] & 0xFFFF0000u);
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) part[pg * C + chunk * 8 + e] = a8[e];
+        __syncthreads();
+        for (int c2 = threadIdx.x; c2 < C; c2 += kHeadThreads) {
+            float a = 0.f;
+            for (int g2 = 0; g2 < G; ++g2) a += part[g2 * C + c2];
+            feat[c2] = a / (float)HW;
+        }
+    } else if (groups > 1) {
         int g = threadIdx.x / C, c = threadIdx.x % C;
         if (g < groups) {
             float a = 0.f;
@@ -474,6 +504,7 @@ hipError_t head_gap_fc(int dtype, const void* x, const void* w, const float* b, 
 {
     if (N <= 0) return hipSuccess;
     int groups = C < kHeadThreads ? kHeadThreads / C : 1;
+    if (dtype == 1 && head_vector_path<uint16_t>(C)) groups = kHeadThreads / (C / 8);      // partial sums of the 16-byte path
     size_t smem = sizeof(float) * ((size_t)C + (size_t)groups * C + (size_t)ncls);
     if (smem > 60 * 1024) return hipErrorInvalidValue;
     if (dtype == 1)
