@@ -59,7 +59,7 @@ def main():
                          "to the launches per forward, so every layer shape is sampled)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py runs on exactly one GPU: this build has no multi-GPU path (--gpus 1 only)", file=sys.stderr)
+        print("bench.py runs on exactly one GPU: the library has no multi-GPU path (--gpus 1 only)", file=sys.stderr)
         sys.exit(2)
 
     import torch
