@@ -369,11 +369,48 @@ __global__ __launch_bounds__(kHeadThreads) void head_gap_fc_kernel(const T* __re
     __syncthreads();
     // phase 2: one wavefront per class, lanes along the feature dimension, wavefront reduction
     int lane = threadIdx.x & (kWave - 1), wid = threadIdx.x / kWave;
-    for (int j = wid; j < ncls; j += kHeadThreads / kWave) {
-        float a = 0.f;
-        for (int c = lane; c < C; c += kWave) a = fmaf(feat[c], Elem<T>::load(w + (size_t)j * C + c), a);
-        a = wave_sum(a);
-        if (lane == 0) logit[j] = a + b[j];
+    if (head_vector_path<T>(C)) {
+        // 16-byte weight loads, four classes per wavefront in flight: with one 2-byte load per multiply-add the loop is
+        // a chain of ~C/64 * classes/4 global-load latencies per wavefront (200 us for a 2048 x 64 head)
+        constexpr int kWaves = kHeadThreads / kWave;
+        const uint16_t* wq = (const uint16_t*)w;
+        const int cpb = C / 8;
+        for (int j0 = wid; j0 < ncls; j0 += 4 * kWaves) {
+            float a[4] = {0.f, 0.f, 0.f, 0.f};
+            for (int ch = lane; ch < cpb; ch += kWave) {
+                uint4 wv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int j = j0 + u * kWaves;
+                    wv[u] = j < ncls ? *(const uint4*)(wq + (size_t)j * C + ch * 8) : make_uint4(0, 0, 0, 0);
+                }
+                const float4 f0 = *(const float4*)(feat + ch * 8), f1 = *(const float4*)(feat + ch * 8 + 4);
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    a[u] = fmaf(f0.x, __uint_as_float(wv[u].x << 16), a[u]);
+                    a[u] = fmaf(f0.y, __uint_as_float(wv[u].x & 0xFFFF0000u), a[u]);
+                    a[u] = fmaf(f0.z, __uint_as_float(wv[u].y << 16), a[u]);
+                    a[u] = fmaf(f0.w, __uint_as_float(wv[u].y & 0xFFFF0000u), a[u]);
+                    a[u] = fmaf(f1.x, __uint_as_float(wv[u].z << 16), a[u]);
+                    a[u] = fmaf(f1.y, __uint_as_float(wv[u].z & 0xFFFF0000u), a[u]);
+                    a[u] = fmaf(f1.z, __uint_as_float(wv[u].w << 16), a[u]);
+                    a[u] = fmaf(f1.w, __uint_as_float(wv[u].w & 0xFFFF0000u), a[u]);
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int j = j0 + u * kWaves;
+                const float t = wave_sum(a[u]);
+                if (lane == 0 && j < ncls) logit[j] = t + b[j];
+            }
+        }
+    } else {
+        for (int j = wid; j < ncls; j += kHeadThreads / kWave) {
+            float a = 0.f;
+            for (int c = lane; c < C; c += kWave) a = fmaf(feat[c], Elem<T>::load(w + (size_t)j * C + c), a);
+            a = wave_sum(a);
+            if (lane == 0) logit[j] = a + b[j];
+        }
     }
     __syncthreads();
     // phase 3: write logits, pick the route
