@@ -84,6 +84,9 @@ typedef struct {
     int64_t cache_cap_bytes;   /* and at most this many bytes of expert weights (0 = no limit) */
     void* compute_stream;      /* borrowed hipStream_t for kernels, or NULL: the library creates one */
     void* copy_stream;         /* borrowed hipStream_t for expert switches, or NULL: the library creates one */
+    int32_t group_small;       /* request arranging leaves many groups of a few requests: groups of at most this many
+                                * requests whose experts share an architecture run as ONE launch per layer (0 = 64,
+                                * negative = never).  Results do not depend on it. */
 } coe_config;
 
 typedef struct {
@@ -95,6 +98,8 @@ typedef struct {
     int32_t n_evictions; /* experts evicted */
     int64_t bytes_switched; /* host-to-device bytes of the switches */
     double host_plan_us; /* host time spent planning (cache policy, splitting) */
+    int32_t n_grouped;   /* groups that shared their launches with other small groups */
+    int32_t n_group_sets; /* launch sequences those groups were packed into */
 } coe_step_stats;
 
 /* Create / destroy a context.  coe_create fails with COE_EDEVICE when no GPU is usable. */

@@ -40,13 +40,13 @@ class coe_arch_desc(C.Structure):
 class coe_config(C.Structure):
     _fields_ = [("device", C.c_int32), ("max_requests", C.c_int32), ("max_batch", C.c_int32), ("max_stages", C.c_int32),
                 ("cache_cap_experts", C.c_int32), ("profile", C.c_int32), ("cache_cap_bytes", C.c_int64),
-                ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p)]
+                ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p), ("group_small", C.c_int32)]
 
 
 class coe_step_stats(C.Structure):
     _fields_ = [("n_pending", C.c_int32), ("n_groups", C.c_int32), ("n_chunks", C.c_int32), ("n_hits", C.c_int32),
                 ("n_misses", C.c_int32), ("n_evictions", C.c_int32), ("bytes_switched", C.c_int64),
-                ("host_plan_us", C.c_double)]
+                ("host_plan_us", C.c_double), ("n_grouped", C.c_int32), ("n_group_sets", C.c_int32)]
 
 
 def _load():
@@ -163,9 +163,9 @@ class Context:
 
     def __init__(self, max_requests: int, max_stages: int = 2, max_batch: int = 0, cache_cap_experts: int = 0,
                  cache_cap_bytes: int = 0, device: int = 0, profile: bool = False, compute_stream: int = 0,
-                 copy_stream: int = 0):
+                 copy_stream: int = 0, group_small: int = 0):
         cfg = coe_config(device, max_requests, max_batch, max_stages, cache_cap_experts, int(profile), cache_cap_bytes,
-                         compute_stream or None, copy_stream or None)
+                         compute_stream or None, copy_stream or None, group_small)
         h = C.c_void_p()
         rc = lib.coe_create(C.byref(cfg), C.byref(h))
         if rc != COE_OK:

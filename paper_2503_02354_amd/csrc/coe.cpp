@@ -40,6 +40,7 @@ struct ArchPlan {
     size_t blob_bytes = 0;
     size_t buf_elems[kMaxBufs] = {0};   // per request
     size_t patch_elems = 0;             // per request: rows of the largest patch-gathered conv
+    bool groupable = false;             // every layer can run several experts' small groups in one launch
     size_t elem() const { return dtype == COE_DT_BF16 ? 2 : 4; }
     size_t in_bytes() const { return (size_t)in_h * in_w * in_c * elem(); }
 };
@@ -297,6 +298,22 @@ int plan_arch(coe_ctx* c, const coe_arch_desc* d, ArchPlan& a)
         pl.fused_away = true;
     }
     a.blob_bytes = align_up(off);
+    // grouped launches: matrix-core convs with K % 64 == 0 take a group table; few-channel convs run once per group;
+    // pools have no weights; the pooled head takes a group table.  Anything else keeps one launch per group.
+    a.groupable = a.dtype == COE_DT_BF16;
+    for (const LayerPlan& L : a.layers) {
+        const coe_layer& l = L.d;
+        coe::k::ConvShape cs{1, L.H, L.W, L.C, L.K, l.r, l.s, l.stride, l.pad, L.P, L.Q, l.act};
+        const bool reads_input = l.src == 0 || l.res == 0;
+        if (reads_input && !(l.op == COE_OP_CONV && !L.packed && l.res != 0)) a.groupable = false;   // only the per-group stem may
+        if (l.op == COE_OP_CONV) {
+            if (L.patchify) a.groupable = false;
+            else if (L.packed) a.groupable = a.groupable && coe::k::conv_mfma_groupable(cs);
+            else if (!L.fuse_pool && !coe::k::conv_smallc_supported(cs, l.res >= 0, false)) a.groupable = false;
+        } else if (l.op != COE_OP_MAXPOOL && l.op != COE_OP_HEAD) {
+            a.groupable = false;
+        }
+    }
     return COE_OK;
 }
 
@@ -501,6 +518,86 @@ int run_expert(coe_ctx* c, const Expert& x, const void* weights, const void* inp
         }
         default:
             return fail(c, COE_EINVAL, "unknown layer op");
+        }
+    }
+    return COE_OK;
+}
+
+// ---- several small groups, experts of one architecture, one launch per layer -------------------------------------------------
+struct SetMember {
+    int32_t expert;
+    int32_t first;       // first request of the group in the group-contiguous order
+    int32_t count;
+};
+
+int run_group_set(coe_ctx* c, const std::vector<SetMember>& set, const uint8_t* staged, size_t ib)
+{
+    const ArchPlan& a = c->archs[c->experts[set[0].expert].arch];
+    coe::k::GroupTable gt{};
+    coe::k::GroupRoutes gr{};
+    gt.n = (int32_t)set.size();
+    int32_t n = 0;
+    for (size_t g = 0; g < set.size(); ++g) {
+        const Expert& x = c->experts[set[g].expert];
+        gt.first_row[g] = n;
+        gt.weights[g] = x.buf->p;
+        gr.expert[g] = set[g].expert;
+        gr.succ_off[g] = c->succ_off[set[g].expert];
+        gr.n_route[g] = c->succ_off[set[g].expert + 1] - c->succ_off[set[g].expert];
+        gr.slot_off[g] = set[g].first;
+        n += set[g].count;
+    }
+    gt.first_row[set.size()] = n;
+    auto buf = [&](int id) -> uint8_t* { return (uint8_t*)c->d_buf[id]; };
+    for (const LayerPlan& L : a.layers) {
+        const coe_layer& l = L.d;
+        switch (l.op) {
+        case COE_OP_CONV: {
+            coe::k::ConvShape s{n, L.H, L.W, L.C, L.K, l.r, l.s, l.stride, l.pad, L.P, L.Q, l.act};
+            double flops = 2.0 * L.macs * n;
+            if (L.packed) {
+                if (l.src == 0) return fail(c, COE_ESTATE, "internal: grouped matrix-core conv on the raw input");
+                const void* res = l.res >= 0 ? buf(l.res) : nullptr;
+                Span sp(c, coe::k::conv_mfma_uses_slab(s) ? COE_K_CONV_SLAB : COE_K_CONV_MFMA, flops, c->sc);
+                HIPCHK(c, coe::k::conv_mfma_grouped(buf(l.src), gt, L.off[0], L.off[1], res, buf(l.dst), s, c->sc));
+            } else {
+                // few input channels (the stem): the filters live in LDS for a whole launch, so one launch per group,
+                // each writing its rows of the shared activation buffer
+                const bool fused = L.fuse_pool;
+                const LayerPlan& outL = fused ? *(&L + 1) : L;
+                const size_t in_row = (size_t)L.H * L.W * L.C * a.elem();
+                const size_t out_row = (size_t)outL.P * outL.Q * outL.K * a.elem();
+                Span sp(c, COE_K_CONV_STEM, flops, c->sc);
+                for (size_t g = 0; g < set.size(); ++g) {
+                    coe::k::ConvShape sg = s;
+                    sg.N = set[g].count;
+                    const uint8_t* in = l.src == 0 ? staged + (size_t)set[g].first * ib : buf(l.src) + (size_t)gt.first_row[g] * in_row;
+                    const uint8_t* wb = (const uint8_t*)gt.weights[g];
+                    HIPCHK(c, coe::k::conv_smallc(in, wb + L.off[0], (const float*)(wb + L.off[1]),
+                                                  buf(outL.d.dst) + (size_t)gt.first_row[g] * out_row, sg, fused, c->sc));
+                }
+            }
+            break;
+        }
+        case COE_OP_MAXPOOL: {
+            if (L.fused_away) break;
+            if (l.src == 0) return fail(c, COE_ESTATE, "internal: grouped pool on the raw input");
+            double bytes = (double)n * ((double)L.H * L.W * L.C + (double)L.P * L.Q * L.K) * a.elem();
+            Span sp(c, COE_K_POOL, bytes, c->sc);
+            HIPCHK(c, coe::k::maxpool(a.dtype, buf(l.src), buf(l.dst), n, L.H, L.W, L.C, l.r, l.s, l.stride, l.pad, L.P, L.Q, c->sc));
+            break;
+        }
+        case COE_OP_HEAD: {
+            if (l.src == 0) return fail(c, COE_ESTATE, "internal: grouped head on the raw input");
+            double bytes = (double)n * L.H * L.W * L.C * a.elem();
+            coe::k::RouteArgs r{c->d_perm, 0, c->d_succ, 0, c->d_cur, c->d_depth, c->d_path, c->cfg.max_stages, c->d_logits,
+                                c->max_classes};
+            Span sp(c, COE_K_HEAD, bytes, c->sc);
+            HIPCHK(c, coe::k::head_gap_fc_grouped(a.dtype, buf(l.src), gt, L.off[0], L.off[1], n, L.H * L.W, L.C, L.K, r, gr, c->sc));
+            break;
+        }
+        default:
+            return fail(c, COE_ESTATE, "internal: architecture is not groupable");
         }
     }
     return COE_OK;
@@ -781,20 +878,69 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
 
     std::vector<uint8_t> launched(E, 0);
     size_t next_load = 0;
-    for (int32_t e : order) {
-        // enqueue every switch whose victims are no longer needed by a group that has not been launched yet;
-        // the copies run on the copy stream while earlier groups compute
+    // enqueue every switch whose victims are no longer needed by a group that has not been launched yet; the copies
+    // run on the copy stream while earlier groups compute
+    auto issue_ready_loads = [&]() -> int {
         while (next_load < switches.size()) {
             const coe::Switch& sw = switches[next_load];
             bool ready = true;
             for (int32_t v : sw.victims) ready = ready && !(has_group[v] && !launched[v]);
             if (!ready) break;
-            rc = issue_load(c, sw, &st);
-            if (rc) return rc;
+            int r2 = issue_load(c, sw, &st);
+            if (r2) return r2;
             ++next_load;
         }
+        return COE_OK;
+    };
+    const int32_t group_small = c->cfg.group_small == 0 ? 64 : c->cfg.group_small;
+    auto small = [&](int32_t e) {
+        return group_small > 0 && c->h_cnt[e] <= group_small && c->archs[c->experts[e].arch].groupable;
+    };
+    for (size_t i = 0; i < order.size();) {
+        const int32_t e = order[i];
+        rc = issue_ready_loads();
+        if (rc) return rc;
         Expert& x = c->experts[e];
         if (!x.buf) return fail(c, COE_ESTATE, "internal: expert not loaded at launch time");
+
+        // small groups that follow in the plan, of the same architecture and with their experts on the device (or on
+        // their way), run together: one launch per layer for all of them
+        std::vector<SetMember> set;
+        if (small(e)) {
+            set.push_back({e, off[e], c->h_cnt[e]});
+            int32_t rows = c->h_cnt[e];
+            size_t j = i + 1;
+            for (; j < order.size() && (int32_t)set.size() < coe::k::kMaxGroups; ++j) {
+                const int32_t f = order[j];
+                if (!small(f) || c->experts[f].arch != x.arch || rows + c->h_cnt[f] > c->cfg.max_batch) break;
+                if (!c->experts[f].buf) break;                 // its switch still waits for a victim of this very set
+                set.push_back({f, off[f], c->h_cnt[f]});
+                rows += c->h_cnt[f];
+            }
+        }
+        if (set.size() >= 2) {
+            for (const SetMember& m : set) {
+                Expert& xm = c->experts[m.expert];
+                if (xm.load_pending) {
+                    HIPCHK(c, hipStreamWaitEvent(c->sc, xm.loaded, 0));
+                    xm.load_pending = false;
+                }
+            }
+            rc = run_group_set(c, set, staged, ib);
+            if (rc) return rc;
+            for (const SetMember& m : set) {
+                Expert& xm = c->experts[m.expert];
+                HIPCHK(c, hipEventRecord(xm.buf->last_use, c->sc));
+                xm.buf->used = true;
+                launched[m.expert] = 1;
+                ++st.n_chunks;
+            }
+            st.n_grouped += (int32_t)set.size();
+            ++st.n_group_sets;
+            i += set.size();
+            continue;
+        }
+
         if (x.load_pending) {
             HIPCHK(c, hipStreamWaitEvent(c->sc, x.loaded, 0));
             x.load_pending = false;
@@ -811,6 +957,7 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
         HIPCHK(c, hipEventRecord(x.buf->last_use, c->sc));
         x.buf->used = true;
         launched[e] = 1;
+        ++i;
     }
     if (stats) *stats = st;
     return COE_OK;

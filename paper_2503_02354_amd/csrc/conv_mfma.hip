@@ -329,6 +329,44 @@ hipError_t launch(const void* x, const void* wp, const float* bias, const void* 
 // ---------------------------------------------------------------------------------------------------------------
 typedef __attribute__((address_space(3))) void lds_void;
 
+// Which group a tile belongs to in a grouped launch, and what that means for the tile: its first output pixel, the end of
+// the group's pixels, its position among the filter tiles, the group's filters and bias.  Tiles are numbered group by
+// group, filter tiles fastest; every group starts a fresh row of tiles, so no tile mixes two experts' weights.
+struct TileOrigin {
+    int m0, m_end, tile_n;
+    const uint16_t* wp;
+    const float* bias;
+};
+template <int BM>
+__device__ __forceinline__ TileOrigin locate_tile(int tile, int tiles_n, int PQ, int M, const uint16_t* wp, const float* bias,
+                                                  const GroupTable& gt, uint32_t off_w, uint32_t off_b)
+{
+    TileOrigin o;
+    if (gt.n == 0) {
+        o.tile_n = tile % tiles_n;
+        o.m0 = (tile / tiles_n) * BM;
+        o.m_end = M;
+        o.wp = wp;
+        o.bias = bias;
+        return o;
+    }
+    int g = 0, t = tile;
+    for (;; ++g) {                                            // the launch has exactly sum-of-tiles workgroups
+        const int rows = (gt.first_row[g + 1] - gt.first_row[g]) * PQ;
+        const int tiles_g = ((rows + BM - 1) / BM) * tiles_n;
+        if (t < tiles_g || g + 1 >= gt.n) break;
+        t -= tiles_g;
+    }
+    o.tile_n = t % tiles_n;
+    o.m0 = gt.first_row[g] * PQ + (t / tiles_n) * BM;
+    o.m_end = gt.first_row[g + 1] * PQ;
+    const char* base = (const char*)gt.weights[g];
+    o.wp = (const uint16_t*)(base + off_w);
+    o.bias = (const float*)(base + off_b);
+    return o;
+}
+
+
 // Epilogue of the direct-to-LDS kernels: + bias (+ residual), activation, round to bf16 in the accumulator layout (a
 // lane holds 4 consecutive channels of one pixel per accumulator quad), then through a wave-private LDS buffer of
 // 32 rows so that the global stores are 16 bytes per lane and cover whole rows of the wave tile (full cache lines
@@ -407,6 +445,19 @@ __device__ __forceinline__ void store_tile_via_lds(f32x16 (&acc)[MB][NB], uint16
     });
 }
 
+// host side of a grouped launch: the table and where a layer's filters and bias sit inside every group's blob
+struct Grouping {
+    GroupTable table{};              // table.n == 0: plain launch
+    uint32_t off_w = 0, off_b = 0;
+};
+inline long long count_tiles(long long M, long long PQ, int BM, int tiles_n, const GroupTable& gt)
+{
+    if (gt.n == 0) return (M + BM - 1) / BM * tiles_n;
+    long long total = 0;
+    for (int g = 0; g < gt.n; ++g) total += ((gt.first_row[g + 1] - gt.first_row[g]) * PQ + BM - 1) / BM * tiles_n;
+    return total;
+}
+
 template <int N> __device__ __forceinline__ void wait_vmcnt()
 {
     // s_waitcnt with only the vector-memory counter armed (expcnt and lgkmcnt fields at their maxima)
@@ -424,11 +475,11 @@ template <int N> __device__ __forceinline__ void wait_before_barrier()
 
 template <int BM, int BN, int WAVES_M, int WAVES_N>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv_igemm_dma_kernel(const uint16_t* __restrict__ x,
-                                                                   const uint16_t* __restrict__ wp,
-                                                                   const float* __restrict__ bias,
+                                                                   const uint16_t* __restrict__ wp_all,
+                                                                   const float* __restrict__ bias_all,
                                                                    const uint16_t* __restrict__ res,
                                                                    uint16_t* __restrict__ y, ConvShape s, int M,
-                                                                   int tiles_n)
+                                                                   int tiles_n, GroupTable gt, uint32_t off_w, uint32_t off_b)
 {
 #if defined(__HIP_DEVICE_COMPILE__)      // the host pass only needs the launch stub (LDS address-space casts do not exist there)
     constexpr int BK = 32, KS = 2, kStages = 3;
@@ -451,8 +502,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv_igemm_dma_kern
         int base = total / kXcds, rem = total % kXcds;
         tile = xcd * base + (xcd < rem ? xcd : rem) + slot;
     }
-    const int tile_n = tile % tiles_n, tile_m = tile / tiles_n;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const TileOrigin org = locate_tile<BM>(tile, tiles_n, s.P * s.Q, M, wp_all, bias_all, gt, off_w, off_b);
+    const int m0 = org.m0, n0 = org.tile_n * BN;
+    M = org.m_end;                                            // rows of this tile's group end here
+    const uint16_t* const wp = org.wp;
+    const float* const bias = org.bias;
     const int tid = threadIdx.x, lane = tid & 63, wid = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wid / WAVES_N, wn = wid % WAVES_N;
 
@@ -571,12 +625,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv_igemm_dma_kern
 
 template <int BM, int BN, int WAVES_M, int WAVES_N>
 hipError_t launch_dma(const void* x, const void* wp, const float* bias, const void* res, void* y, const ConvShape& s,
-                      hipStream_t stream)
+                      hipStream_t stream, const Grouping& grp = Grouping())
 {
     long long M = (long long)s.N * s.P * s.Q;
-    int tiles_m = (int)((M + BM - 1) / BM), tiles_n = s.K / BN;
-    long long total = (long long)tiles_m * tiles_n;
+    int tiles_n = s.K / BN;
+    long long total = count_tiles(M, (long long)s.P * s.Q, BM, tiles_n, grp.table);
     if (total > 0x7FFFFFFFll) return hipErrorInvalidValue;
+    if (total == 0) return hipSuccess;
     constexpr size_t kLdsBytes = 3 * (size_t)(BM + BN) * 32 * sizeof(uint16_t);
     constexpr int kThreads = 64 * WAVES_M * WAVES_N;
     static bool configured = false;
@@ -587,7 +642,8 @@ hipError_t launch_dma(const void* x, const void* wp, const float* bias, const vo
         configured = true;
     }
     hipLaunchKernelGGL((conv_igemm_dma_kernel<BM, BN, WAVES_M, WAVES_N>), dim3((unsigned)total), dim3(kThreads), kLdsBytes, stream,
-                       (const uint16_t*)x, (const uint16_t*)wp, bias, (const uint16_t*)res, (uint16_t*)y, s, (int)M, tiles_n);
+                       (const uint16_t*)x, (const uint16_t*)wp, bias, (const uint16_t*)res, (uint16_t*)y, s, (int)M, tiles_n,
+                       grp.table, grp.off_w, grp.off_b);
     return hipGetLastError();
 }
 
@@ -606,11 +662,11 @@ constexpr int kSlabMaxW = 56;
 
 template <int BM, int BN, int WAVES_M, int WAVES_N>
 __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_slab_kernel(const uint16_t* __restrict__ x,
-                                                                    const uint16_t* __restrict__ wp,
-                                                                    const float* __restrict__ bias,
+                                                                    const uint16_t* __restrict__ wp_all,
+                                                                    const float* __restrict__ bias_all,
                                                                     const uint16_t* __restrict__ res,
                                                                     uint16_t* __restrict__ y, ConvShape s, int M,
-                                                                    int tiles_n)
+                                                                    int tiles_n, GroupTable gt, uint32_t off_w, uint32_t off_b)
 {
 #if defined(__HIP_DEVICE_COMPILE__)
     constexpr int BK = 32, KS = 2, kTaps = 9;
@@ -638,8 +694,11 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_slab_kernel
         int base = total / kXcds, rem = total % kXcds;
         tile = xcd * base + (xcd < rem ? xcd : rem) + slot;
     }
-    const int tile_n = tile % tiles_n, tile_m = tile / tiles_n;
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const TileOrigin org = locate_tile<BM>(tile, tiles_n, s.H * s.W, M, wp_all, bias_all, gt, off_w, off_b);
+    const int m0 = org.m0, n0 = org.tile_n * BN;
+    M = org.m_end;                                            // rows of this tile's group end here
+    const uint16_t* const wp = org.wp;
+    const float* const bias = org.bias;
     const int tid = threadIdx.x, lane = tid & 63, wid = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wid / WAVES_N, wn = wid % WAVES_N;
     const int W = s.W, H = s.H;
@@ -811,12 +870,13 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_slab_kernel
 
 template <int BM, int BN, int WAVES_M, int WAVES_N>
 hipError_t launch_slab(const void* x, const void* wp, const float* bias, const void* res, void* y, const ConvShape& s,
-                       hipStream_t stream)
+                       hipStream_t stream, const Grouping& grp = Grouping())
 {
     long long M = (long long)s.N * s.P * s.Q;
-    int tiles_m = (int)((M + BM - 1) / BM), tiles_n = s.K / BN;
-    long long total = (long long)tiles_m * tiles_n;
+    int tiles_n = s.K / BN;
+    long long total = count_tiles(M, (long long)s.P * s.Q, BM, tiles_n, grp.table);
     if (total > 0x7FFFFFFFll) return hipErrorInvalidValue;
+    if (total == 0) return hipSuccess;
     constexpr int kSbCap = (BM + 2 * kSlabMaxW + 2 + 15) / 16;
     constexpr size_t kLdsBytes = (2 * (size_t)(kSbCap * 512 + 64) + 512 + 3 * (size_t)BN * 32) * sizeof(uint16_t);
     constexpr int kThreads = 64 * WAVES_M * WAVES_N;
@@ -828,7 +888,8 @@ hipError_t launch_slab(const void* x, const void* wp, const float* bias, const v
         configured = true;
     }
     hipLaunchKernelGGL((conv3x3_slab_kernel<BM, BN, WAVES_M, WAVES_N>), dim3((unsigned)total), dim3(kThreads), kLdsBytes, stream,
-                       (const uint16_t*)x, (const uint16_t*)wp, bias, (const uint16_t*)res, (uint16_t*)y, s, (int)M, tiles_n);
+                       (const uint16_t*)x, (const uint16_t*)wp, bias, (const uint16_t*)res, (uint16_t*)y, s, (int)M, tiles_n,
+                       grp.table, grp.off_w, grp.off_b);
     return hipGetLastError();
 }
 
@@ -891,6 +952,37 @@ hipError_t conv_mfma(const void* x, const void* wp, const float* bias, const voi
     if (s.K % 64 == 0) return launch_dma<128, 64, 2, 2>(x, wp, bias, res, y, s, stream);
     // filter counts that are not a multiple of 64: the register-staged kernel
     return pick_tile<32>(x, wp, bias, res, y, s, stream);
+}
+
+bool conv_mfma_groupable(const ConvShape& s)
+{
+    return conv_mfma_supported(s) && s.K % 64 == 0;
+}
+
+hipError_t conv_mfma_grouped(const void* x, const GroupTable& groups, size_t off_w, size_t off_b, const void* res, void* y,
+                             const ConvShape& s, hipStream_t stream)
+{
+    if (!conv_mfma_groupable(s) || groups.n <= 0 || groups.n > kMaxGroups || groups.first_row[0] != 0 ||
+        groups.first_row[groups.n] != s.N || off_w > 0x7FFFFFFFull || off_b > 0x7FFFFFFFull)
+        return hipErrorInvalidValue;
+    for (int g = 0; g < groups.n; ++g)
+        if (groups.first_row[g + 1] < groups.first_row[g] || !groups.weights[g]) return hipErrorInvalidValue;
+    long long M = (long long)s.N * s.P * s.Q;
+    if (M <= 0) return hipSuccess;
+    if ((long long)s.N * s.H * s.W * s.C * 2 >= 0x7FFFFFFFll || (long long)s.K * s.R * s.S * s.C * 2 >= 0x7FFFFFFFll ||
+        M >= 0x7FFFFFFFll - 256)
+        return hipErrorInvalidValue;
+    Grouping grp;
+    grp.table = groups;
+    grp.off_w = (uint32_t)off_w;
+    grp.off_b = (uint32_t)off_b;
+    // groups are small: 128-row tiles waste fewer rows past a group's end than 256-row ones
+    if (conv_mfma_uses_slab(s)) {
+        if (s.K % 128 == 0) return launch_slab<128, 128, 2, 2>(x, nullptr, nullptr, res, y, s, stream, grp);
+        return launch_slab<128, 64, 4, 1>(x, nullptr, nullptr, res, y, s, stream, grp);
+    }
+    if (s.K % 128 == 0) return launch_dma<128, 128, 2, 2>(x, nullptr, nullptr, res, y, s, stream, grp);
+    return launch_dma<128, 64, 2, 2>(x, nullptr, nullptr, res, y, s, stream, grp);
 }
 
 }  // namespace k

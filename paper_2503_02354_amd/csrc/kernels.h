@@ -40,6 +40,24 @@ struct ConvShape {
     int32_t N, H, W, C, K, R, S, stride, pad, P, Q, act;
 };
 
+// Several groups of requests in ONE launch, each group with the weights of its own expert; the experts share an
+// architecture, so only the weight base differs (request arranging leaves many groups of a handful of requests, and a
+// launch per layer and group would be all launch latency).  The requests of the groups are consecutive rows of the
+// batch.  The table travels as a kernel argument: no device copy per launch.
+constexpr int kMaxGroups = 32;
+struct GroupTable {
+    int32_t n;                            // groups; 0 = plain launch with one set of weights
+    int32_t first_row[kMaxGroups + 1];    // requests [first_row[g], first_row[g + 1]) of the batch belong to group g
+    const void* weights[kMaxGroups];      // device blob of group g's expert
+};
+// per-group routing data for the head kernel
+struct GroupRoutes {
+    int32_t expert[kMaxGroups];           // expert id
+    int32_t succ_off[kMaxGroups];         // offset of its successor list in RouteArgs::succ
+    int32_t n_route[kMaxGroups];
+    int32_t slot_off[kMaxGroups];         // offset of the group's first request in RouteArgs::slot
+};
+
 // Plain convolution kernel for any shape, fp32 or bf16 storage, fp32 FMA accumulation.
 hipError_t conv_direct(int dtype, const void* x, const void* w, const float* bias, const void* res, void* y,
                        const ConvShape& s, hipStream_t stream);
@@ -53,6 +71,11 @@ bool conv_mfma_uses_slab(const ConvShape& s);
 void pack_filters_mfma(const uint16_t* w, uint16_t* out, int K, int red);
 hipError_t conv_mfma(const void* x, const void* w, const float* bias, const void* res, void* y, const ConvShape& s,
                      hipStream_t stream);
+// Grouped form: s.N = requests of all groups; group g's (repacked) filters sit at weights[g] + off_w, its bias at
+// weights[g] + off_b.  Output tiles never straddle two groups.  Only shapes with K % 64 == 0 (conv_mfma_groupable).
+bool conv_mfma_groupable(const ConvShape& s);
+hipError_t conv_mfma_grouped(const void* x, const GroupTable& groups, size_t off_w, size_t off_b, const void* res, void* y,
+                             const ConvShape& s, hipStream_t stream);
 
 // bf16 convolution with few input channels (C not a multiple of 32, e.g. the C=3 stem) on the matrix cores.
 // Requires K in {32, 64}, stride*C even, no residual.  fused_pool: the 3x3 / stride 2 / pad 1 max pool that follows is
@@ -67,6 +90,11 @@ hipError_t maxpool(int dtype, const void* x, void* y, int32_t N, int32_t H, int3
 // Global average pool + FC + argmax routing.  x: [N][HW][C]; w: [ncls][C] in dtype; b: [ncls] fp32.
 hipError_t head_gap_fc(int dtype, const void* x, const void* w, const float* b, int32_t N, int32_t HW, int32_t C,
                        int32_t ncls, const RouteArgs& r, hipStream_t stream);
+// Grouped form: FC weights at weights[g] + off_w, bias at + off_b; r.succ is the base of all successor lists and r.slot
+// the base of the slot array, both indexed through `routes`; r.expert and r.n_route are ignored.
+hipError_t head_gap_fc_grouped(int dtype, const void* x, const GroupTable& groups, size_t off_w, size_t off_b, int32_t N,
+                               int32_t HW, int32_t C, int32_t ncls, const RouteArgs& r, const GroupRoutes& routes,
+                               hipStream_t stream);
 
 // ---- transformer-shaped experts (bf16 only) --------------------------------------------------------------------
 // Patches of a non-overlapping convolution (stride == window, no padding) as GEMM rows:

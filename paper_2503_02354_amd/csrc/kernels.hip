@@ -312,10 +312,23 @@ template <typename T> __host__ __device__ inline bool head_vector_path(int C)
 template <typename T>
 __global__ __launch_bounds__(kHeadThreads) void head_gap_fc_kernel(const T* __restrict__ x, const T* __restrict__ w,
                                                                    const float* __restrict__ b, int HW, int C, int ncls,
-                                                                   RouteArgs r)
+                                                                   RouteArgs r, GroupTable gt, GroupRoutes gr, uint32_t off_w,
+                                                                   uint32_t off_b)
 {
     extern __shared__ float smem[];          // feat[C] | part[groups][C] | logit[ncls]
     int row = blockIdx.x;
+    if (gt.n > 0) {
+        // grouped launch: this request's group decides the FC weights and the routing rule
+        int g = 0;
+        while (g + 1 < gt.n && row >= gt.first_row[g + 1]) ++g;
+        const char* base = (const char*)gt.weights[g];
+        w = (const T*)(base + off_w);
+        b = (const float*)(base + off_b);
+        r.expert = gr.expert[g];
+        r.succ = r.succ + gr.succ_off[g];
+        r.n_route = gr.n_route[g];
+        if (r.slot) r.slot = r.slot + (gr.slot_off[g] - gt.first_row[g]);
+    }
     const T* xp = x + (size_t)row * HW * C;
     int groups = C < kHeadThreads ? kHeadThreads / C : 1;      // position groups when there are few channels
     if (head_vector_path<T>(C)) groups = kHeadThreads / (C / 8);
@@ -544,12 +557,37 @@ hipError_t head_gap_fc(int dtype, const void* x, const void* w, const float* b, 
     if (dtype == 1 && head_vector_path<uint16_t>(C)) groups = kHeadThreads / (C / 8);      // partial sums of the 16-byte path
     size_t smem = sizeof(float) * ((size_t)C + (size_t)groups * C + (size_t)ncls);
     if (smem > 60 * 1024) return hipErrorInvalidValue;
+    const GroupTable gt{};
+    const GroupRoutes gr{};
     if (dtype == 1)
         hipLaunchKernelGGL(head_gap_fc_kernel<uint16_t>, dim3(N), dim3(kHeadThreads), smem, stream, (const uint16_t*)x,
-                           (const uint16_t*)w, b, HW, C, ncls, r);
+                           (const uint16_t*)w, b, HW, C, ncls, r, gt, gr, 0u, 0u);
     else
         hipLaunchKernelGGL(head_gap_fc_kernel<float>, dim3(N), dim3(kHeadThreads), smem, stream, (const float*)x,
-                           (const float*)w, b, HW, C, ncls, r);
+                           (const float*)w, b, HW, C, ncls, r, gt, gr, 0u, 0u);
+    return hipGetLastError();
+}
+
+hipError_t head_gap_fc_grouped(int dtype, const void* x, const GroupTable& groups, size_t off_w, size_t off_b, int32_t N,
+                               int32_t HW, int32_t C, int32_t ncls, const RouteArgs& r, const GroupRoutes& routes,
+                               hipStream_t stream)
+{
+    if (N <= 0) return hipSuccess;
+    if (groups.n <= 0 || groups.n > kMaxGroups || groups.first_row[0] != 0 || groups.first_row[groups.n] != N ||
+        off_w > 0x7FFFFFFFull || off_b > 0x7FFFFFFFull)
+        return hipErrorInvalidValue;
+    int pgroups = C < kHeadThreads ? kHeadThreads / C : 1;
+    if (dtype == 1 && head_vector_path<uint16_t>(C)) pgroups = kHeadThreads / (C / 8);
+    size_t smem = sizeof(float) * ((size_t)C + (size_t)pgroups * C + (size_t)ncls);
+    if (smem > 60 * 1024) return hipErrorInvalidValue;
+    if (dtype == 1)
+        hipLaunchKernelGGL(head_gap_fc_kernel<uint16_t>, dim3(N), dim3(kHeadThreads), smem, stream, (const uint16_t*)x,
+                           (const uint16_t*)nullptr, (const float*)nullptr, HW, C, ncls, r, groups, routes, (uint32_t)off_w,
+                           (uint32_t)off_b);
+    else
+        hipLaunchKernelGGL(head_gap_fc_kernel<float>, dim3(N), dim3(kHeadThreads), smem, stream, (const float*)x,
+                           (const float*)nullptr, (const float*)nullptr, HW, C, ncls, r, groups, routes, (uint32_t)off_w,
+                           (uint32_t)off_b);
     return hipGetLastError();
 }
 

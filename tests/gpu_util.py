@@ -13,7 +13,7 @@ def device_tensor(x: np.ndarray):
 
 
 def run_chain_gpu(B, wl, blobs, x, first_expert=None, *, max_batch=0, cap_experts=None, arrival=None, on_device=True,
-                  profile=False, ctx=None, keep=False):
+                  profile=False, ctx=None, keep=False, group_small=0):
     """Submit x in arrival batches, one coe_step after each submit, then step until done; collect everything.
     Returns dict(logits, path, ids, stats, switch_log[, ctx])."""
     import torch
@@ -21,7 +21,8 @@ def run_chain_gpu(B, wl, blobs, x, first_expert=None, *, max_batch=0, cap_expert
     own = ctx is None
     if own:
         ctx = B.Context(max_requests=max(n, 1), max_stages=wl.max_stages, max_batch=max_batch,
-                        cache_cap_experts=wl.cache_cap_experts if cap_experts is None else cap_experts, profile=profile)
+                        cache_cap_experts=wl.cache_cap_experts if cap_experts is None else cap_experts, profile=profile,
+                        group_small=group_small)
         B.setup_workload(ctx, wl, blobs)
     arrival = arrival or n or 1
     stats = []

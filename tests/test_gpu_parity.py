@@ -451,3 +451,29 @@ def test_forward_is_deterministic_and_batch_independent(B):
     for r in runs[1:]:
         assert np.array_equal(r, runs[0])
     assert np.array_equal(small, runs[0][:48])
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# small groups sharing launches: same bits as one launch sequence per group, with and without a capped cache
+# ---------------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("cap", [0, 5])
+def test_grouped_launches_give_the_same_bits(B, oracle, G, cap):
+    """Full-width ResNet-18-shaped experts (every conv has a multiple of 64 filters, so the architecture is
+    groupable), 1 root -> 15 leaves, 160 requests: the leaf groups hold ~10 requests each and share launches.
+    Grouping must not change a bit, must respect the cache policy's switch log, and must still match the oracle."""
+    wl = W.config2(160, hw=64, n_experts=16, width=64, calibrated=False)
+    G.calibrate_workload(wl, n_cal=48)
+    blobs = [wl.blob(e) for e in range(16)]
+    x, sub, want, _ = G.guarded_inputs(wl, blobs, range(160))
+    one = run_chain_gpu(B, wl, blobs, x, max_batch=128, cap_experts=cap, group_small=-1)
+    grp = run_chain_gpu(B, wl, blobs, x, max_batch=128, cap_experts=cap)
+    assert sum(st.n_grouped for rc, st in one["stats"]) == 0
+    stats = [st for rc, st in grp["stats"] if rc == B.COE_OK]
+    assert stats[1].n_grouped >= 8 and 1 <= stats[1].n_group_sets < stats[1].n_grouped     # several groups per launch set
+    assert np.array_equal(one["path"], grp["path"])
+    assert np.array_equal(one["logits"], grp["logits"])
+    assert one["switch_log"] == grp["switch_log"]
+    assert [st.n_chunks for rc, st in one["stats"]] == [st.n_chunks for rc, st in grp["stats"]]
+    assert_chain_parity(grp, want, REL_TOL_BF16)
+    if cap:
+        assert sum(st.n_misses for st in stats) > 0
