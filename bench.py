@@ -48,6 +48,8 @@ WORKLOAD_TEXT = {
                "all resident",
     "config3": "config3: 64 ResNet-50-shaped bf16 experts, 16384 requests 3x224x224 arriving in batches of 512, 2-stage tree "
                "(1 root -> 63 leaves, Zipf(1.1) usage), device cache capped at 16 experts",
+    "config4": "config4: 120 mixed ResNet-18/ResNet-50-shaped bf16 experts in a 3-stage DAG with shared downstream experts, "
+               "8192 requests 3x224x224 with skewed group sizes, all resident",
     "config5": "config5: 32 ViT-B/16-shaped bf16 experts, 4096 requests 3x224x224, 2-stage tree (1 root -> 31 leaves, uniform "
                "usage), device cache capped at 12 experts",
 }
@@ -58,12 +60,14 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="config2", choices=["config2", "config3", "config5"],
+    ap.add_argument("--workload", default="config2", choices=["config2", "config3", "config4", "config5"],
                     help="config2 (default) is the benchmark line; config3 / config5 have a capped expert cache and report "
                          "switch bandwidth, overlap and host planning time next to their throughput")
     ap.add_argument("--requests", type=int, default=0, help="0 = the workload's own request count")
     ap.add_argument("--max-batch", type=int, default=512)
     ap.add_argument("--cpu-sample", type=int, default=384, help="requests the oracle is timed on (0 = skip)")
+    ap.add_argument("--group-small", type=int, default=0,
+                    help="groups of at most this many requests share launches (0 = the library's default, -1 = never)")
     ap.add_argument("--no-profile", action="store_true", help="do not time kernel classes with events")
     ap.add_argument("--profile-every", type=int, default=7,
                     help="time every k-th launch of each kernel class (an event pair costs a pipeline bubble; 7 is coprime "
@@ -80,7 +84,7 @@ def main():
     from paper_2503_02354_amd import binding as B
     from paper_2503_02354_amd import workloads as W
 
-    make = {"config2": W.config2, "config3": W.config3, "config5": W.config5}[args.workload]
+    make = {"config2": W.config2, "config3": W.config3, "config4": W.config4, "config5": W.config5}[args.workload]
     wl = make(args.requests) if args.requests else make()
     n = wl.n_requests
     arch = wl.archs[0]
@@ -92,7 +96,8 @@ def main():
     t_gen = time.time() - t0
 
     ctx = B.Context(max_requests=n, max_stages=wl.max_stages, max_batch=args.max_batch,
-                    cache_cap_experts=wl.cache_cap_experts, profile=0 if args.no_profile else args.profile_every)
+                    cache_cap_experts=wl.cache_cap_experts, profile=0 if args.no_profile else args.profile_every,
+                    group_small=args.group_small)
     B.setup_workload(ctx, wl, blobs)
     dev = torch.from_numpy(x.view(np.int16)).cuda()
     torch.cuda.synchronize()
@@ -105,7 +110,8 @@ def main():
         # requests arrive in batches of `arrival`; every arrival is followed by one stage over everything pending
         steps_run = 0
         for s0 in range(0, n, arrival):
-            ctx.coe_submit(min(arrival, n - s0), dev.data_ptr() + s0 * per, True)
+            m = min(arrival, n - s0)
+            ctx.coe_submit(m, dev.data_ptr() + s0 * per, True, None if wl.first_expert is None else wl.first_expert[s0:s0 + m])
             rc, st = ctx.coe_step()
             step_stats.append(st)
             steps_run += 1
@@ -143,7 +149,8 @@ def main():
             issued = ctx.coe_profile_issued(k)
             if launches:
                 prof[name] = {"launches": launches, "ms": round(ms, 3), "work": work, "issued": issued}
-    flops_per_step = 2.0 * sum(W.arch_macs(wl.archs[wl.expert_arch[0]]) for _ in range(wl.max_stages)) * n
+    # (FLOPs of the experts every request actually visited, from the collected paths)
+    macs_of = [W.arch_macs(wl.archs[wl.expert_arch[e]]) for e in range(wl.graph.n_experts)]
     # the matrix-core convolution classes; the roofline object is for the one that takes the most time
     mfma_kernels = {"conv_slab": "conv3x3_slab_kernel", "conv_mfma": "conv_igemm_dma_kernel", "attention": "attention_kernel"}
     est_ms = {name: prof[name]["ms"] / prof[name]["launches"] * prof[name]["issued"] for name in mfma_kernels if name in prof}
@@ -173,6 +180,8 @@ def main():
             other[name] = entry
 
     leaves = np.bincount(path[:, 1][path[:, 1] >= 0], minlength=wl.graph.n_experts)[1:]
+    visits = np.bincount(path[path >= 0].ravel(), minlength=wl.graph.n_experts)
+    flops_per_step = 2.0 * float(np.dot(visits, macs_of))
 
     # expert cache: switches of the timed region (copy-stream events bracket every H2D copy) and the host planning time
     cache = None
@@ -210,7 +219,12 @@ def main():
                    "stages": wl.max_stages, "gflop_per_request": round(flops_per_step / n / 1e9, 3)},
         "end_to_end_tflops": round(flops_per_step / (ms_per_step * 1e-3) / 1e12, 2),
         "end_to_end_frac_of_bf16_peak": round(flops_per_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-        "roofline": roofline, "kernel_classes": other, "expert_cache": cache, "cpu_baseline": cpu,
+        "roofline": roofline, "kernel_classes": other, "expert_cache": cache,
+        "grouped_launches": None if not step_stats else {
+            "groups_per_pass": sum(st.n_groups for st in step_stats) // max(args.steps, 1),
+            "of_them_in_shared_launches": sum(st.n_grouped for st in step_stats) // max(args.steps, 1),
+            "shared_launch_sequences": sum(st.n_group_sets for st in step_stats) // max(args.steps, 1)},
+        "cpu_baseline": cpu,
         "leaf_group_sizes": {"min": int(leaves.min()), "max": int(leaves.max())},
         "input_generation_s": round(t_gen, 1),
         "paper_context": "the paper reports 4.5x-12x throughput over prior systems (Samba-CoE variants) on an RTX 3080Ti/"

@@ -896,24 +896,27 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
     auto small = [&](int32_t e) {
         return group_small > 0 && c->h_cnt[e] <= group_small && c->archs[c->experts[e].arch].groupable;
     };
-    for (size_t i = 0; i < order.size();) {
+    for (size_t i = 0; i < order.size(); ++i) {
         const int32_t e = order[i];
+        if (launched[e]) continue;                             // ran earlier, in a set with other small groups
         rc = issue_ready_loads();
         if (rc) return rc;
         Expert& x = c->experts[e];
         if (!x.buf) return fail(c, COE_ESTATE, "internal: expert not loaded at launch time");
 
-        // small groups that follow in the plan, of the same architecture and with their experts on the device (or on
-        // their way), run together: one launch per layer for all of them
+        // small groups further down the plan, of the same architecture and with their experts on the device (or on
+        // their way), run together with this one: one launch per layer for all of them.  Pulling a group forward changes
+        // neither results (they do not depend on the order) nor the switches (those are issued in plan order above, and
+        // a group that has run only frees its expert earlier).
         std::vector<SetMember> set;
         if (small(e)) {
             set.push_back({e, off[e], c->h_cnt[e]});
             int32_t rows = c->h_cnt[e];
-            size_t j = i + 1;
-            for (; j < order.size() && (int32_t)set.size() < coe::k::kMaxGroups; ++j) {
+            for (size_t j = i + 1; j < order.size() && (int32_t)set.size() < coe::k::kMaxGroups; ++j) {
                 const int32_t f = order[j];
-                if (!small(f) || c->experts[f].arch != x.arch || rows + c->h_cnt[f] > c->cfg.max_batch) break;
-                if (!c->experts[f].buf) break;                 // its switch still waits for a victim of this very set
+                if (launched[f] || !small(f) || c->experts[f].arch != x.arch) continue;
+                if (!c->experts[f].buf) continue;              // its switch has not been issued yet
+                if (rows + c->h_cnt[f] > c->cfg.max_batch) continue;
                 set.push_back({f, off[f], c->h_cnt[f]});
                 rows += c->h_cnt[f];
             }
@@ -937,7 +940,6 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
             }
             st.n_grouped += (int32_t)set.size();
             ++st.n_group_sets;
-            i += set.size();
             continue;
         }
 
@@ -957,7 +959,6 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
         HIPCHK(c, hipEventRecord(x.buf->last_use, c->sc));
         x.buf->used = true;
         launched[e] = 1;
-        ++i;
     }
     if (stats) *stats = st;
     return COE_OK;
