@@ -718,37 +718,6 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_slab_kernel
     }
     __syncthreads();
 
-    // operand addresses (elements, relative to a slab buffer) of this lane's pixel rows for the nine positions.
-    // Slab row rho, chunk c sits at element 32 rho + 8 (c ^ f(rho & 15)) (16-row blocks of 512 elements are contiguous).
-    // Kept free of branches and integer divisions: this runs once per tile and a 64-channel layer has only 18 steps
-    // to amortise it over.  Pixel coordinates come from the tile's first pixel (one wave-uniform division) plus small
-    // exact float divisions (numerators below 2^13, divisors up to 56^2).
-    int32_t a_addr[MB][kTaps];
-    {
-        const int HW = H * W;
-        const int pq0 = __builtin_amdgcn_readfirstlane(m0 % HW);
-        const float inv_hw = 1.0f / (float)HW, inv_w = 1.0f / (float)W;
-        const int khalf = lane >> 5;
-#pragma unroll
-        for (int i = 0; i < MB; ++i) {
-            const int ml = wm * WM + i * 32 + (lane & 31);
-            const int ok = (m0 + ml) < M;
-            const int t0 = pq0 + ml;                                       // < H*W + BM
-            const int pq = t0 - (int)(((float)t0 + 0.5f) * inv_hw) * HW;
-            const int p = (int)(((float)pq + 0.5f) * inv_w), q = pq - p * W;
-            const int row_in[3] = {ok & (p > 0), ok, ok & (p < H - 1)};
-            const int col_in[3] = {q > 0, 1, q < W - 1};
-#pragma unroll
-            for (int rr = 0; rr < 3; ++rr)
-#pragma unroll
-                for (int tt = 0; tt < 3; ++tt) {
-                    const int rho = ml + rr * W + tt;                      // = ml + (W + 1) + (rr - 1) W + (tt - 1)
-                    const int chunk = (khalf ^ (rho >> 1) ^ ((rho >> 3) & 1)) & 3;
-                    const int a = rho * 32 + chunk * 8;
-                    a_addr[i][rr * 3 + tt] = (row_in[rr] & col_in[tt]) ? a : ZERO_OFF + khalf * 8;
-                }
-        }
-    }
     // slab loader: row lane / 4 of a block, chunk chosen by the slot this lane fills
     const int ld_row = lane >> 2;
     const int ld_chunk = (lane & 3) ^ swz(ld_row);
@@ -792,6 +761,39 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_slab_kernel
     issue_b(0, 0, 0);
     issue_slab(cblocks, 8, 0);                                              // lands in the spare block
     issue_b(0, 1, 1);
+
+    // (built while the first loads are in flight)
+    // operand addresses (elements, relative to a slab buffer) of this lane's pixel rows for the nine positions.
+    // Slab row rho, chunk c sits at element 32 rho + 8 (c ^ f(rho & 15)) (16-row blocks of 512 elements are contiguous).
+    // Kept free of branches and integer divisions: this runs once per tile and a 64-channel layer has only 18 steps
+    // to amortise it over.  Pixel coordinates come from the tile's first pixel (one wave-uniform division) plus small
+    // exact float divisions (numerators below 2^13, divisors up to 56^2).
+    int32_t a_addr[MB][kTaps];
+    {
+        const int HW = H * W;
+        const int pq0 = __builtin_amdgcn_readfirstlane(m0 % HW);
+        const float inv_hw = 1.0f / (float)HW, inv_w = 1.0f / (float)W;
+        const int khalf = lane >> 5;
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
+            const int ml = wm * WM + i * 32 + (lane & 31);
+            const int ok = (m0 + ml) < M;
+            const int t0 = pq0 + ml;                                       // < H*W + BM
+            const int pq = t0 - (int)(((float)t0 + 0.5f) * inv_hw) * HW;
+            const int p = (int)(((float)pq + 0.5f) * inv_w), q = pq - p * W;
+            const int row_in[3] = {ok & (p > 0), ok, ok & (p < H - 1)};
+            const int col_in[3] = {q > 0, 1, q < W - 1};
+#pragma unroll
+            for (int rr = 0; rr < 3; ++rr)
+#pragma unroll
+                for (int tt = 0; tt < 3; ++tt) {
+                    const int rho = ml + rr * W + tt;                      // = ml + (W + 1) + (rr - 1) W + (tt - 1)
+                    const int chunk = (khalf ^ (rho >> 1) ^ ((rho >> 3) & 1)) & 3;
+                    const int a = rho * 32 + chunk * 8;
+                    a_addr[i][rr * 3 + tt] = (row_in[rr] & col_in[tt]) ? a : ZERO_OFF + khalf * 8;
+                }
+        }
+    }
 
     // Activation operands of position tap+1 are read while position tap is multiplied: the slab does not change
     // inside a channel block, so only the filter operands have to wait for the step's barrier.  (With 128-row wave
