@@ -66,6 +66,10 @@ def main():
     ap.add_argument("--requests", type=int, default=0, help="0 = the workload's own request count")
     ap.add_argument("--max-batch", type=int, default=512)
     ap.add_argument("--cpu-sample", type=int, default=384, help="requests the oracle is timed on (0 = skip)")
+    ap.add_argument("--arrivals-per-step", type=int, default=1,
+                    help="arrival batches that queue up between two stages (1: a stage after every arrival, the least "
+                         "favourable case; more: later arrivals join the groups of earlier ones before they run, which is "
+                         "what request arranging is for)")
     ap.add_argument("--group-small", type=int, default=0,
                     help="groups of at most this many requests share launches (0 = the library's default, -1 = never)")
     ap.add_argument("--no-profile", action="store_true", help="do not time kernel classes with events")
@@ -109,9 +113,11 @@ def main():
     def one_step():
         # requests arrive in batches of `arrival`; every arrival is followed by one stage over everything pending
         steps_run = 0
-        for s0 in range(0, n, arrival):
+        for k, s0 in enumerate(range(0, n, arrival)):
             m = min(arrival, n - s0)
             ctx.coe_submit(m, dev.data_ptr() + s0 * per, True, None if wl.first_expert is None else wl.first_expert[s0:s0 + m])
+            if (k + 1) % max(args.arrivals_per_step, 1) and s0 + arrival < n:
+                continue
             rc, st = ctx.coe_step()
             step_stats.append(st)
             steps_run += 1
@@ -215,7 +221,8 @@ def main():
         "metric": "requests/s through a multi-stage CoE chain (1 GPU)", "value": round(value, 1), "unit": "requests/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": WORKLOAD_TEXT[args.workload], "requests": n, "arrival_batch": arrival, "max_batch": args.max_batch,
+        "config": {"workload": WORKLOAD_TEXT[args.workload], "requests": n, "arrival_batch": arrival,
+                   "arrivals_per_step": args.arrivals_per_step, "max_batch": args.max_batch,
                    "stages": wl.max_stages, "gflop_per_request": round(flops_per_step / n / 1e9, 3)},
         "end_to_end_tflops": round(flops_per_step / (ms_per_step * 1e-3) / 1e12, 2),
         "end_to_end_frac_of_bf16_peak": round(flops_per_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
