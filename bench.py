@@ -26,9 +26,9 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 # HBM bytes per launch of conv3x3_slab_kernel on this workload, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
 # scaled by what the same counters read for the gather kernel's plain copy (profiles/conv3x3_slab_config2_hbm_counters.md).
 # Tied to the kernel source it was measured on: any edit of that file makes bench.py report null again.
-SLAB_TRAFFIC_BYTES_PER_LAUNCH = 205.0e6
+SLAB_TRAFFIC_BYTES_PER_LAUNCH = 205.2e6
 SLAB_TRAFFIC_SOURCE = ("paper_2503_02354_amd/csrc/conv_mfma.hip",
-                       "9bf5e6deb126dc94d616c46622d0565927fe578785cec6f5f54b027b684a7ded")
+                       "088fe84c84bdd03510c3829c25b1a9adada2b3df5f9f2502d4924600c2d8a68c")
 
 
 def measured_traffic(kernel: str):
