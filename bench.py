@@ -28,7 +28,7 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 # Tied to the kernel source it was measured on: any edit of that file makes bench.py report null again.
 SLAB_TRAFFIC_BYTES_PER_LAUNCH = 205.2e6
 SLAB_TRAFFIC_SOURCE = ("paper_2503_02354_amd/csrc/conv_mfma.hip",
-                       "088fe84c84bdd03510c3829c25b1a9adada2b3df5f9f2502d4924600c2d8a68c")
+                       "e962cc54a067c87b8364153a90c8763675bd17675ae8f53583eeb9e7f3ce6cda")
 
 
 def measured_traffic(kernel: str):

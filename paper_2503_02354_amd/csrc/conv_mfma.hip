@@ -2,22 +2,29 @@
 //
 // GEMM view: out[m][k] = sum_{r,s,c} x[n][p*stride-pad+r][q*stride-pad+s][c] * w[k][r][s][c], m = (n,p,q) flattened.
 // NHWC activations make the reduction index contiguous in c, so a reduction step is one (r,s) position and a run
-// of BK channels.  A workgroup (4 or 8 wavefronts of 64) owns a BM x BN output tile.
+// of 32 channels.  A workgroup of four wavefronts owns a BM x BN output tile.  Three kernels, picked by conv_mfma():
+//   1. conv3x3_slab_kernel   3x3, stride 1, pad 1, filter count a multiple of 64: the activation rows a tile needs are
+//                            DMA'd into LDS once per 32-channel block and serve all nine window positions;
+//   2. conv_igemm_dma_kernel any other shape with a filter count that is a multiple of 64: both operands DMA'd
+//                            global -> LDS per reduction step;
+//   3. conv_igemm_bf16_kernel (below) the rest: operands staged through registers.
+// Common to all three:
+//   * Filters are repacked once, when an expert is registered, into matrix-core fragment order (pack_filters_mfma),
+//     so a filter slab is contiguous in memory and in LDS and an operand read is one linear 1 KiB access.
+//   * v_mfma_f32_32x32x16_bf16 is issued with the filter fragment as the first operand, so a lane ends up holding 4
+//     consecutive output channels of one pixel per accumulator quad.
+//   * Epilogue in fp32: + bias (+ residual), activation, one round-to-nearest-even to bf16 (v_cvt_pk_bf16_f32).
+//   * Zero padding of the convolution and rows past the end of a tile come from buffer loads whose out-of-range
+//     offsets return zero; which window positions fall inside the image is a per-row bit mask computed once.
+// The register-staged kernel:
 //   * Loads run kDepth steps ahead: each step's activation slab (BM x BK) and filter slab (BN x BK) travel
 //     global -> registers (kDepth register stages) -> LDS (two stages) -> matrix-core operands.  Every step issues
 //     the same loads unconditionally, so the wait before a register stage is moved to LDS can leave the younger
 //     stages in flight.
 //   * A wave64 vector instruction occupies a SIMD for 4 cycles and a step has only 16 matrix-core instructions per
-//     wavefront, so per-step address arithmetic is kept to a few instructions per load: activations are fetched with
-//     buffer loads whose out-of-range offsets return zero (the zero padding of the convolution and the rows past
-//     the end of the tile cost one select of the offset), the position inside the window is a scalar offset shared
-//     by all lanes, and which window positions fall inside the image is a per-row bit mask computed once.
+//     wavefront, so per-step address arithmetic is kept to a few instructions per load (the position inside the
+//     window is a scalar offset shared by all lanes).
 //   * Activation rows are padded by 16 bytes in LDS so the 16-byte operand reads are bank-conflict free.
-//   * Filters are repacked once, when an expert is registered, into matrix-core fragment order (pack_filters_mfma),
-//     so a filter slab is contiguous in memory and in LDS and an operand read is one linear 1 KiB access.
-//   * v_mfma_f32_32x32x16_bf16 is issued with the filter fragment as the first operand, so a lane ends up holding 4
-//     consecutive output channels of one pixel per accumulator quad: the epilogue stores 8 bytes at a time.
-// Epilogue in fp32: + bias (+ residual), activation, one round-to-nearest-even to bf16 (v_cvt_pk_bf16_f32).
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
