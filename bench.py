@@ -64,19 +64,30 @@ def main():
                     help="config2 (default) is the benchmark line; config3 / config5 have a capped expert cache and report "
                          "switch bandwidth, overlap and host planning time next to their throughput")
     ap.add_argument("--requests", type=int, default=0, help="0 = the workload's own request count")
-    ap.add_argument("--max-batch", type=int, default=512)
+    ap.add_argument("--max-batch", type=int, default=0,
+                    help="most requests per launch sequence (0 = 4096 for config2 / config4, where 288 GB of HBM hold the "
+                         "activations of a whole stage and large launches fill whole rounds of compute units; 512 otherwise)")
     ap.add_argument("--cpu-sample", type=int, default=384, help="requests the oracle is timed on (0 = skip)")
     ap.add_argument("--arrivals-per-step", type=int, default=1,
                     help="arrival batches that queue up between two stages (1: a stage after every arrival, the least "
                          "favourable case; more: later arrivals join the groups of earlier ones before they run, which is "
                          "what request arranging is for)")
-    ap.add_argument("--group-small", type=int, default=0,
-                    help="groups of at most this many requests share launches (0 = the library's default, -1 = never)")
+    ap.add_argument("--group-small", type=int, default=None,
+                    help="groups of at most this many requests share launches (default: 512 for config2 / config4, so the "
+                         "leaf groups of a stage run as one launch per layer; otherwise 0 = the library's default; -1 = never)")
     ap.add_argument("--no-profile", action="store_true", help="do not time kernel classes with events")
-    ap.add_argument("--profile-every", type=int, default=7,
-                    help="time every k-th launch of each kernel class (an event pair costs a pipeline bubble; 7 is coprime "
-                         "to the launches per forward, so every layer shape is sampled)")
+    ap.add_argument("--profile-every", type=int, default=0,
+                    help="time every k-th launch of each kernel class (0 = every launch for config2 / config4, whose steps "
+                         "are a few dozen large launches; 7 otherwise: an event pair costs a pipeline bubble, and 7 is "
+                         "coprime to the launches per forward, so every layer shape is sampled)")
     args = ap.parse_args()
+    big = args.workload in ("config2", "config4")
+    if args.max_batch == 0:
+        args.max_batch = 4096 if big else 512
+    if args.group_small is None:
+        args.group_small = 512 if big else 0
+    if args.profile_every == 0:
+        args.profile_every = 1 if args.workload == "config2" else 7
     if args.gpus != 1:
         print("bench.py runs on exactly one GPU: the library has no multi-GPU path (--gpus 1 only)", file=sys.stderr)
         sys.exit(2)

@@ -41,6 +41,7 @@ struct ArchPlan {
     size_t buf_elems[kMaxBufs] = {0};   // per request
     size_t patch_elems = 0;             // per request: rows of the largest patch-gathered conv
     bool groupable = false;             // every layer can run several experts' small groups in one launch
+    int32_t row_cap = INT32_MAX;        // most requests one launch may cover: the kernels address a tensor with 31-bit byte offsets
     size_t elem() const { return dtype == COE_DT_BF16 ? 2 : 4; }
     size_t in_bytes() const { return (size_t)in_h * in_w * in_c * elem(); }
 };
@@ -272,10 +273,7 @@ int plan_arch(coe_ctx* c, const coe_arch_desc* d, ArchPlan& a)
         default:
             return fail(c, COE_EINVAL, "arch: unknown op");
         }
-        if (!is_head) {
-            shp[l.dst] = {L.P, L.Q, L.K, true};
-            a.buf_elems[l.dst] = std::max(a.buf_elems[l.dst], (size_t)L.P * L.Q * L.K);
-        }
+        if (!is_head) shp[l.dst] = {L.P, L.Q, L.K, true};
         a.layers.push_back(L);
     }
     int last = a.layers.back().d.op;
@@ -297,7 +295,20 @@ int plan_arch(coe_ctx* c, const coe_arch_desc* d, ArchPlan& a)
         cv.fuse_pool = true;
         pl.fused_away = true;
     }
+    // activation buffers per request: what the launched kernels write (a conv fused with its pool writes the pool's output)
+    for (const LayerPlan& L : a.layers) {
+        const int op = L.d.op;
+        if (op == COE_OP_HEAD || op == COE_OP_HEAD_CLS || L.fuse_pool) continue;
+        a.buf_elems[L.d.dst] = std::max(a.buf_elems[L.d.dst], (size_t)L.P * L.Q * L.K);
+    }
     a.blob_bytes = align_up(off);
+    {
+        size_t widest = a.in_bytes();
+        for (int b = 1; b < kMaxBufs; ++b) widest = std::max(widest, a.buf_elems[b] * a.elem());
+        widest = std::max(widest, a.patch_elems * a.elem());
+        a.row_cap = (int32_t)std::min<size_t>((size_t)INT32_MAX, (size_t)0x7FFFFFFE / widest);
+        if (a.row_cap < 1) return fail(c, COE_EINVAL, "arch: one request's largest tensor exceeds 2 GiB");
+    }
     // grouped launches: matrix-core convs with K % 64 == 0 take a group table; few-channel convs run once per group;
     // pools have no weights; the pooled head takes a group table.  Anything else keeps one launch per group.
     a.groupable = a.dtype == COE_DT_BF16;
@@ -336,11 +347,15 @@ int ensure_store(coe_ctx* c)
     return COE_OK;
 }
 
+// requests per launch sequence of an architecture: the configured maximum batch, cut where a tensor would outgrow the
+// kernels' 31-bit byte offsets
+int32_t chunk_rows(const coe_ctx* c, const ArchPlan& a) { return std::min(c->cfg.max_batch, a.row_cap); }
+
 int ensure_workspace(coe_ctx* c)
 {
     for (int b = 1; b < kMaxBufs; ++b) {
         size_t need = 0;
-        for (const ArchPlan& a : c->archs) need = std::max(need, a.buf_elems[b] * a.elem() * (size_t)c->cfg.max_batch);
+        for (const ArchPlan& a : c->archs) need = std::max(need, a.buf_elems[b] * a.elem() * (size_t)chunk_rows(c, a));
         if (need > c->buf_bytes[b]) {
             HIPCHK(c, hipStreamSynchronize(c->sc));
             if (c->d_buf[b]) HIPCHK(c, hipFree(c->d_buf[b]));
@@ -350,7 +365,7 @@ int ensure_workspace(coe_ctx* c)
         }
     }
     size_t need = 0;
-    for (const ArchPlan& a : c->archs) need = std::max(need, a.patch_elems * a.elem() * (size_t)c->cfg.max_batch);
+    for (const ArchPlan& a : c->archs) need = std::max(need, a.patch_elems * a.elem() * (size_t)chunk_rows(c, a));
     if (need > c->patch_bytes) {
         HIPCHK(c, hipStreamSynchronize(c->sc));
         if (c->d_patch) HIPCHK(c, hipFree(c->d_patch));
@@ -894,7 +909,8 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
     };
     const int32_t group_small = c->cfg.group_small == 0 ? 64 : c->cfg.group_small;
     auto small = [&](int32_t e) {
-        return group_small > 0 && c->h_cnt[e] <= group_small && c->archs[c->experts[e].arch].groupable;
+        const ArchPlan& a = c->archs[c->experts[e].arch];
+        return group_small > 0 && c->h_cnt[e] <= group_small && c->h_cnt[e] <= chunk_rows(c, a) && a.groupable;
     };
     for (size_t i = 0; i < order.size(); ++i) {
         const int32_t e = order[i];
@@ -916,7 +932,7 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
                 const int32_t f = order[j];
                 if (launched[f] || !small(f) || c->experts[f].arch != x.arch) continue;
                 if (!c->experts[f].buf) continue;              // its switch has not been issued yet
-                if (rows + c->h_cnt[f] > c->cfg.max_batch) continue;
+                if (rows + c->h_cnt[f] > chunk_rows(c, c->archs[x.arch])) continue;
                 set.push_back({f, off[f], c->h_cnt[f]});
                 rows += c->h_cnt[f];
             }
@@ -948,8 +964,12 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
             x.load_pending = false;
         }
         const int32_t n_route = c->succ_off[e + 1] - c->succ_off[e];
-        for (int32_t s = off[e]; s < off[e + 1]; s += c->cfg.max_batch) {
-            int32_t cnt = std::min(c->cfg.max_batch, off[e + 1] - s);
+        // request splitting: as few launch sequences as the cap allows, of equal size (no short last one)
+        const int32_t cap_rows = chunk_rows(c, c->archs[x.arch]);
+        const int32_t n_seq = (c->h_cnt[e] + cap_rows - 1) / cap_rows;
+        const int32_t chunk = (c->h_cnt[e] + n_seq - 1) / n_seq;
+        for (int32_t s = off[e]; s < off[e + 1]; s += chunk) {
+            int32_t cnt = std::min(chunk, off[e + 1] - s);
             coe::k::RouteArgs r{c->d_perm + s, e, c->d_succ + c->succ_off[e], n_route, c->d_cur, c->d_depth, c->d_path,
                                 c->cfg.max_stages, c->d_logits, c->max_classes};
             rc = run_expert(c, x, x.buf->p, staged + (size_t)s * ib, cnt, r);
@@ -1068,8 +1088,9 @@ int coe_debug_forward(coe_ctx* c, int32_t e, int32_t n, const void* dev_in, floa
     }
     HIPCHK(c, hipMalloc((void**)&d_log, (size_t)n * a.n_classes * 4));
     const size_t ib = a.in_bytes();
-    for (int32_t s = 0; s < n && rc == COE_OK; s += c->cfg.max_batch) {
-        int32_t cnt = std::min(c->cfg.max_batch, n - s);
+    const int32_t chunk = chunk_rows(c, a);
+    for (int32_t s = 0; s < n && rc == COE_OK; s += chunk) {
+        int32_t cnt = std::min(chunk, n - s);
         coe::k::RouteArgs r{nullptr, e, nullptr, 0, nullptr, nullptr, nullptr, 0, d_log + (size_t)s * a.n_classes, a.n_classes};
         rc = run_expert(c, x, w, (const uint8_t*)dev_in + (size_t)s * ib, cnt, r);
     }
@@ -1086,9 +1107,9 @@ int coe_debug_layer_output(coe_ctx* c, int32_t e, int32_t n, const void* dev_in,
 {
     if (!c || !dev_in || !out || n <= 0) return fail(c, COE_EINVAL, "bad argument");
     if (e < 0 || e >= (int32_t)c->experts.size() || !c->experts[e].registered) return fail(c, COE_EINVAL, "unknown expert");
-    if (n > c->cfg.max_batch) return fail(c, COE_ERANGE, "more inputs than max_batch");
     Expert& x = c->experts[e];
     const ArchPlan& a = c->archs[x.arch];
+    if (n > chunk_rows(c, a)) return fail(c, COE_ERANGE, "more inputs than one launch sequence takes");
     if (layer < 0 || layer >= (int32_t)a.layers.size() - 1) return fail(c, COE_EINVAL, "layer index out of range (heads have no output tensor)");
     const LayerPlan& L = a.layers[layer];
     if (L.fuse_pool || L.fused_away) return fail(c, COE_EINVAL, "layer is fused with its neighbour");

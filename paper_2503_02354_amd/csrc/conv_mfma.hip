@@ -985,10 +985,16 @@ hipError_t conv_mfma_grouped(const void* x, const GroupTable& groups, size_t off
     grp.table = groups;
     grp.off_w = (uint32_t)off_w;
     grp.off_b = (uint32_t)off_b;
-    // groups are small: 128-row tiles waste fewer rows past a group's end than 256-row ones
+    // every group starts a fresh row of tiles: 128-row tiles waste fewer rows past the end of a small group, 256-row
+    // tiles (twice the accumulator rows per wave and operand read) are the faster ones where that waste stays small
     if (conv_mfma_uses_slab(s)) {
-        if (s.K % 128 == 0) return launch_slab<128, 128, 2, 2>(x, nullptr, nullptr, res, y, s, stream, grp);
-        return launch_slab<128, 64, 4, 1>(x, nullptr, nullptr, res, y, s, stream, grp);
+        const long long PQ = (long long)s.P * s.Q;
+        const bool tall = 256 * count_tiles(M, PQ, 256, 1, groups) * 100 <= 128 * count_tiles(M, PQ, 128, 1, groups) * 104;
+        if (s.K % 128 == 0)
+            return tall ? launch_slab<256, 128, 2, 2>(x, nullptr, nullptr, res, y, s, stream, grp)
+                        : launch_slab<128, 128, 2, 2>(x, nullptr, nullptr, res, y, s, stream, grp);
+        return tall ? launch_slab<256, 64, 4, 1>(x, nullptr, nullptr, res, y, s, stream, grp)
+                    : launch_slab<128, 64, 4, 1>(x, nullptr, nullptr, res, y, s, stream, grp);
     }
     if (s.K % 128 == 0) return launch_dma<128, 128, 2, 2>(x, nullptr, nullptr, res, y, s, stream, grp);
     return launch_dma<128, 64, 2, 2>(x, nullptr, nullptr, res, y, s, stream, grp);

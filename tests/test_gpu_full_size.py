@@ -32,7 +32,7 @@ def _valid_paths(path, wl):
         assert len(succ) == 0 or -1 in succ, "request stopped at an expert that still routes"
 
 
-def _sampled_case(B, oracle, wl, n_sample, max_batch, arrival=None, seed=1):
+def _sampled_case(B, oracle, wl, n_sample, max_batch, arrival=None, seed=1, group_small=0):
     from oracle import guard as G
     n = wl.n_requests
     E = wl.graph.n_experts
@@ -52,7 +52,8 @@ def _sampled_case(B, oracle, wl, n_sample, max_batch, arrival=None, seed=1):
     x = wl.inputs(range(n), subseeds)
     assert np.array_equal(x[sample], xs)
     print(f"{wl.name}: inputs ready", flush=True)
-    got = run_chain_gpu(B, wl, blobs, x, wl.first_expert, max_batch=max_batch, arrival=arrival, keep=True)
+    got = run_chain_gpu(B, wl, blobs, x, wl.first_expert, max_batch=max_batch, arrival=arrival, keep=True,
+                        group_small=group_small)
     ctx = got.pop("ctx")
     # sampled requests against the oracle (requests the guard left ambiguous: any admissible outcome)
     print(f"{wl.name}: GPU chain done", flush=True)
@@ -62,18 +63,22 @@ def _sampled_case(B, oracle, wl, n_sample, max_batch, arrival=None, seed=1):
     # every request: valid path
     _valid_paths(got["path"], wl)
     # the sampled requests alone give the same bits: results do not depend on grouping or batch composition
-    alone = run_chain_gpu(B, wl, blobs, xs, None if wl.first_expert is None else wl.first_expert[sample], max_batch=max_batch)
+    alone = run_chain_gpu(B, wl, blobs, xs, None if wl.first_expert is None else wl.first_expert[sample], max_batch=max_batch,
+                          group_small=group_small)
     assert np.array_equal(alone["path"], got["path"][sample])
     assert np.array_equal(alone["logits"], got["logits"][sample])
     ctx.close()
     return got, want, sample, float(err), redraws
 
 
-def test_config2_full_size(B, oracle):
-    """16 ResNet-18-shaped bf16 experts, 4096 requests of 3x224x224, root routes 15 ways, all resident."""
+@pytest.mark.parametrize("max_batch,group_small", [(4096, 512), (512, 0)])
+def test_config2_full_size(B, oracle, max_batch, group_small):
+    """16 ResNet-18-shaped bf16 experts, 4096 requests of 3x224x224, root routes 15 ways, all resident.  First in the
+    launch configuration the benchmark times (a whole stage per launch sequence: the root's 4096 requests in one, the
+    leaf groups sharing one), then with 512-request launch sequences and the library's default grouping."""
     wl = W.config2()
     assert wl.head_bias, "calibration file missing"
-    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=48, max_batch=512)
+    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=48, max_batch=max_batch, group_small=group_small)
     # the regroup of the second stage is the stable sort of the routed ids (all 4096 requests, bit exact):
     # replay stage 2's keys through the library's regroup and the oracle's
     keys = got["path"][:, 1].astype(np.int32)
@@ -84,6 +89,9 @@ def test_config2_full_size(B, oracle):
     for k in ("cnt", "off", "perm", "inv"):
         assert np.array_equal(dev[k], ref[k]), k
     assert [st.n_groups for rc, st in got["stats"][:2]] == [1, int((ref["cnt"] > 0).sum())]
+    if group_small == 512:
+        st = got["stats"][1][1]
+        assert st.n_grouped == int((ref["cnt"][1:] <= 512).sum()) >= 13 and st.n_group_sets == 1
     leaves = ref["cnt"][1:]
     assert leaves.min() > 100 and leaves.max() < 600, leaves          # calibration spreads the 15 routes
     print(f"config2 full size: {len(sample)} sampled requests, max rel err {err:.2e}, {redraws} re-draws, leaves {leaves.tolist()}")
@@ -134,13 +142,16 @@ def test_config4_full_size(B, oracle):
     8192 requests, everything resident."""
     wl = W.config4()
     assert wl.head_bias, "calibration file missing"
-    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=24, max_batch=512, seed=4)
+    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=24, max_batch=4096, seed=4, group_small=512)
     stats = [st for rc, st in got["stats"] if rc == B.COE_OK]
     assert len(stats) == 3 and all(st.n_pending == wl.n_requests for st in stats)
     assert np.all(got["path"][:, 2] >= 0)
     # regroup at every stage = stable sort of that stage's expert ids, all 8192 requests, bit exact
     ctx = B.Context(max_requests=wl.n_requests)
-    sizes = []
+    sizes, want_chunks = [], []
+    # a launch sequence takes at most max_batch requests and no tensor beyond 31-bit byte offsets: 1337 requests for the
+    # ResNet-50-shaped experts (56x56x256 bf16 per request), all 4096 for the ResNet-18-shaped ones (even ids)
+    cap = np.where(np.asarray(wl.expert_arch) == 0, 4096, 1337)
     for stage in range(3):
         keys = got["path"][:, stage].astype(np.int32)
         dev = ctx.coe_debug_regroup(keys, wl.graph.n_experts)
@@ -149,9 +160,11 @@ def test_config4_full_size(B, oracle):
             assert np.array_equal(dev[k], ref[k]), (stage, k)
         assert stats[stage].n_groups == int((ref["cnt"] > 0).sum())
         sizes.append(ref["cnt"][ref["cnt"] > 0])
+        want_chunks.append(int(np.sum(-(-ref["cnt"] // cap))))
     ctx.close()
-    # chunks: every group cut into ceil(size / max_batch) batches
-    assert [st.n_chunks for st in stats] == [int(np.sum(-(-s // 512))) for s in sizes]
+    # launch sequences per stage
+    assert [st.n_chunks for st in stats] == want_chunks
+    assert sum(st.n_grouped for st in stats) >= 90
     allsz = np.concatenate(sizes)
     print(f"config4 full size: {len(sample)} sampled, max rel err {err:.2e}, {redraws} re-draws, groups per stage "
           f"{[len(s) for s in sizes]}, sizes min {allsz.min()} median {int(np.median(allsz))} max {allsz.max()}")
