@@ -75,6 +75,10 @@ def main():
     ap.add_argument("--group-small", type=int, default=None,
                     help="groups of at most this many requests share launches (default: 512 for config2 / config4, so the "
                          "leaf groups of a stage run as one launch per layer; otherwise 0 = the library's default; -1 = never)")
+    ap.add_argument("--arrange", default="",
+                    help="arranging window 'min_resident,min_missing,max_wait' for every architecture: a queued group "
+                         "smaller than min_resident (expert on the device) or min_missing (expert missing) waits up to "
+                         "max_wait steps for later arrivals to join it (empty = off: every queued group runs in every step)")
     ap.add_argument("--no-profile", action="store_true", help="do not time kernel classes with events")
     ap.add_argument("--profile-every", type=int, default=0,
                     help="time every k-th launch of each kernel class (0 = every launch for config2 / config4, whose steps "
@@ -114,6 +118,11 @@ def main():
                     cache_cap_experts=wl.cache_cap_experts, profile=0 if args.no_profile else args.profile_every,
                     group_small=args.group_small)
     B.setup_workload(ctx, wl, blobs)
+    window = [int(v) for v in args.arrange.split(",")] if args.arrange else None
+    if window:
+        assert len(window) == 3, "--arrange takes min_resident,min_missing,max_wait"
+        for a in range(len(wl.archs)):
+            ctx.coe_set_arranging(a, *window)
     dev = torch.from_numpy(x.view(np.int16)).cuda()
     torch.cuda.synchronize()
 
@@ -132,7 +141,9 @@ def main():
             rc, st = ctx.coe_step()
             step_stats.append(st)
             steps_run += 1
-        for _ in range(wl.max_stages - 1):   # the graph has no deeper path: no empty probing step after these
+        # without a window the graph's depth bounds the steps left (no empty probing step after them); with one, groups
+        # may still be waiting: step until the queue is empty
+        for _ in range(wl.max_stages - 1 if not window else 10 ** 6):
             rc, st = ctx.coe_step()
             if rc == B.COE_DONE:
                 break
@@ -234,6 +245,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[args.workload], "requests": n, "arrival_batch": arrival,
                    "arrivals_per_step": args.arrivals_per_step, "max_batch": args.max_batch,
+                   "arranging_window": None if not window else {"min_group_resident": window[0], "min_group_missing": window[1],
+                                                                "max_wait_steps": window[2]},
                    "stages": wl.max_stages, "gflop_per_request": round(flops_per_step / n / 1e9, 3)},
         "end_to_end_tflops": round(flops_per_step / (ms_per_step * 1e-3) / 1e12, 2),
         "end_to_end_frac_of_bf16_peak": round(flops_per_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
@@ -242,6 +255,10 @@ def main():
             "groups_per_pass": sum(st.n_groups for st in step_stats) // max(args.steps, 1),
             "of_them_in_shared_launches": sum(st.n_grouped for st in step_stats) // max(args.steps, 1),
             "shared_launch_sequences": sum(st.n_group_sets for st in step_stats) // max(args.steps, 1)},
+        "arranging": None if not (step_stats and window) else {
+            "steps_per_pass": len(step_stats) // max(args.steps, 1),
+            "group_waits_per_pass": sum(st.n_deferred_groups for st in step_stats) // max(args.steps, 1),
+            "request_waits_per_pass": sum(st.n_deferred_requests for st in step_stats) // max(args.steps, 1)},
         "cpu_baseline": cpu,
         "leaf_group_sizes": {"min": int(leaves.min()), "max": int(leaves.max())},
         "input_generation_s": round(t_gen, 1),

@@ -100,6 +100,8 @@ typedef struct {
     double host_plan_us; /* host time spent planning (cache policy, splitting) */
     int32_t n_grouped;   /* groups that shared their launches with other small groups */
     int32_t n_group_sets; /* launch sequences those groups were packed into */
+    int32_t n_deferred_groups;   /* groups left queued by the arranging window (see coe_set_arranging) */
+    int32_t n_deferred_requests; /* their requests; these are counted in n_pending but ran no stage in this step */
 } coe_step_stats;
 
 /* Create / destroy a context.  coe_create fails with COE_EDEVICE when no GPU is usable. */
@@ -142,6 +144,20 @@ int coe_submit(coe_ctx* ctx, int32_t n, const void* inputs, int on_device, const
  * run each expert on its batches, and route.  Work is enqueued asynchronously except for one small count
  * read-back.  Returns COE_DONE when nothing is pending.  stats is nullable. */
 int coe_step(coe_ctx* ctx, coe_step_stats* stats);
+
+/* Arranging window (paper Section 4.2, "Request arranging": a new request is placed behind the queued requests of
+ * the same expert, so that they run together and the expert is loaded at most once for all of them).  coe_step
+ * runs every queued group, so requests only meet the ones that arrived before the same step.  With a window, a group
+ * of an expert of architecture arch_id that is still small stays queued instead: it is skipped in a step when it
+ * holds fewer than min_group_resident requests (expert on the device) or min_group_missing requests (expert not on
+ * the device: running it costs a switch), unless its oldest request has already waited max_wait_steps steps
+ * (age = number of coe_step calls since the one that first saw the request; a request never waits longer).  Later
+ * arrivals for the same expert join the queued group before it runs.  The thresholds are what the latency model of
+ * Section 4.2 (K n + B per batch, plus the load time of a missing expert) says about when the fixed cost per request
+ * has become small; a profiler computes them offline.  max_wait_steps = 0 (the default) switches the window off.
+ * Results per request do not depend on any of this.  Errors: COE_EINVAL (unknown architecture, negative value). */
+int coe_set_arranging(coe_ctx* ctx, int32_t arch_id, int32_t min_group_resident, int32_t min_group_missing,
+                      int32_t max_wait_steps);
 
 /* Wait for all enqueued work. */
 int coe_sync(coe_ctx* ctx);
@@ -192,6 +208,13 @@ int coe_profile_issued(coe_ctx* ctx, int32_t kernel_class, int64_t* issued);
 /* ---- host-only pieces (no GPU needed) -------------------------------------------------------------------------- */
 /* Graph check used by coe_set_dependency_graph.  n_classes: [n_experts] or NULL (skip the route-count check). */
 int coe_validate_graph(int32_t n_experts, const int32_t* succ_off, const int32_t* succ, const int32_t* n_classes);
+
+/* The arranging window's rule on its own: for every expert e with count[e] > 0 queued requests, age[e] steps waited by
+ * the oldest of them, resident[e] != 0 when the expert is on the device, and its architecture's thresholds (arrays
+ * indexed by expert), defer[e] = 1 when the group stays queued in this step, else 0.  Returns the number deferred. */
+int coe_arrange_defer(int32_t n_experts, const int32_t* count, const int32_t* age, const uint8_t* resident,
+                      const int32_t* min_group_resident, const int32_t* min_group_missing, const int32_t* max_wait_steps,
+                      uint8_t* defer);
 
 /* The expert-cache policy on its own (paper Section 4.1 initial fill, Section 4.3 two-stage eviction).
  * coe_policy_stage: has_group[E] marks experts with pending requests; order[E] receives the execution order

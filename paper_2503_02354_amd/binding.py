@@ -24,7 +24,7 @@ EXPORTS = [
     "coe_set_dependency_graph", "coe_submit", "coe_step", "coe_sync", "coe_collect", "coe_reset_requests",
     "coe_debug_last_regroup", "coe_debug_switch_log", "coe_debug_resident", "coe_debug_forward", "coe_debug_layer_output", "coe_debug_regroup", "coe_debug_conv",
     "coe_profile_read", "coe_profile_issued", "coe_validate_graph", "coe_policy_create", "coe_policy_destroy", "coe_policy_init_fill",
-    "coe_policy_stage", "coe_policy_resident",
+    "coe_policy_stage", "coe_policy_resident", "coe_set_arranging", "coe_arrange_defer",
 ]
 
 
@@ -46,7 +46,8 @@ class coe_config(C.Structure):
 class coe_step_stats(C.Structure):
     _fields_ = [("n_pending", C.c_int32), ("n_groups", C.c_int32), ("n_chunks", C.c_int32), ("n_hits", C.c_int32),
                 ("n_misses", C.c_int32), ("n_evictions", C.c_int32), ("bytes_switched", C.c_int64),
-                ("host_plan_us", C.c_double), ("n_grouped", C.c_int32), ("n_group_sets", C.c_int32)]
+                ("host_plan_us", C.c_double), ("n_grouped", C.c_int32), ("n_group_sets", C.c_int32),
+                ("n_deferred_groups", C.c_int32), ("n_deferred_requests", C.c_int32)]
 
 
 def _load():
@@ -82,6 +83,8 @@ def _load():
     L.coe_policy_init_fill.argtypes = [vp, vp]
     L.coe_policy_stage.argtypes = [vp, vp, vp, C.POINTER(i32), vp, i32]
     L.coe_policy_resident.argtypes = [vp, vp]
+    L.coe_set_arranging.argtypes = [vp, i32, i32, i32, i32]
+    L.coe_arrange_defer.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp]
     return L
 
 
@@ -103,6 +106,19 @@ def _ptr(a):
 
 
 # ---- host-only functions --------------------------------------------------------------------------------------
+def coe_arrange_defer(count, age, resident, min_group_resident, min_group_missing, max_wait_steps) -> np.ndarray:
+    """The arranging window's rule (host only): which queued groups stay queued in this step."""
+    a = [np.ascontiguousarray(v, np.int32) for v in (count, age, min_group_resident, min_group_missing, max_wait_steps)]
+    res = np.ascontiguousarray(np.asarray(resident, dtype=np.uint8))
+    n = a[0].shape[0]
+    assert all(v.shape == (n,) for v in a) and res.shape == (n,)
+    out = np.zeros(n, np.uint8)
+    rc = lib.coe_arrange_defer(n, _ptr(a[0]), _ptr(a[1]), _ptr(res), _ptr(a[2]), _ptr(a[3]), _ptr(a[4]), _ptr(out))
+    if rc < 0:
+        raise CoEError(rc, "coe_arrange_defer")
+    return out.astype(bool)
+
+
 def coe_validate_graph(n_experts: int, succ_off, succ, n_classes=None) -> int:
     so = np.ascontiguousarray(succ_off, np.int32); su = np.ascontiguousarray(succ, np.int32)
     nc = None if n_classes is None else np.ascontiguousarray(n_classes, np.int32)
@@ -233,6 +249,9 @@ class Context:
 
     def coe_sync(self):
         self._chk(lib.coe_sync(self._h))
+
+    def coe_set_arranging(self, arch_id: int, min_group_resident: int, min_group_missing: int, max_wait_steps: int):
+        self._chk(lib.coe_set_arranging(self._h, arch_id, min_group_resident, min_group_missing, max_wait_steps))
 
     def coe_collect(self, cap: int):
         ids = np.zeros(cap, np.int64); logits = np.zeros((cap, max(self.max_classes, 1)), np.float32)

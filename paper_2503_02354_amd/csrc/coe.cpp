@@ -42,6 +42,7 @@ struct ArchPlan {
     size_t patch_elems = 0;             // per request: rows of the largest patch-gathered conv
     bool groupable = false;             // every layer can run several experts' small groups in one launch
     int32_t row_cap = INT32_MAX;        // most requests one launch may cover: the kernels address a tensor with 31-bit byte offsets
+    int32_t arr_min_res = 0, arr_min_miss = 0, arr_wait = 0;   // arranging window (coe_set_arranging); arr_wait 0 = off
     size_t elem() const { return dtype == COE_DT_BF16 ? 2 : 4; }
     size_t in_bytes() const { return (size_t)in_h * in_w * in_c * elem(); }
 };
@@ -105,6 +106,8 @@ struct coe_ctx {
     int32_t *d_cnt = nullptr, *d_off = nullptr, *d_perm = nullptr, *d_inv = nullptr, *d_blockhist = nullptr;
     int32_t* h_cnt = nullptr;        // pinned
     int32_t last_pending = 0, last_live = 0, last_E = 0;
+    std::vector<int32_t> submit_step;   // per request slot: number of the first step that sees the request
+    int32_t step_no = 0;
 
     // activation workspace
     void* d_buf[kMaxBufs] = {nullptr};
@@ -665,12 +668,13 @@ int coe_create(const coe_config* cfg, coe_ctx** out)
     bool ok = hipMalloc((void**)&c->d_cur, nreq * 4) == hipSuccess && hipMalloc((void**)&c->d_depth, nreq * 4) == hipSuccess &&
               hipMalloc((void**)&c->d_path, nreq * 4 * (size_t)cfg->max_stages) == hipSuccess &&
               hipMalloc((void**)&c->d_perm, nreq * 4) == hipSuccess && hipMalloc((void**)&c->d_inv, nreq * 4) == hipSuccess &&
-              hipMalloc((void**)&c->d_cnt, coe::k::kRegroupMaxExperts * 4) == hipSuccess &&
+              hipMalloc((void**)&c->d_cnt, 2 * coe::k::kRegroupMaxExperts * 4) == hipSuccess &&
               hipMalloc((void**)&c->d_off, (coe::k::kRegroupMaxExperts + 1) * 4) == hipSuccess &&
               hipMalloc((void**)&c->d_blockhist, nblocks * coe::k::kRegroupMaxExperts * 4) == hipSuccess &&
-              hipHostMalloc((void**)&c->h_cnt, coe::k::kRegroupMaxExperts * 4, hipHostMallocDefault) == hipSuccess;
+              hipHostMalloc((void**)&c->h_cnt, 2 * coe::k::kRegroupMaxExperts * 4, hipHostMallocDefault) == hipSuccess;
     if (!ok) return bail(COE_ENOMEM);
     c->collected.assign(nreq, 0);
+    c->submit_step.assign(nreq, 0);
     *out = c;
     return COE_OK;
 }
@@ -832,6 +836,7 @@ int coe_submit(coe_ctx* c, int32_t n, const void* inputs, int on_device, const i
     // `cur` is pageable host memory: the copy above has been staged by the runtime when the call returns only if we wait
     HIPCHK(c, hipStreamSynchronize(c->sc));
     std::fill(c->collected.begin() + base, c->collected.begin() + base + n, 0);
+    std::fill(c->submit_step.begin() + base, c->submit_step.begin() + base + n, c->step_no);
     c->n_live += n;
     return COE_OK;
 }
@@ -854,18 +859,45 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
         Span sp(c, COE_K_REGROUP_INDEX, (double)c->n_live * 16.0, c->sc);
         HIPCHK(c, coe::k::regroup_index(c->d_cur, c->n_live, E, c->d_cnt, c->d_off, c->d_perm, c->d_inv, c->d_blockhist, c->sc));
     }
-    HIPCHK(c, hipMemcpyAsync(c->h_cnt, c->d_cnt, (size_t)E * 4, hipMemcpyDeviceToHost, c->sc));
+    bool arranging = false;
+    for (const ArchPlan& a : c->archs) arranging = arranging || a.arr_wait > 0;
+    if (arranging)   // the oldest queued request of every group, behind the counts
+        HIPCHK(c, coe::k::group_heads(c->d_perm, c->d_off, c->d_cnt, E, c->d_cnt + E, c->sc));
+    HIPCHK(c, hipMemcpyAsync(c->h_cnt, c->d_cnt, (size_t)E * 4 * (arranging ? 2 : 1), hipMemcpyDeviceToHost, c->sc));
     HIPCHK(c, hipStreamSynchronize(c->sc));
     auto t0 = std::chrono::steady_clock::now();
     std::vector<int32_t> off(E + 1, 0);
     std::vector<uint8_t> has_group(E, 0);
+    int32_t n_groups_queued = 0;
     for (int32_t e = 0; e < E; ++e) {
         off[e + 1] = off[e] + c->h_cnt[e];
         has_group[e] = c->h_cnt[e] > 0;
+        n_groups_queued += has_group[e];
     }
     const int32_t n_pending = off[E];
     c->last_pending = n_pending; c->last_live = c->n_live; c->last_E = E;
     if (n_pending == 0) return COE_DONE;
+    const int32_t step_no = c->step_no++;
+
+    // arranging window: small groups stay queued for later arrivals to join (they keep their place in the regrouped
+    // order; only the plan and the launches skip them)
+    if (arranging) {
+        std::vector<int32_t> age(E, 0), min_res(E, 0), min_miss(E, 0), wait(E, 0);
+        std::vector<uint8_t> resident(E, 0), defer(E, 0);
+        for (int32_t e = 0; e < E; ++e) {
+            const ArchPlan& a = c->archs[c->experts[e].arch];
+            min_res[e] = a.arr_min_res; min_miss[e] = a.arr_min_miss; wait[e] = a.arr_wait;
+            resident[e] = c->policy->resident(e);
+            if (has_group[e]) age[e] = step_no - c->submit_step[c->h_cnt[E + e]];
+        }
+        coe_arrange_defer(E, c->h_cnt, age.data(), resident.data(), min_res.data(), min_miss.data(), wait.data(), defer.data());
+        for (int32_t e = 0; e < E; ++e)
+            if (defer[e]) {
+                has_group[e] = 0;
+                ++st.n_deferred_groups;
+                st.n_deferred_requests += c->h_cnt[e];
+            }
+    }
 
     // cache plan: execution order and switches
     std::vector<int32_t> order;
@@ -884,9 +916,9 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
     // request arranging, activation part: inputs into group-contiguous order
     // (one group that holds every stored request: the stable sort is the identity and the inputs are already in order)
     const size_t ib = c->archs[0].in_bytes();
-    const bool in_place = order.size() == 1 && n_pending == c->n_live;
+    const bool in_place = n_groups_queued == 1 && n_pending == c->n_live;
     const uint8_t* staged = (const uint8_t*)(in_place ? c->d_inputs : c->d_staged);
-    if (!in_place) {
+    if (!in_place && !order.empty()) {
         Span sp(c, COE_K_REGROUP_GATHER, 2.0 * (double)n_pending * (double)ib, c->sc);
         HIPCHK(c, coe::k::gather_rows(c->d_inputs, c->d_perm, n_pending, ib, c->d_staged, c->sc));
     }
@@ -982,6 +1014,33 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
     }
     if (stats) *stats = st;
     return COE_OK;
+}
+
+int coe_set_arranging(coe_ctx* c, int32_t arch_id, int32_t min_group_resident, int32_t min_group_missing, int32_t max_wait_steps)
+{
+    if (!c) return COE_EINVAL;
+    if (arch_id < 0 || arch_id >= (int32_t)c->archs.size()) return fail(c, COE_EINVAL, "unknown architecture");
+    if (min_group_resident < 0 || min_group_missing < 0 || max_wait_steps < 0) return fail(c, COE_EINVAL, "negative arranging parameter");
+    ArchPlan& a = c->archs[arch_id];
+    a.arr_min_res = min_group_resident;
+    a.arr_min_miss = min_group_missing;
+    a.arr_wait = max_wait_steps;
+    return COE_OK;
+}
+
+int coe_arrange_defer(int32_t n_experts, const int32_t* count, const int32_t* age, const uint8_t* resident,
+                      const int32_t* min_group_resident, const int32_t* min_group_missing, const int32_t* max_wait_steps,
+                      uint8_t* defer)
+{
+    if (n_experts < 0 || !count || !age || !resident || !min_group_resident || !min_group_missing || !max_wait_steps || !defer)
+        return COE_EINVAL;
+    int n = 0;
+    for (int32_t e = 0; e < n_experts; ++e) {
+        const int32_t enough = resident[e] ? min_group_resident[e] : min_group_missing[e];
+        defer[e] = count[e] > 0 && age[e] < max_wait_steps[e] && count[e] < enough;
+        n += defer[e];
+    }
+    return n;
 }
 
 int coe_sync(coe_ctx* c)

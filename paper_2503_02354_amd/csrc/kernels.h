@@ -33,6 +33,9 @@ hipError_t regroup_index(const int32_t* cur, int32_t n, int32_t E, int32_t* cnt,
                          int32_t* inv, int32_t* blockhist, hipStream_t stream);
 
 // Request arranging, activation part: dst row i = src row perm[i]; rows of row_bytes (multiple of 4) bytes.
+// heads[e] = perm[off[e]] (the oldest queued request of expert e: the regroup is stable) or -1 for an empty group
+hipError_t group_heads(const int32_t* perm, const int32_t* off, const int32_t* cnt, int32_t E, int32_t* heads,
+                       hipStream_t stream);
 hipError_t gather_rows(const void* src, const int32_t* perm, int32_t n_rows, size_t row_bytes, void* dst,
                        hipStream_t stream);
 

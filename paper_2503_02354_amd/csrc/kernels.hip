@@ -487,6 +487,21 @@ hipError_t regroup_index(const int32_t* cur, int32_t n, int32_t E, int32_t* cnt,
     return hipGetLastError();
 }
 
+__global__ void group_heads_kernel(const int32_t* __restrict__ perm, const int32_t* __restrict__ off,
+                                   const int32_t* __restrict__ cnt, int32_t E, int32_t* __restrict__ heads)
+{
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e < E) heads[e] = cnt[e] > 0 ? perm[off[e]] : -1;
+}
+
+hipError_t group_heads(const int32_t* perm, const int32_t* off, const int32_t* cnt, int32_t E, int32_t* heads,
+                       hipStream_t stream)
+{
+    if (E <= 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(group_heads_kernel, dim3((E + 255) / 256), dim3(256), 0, stream, perm, off, cnt, E, heads);
+    return hipGetLastError();
+}
+
 hipError_t gather_rows(const void* src, const int32_t* perm, int32_t n_rows, size_t row_bytes, void* dst,
                        hipStream_t stream)
 {

@@ -13,8 +13,9 @@ def device_tensor(x: np.ndarray):
 
 
 def run_chain_gpu(B, wl, blobs, x, first_expert=None, *, max_batch=0, cap_experts=None, arrival=None, on_device=True,
-                  profile=False, ctx=None, keep=False, group_small=0):
+                  profile=False, ctx=None, keep=False, group_small=0, arranging=None):
     """Submit x in arrival batches, one coe_step after each submit, then step until done; collect everything.
+    arranging: (min_group_resident, min_group_missing, max_wait_steps) set for every architecture.
     Returns dict(logits, path, ids, stats, switch_log[, ctx])."""
     import torch
     n = x.shape[0]
@@ -24,6 +25,9 @@ def run_chain_gpu(B, wl, blobs, x, first_expert=None, *, max_batch=0, cap_expert
                         cache_cap_experts=wl.cache_cap_experts if cap_experts is None else cap_experts, profile=profile,
                         group_small=group_small)
         B.setup_workload(ctx, wl, blobs)
+    if arranging is not None:
+        for a in range(len(wl.archs)):
+            ctx.coe_set_arranging(a, *arranging)
     arrival = arrival or n or 1
     stats = []
     dev = device_tensor(x) if on_device and n else None

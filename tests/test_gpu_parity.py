@@ -477,3 +477,40 @@ def test_grouped_launches_give_the_same_bits(B, oracle, G, cap):
     assert_chain_parity(grp, want, REL_TOL_BF16)
     if cap:
         assert sum(st.n_misses for st in stats) > 0
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# arranging window: small groups of missing experts wait for later arrivals; same results, fewer switches, and the
+# schedule (who runs in which step, which switches) equals the oracle's replay
+# ---------------------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("window", [(0, 6, 3), (3, 8, 2)])
+def test_arranging_window_matches_replay_and_keeps_results(B, oracle, G, window):
+    from oracle import arrange
+    n, E, arrival = 120, 10, 20
+    wl = W.config3(n, hw=64, n_experts=E, width=16, cap=4, arrival_batch=arrival, calibrated=False)
+    G.calibrate_workload(wl, n_cal=64, targets={0: W.zipf_probs(E - 1, 1.1)})
+    blobs = [wl.blob(e) for e in range(E)]
+    x, sub, want, _ = G.guarded_inputs(wl, blobs, range(n))
+    assert not want["ambiguous"].any()
+    plain = run_chain_gpu(B, wl, blobs, x, max_batch=16, arrival=arrival)
+    got = run_chain_gpu(B, wl, blobs, x, max_batch=16, arrival=arrival, arranging=window)
+    assert_chain_parity(got, want, REL_TOL_BF16)
+    assert np.array_equal(got["path"], plain["path"]) and np.array_equal(got["logits"], plain["logits"])
+    # the oracle's replay of the same arrivals, routes from the chain oracle
+    sim = oracle.CacheSim([b.nbytes for b in blobs], wl.usage_prob, wl.graph.succ_off, wl.graph.succ, cap_experts=4)
+    log = [(e, []) for e in sim.init_fill()]
+    paths = [[int(e) for e in p if e >= 0] for p in want["path"]]
+    submits = [list(range(s, min(s + arrival, n))) for s in range(0, n, arrival)]
+    rec = arrange.replay(submits, paths, wl.expert_arch, {0: window}, sim)
+    stats = [st for rc, st in got["stats"] if rc == B.COE_OK]
+    assert len(stats) == len(rec)
+    for st, r in zip(stats, rec):
+        assert st.n_pending == r["n_pending"] and st.n_groups == len(r["run"]) and st.n_misses == len(r["switches"])
+        assert st.n_deferred_groups == len(r["deferred"])
+        assert st.n_deferred_requests == sum(len(m) for m in r["deferred"].values())
+        log += r["switches"]
+    assert got["switch_log"] == log
+    assert sum(st.n_deferred_groups for st in stats) > 0
+    assert len(got["switch_log"]) < len(plain["switch_log"])         # waiting groups merged: fewer switches
+    print(f"window {window}: {len(plain['switch_log']) - 4} -> {len(log) - 4} switches, "
+          f"{len([1 for rc, st in plain['stats'] if rc == B.COE_OK])} -> {len(stats)} steps")

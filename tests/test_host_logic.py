@@ -108,3 +108,16 @@ def test_policy_zipf_tree_keeps_hot_experts(B, oracle):
         hg[leaves] = 1
         stages.append(hg)
     _compare_policy(B, oracle, nbytes, wl.usage_prob, wl.graph, 5, 0, stages)
+
+
+def test_arranging_rule_matches_oracle(B):
+    """The library's arranging-window rule (host only) against the oracle's, on random queues."""
+    from oracle.arrange import stays_queued
+    rng = np.random.default_rng(7)
+    for _ in range(200):
+        E = int(rng.integers(1, 40))
+        count = rng.integers(0, 12, E); age = rng.integers(0, 6, E); res = rng.integers(0, 2, E)
+        mr = rng.integers(0, 10, E); mm = rng.integers(0, 10, E); mw = rng.integers(0, 6, E)
+        got = B.coe_arrange_defer(count, age, res, mr, mm, mw)
+        want = [stays_queued(int(count[e]), int(age[e]), bool(res[e]), int(mr[e]), int(mm[e]), int(mw[e])) for e in range(E)]
+        assert got.tolist() == want

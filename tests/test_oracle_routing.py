@@ -289,3 +289,93 @@ def test_admissible_outcomes_planted(oracle):
     b2 = [wl2.blob(e) for e in range(4)]
     x, sub, res, redraws = G.guarded_inputs(wl2, b2, range(6), delta=10.0, max_rounds=1)    # absurd delta: nothing passes
     assert res["ambiguous"].all() and redraws == 6 and sub.tolist() == [1] * 6
+
+
+# ---------------------------------------------------------------------------------------------------------------
+# arranging window (paper Section 4.2 "Request arranging"): replay of which group waits and which runs
+# ---------------------------------------------------------------------------------------------------------------
+def _tree_cache(oracle, probs, cap):
+    """root 0 -> leaves 1..n, equal sizes, capped by expert count, past its initial fill"""
+    E = len(probs)
+    succ_off = [0, E - 1] + [E - 1] * (E - 1)
+    sim = oracle.CacheSim([100] * E, probs, succ_off, list(range(1, E)), cap_experts=cap)
+    sim.init_fill()
+    return sim
+
+
+def test_arranging_hand_worked_schedule(oracle):
+    """Root 0 and leaves 1 (probability 0.6), 2 (0.4); the cache holds two experts, so after the initial fill 0 and 1
+    are on the device.  Window: a group of a missing expert waits until it has 3 requests, at most 2 steps.
+    Requests r0..r5 visit [0,1] [0,2] [0,2] [0,1] [0,2] [0,2]; hand-overs: {r0,r1} {r2,r3} {r4} {r5}.
+      step 0: group 0 = {r0,r1} runs.
+      step 1: 0 = {r2,r3} runs; 1 = {r0} runs (on the device: no threshold); 2 = {r1}: missing, 1 < 3, age 1 < 2: waits.
+      step 2: 0 = {r4} runs; 1 = {r3} runs; 2 = {r1,r2}: the oldest has waited 2 steps: runs, loaded in place of
+              expert 1 (both residents have run by then; 1 has the lower usage probability).
+      step 3: 0 = {r5} runs; 2 = {r4} runs (on the device now).
+      step 4: 2 = {r5} runs.
+    One switch.  Without the window the same arrivals alternate experts 1 and 2 in the second slot: three switches."""
+    from oracle import arrange
+    paths = [[0, 1], [0, 2], [0, 2], [0, 1], [0, 2], [0, 2]]
+    submits = [[0, 1], [2, 3], [4], [5]]
+    rec = arrange.replay(submits, paths, [0, 0, 0], {0: (0, 3, 2)}, _tree_cache(oracle, [1.0, 0.6, 0.4], 2))
+    assert [r["run"] for r in rec] == [{0: [0, 1]}, {0: [2, 3], 1: [0]}, {0: [4], 1: [3], 2: [1, 2]}, {0: [5], 2: [4]}, {2: [5]}]
+    assert [r["deferred"] for r in rec] == [{}, {2: [1]}, {}, {}, {}]
+    assert [r["n_pending"] for r in rec] == [2, 4, 4, 2, 1]
+    assert [r["switches"] for r in rec] == [[], [], [(2, [1])], [], []]
+    assert [r["order"] for r in rec] == [[0], [0, 1], [0, 1, 2], [0, 2], [2]]
+    plain = arrange.replay(submits, paths, [0, 0, 0], {}, _tree_cache(oracle, [1.0, 0.6, 0.4], 2))
+    assert [r["deferred"] for r in plain] == [{}] * len(plain)
+    assert [r["switches"] for r in plain] == [[], [(2, [1])], [(1, [2])], [(2, [1])], []]
+
+
+def test_arranging_rule_cases():
+    from oracle.arrange import stays_queued
+    assert not stays_queued(0, 0, False, 5, 5, 5)                  # nothing queued
+    assert stays_queued(2, 0, False, 0, 3, 1)                      # missing, small, young
+    assert not stays_queued(3, 0, False, 0, 3, 1)                  # reached the threshold
+    assert not stays_queued(2, 1, False, 0, 3, 1)                  # waited long enough
+    assert not stays_queued(2, 0, True, 0, 3, 1)                   # on the device: its own threshold (none)
+    assert stays_queued(2, 0, True, 4, 0, 1) and not stays_queued(2, 0, False, 4, 0, 1)
+    assert not stays_queued(1, 0, False, 100, 100, 0)              # window off
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_arranging_invariants_random(oracle, seed):
+    """Random trees, arrival sequences and windows: every request runs the stages of its path once each and in order,
+    one stage per step at most; nobody waits beyond max_wait; a waiting group is small and young; with max_wait = 0
+    the schedule is the plain one (every queued group runs in every step)."""
+    from oracle import arrange
+    rng = np.random.default_rng(100 + seed)
+    n_leaves = int(rng.integers(2, 9))
+    E = n_leaves + 1
+    probs = [1.0] + list(np.sort(rng.random(n_leaves))[::-1] * 0.9 + 0.01)
+    n = int(rng.integers(20, 120))
+    paths = [[0, int(rng.integers(1, E))] if rng.random() < 0.9 else [0] for _ in range(n)]
+    cuts = np.sort(rng.choice(np.arange(1, n), size=int(rng.integers(1, 8)), replace=False))
+    submits = [list(range(a, b)) for a, b in zip([0] + list(cuts), list(cuts) + [n])]
+    win = (int(rng.integers(0, 4)), int(rng.integers(0, 12)), int(rng.integers(0, 5)))
+    cap = int(rng.integers(2, E + 1))
+    rec = arrange.replay(submits, paths, [0] * E, {0: win}, _tree_cache(oracle, probs, cap))
+    first_seen = {r: k for k, batch in enumerate(submits) for r in batch}
+    ran = {r: [] for r in range(n)}
+    for k, st in enumerate(rec):
+        assert st["step"] == k and not (set(st["run"]) & set(st["deferred"]))
+        for e, members in st["run"].items():
+            for r in members:
+                ran[r].append((k, e))
+        for e, members in st["deferred"].items():
+            age = k - min(first_seen[r] for r in members)
+            assert age < win[2] and len(members) < max(win[0], win[1])
+        assert st["n_pending"] == sum(len(m) for m in st["run"].values()) + sum(len(m) for m in st["deferred"].values())
+    for r in range(n):
+        assert [e for k, e in ran[r]] == paths[r]
+        steps = [k for k, e in ran[r]]
+        assert steps == sorted(set(steps)) and steps[0] >= first_seen[r]
+        # stage i is queued from step max(first_seen, previous stage + 1) on and runs before the request's age passes max_wait
+        for i, k in enumerate(steps):
+            queued_from = first_seen[r] if i == 0 else steps[i - 1] + 1
+            assert k <= max(queued_from, first_seen[r] + win[2])
+    off = arrange.replay(submits, paths, [0] * E, {0: (win[0], win[1], 0)}, _tree_cache(oracle, probs, cap))
+    assert all(not st["deferred"] for st in off)
+    plain = arrange.replay(submits, paths, [0] * E, {}, _tree_cache(oracle, probs, cap))
+    assert [(st["run"], st["switches"]) for st in off] == [(st["run"], st["switches"]) for st in plain]
