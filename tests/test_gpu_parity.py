@@ -514,3 +514,25 @@ def test_arranging_window_matches_replay_and_keeps_results(B, oracle, G, window)
     assert len(got["switch_log"]) < len(plain["switch_log"])         # waiting groups merged: fewer switches
     print(f"window {window}: {len(plain['switch_log']) - 4} -> {len(log) - 4} switches, "
           f"{len([1 for rc, st in plain['stats'] if rc == B.COE_OK])} -> {len(stats)} steps")
+
+
+def test_offline_profiler_measures_a_usable_latency_model(B):
+    """Section 4.5 microbenchmark on a small ResNet-50-shaped architecture: latency grows with the batch, the fitted
+    line has a positive slope and intercept, a switch moves exactly the blob, thresholds are ordered."""
+    from paper_2503_02354_amd import profiler as P
+    arch = W.resnet50(8, 64, W.DT_BF16, 32)
+    blob = W.make_expert_blob(arch, 3, 0)
+    ctx = B.Context(max_requests=4, max_batch=256)
+    aid = ctx.coe_register_arch(arch)
+    ctx.coe_register_expert(0, aid, blob, 1.0)
+    sizes = [1, 16, 64, 128, 256]
+    lat = P.measure_batch_latency(ctx, 0, (64, 64, 3), sizes, repeats=5)
+    ctx.close()
+    K, Bc = P.fit_latency(sizes, [lat[n] for n in sizes])
+    assert lat[256] > lat[1] and K > 0 and Bc > 0, (lat, K, Bc)
+    assert P.plateau_batch(sizes, [lat[n] for n in sizes]) in sizes
+    load = P.measure_load_latency(B, arch, blob)
+    assert load["bytes"] == blob.nbytes and load["us"] > 0 and 1.0 < load["GBps"] < 100.0, load
+    lo, hi, wait = P.arranging_window(K, Bc, load["us"], 0.2, 4)
+    assert 0 <= lo <= hi and wait == 4
+    print(f"latency model K {K:.2f} us/request, B {Bc:.0f} us, load {load['us']:.0f} us at {load['GBps']:.1f} GB/s, window {lo, hi, wait}")

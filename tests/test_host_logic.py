@@ -121,3 +121,19 @@ def test_arranging_rule_matches_oracle(B):
         got = B.coe_arrange_defer(count, age, res, mr, mm, mw)
         want = [stays_queued(int(count[e]), int(age[e]), bool(res[e]), int(mr[e]), int(mm[e]), int(mw[e])) for e in range(E)]
         assert got.tolist() == want
+
+
+def test_profiler_arithmetic():
+    """Latency model fit, batch plateau and arranging thresholds (paper Sections 4.2, 4.5) on hand-made numbers."""
+    from paper_2503_02354_amd import profiler as P
+    K, Bc = P.fit_latency([1, 2, 4, 8, 16], [103.0, 106.0, 112.0, 124.0, 148.0])     # exactly 3 n + 100
+    assert abs(K - 3.0) < 1e-9 and abs(Bc - 100.0) < 1e-9
+    K, Bc = P.fit_latency([10, 20, 30], [25.0, 45.0, 59.0])                           # textbook least squares: 1.7 n + 9
+    assert abs(K - 1.7) < 1e-9 and abs(Bc - 9.0) < 1e-9
+    # per-request latency 110, 60, 35, 22.5, 21.2, 21.0: within 5 % of the best from n = 16 on
+    assert P.plateau_batch([1, 2, 4, 8, 16, 32], [110, 120, 140, 180, 339.2, 672], tol=0.05) == 16
+    assert P.plateau_batch([1, 2, 4], [10, 20, 40]) == 1
+    # K = 10, B = 1000, load = 800; half of the time useful: n >= 100 resident, 180 missing; a fifth: 25 and 45
+    assert P.arranging_window(10.0, 1000.0, 800.0, 0.5, 8) == (100, 180, 8)
+    assert P.arranging_window(10.0, 1000.0, 800.0, 0.2, 3) == (25, 45, 3)
+    assert P.arranging_window(10.0, 1000.0, 800.0, 0.0, 3) == (0, 0, 3)
