@@ -25,14 +25,16 @@ sys.path.insert(0, ROOT)
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 # HBM bytes per launch of conv3x3_slab_kernel on this workload, from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE)
 # scaled by what the same counters read for the gather kernel's plain copy (profiles/conv3x3_slab_config2_hbm_counters.md).
-# Tied to the kernel source it was measured on: any edit of that file makes bench.py report null again.
-SLAB_TRAFFIC_BYTES_PER_LAUNCH = 205.2e6
+# Tied to the kernel source and the launch configuration it was measured on: an edit of that file, another workload,
+# batch cap or grouping threshold make bench.py report null again.
+SLAB_TRAFFIC_BYTES_PER_LAUNCH = 2329.8e6
 SLAB_TRAFFIC_SOURCE = ("paper_2503_02354_amd/csrc/conv_mfma.hip",
-                       "e962cc54a067c87b8364153a90c8763675bd17675ae8f53583eeb9e7f3ce6cda")
+                       "da23a53c7c541e6dd6397032f79f58e0a921a3f097e18b8be3344e87c0625597")
+SLAB_TRAFFIC_LAUNCH_CONFIG = ("config2", 0, 4096, 512, 1, "")   # workload, requests, max_batch, group_small, arrivals per step, window
 
 
-def measured_traffic(kernel: str):
-    if kernel != "conv3x3_slab_kernel":
+def measured_traffic(kernel: str, launch_config=None):
+    if kernel != "conv3x3_slab_kernel" or launch_config != SLAB_TRAFFIC_LAUNCH_CONFIG:
         return None
     import hashlib
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), SLAB_TRAFFIC_SOURCE[0])
@@ -189,7 +191,9 @@ def main():
         achieved = p["work"] / (p["ms"] * 1e-3) / 1e12
         roofline = {"bound": "mfma", "kernel": mfma_kernels[dom], "achieved": round(achieved, 2),
                     "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "traffic": measured_traffic(mfma_kernels[dom]), "traffic_unit": "HBM bytes per launch",
+                    "traffic": measured_traffic(mfma_kernels[dom], (args.workload, args.requests, args.max_batch, args.group_small,
+                                                                              args.arrivals_per_step, args.arrange)),
+                    "traffic_unit": "HBM bytes per launch",
                     "launches_timed": p["launches"], "launches": p["issued"],
                     "avg_launch_us": round(p["ms"] * 1e3 / p["launches"], 2),
                     "share_of_step": round(est_ms[dom] / args.steps / ms_per_step, 3)}
