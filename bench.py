@@ -81,6 +81,12 @@ def main():
                     help="arranging window 'min_resident,min_missing,max_wait' for every architecture: a queued group "
                          "smaller than min_resident (expert on the device) or min_missing (expert missing) waits up to "
                          "max_wait steps for later arrivals to join it (empty = off: every queued group runs in every step)")
+    ap.add_argument("--eviction", default="two-stage", choices=["two-stage", "lru", "fifo"],
+                    help="replacement rule of the expert cache: the paper's two-stage rule (default) or the rules of the "
+                         "systems it compares with")
+    ap.add_argument("--prefetch-depth", type=int, default=0,
+                    help="experts of this many groups right before a missing one in the plan count as in use while its copy "
+                         "is in flight (0: consecutive misses reuse one slot and each copy waits for the group before it)")
     ap.add_argument("--no-profile", action="store_true", help="do not time kernel classes with events")
     ap.add_argument("--profile-every", type=int, default=0,
                     help="time every k-th launch of each kernel class (0 = every launch for config2 / config4, whose steps "
@@ -118,7 +124,7 @@ def main():
 
     ctx = B.Context(max_requests=n, max_stages=wl.max_stages, max_batch=args.max_batch,
                     cache_cap_experts=wl.cache_cap_experts, profile=0 if args.no_profile else args.profile_every,
-                    group_small=args.group_small)
+                    group_small=args.group_small, eviction=["two-stage", "lru", "fifo"].index(args.eviction), prefetch_depth=args.prefetch_depth)
     B.setup_workload(ctx, wl, blobs)
     window = [int(v) for v in args.arrange.split(",")] if args.arrange else None
     if window:
@@ -219,7 +225,7 @@ def main():
     cache = None
     if step_stats:
         misses = sum(st.n_misses for st in step_stats)
-        cache = {"cap_experts": wl.cache_cap_experts, "switches_per_pass": misses // max(args.steps, 1),
+        cache = {"cap_experts": wl.cache_cap_experts, "replacement": args.eviction, "prefetch_depth": args.prefetch_depth, "switches_per_pass": misses // max(args.steps, 1),
                  "evictions_per_pass": sum(st.n_evictions for st in step_stats) // max(args.steps, 1),
                  "bytes_switched_per_pass": sum(st.bytes_switched for st in step_stats) // max(args.steps, 1),
                  "host_plan_us_per_step": round(float(np.mean([st.host_plan_us for st in step_stats])), 1)}

@@ -87,6 +87,15 @@ typedef struct {
     int32_t group_small;       /* request arranging leaves many groups of a few requests: groups of at most this many
                                 * requests whose experts share an architecture run as ONE launch per layer (0 = 64,
                                 * negative = never).  Results do not depend on it. */
+    int32_t eviction;          /* replacement rule of the expert cache: 0 = the two-stage rule of paper Section 4.3;
+                                * 1 = least recently used, 2 = first in first out (the rules of the systems the paper
+                                * compares with, Section 5.1; for measuring what the two-stage rule buys) */
+    int32_t prefetch_depth;    /* expert switches are issued ahead of the groups that need them, so that the copy runs
+                                * while earlier groups compute (paper Section 4.2: an expert can be loaded during the
+                                * processing of a preceding request).  The experts of this many groups right before a
+                                * missing one in the plan count as in use while its copy is in flight and are not
+                                * evicted for it; 0 = only groups that have not run yet in the stage are protected, and
+                                * consecutive misses then reuse one slot: each copy waits for the group before it. */
 } coe_config;
 
 typedef struct {
@@ -228,6 +237,10 @@ int coe_policy_init_fill(coe_policy* p, int32_t* loaded /*[E]*/);
 int coe_policy_stage(coe_policy* p, const uint8_t* has_group, int32_t* order, int32_t* n_order, int32_t* log,
                      int32_t log_cap);
 int coe_policy_resident(const coe_policy* p, uint8_t* out /*[E]*/);
+/* Replacement rule as in coe_config.eviction; COE_EINVAL for an unknown kind.  Call before the first stage. */
+int coe_policy_set_eviction(coe_policy* p, int32_t kind);
+/* As coe_config.prefetch_depth; COE_EINVAL for a negative depth. */
+int coe_policy_set_in_use_depth(coe_policy* p, int32_t depth);
 
 #ifdef __cplusplus
 }

@@ -475,6 +475,13 @@ typedef struct {
     int64_t cap_bytes;        /* 0 = unlimited */
     uint8_t* resident;        /* [E] */
     int n_res; int64_t res_bytes;
+    int rule;                 /* 0 = two-stage (Section 4.3); 1 = least recently used; 2 = first in, first out */
+    int in_use;               /* a load is started while the groups before it in the plan still run (Section 4.2: an
+                                 expert can be loaded during the processing of a preceding request): the experts of this
+                                 many preceding groups cannot be its victims */
+    int64_t now;              /* event counter: every load and every executed group is one event */
+    int64_t* t_load;          /* [E] event of the last load */
+    int64_t* t_use;           /* [E] event of the last use (a load counts as a use) */
 } orc_cache;
 
 orc_cache* orc_cache_new(int E, const int64_t* bytes, const float* prob, const int32_t* succ_off, const int32_t* succ,
@@ -484,9 +491,24 @@ orc_cache* orc_cache_new(int E, const int64_t* bytes, const float* prob, const i
     c->E = E; c->bytes = bytes; c->prob = prob; c->succ_off = succ_off; c->succ = succ;
     c->cap_experts = cap_experts; c->cap_bytes = cap_bytes;
     c->resident = (uint8_t*)calloc((size_t)E, 1);
+    c->t_load = (int64_t*)calloc((size_t)E, sizeof(int64_t));
+    c->t_use = (int64_t*)calloc((size_t)E, sizeof(int64_t));
     return c;
 }
-void orc_cache_free(orc_cache* c) { if (c) { free(c->resident); free(c); } }
+void orc_cache_free(orc_cache* c) { if (c) { free(c->resident); free(c->t_load); free(c->t_use); free(c); } }
+/* Replacement rule of the comparison systems (Section 5.1: LRU, FIFO) instead of the two-stage rule; the textbook
+ * definitions: the victim is the resident expert used (LRU) / loaded (FIFO) longest ago.  As under the two-stage rule,
+ * an expert whose group has not run yet in the stage is not a candidate. */
+int orc_cache_set_rule(orc_cache* c, int rule) { if (rule < 0 || rule > 2) return -1; c->rule = rule; return 0; }
+int orc_cache_set_in_use(orc_cache* c, int depth) { if (depth < 0) return -1; c->in_use = depth; return 0; }
+
+/* is expert x one of the `depth` plan entries right before position i? */
+static int runs_just_before(const int32_t* order, int i, int depth, int x)
+{
+    for (int q = i - 1; q >= 0 && q >= i - depth; --q)
+        if (order[q] == x) return 1;
+    return 0;
+}
 int orc_cache_resident(const orc_cache* c, uint8_t* out) { memcpy(out, c->resident, (size_t)c->E); return c->n_res; }
 
 static int fits(const orc_cache* c, int e)
@@ -508,6 +530,7 @@ int orc_cache_init_fill(orc_cache* c, int32_t* loaded)
             if (!done[e] && (best < 0 || c->prob[e] > c->prob[best])) best = e;
         if (best < 0 || !fits(c, best)) break;
         done[best] = 1; c->resident[best] = 1; c->n_res++; c->res_bytes += c->bytes[best];
+        c->t_load[best] = c->t_use[best] = ++c->now;
         loaded[n++] = best;
     }
     free(done);
@@ -534,6 +557,20 @@ int orc_cache_stage(orc_cache* c, const uint8_t* has_group, int32_t* order, int*
         if (!c->resident[e]) {
             if (nl + 2 > log_cap) { free(todo); return -1; }
             int head = nl; log[nl++] = e; log[nl++] = 0;
+            if (c->rule != 0) {
+                const int64_t* t = c->rule == 1 ? c->t_use : c->t_load;
+                while (!fits(c, e)) {
+                    int v = -1;
+                    for (int x = 0; x < E; ++x) {
+                        if (!c->resident[x] || todo[x] || runs_just_before(order, i, c->in_use, x)) continue;
+                        if (v < 0 || t[x] < t[v]) v = x;
+                    }
+                    if (v < 0) { free(todo); return -1; }
+                    c->resident[v] = 0; c->n_res--; c->res_bytes -= c->bytes[v];
+                    if (nl >= log_cap) { free(todo); return -1; }
+                    log[nl++] = v; log[head + 1]++;
+                }
+            }
             /* stage 1: the candidate set is fixed when the miss occurs, then evicted largest first */
             uint8_t* cand = (uint8_t*)calloc((size_t)E, 1);
             for (int x = 0; x < E; ++x) {
@@ -559,7 +596,7 @@ int orc_cache_stage(orc_cache* c, const uint8_t* has_group, int32_t* order, int*
             while (!fits(c, e)) {
                 int v = -1;
                 for (int x = 0; x < E; ++x) {
-                    if (!c->resident[x] || todo[x]) continue;
+                    if (!c->resident[x] || todo[x] || runs_just_before(order, i, c->in_use, x)) continue;
                     if (v < 0 || c->prob[x] < c->prob[v]) v = x;
                 }
                 if (v < 0) { free(todo); return -1; }
@@ -568,7 +605,9 @@ int orc_cache_stage(orc_cache* c, const uint8_t* has_group, int32_t* order, int*
                 log[nl++] = v; log[head + 1]++;
             }
             c->resident[e] = 1; c->n_res++; c->res_bytes += c->bytes[e];
+            c->t_load[e] = ++c->now;
         }
+        c->t_use[e] = ++c->now;
         todo[e] = 0;
     }
     free(todo);

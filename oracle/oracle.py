@@ -44,6 +44,8 @@ def lib():
         L.orc_bf16_round.argtypes = [C.c_float]
         L.orc_cache_new.restype = C.c_void_p
         L.orc_cache_free.argtypes = [C.c_void_p]
+        L.orc_cache_set_rule.argtypes = [C.c_void_p, C.c_int]
+        L.orc_cache_set_in_use.argtypes = [C.c_void_p, C.c_int]
         L.orc_cache_init_fill.argtypes = [C.c_void_p, C.c_void_p]
         L.orc_cache_resident.argtypes = [C.c_void_p, C.c_void_p]
         L.orc_cache_stage.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(C.c_int), C.c_void_p, C.c_int]
@@ -182,7 +184,8 @@ def split(off: np.ndarray, order: Sequence[int], max_batch: int) -> np.ndarray:
 class CacheSim:
     """Replay of the expert-cache policy: initial fill, then one call per stage."""
 
-    def __init__(self, nbytes: Sequence[int], prob: Sequence[float], succ_off, succ, cap_experts: int = 0, cap_bytes: int = 0):
+    def __init__(self, nbytes: Sequence[int], prob: Sequence[float], succ_off, succ, cap_experts: int = 0, cap_bytes: int = 0,
+                 rule: int = 0, in_use: int = 0):
         self.E = len(nbytes)
         self._bytes = np.ascontiguousarray(nbytes, np.int64); self._prob = np.ascontiguousarray(prob, np.float32)
         self._so = np.ascontiguousarray(succ_off, np.int32); self._su = np.ascontiguousarray(succ, np.int32)
@@ -191,6 +194,10 @@ class CacheSim:
         L = lib()
         L.orc_cache_new.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int64]
         self._h = L.orc_cache_new(self.E, _p(self._bytes), _p(self._prob), _p(self._so), _p(self._su), cap_experts, cap_bytes)
+        if L.orc_cache_set_rule(self._h, rule):          # 0 two-stage, 1 least recently used, 2 first in first out
+            raise ValueError("unknown replacement rule")
+        if L.orc_cache_set_in_use(self._h, in_use):      # experts of this many preceding groups are busy during a load
+            raise ValueError("negative depth")
 
     def __del__(self):
         if getattr(self, "_h", None):

@@ -24,7 +24,7 @@ EXPORTS = [
     "coe_set_dependency_graph", "coe_submit", "coe_step", "coe_sync", "coe_collect", "coe_reset_requests",
     "coe_debug_last_regroup", "coe_debug_switch_log", "coe_debug_resident", "coe_debug_forward", "coe_debug_layer_output", "coe_debug_regroup", "coe_debug_conv",
     "coe_profile_read", "coe_profile_issued", "coe_validate_graph", "coe_policy_create", "coe_policy_destroy", "coe_policy_init_fill",
-    "coe_policy_stage", "coe_policy_resident", "coe_set_arranging", "coe_arrange_defer",
+    "coe_policy_stage", "coe_policy_resident", "coe_policy_set_eviction", "coe_policy_set_in_use_depth", "coe_set_arranging", "coe_arrange_defer",
 ]
 
 
@@ -40,7 +40,7 @@ class coe_arch_desc(C.Structure):
 class coe_config(C.Structure):
     _fields_ = [("device", C.c_int32), ("max_requests", C.c_int32), ("max_batch", C.c_int32), ("max_stages", C.c_int32),
                 ("cache_cap_experts", C.c_int32), ("profile", C.c_int32), ("cache_cap_bytes", C.c_int64),
-                ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p), ("group_small", C.c_int32)]
+                ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p), ("group_small", C.c_int32), ("eviction", C.c_int32), ("prefetch_depth", C.c_int32)]
 
 
 class coe_step_stats(C.Structure):
@@ -83,6 +83,8 @@ def _load():
     L.coe_policy_init_fill.argtypes = [vp, vp]
     L.coe_policy_stage.argtypes = [vp, vp, vp, C.POINTER(i32), vp, i32]
     L.coe_policy_resident.argtypes = [vp, vp]
+    L.coe_policy_set_eviction.argtypes = [vp, i32]
+    L.coe_policy_set_in_use_depth.argtypes = [vp, i32]
     L.coe_set_arranging.argtypes = [vp, i32, i32, i32, i32]
     L.coe_arrange_defer.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp]
     return L
@@ -128,7 +130,7 @@ def coe_validate_graph(n_experts: int, succ_off, succ, n_classes=None) -> int:
 class Policy:
     """coe_policy_* : the library's cache policy without a device."""
 
-    def __init__(self, nbytes, prob, succ_off, succ, cap_experts=0, cap_bytes=0):
+    def __init__(self, nbytes, prob, succ_off, succ, cap_experts=0, cap_bytes=0, eviction=0, in_use_depth=0):
         self.E = len(nbytes)
         b = np.ascontiguousarray(nbytes, np.int64); p = np.ascontiguousarray(prob, np.float32)
         so = np.ascontiguousarray(succ_off, np.int32); su = np.ascontiguousarray(succ, np.int32)
@@ -137,6 +139,9 @@ class Policy:
         self._h = lib.coe_policy_create(self.E, _ptr(b), _ptr(p), _ptr(so), _ptr(su), cap_experts, cap_bytes)
         if not self._h:
             raise CoEError(COE_EINVAL, "coe_policy_create failed")
+        rc = lib.coe_policy_set_eviction(self._h, eviction) or lib.coe_policy_set_in_use_depth(self._h, in_use_depth)
+        if rc:
+            raise CoEError(rc, "coe_policy_set_eviction / coe_policy_set_in_use_depth")
 
     def __del__(self):
         if getattr(self, "_h", None):
@@ -179,9 +184,9 @@ class Context:
 
     def __init__(self, max_requests: int, max_stages: int = 2, max_batch: int = 0, cache_cap_experts: int = 0,
                  cache_cap_bytes: int = 0, device: int = 0, profile: bool = False, compute_stream: int = 0,
-                 copy_stream: int = 0, group_small: int = 0):
+                 copy_stream: int = 0, group_small: int = 0, eviction: int = 0, prefetch_depth: int = 0):
         cfg = coe_config(device, max_requests, max_batch, max_stages, cache_cap_experts, int(profile), cache_cap_bytes,
-                         compute_stream or None, copy_stream or None, group_small)
+                         compute_stream or None, copy_stream or None, group_small, eviction, prefetch_depth)
         h = C.c_void_p()
         rc = lib.coe_create(C.byref(cfg), C.byref(h))
         if rc != COE_OK:

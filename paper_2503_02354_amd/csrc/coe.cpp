@@ -806,6 +806,8 @@ int coe_set_dependency_graph(coe_ctx* c, int32_t n, const int32_t* succ_off, con
     for (int32_t e = 0; e < n; ++e) { bytes[e] = (int64_t)c->experts[e].nbytes; prob[e] = c->experts[e].prob; }
     c->policy.reset(new coe::Policy(n, bytes.data(), prob.data(), c->succ_off.data(), c->succ.data(), c->cfg.cache_cap_experts,
                                     c->cfg.cache_cap_bytes));
+    if (!c->policy->set_eviction(c->cfg.eviction)) return fail(c, COE_EINVAL, "unknown eviction rule");
+    if (!c->policy->set_in_use_depth(c->cfg.prefetch_depth)) return fail(c, COE_EINVAL, "negative prefetch depth");
     c->E = n;
     c->graph_set = true;
     return COE_OK;

@@ -11,7 +11,8 @@ namespace coe {
 Policy::Policy(int32_t n_experts, const int64_t* nbytes, const float* prob, const int32_t* succ_off,
                const int32_t* succ, int32_t cap_experts, int64_t cap_bytes)
     : n_(n_experts), bytes_(nbytes, nbytes + n_experts), prob_(prob, prob + n_experts), preds_(n_experts),
-      cap_experts_(cap_experts), cap_bytes_(cap_bytes), resident_(n_experts, 0)
+      cap_experts_(cap_experts), cap_bytes_(cap_bytes), resident_(n_experts, 0), loaded_at_(n_experts, 0),
+      used_at_(n_experts, 0)
 {
     for (int32_t p = 0; p < n_; ++p)
         for (int32_t j = succ_off[p]; j < succ_off[p + 1]; ++j) {
@@ -35,6 +36,20 @@ void Policy::evict(int32_t v)
     res_bytes_ -= bytes_[v];
 }
 
+bool Policy::set_eviction(int32_t kind)
+{
+    if (kind < 0 || kind > 2) return false;
+    eviction_ = kind;
+    return true;
+}
+
+bool Policy::set_in_use_depth(int32_t depth)
+{
+    if (depth < 0) return false;
+    in_use_depth_ = depth;
+    return true;
+}
+
 std::vector<int32_t> Policy::init_fill()
 {
     std::vector<int32_t> ids(n_);
@@ -47,6 +62,7 @@ std::vector<int32_t> Policy::init_fill()
         resident_[e] = 1;
         ++n_res_;
         res_bytes_ += bytes_[e];
+        loaded_at_[e] = used_at_[e] = ++clock_;
         loaded.push_back(e);
     }
     return loaded;
@@ -64,10 +80,25 @@ bool Policy::plan_stage(const uint8_t* has_group, std::vector<int32_t>& order, s
     std::vector<uint8_t> waiting(n_, 0);  // group not yet executed in this stage
     for (int32_t e : order) waiting[e] = 1;
 
-    for (int32_t e : order) {
+    for (size_t pos = 0; pos < order.size(); ++pos) {
+        const int32_t e = order[pos];
         if (!resident_[e]) {
             Switch sw;
             sw.expert = e;
+            // the groups right before this one are still running when the copy starts: their experts stay
+            for (size_t q = pos > (size_t)in_use_depth_ ? pos - in_use_depth_ : 0; q < pos; ++q) waiting[order[q]] = 2;
+            if (!fits(e) && eviction_ != 0) {
+                // comparison rules: oldest use (LRU) or oldest load (FIFO) among everything that is not waiting to run
+                const std::vector<int64_t>& key = eviction_ == 1 ? used_at_ : loaded_at_;
+                while (!fits(e)) {
+                    int32_t v = -1;
+                    for (int32_t x = 0; x < n_; ++x)
+                        if (resident_[x] && !waiting[x] && (v < 0 || key[x] < key[v])) v = x;
+                    if (v < 0) break;
+                    evict(v);
+                    sw.victims.push_back(v);
+                }
+            }
             if (!fits(e)) {
                 // Stage 1: dependent experts none of whose predecessors is resident or requested in this stage
                 // (they cannot be reached soon), largest footprint first.
@@ -103,8 +134,11 @@ bool Policy::plan_stage(const uint8_t* has_group, std::vector<int32_t>& order, s
             resident_[e] = 1;
             ++n_res_;
             res_bytes_ += bytes_[e];
+            loaded_at_[e] = ++clock_;
             switches.push_back(std::move(sw));
+            for (size_t q = pos > (size_t)in_use_depth_ ? pos - in_use_depth_ : 0; q < pos; ++q) waiting[order[q]] = 0;
         }
+        used_at_[e] = ++clock_;
         waiting[e] = 0;
     }
     return true;
@@ -187,6 +221,18 @@ int coe_policy_stage(coe_policy* p, const uint8_t* has_group, int32_t* order, in
         for (int32_t v : s.victims) log[n++] = v;
     }
     return n;
+}
+
+int coe_policy_set_eviction(coe_policy* p, int32_t kind)
+{
+    if (!p) return COE_EINVAL;
+    return p->impl.set_eviction(kind) ? COE_OK : COE_EINVAL;
+}
+
+int coe_policy_set_in_use_depth(coe_policy* p, int32_t depth)
+{
+    if (!p) return COE_EINVAL;
+    return p->impl.set_in_use_depth(depth) ? COE_OK : COE_EINVAL;
 }
 
 int coe_policy_resident(const coe_policy* p, uint8_t* out)

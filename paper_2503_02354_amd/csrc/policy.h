@@ -27,6 +27,17 @@ public:
     bool resident(int32_t e) const { return resident_[e] != 0; }
     int32_t n_experts() const { return n_; }
 
+    // Replacement rule: 0 = the two-stage rule of Section 4.3 (default); 1 = least recently used, 2 = first in first
+    // out: the rules of the systems the paper compares with (Section 5.1), kept for measuring what the two-stage rule
+    // buys.  Under all three an expert whose group has not run yet in the stage is never evicted.
+    bool set_eviction(int32_t kind);
+
+    // Loads are issued ahead of the groups that need them, so that the copy runs while earlier groups compute (paper
+    // Section 4.2: an expert can be loaded during the processing of a preceding request).  The experts of the `depth`
+    // groups that precede a missing one in the plan then still have kernels queued or running when its copy starts:
+    // they count as in use and are not evicted for it.  0 (default): only groups that have not run yet are protected.
+    bool set_in_use_depth(int32_t depth);
+
 private:
     bool fits(int32_t e) const;
     void evict(int32_t v);
@@ -40,6 +51,10 @@ private:
     std::vector<uint8_t> resident_;
     int32_t n_res_ = 0;
     int64_t res_bytes_ = 0;
+    int32_t eviction_ = 0;
+    int32_t in_use_depth_ = 0;
+    int64_t clock_ = 0;                        // counts loads and group executions, in plan order
+    std::vector<int64_t> loaded_at_, used_at_;
 };
 
 // Dependency-graph check: ids in range (or -1), acyclic, n_route <= n_classes.  Returns 0 or COE_EGRAPH / COE_EINVAL.

@@ -536,3 +536,31 @@ def test_offline_profiler_measures_a_usable_latency_model(B):
     lo, hi, wait = P.arranging_window(K, Bc, load["us"], 0.2, 4)
     assert 0 <= lo <= hi and wait == 4
     print(f"latency model K {K:.2f} us/request, B {Bc:.0f} us, load {load['us']:.0f} us at {load['GBps']:.1f} GB/s, window {lo, hi, wait}")
+
+
+@pytest.mark.parametrize("rule,depth", [(1, 0), (2, 0), (0, 1), (0, 2), (1, 2)])
+def test_replacement_rules_and_in_use_depth_follow_the_replay(B, oracle, G, rule, depth):
+    """Least-recently-used (1) and first-in-first-out (2) replacement in the device cache, and the two-stage rule (0)
+    with the experts of the preceding groups protected while a load is in flight: same results as the plain two-stage
+    rule, switch log equal to the oracle's replay of that rule."""
+    from oracle import arrange
+    n, E, arrival = 120, 10, 20
+    wl = W.config3(n, hw=64, n_experts=E, width=16, cap=4, arrival_batch=arrival, calibrated=False)
+    G.calibrate_workload(wl, n_cal=64, targets={0: W.zipf_probs(E - 1, 1.1)})
+    blobs = [wl.blob(e) for e in range(E)]
+    x, sub, want, _ = G.guarded_inputs(wl, blobs, range(n))
+    assert not want["ambiguous"].any()
+    base = run_chain_gpu(B, wl, blobs, x, max_batch=16, arrival=arrival)
+    got = run_chain_gpu(B, wl, blobs, x, max_batch=16, arrival=arrival, eviction=rule, prefetch_depth=depth)
+    assert np.array_equal(got["path"], base["path"]) and np.array_equal(got["logits"], base["logits"])
+    assert_chain_parity(got, want, REL_TOL_BF16)
+    sim = oracle.CacheSim([b.nbytes for b in blobs], wl.usage_prob, wl.graph.succ_off, wl.graph.succ, cap_experts=4, rule=rule,
+                          in_use=depth)
+    log = [(e, []) for e in sim.init_fill()]
+    paths = [[int(e) for e in p if e >= 0] for p in want["path"]]
+    submits = [list(range(s, min(s + arrival, n))) for s in range(0, n, arrival)]
+    for r in arrange.replay(submits, paths, wl.expert_arch, {}, sim):
+        log += r["switches"]
+    assert got["switch_log"] == log
+    assert got["switch_log"] != base["switch_log"]
+    print(f"rule {rule} depth {depth}: {len(log) - 4} switches, plain two-stage rule: {len(base['switch_log']) - 4}")

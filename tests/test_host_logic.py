@@ -57,9 +57,9 @@ def test_create_without_gpu_fails_loudly(B):
     assert ei.value.code == B.COE_EDEVICE
 
 
-def _compare_policy(B, oracle, nbytes, prob, graph, cap_experts, cap_bytes, stages):
-    sim = oracle.CacheSim(nbytes, prob, graph.succ_off, graph.succ, cap_experts, cap_bytes)
-    pol = B.Policy(nbytes, prob, graph.succ_off, graph.succ, cap_experts, cap_bytes)
+def _compare_policy(B, oracle, nbytes, prob, graph, cap_experts, cap_bytes, stages, rule=0, depth=0):
+    sim = oracle.CacheSim(nbytes, prob, graph.succ_off, graph.succ, cap_experts, cap_bytes, rule=rule, in_use=depth)
+    pol = B.Policy(nbytes, prob, graph.succ_off, graph.succ, cap_experts, cap_bytes, eviction=rule, in_use_depth=depth)
     assert sim.init_fill() == pol.init_fill()
     for hg in stages:
         try:
@@ -92,6 +92,32 @@ def test_policy_matches_oracle_random(B, oracle, seed):
     prob = np.round(np.asarray(wl.usage_prob), 2) if seed % 3 == 0 else wl.usage_prob      # rounded: exercises ties
     stages = [(rng.random(E) < rng.choice([0.1, 0.3, 0.6])).astype(np.uint8) for _ in range(40)]
     _compare_policy(B, oracle, nbytes, prob, wl.graph, 0 if seed % 2 else 6, 110 if seed % 2 else 0, stages)
+
+
+@pytest.mark.parametrize("rule", [1, 2])
+@pytest.mark.parametrize("seed", range(4))
+def test_comparison_rules_match_oracle_random(B, oracle, seed, rule):
+    """Least-recently-used and first-in-first-out replacement (the rules of the paper's comparison systems,
+    Section 5.1): the library's policy against the oracle's replay, random stages, count and byte caps."""
+    rng = np.random.default_rng(50 + seed)
+    wl = W.config4(8, hw=32, tiers=(4, 8, 12), width=8, fan=(3, 2), calibrated=False)
+    E = wl.graph.n_experts
+    nbytes = rng.integers(5, 30, E) if seed % 2 else np.full(E, 10)
+    stages = [(rng.random(E) < rng.choice([0.1, 0.3, 0.6])).astype(np.uint8) for _ in range(40)]
+    _compare_policy(B, oracle, nbytes, wl.usage_prob, wl.graph, 0 if seed % 2 else 6, 110 if seed % 2 else 0, stages, rule=rule,
+                    depth=seed % 3)
+
+
+@pytest.mark.parametrize("depth", [1, 2, 3])
+@pytest.mark.parametrize("seed", range(4))
+def test_in_use_depth_matches_oracle_random(B, oracle, seed, depth):
+    """Two-stage rule with the experts of the preceding groups protected while a load is in flight."""
+    rng = np.random.default_rng(80 + seed)
+    wl = W.config4(8, hw=32, tiers=(4, 8, 12), width=8, fan=(3, 2), calibrated=False)
+    E = wl.graph.n_experts
+    nbytes = rng.integers(5, 30, E) if seed % 2 else np.full(E, 10)
+    stages = [(rng.random(E) < rng.choice([0.1, 0.3, 0.6])).astype(np.uint8) for _ in range(40)]
+    _compare_policy(B, oracle, nbytes, wl.usage_prob, wl.graph, 0 if seed % 2 else 8, 130 if seed % 2 else 0, stages, depth=depth)
 
 
 def test_policy_zipf_tree_keeps_hot_experts(B, oracle):

@@ -258,6 +258,49 @@ def test_cache_invariants_random(oracle):
 # ---------------------------------------------------------------------------------------------
 # margin guard: admissible outcomes at near-ties
 # ---------------------------------------------------------------------------------------------
+def test_cache_in_use_depth_rotates_slots(oracle):
+    """Root 0 (probability 1) and leaves 1..6 with probabilities 0.6 .. 0.1; four experts fit: 0, 1, 2, 3 after the
+    initial fill.  One stage needs 0, 1, 4, 5, 6: plan order 0, 1 (on the device), then 4, 5, 6 (missing).
+    Depth 0 (only groups that have not run are protected): 4 replaces 3 (least probable idle expert), 5 replaces 4
+    (it has run and is the least probable), 6 replaces 5: one slot, every copy waits for the group before it.
+    Depth 1 (the group right before a missing one is still running): 4 replaces 3; for 5 expert 4 is busy, so the
+    least probable of the others goes: 2; 6 then replaces 4 (5 is busy, 4 has finished): two slots alternate."""
+    E = 7
+    prob = [1.0, 0.6, 0.5, 0.4, 0.3, 0.2, 0.1]
+    succ_off = [0, 6] + [6] * 6
+    hg = np.zeros(E, np.uint8); hg[[0, 1, 4, 5, 6]] = 1
+    want = {0: [(4, [3]), (5, [4]), (6, [5])], 1: [(4, [3]), (5, [2]), (6, [4])]}
+    for depth in (0, 1):
+        sim = oracle.CacheSim([10] * E, prob, succ_off, list(range(1, E)), cap_experts=4, in_use=depth)
+        assert sim.init_fill() == [0, 1, 2, 3]
+        order, sw = sim.stage(hg)
+        assert order == [0, 1, 4, 5, 6] and sw == want[depth], (depth, sw)
+
+
+def test_cache_comparison_rules_textbook_reference_string(oracle):
+    """The replacement rules of the paper's comparison systems (Section 5.1) on the textbook reference string
+    1 2 3 4 1 2 5 1 2 3 4 5 with three frames (Belady's example: 9 faults first-in-first-out, 10 least-recently-used).
+    The initial fill loads 1, 2, 3 in that order (descending probability), which is the state after the three cold
+    faults; the remaining references then cost 6 and 7 switches with the victims worked out by hand:
+      FIFO: 4 evicts 1, 1 evicts 2, 2 evicts 3, 5 evicts 4, (1, 2 hit), 3 evicts 1, 4 evicts 2, (5 hits)
+      LRU : 4 evicts 1, 1 evicts 2, 2 evicts 3, 5 evicts 4, (1, 2 hit), 3 evicts 5, 4 evicts 1, 5 evicts 2"""
+    E = 6
+    prob = [0.0, 0.9, 0.8, 0.7, 0.1, 0.05]
+    refs = [1, 2, 3, 4, 1, 2, 5, 1, 2, 3, 4, 5]
+    want = {2: [(4, [1]), (1, [2]), (2, [3]), (5, [4]), (3, [1]), (4, [2])],
+            1: [(4, [1]), (1, [2]), (2, [3]), (5, [4]), (3, [5]), (4, [1]), (5, [2])]}
+    for rule in (1, 2):
+        sim = oracle.CacheSim([10] * E, prob, [0] * (E + 1), [], cap_experts=3, rule=rule)
+        assert sim.init_fill() == [1, 2, 3]
+        log = []
+        for r in refs:
+            hg = np.zeros(E, np.uint8); hg[r] = 1
+            order, sw = sim.stage(hg)
+            assert order == [r]
+            log += sw
+        assert log == want[rule], (rule, log)
+
+
 def test_admissible_outcomes_planted(oracle):
     from oracle import guard as G
     a = _head_only_arch(4)
