@@ -99,8 +99,8 @@ typedef struct {
 } coe_config;
 
 typedef struct {
-    int32_t n_pending;   /* requests that ran a stage in this step */
-    int32_t n_groups;    /* experts with at least one request */
+    int32_t n_pending;   /* requests queued for a stage when the step began (those of waiting groups included) */
+    int32_t n_groups;    /* experts whose group ran in this step */
     int32_t n_chunks;    /* batches after splitting */
     int32_t n_hits;      /* groups whose expert was resident */
     int32_t n_misses;    /* groups that needed an expert switch */

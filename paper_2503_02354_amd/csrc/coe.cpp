@@ -43,6 +43,7 @@ struct ArchPlan {
     bool groupable = false;             // every layer can run several experts' small groups in one launch
     int32_t row_cap = INT32_MAX;        // most requests one launch may cover: the kernels address a tensor with 31-bit byte offsets
     int32_t arr_min_res = 0, arr_min_miss = 0, arr_wait = 0;   // arranging window (coe_set_arranging); arr_wait 0 = off
+    bool gathers_input = false;         // the only reader of the input is a few-channel conv kernel, which can follow a row table
     size_t elem() const { return dtype == COE_DT_BF16 ? 2 : 4; }
     size_t in_bytes() const { return (size_t)in_h * in_w * in_c * elem(); }
 };
@@ -312,6 +313,16 @@ int plan_arch(coe_ctx* c, const coe_arch_desc* d, ArchPlan& a)
         a.row_cap = (int32_t)std::min<size_t>((size_t)INT32_MAX, (size_t)0x7FFFFFFE / widest);
         if (a.row_cap < 1) return fail(c, COE_EINVAL, "arch: one request's largest tensor exceeds 2 GiB");
     }
+    // request arranging's gather can happen inside the first kernel when that is the few-channel conv and nothing else
+    // reads the input
+    {
+        int readers = 0;
+        for (const LayerPlan& L : a.layers) readers += (L.d.src == 0) + (L.d.res == 0);
+        const LayerPlan& L0 = a.layers[0];
+        coe::k::ConvShape cs{1, L0.H, L0.W, L0.C, L0.K, L0.d.r, L0.d.s, L0.d.stride, L0.d.pad, L0.P, L0.Q, L0.d.act};
+        a.gathers_input = readers == 1 && L0.d.op == COE_OP_CONV && L0.d.src == 0 && a.dtype == COE_DT_BF16 && !L0.packed &&
+                          (L0.fuse_pool || coe::k::conv_smallc_supported(cs, L0.d.res >= 0, false));
+    }
     // grouped launches: matrix-core convs with K % 64 == 0 take a group table; few-channel convs run once per group;
     // pools have no weights; the pooled head takes a group table.  Anything else keeps one launch per group.
     a.groupable = a.dtype == COE_DT_BF16;
@@ -455,8 +466,9 @@ int issue_load(coe_ctx* c, const coe::Switch& sw, coe_step_stats* st)
 }
 
 // ---- one expert over one batch ---------------------------------------------------------------------------------------
+// rows: the batch is rows[0..n) of the array at `input` (only for architectures whose first kernel follows a row table)
 int run_expert(coe_ctx* c, const Expert& x, const void* weights, const void* input, int32_t n, const coe::k::RouteArgs& route,
-               int32_t last_layer = -1)
+               int32_t last_layer = -1, const int32_t* rows = nullptr)
 {
     int32_t li = -1;
     const ArchPlan& a = c->archs[x.arch];
@@ -485,10 +497,12 @@ int run_expert(coe_ctx* c, const Expert& x, const void* weights, const void* inp
             } else if (L.fuse_pool) {
                 const LayerPlan& pool = *(&L + 1);
                 Span sp(c, COE_K_CONV_STEM, flops, c->sc);
-                HIPCHK(c, coe::k::conv_smallc(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), buf(pool.d.dst), s, true, c->sc));
+                HIPCHK(c, coe::k::conv_smallc(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), buf(pool.d.dst), s, true, c->sc,
+                                              l.src == 0 ? rows : nullptr));
             } else if (a.dtype == COE_DT_BF16 && coe::k::conv_smallc_supported(s, res != nullptr, false)) {
                 Span sp(c, COE_K_CONV_STEM, flops, c->sc);
-                HIPCHK(c, coe::k::conv_smallc(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), buf(l.dst), s, false, c->sc));
+                HIPCHK(c, coe::k::conv_smallc(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), buf(l.dst), s, false, c->sc,
+                                              l.src == 0 ? rows : nullptr));
             } else {
                 Span sp(c, COE_K_CONV_DIRECT, flops, c->sc);
                 HIPCHK(c, coe::k::conv_direct(a.dtype, buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), res, buf(l.dst), s, c->sc));
@@ -548,7 +562,8 @@ struct SetMember {
     int32_t count;
 };
 
-int run_group_set(coe_ctx* c, const std::vector<SetMember>& set, const uint8_t* staged, size_t ib)
+// rows: as in run_expert; the members' inputs are rows[first..first+count) of the array at `staged`
+int run_group_set(coe_ctx* c, const std::vector<SetMember>& set, const uint8_t* staged, size_t ib, const int32_t* rows)
 {
     const ArchPlan& a = c->archs[c->experts[set[0].expert].arch];
     coe::k::GroupTable gt{};
@@ -589,10 +604,13 @@ int run_group_set(coe_ctx* c, const std::vector<SetMember>& set, const uint8_t* 
                 for (size_t g = 0; g < set.size(); ++g) {
                     coe::k::ConvShape sg = s;
                     sg.N = set[g].count;
-                    const uint8_t* in = l.src == 0 ? staged + (size_t)set[g].first * ib : buf(l.src) + (size_t)gt.first_row[g] * in_row;
+                    const bool via_rows = l.src == 0 && rows;
+                    const uint8_t* in = via_rows ? staged
+                                      : l.src == 0 ? staged + (size_t)set[g].first * ib : buf(l.src) + (size_t)gt.first_row[g] * in_row;
                     const uint8_t* wb = (const uint8_t*)gt.weights[g];
                     HIPCHK(c, coe::k::conv_smallc(in, wb + L.off[0], (const float*)(wb + L.off[1]),
-                                                  buf(outL.d.dst) + (size_t)gt.first_row[g] * out_row, sg, fused, c->sc));
+                                                  buf(outL.d.dst) + (size_t)gt.first_row[g] * out_row, sg, fused, c->sc,
+                                                  via_rows ? rows + set[g].first : nullptr));
                 }
             }
             break;
@@ -919,8 +937,12 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
     // (one group that holds every stored request: the stable sort is the identity and the inputs are already in order)
     const size_t ib = c->archs[0].in_bytes();
     const bool in_place = n_groups_queued == 1 && n_pending == c->n_live;
-    const uint8_t* staged = (const uint8_t*)(in_place ? c->d_inputs : c->d_staged);
-    if (!in_place && !order.empty()) {
+    // (every architecture's first kernel can follow the regrouped order itself: no copy either)
+    bool via_rows = !in_place;
+    for (const ArchPlan& a : c->archs) via_rows = via_rows && a.gathers_input;
+    const uint8_t* staged = (const uint8_t*)(in_place || via_rows ? c->d_inputs : c->d_staged);
+    const int32_t* rows = via_rows ? c->d_perm : nullptr;
+    if (!in_place && !via_rows && !order.empty()) {
         Span sp(c, COE_K_REGROUP_GATHER, 2.0 * (double)n_pending * (double)ib, c->sc);
         HIPCHK(c, coe::k::gather_rows(c->d_inputs, c->d_perm, n_pending, ib, c->d_staged, c->sc));
     }
@@ -979,7 +1001,7 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
                     xm.load_pending = false;
                 }
             }
-            rc = run_group_set(c, set, staged, ib);
+            rc = run_group_set(c, set, staged, ib, rows);
             if (rc) return rc;
             for (const SetMember& m : set) {
                 Expert& xm = c->experts[m.expert];
@@ -1006,7 +1028,7 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
             int32_t cnt = std::min(chunk, off[e + 1] - s);
             coe::k::RouteArgs r{c->d_perm + s, e, c->d_succ + c->succ_off[e], n_route, c->d_cur, c->d_depth, c->d_path,
                                 c->cfg.max_stages, c->d_logits, c->max_classes};
-            rc = run_expert(c, x, x.buf->p, staged + (size_t)s * ib, cnt, r);
+            rc = run_expert(c, x, x.buf->p, rows ? staged : staged + (size_t)s * ib, cnt, r, -1, rows ? rows + s : nullptr);
             if (rc) return rc;
             ++st.n_chunks;
         }

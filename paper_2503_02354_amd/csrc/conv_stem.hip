@@ -77,7 +77,8 @@ template <int NB, bool POOL, int CPR_, int R_>
 __global__ __launch_bounds__(kThreads, 4) void conv_smallc_bf16_kernel(const uint16_t* __restrict__ x,
                                                                      const uint16_t* __restrict__ w,
                                                                      const float* __restrict__ bias,
-                                                                     uint16_t* __restrict__ y, ConvShape s, StemGeom g)
+                                                                     uint16_t* __restrict__ y, ConvShape s, StemGeom g,
+                                                                     const int32_t* __restrict__ rows)
 {
     constexpr int K = 32 * NB;
     constexpr int OUT_STRIDE = K + kOutPad;
@@ -122,8 +123,11 @@ __global__ __launch_bounds__(kThreads, 4) void conv_smallc_bf16_kernel(const uin
         pre_shift = g_base - e0;
         // one descriptor per image; a dword outside its row (left or right of the image) or in a row outside the image
         // gets an offset beyond the descriptor's range and reads as zero
+        // (with a row table, image n of the launch is image rows[n] of the array at x: request arranging's gather of
+        // the inputs happens here instead of in a copy of its own)
+        const int n_src = rows ? __builtin_amdgcn_readfirstlane(rows[n]) : n;
         const __amdgpu_buffer_rsrc_t rs =
-            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(x + (size_t)n * s.H * WC), 0, s.H * WC * 2, 0x00020000);
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(x + (size_t)n_src * s.H * WC), 0, s.H * WC * 2, 0x00020000);
 #pragma unroll
         for (int j = 0; j < kMaxDwordsPerLane; ++j) {
             const int e = e0 + 2 * (lane + 64 * j);
@@ -345,7 +349,7 @@ bool geometry(const ConvShape& s, bool pool, StemGeom& g, size_t& smem)
 
 template <int NB, bool POOL, int CPR_, int R_>
 hipError_t launch(const void* x, const void* w, const float* bias, void* y, const ConvShape& s, const StemGeom& g, size_t smem,
-                  hipStream_t stream)
+                  hipStream_t stream, const int32_t* rows)
 {
     static bool configured = false;
     if (!configured) {   // more than the default 64 KiB of LDS per workgroup needs an explicit opt-in
@@ -356,7 +360,7 @@ hipError_t launch(const void* x, const void* w, const float* bias, void* y, cons
     }
     int grid = g.total_tiles < 1024 ? g.total_tiles : 1024;
     hipLaunchKernelGGL((conv_smallc_bf16_kernel<NB, POOL, CPR_, R_>), dim3(grid), dim3(kThreads), smem, stream, (const uint16_t*)x,
-                       (const uint16_t*)w, bias, (uint16_t*)y, s, g);
+                       (const uint16_t*)w, bias, (uint16_t*)y, s, g, rows);
     return hipGetLastError();
 }
 
@@ -370,7 +374,7 @@ bool conv_smallc_supported(const ConvShape& s, bool has_res, bool fused_pool)
 }
 
 hipError_t conv_smallc(const void* x, const void* w, const float* bias, void* y, const ConvShape& s, bool fused_pool,
-                       hipStream_t stream)
+                       hipStream_t stream, const int32_t* rows)
 {
     StemGeom g;
     size_t smem = 0;
@@ -378,12 +382,12 @@ hipError_t conv_smallc(const void* x, const void* w, const float* bias, void* y,
     if (g.total_tiles == 0) return hipSuccess;
     if (s.K == 64) {
         if (fused_pool && g.cpr == 3 && s.R == 7)         // the ResNet stem: reduction loop unrolled with constant offsets
-            return launch<2, true, 3, 7>(x, w, bias, y, s, g, smem, stream);
-        return fused_pool ? launch<2, true, 0, 0>(x, w, bias, y, s, g, smem, stream)
-                          : launch<2, false, 0, 0>(x, w, bias, y, s, g, smem, stream);
+            return launch<2, true, 3, 7>(x, w, bias, y, s, g, smem, stream, rows);
+        return fused_pool ? launch<2, true, 0, 0>(x, w, bias, y, s, g, smem, stream, rows)
+                          : launch<2, false, 0, 0>(x, w, bias, y, s, g, smem, stream, rows);
     }
-    return fused_pool ? launch<1, true, 0, 0>(x, w, bias, y, s, g, smem, stream)
-                      : launch<1, false, 0, 0>(x, w, bias, y, s, g, smem, stream);
+    return fused_pool ? launch<1, true, 0, 0>(x, w, bias, y, s, g, smem, stream, rows)
+                      : launch<1, false, 0, 0>(x, w, bias, y, s, g, smem, stream, rows);
 }
 
 }  // namespace k

@@ -83,9 +83,11 @@ hipError_t conv_mfma_grouped(const void* x, const GroupTable& groups, size_t off
 // bf16 convolution with few input channels (C not a multiple of 32, e.g. the C=3 stem) on the matrix cores.
 // Requires K in {32, 64}, stride*C even, no residual.  fused_pool: the 3x3 / stride 2 / pad 1 max pool that follows is
 // applied in the same kernel and y receives the pooled tensor [N][(P-1)/2+1][(Q-1)/2+1][K] instead of the conv output.
+// rows != nullptr: image n of the launch is image rows[n] of the array at x (the gather of request arranging, done
+// while the patches are fetched instead of in a copy of its own).
 bool conv_smallc_supported(const ConvShape& s, bool has_res, bool fused_pool);
 hipError_t conv_smallc(const void* x, const void* w, const float* bias, void* y, const ConvShape& s, bool fused_pool,
-                       hipStream_t stream);
+                       hipStream_t stream, const int32_t* rows = nullptr);
 
 hipError_t maxpool(int dtype, const void* x, void* y, int32_t N, int32_t H, int32_t W, int32_t C, int32_t R, int32_t S,
                    int32_t stride, int32_t pad, int32_t P, int32_t Q, hipStream_t stream);
