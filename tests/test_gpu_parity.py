@@ -309,6 +309,9 @@ def test_error_codes_and_empty_inputs(B):
     (40, 8, 8, 128, 256, 1, 1, 0, False, 2),      # MFMA 1x1 with GELU, 2560 rows
     (2, 33, 30, 3, 64, 7, 2, 3, False, 1),        # stem kernel
     (2, 12, 12, 16, 24, 3, 1, 1, True, 1),        # plain kernel (bf16)
+    (21, 57, 57, 64, 256, 1, 1, 0, True, 1),      # large 1x1: 68229 rows (ragged), two filter tiles per row tile, residual
+    (11, 57, 57, 32, 512, 1, 1, 0, False, 2),     # one 32-channel step, four filter tiles per row tile, GELU
+    (6, 57, 57, 64, 256, 3, 2, 1, False, 1),      # 3x3 stride 2 at an odd size
 ])
 def test_conv_elementwise_bf16(B, oracle, n, H, Wd, C, K, R, stride, pad, use_res, act):
     rng = np.random.default_rng(n * 1000 + H * 10 + K)
