@@ -133,24 +133,31 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
     const size_t row_stride = (size_t)3 * D;
     const uint16_t* base = qkv + (size_t)n * T * row_stride + (size_t)head * kDh;
 
-    for (int c = tid; c < TB * 32 * 8; c += 256) {
-        int t = c >> 3, part = c & 7;
-        uint4 kv = make_uint4(0, 0, 0, 0), vv = make_uint4(0, 0, 0, 0);
-        if (t < T) {
-            kv = *(const uint4*)(base + (size_t)t * row_stride + D + part * 8);
-            vv = *(const uint4*)(base + (size_t)t * row_stride + 2 * D + part * 8);
+    // K as it is, V transposed; two tokens per thread so that the transposed stores are 4 bytes (token pairs)
+    for (int c = tid; c < TB * 16 * 8; c += 256) {
+        const int t = (c >> 3) * 2, part = c & 7;
+        uint4 kv[2], vv[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            kv[j] = make_uint4(0, 0, 0, 0);
+            vv[j] = make_uint4(0, 0, 0, 0);
+            if (t + j < T) {
+                kv[j] = *(const uint4*)(base + (size_t)(t + j) * row_stride + D + part * 8);
+                vv[j] = *(const uint4*)(base + (size_t)(t + j) * row_stride + 2 * D + part * 8);
+            }
+            *(uint4*)(Kl + (t + j) * kKStride + part * 8) = kv[j];
         }
-        *(uint4*)(Kl + t * kKStride + part * 8) = kv;
-        const uint32_t w[4] = {vv.x, vv.y, vv.z, vv.w};
+        const uint32_t w0[4] = {vv[0].x, vv[0].y, vv[0].z, vv[0].w}, w1[4] = {vv[1].x, vv[1].y, vv[1].z, vv[1].w};
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            Vt[(part * 8 + 2 * i) * kVStride + t] = (uint16_t)(w[i] & 0xFFFFu);
-            Vt[(part * 8 + 2 * i + 1) * kVStride + t] = (uint16_t)(w[i] >> 16);
+            *(uint32_t*)(Vt + (part * 8 + 2 * i) * kVStride + t) = (w0[i] & 0xFFFFu) | (w1[i] << 16);
+            *(uint32_t*)(Vt + (part * 8 + 2 * i + 1) * kVStride + t) = (w0[i] >> 16) | (w1[i] & 0xFFFF0000u);
         }
     }
     __syncthreads();
 
     const int l32 = lane & 31, half = lane >> 5;
+    const float scale2 = scale * 1.44269504088896340736f;
     for (int qb = wid; qb < TB; qb += 4) {
         const int query = qb * 32 + l32;
         bf16x8 qf[kDh / 16];
@@ -175,7 +182,7 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
 #pragma unroll
                 for (int v = 0; v < 16; ++v) {
                     int key = kb * 32 + 8 * (v >> 2) + 4 * half + (v & 3);
-                    float s = key < T ? sc[kb][v] * scale : -INFINITY;
+                    float s = key < T ? sc[kb][v] * scale2 : -INFINITY;       // scores in units of ln 2
                     sc[kb][v] = s;
                     m = fmaxf(m, s);
                 }
@@ -189,7 +196,8 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
             if (kb < TB) {
 #pragma unroll
                 for (int v = 0; v < 16; v += 2) {
-                    float e0 = expf(sc[kb][v] - m), e1 = expf(sc[kb][v + 1] - m);
+                    // 2^x on the transcendental unit (one instruction; exp(s - max) = 2^((s - max) / ln 2))
+                    float e0 = __builtin_amdgcn_exp2f(sc[kb][v] - m), e1 = __builtin_amdgcn_exp2f(sc[kb][v + 1] - m);
                     lsum += e0 + e1;
                     pw[kb][v >> 1] = pack_bf16(e0, e1);
                 }
