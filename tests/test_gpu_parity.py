@@ -567,3 +567,33 @@ def test_replacement_rules_and_in_use_depth_follow_the_replay(B, oracle, G, rule
     assert got["switch_log"] == log
     assert got["switch_log"] != base["switch_log"]
     print(f"rule {rule} depth {depth}: {len(log) - 4} switches, plain two-stage rule: {len(base['switch_log']) - 4}")
+
+
+def test_launch_sequences_respect_the_address_limit(B):
+    """Kernels address a tensor with 31-bit byte offsets, so a launch sequence covers at most 2^31 / (largest tensor of
+    one request) requests whatever max_batch says.  Here the largest tensor is 256x256x64 bf16 = 8 MiB: 255 requests.
+    300 requests with max_batch 4096 must run as two sequences of 150 and give the bits of a run in chunks of 64."""
+    p = W._Prog(256, 256, 4)
+    p.conv(0, 1, 64, 3, 1, 1, W.ACT_RELU)
+    p.head(1, 8)
+    arch = W.Arch("wide", W.DT_BF16, 256, 256, 4, 8, np.array(p.layers, dtype=np.int32), p.gains)
+    blob = W.make_expert_blob(arch, 5, 0)
+    n = 300
+    x = W.make_inputs(arch, 5, range(16))
+    x = np.concatenate([x] * 19)[:n]                                  # 16 distinct images, repeated
+    dev = device_tensor(x)
+    outs = []
+    for max_batch in (4096, 64):
+        ctx = B.Context(max_requests=n, max_stages=1, max_batch=max_batch)
+        aid = ctx.coe_register_arch(arch)
+        ctx.coe_register_expert(0, aid, blob, 1.0)
+        ctx.coe_set_dependency_graph(np.zeros(2, np.int32), np.zeros(0, np.int32))
+        ctx.coe_submit(n, dev.data_ptr(), True)
+        rc, st = ctx.coe_step()
+        assert rc == B.COE_OK and st.n_chunks == (2 if max_batch == 4096 else 5)
+        ids, logits, path = ctx.coe_collect(n)
+        ctx.close()
+        outs.append(logits[np.argsort(ids)])
+    assert np.isfinite(outs[0]).all() and np.abs(outs[0]).max() > 0
+    assert np.array_equal(outs[0], outs[1])
+    assert np.array_equal(outs[0][:16], outs[0][16:32])               # repeated images, repeated results
