@@ -80,13 +80,16 @@ def main():
     ap.add_argument("--arrange", default="",
                     help="arranging window 'min_resident,min_missing,max_wait' for every architecture: a queued group "
                          "smaller than min_resident (expert on the device) or min_missing (expert missing) waits up to "
-                         "max_wait steps for later arrivals to join it (empty = off: every queued group runs in every step)")
+                         "max_wait steps for later arrivals to join it.  Default: '0,43,8' for config3 (requests arrive in "
+                         "512-request batches there; 43 is where the offline profiler puts a missing ResNet-50 group at "
+                         "20 %% efficiency), off elsewhere; 'off' = every queued group runs in every step")
     ap.add_argument("--eviction", default="two-stage", choices=["two-stage", "lru", "fifo"],
                     help="replacement rule of the expert cache: the paper's two-stage rule (default) or the rules of the "
                          "systems it compares with")
-    ap.add_argument("--prefetch-depth", type=int, default=0,
+    ap.add_argument("--prefetch-depth", type=int, default=-1,
                     help="experts of this many groups right before a missing one in the plan count as in use while its copy "
-                         "is in flight (0: consecutive misses reuse one slot and each copy waits for the group before it)")
+                         "is in flight (0: consecutive misses reuse one slot and each copy waits for the group before it).  "
+                         "Default: 4 for config3, 2 for config5 (the workloads with a capped cache), 0 elsewhere")
     ap.add_argument("--no-profile", action="store_true", help="do not time kernel classes with events")
     ap.add_argument("--profile-every", type=int, default=0,
                     help="time every k-th launch of each kernel class (0 = every launch for config2 / config4, whose steps "
@@ -100,6 +103,12 @@ def main():
         args.group_small = 512 if big else 0
     if args.profile_every == 0:
         args.profile_every = 1 if args.workload == "config2" else 7
+    if args.arrange == "":
+        args.arrange = "0,43,8" if args.workload == "config3" else "off"
+    if args.arrange == "off":
+        args.arrange = ""
+    if args.prefetch_depth < 0:
+        args.prefetch_depth = {"config3": 4, "config5": 2}.get(args.workload, 0)
     if args.gpus != 1:
         print("bench.py runs on exactly one GPU: the library has no multi-GPU path (--gpus 1 only)", file=sys.stderr)
         sys.exit(2)

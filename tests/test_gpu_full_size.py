@@ -32,7 +32,9 @@ def _valid_paths(path, wl):
         assert len(succ) == 0 or -1 in succ, "request stopped at an expert that still routes"
 
 
-def _sampled_case(B, oracle, wl, n_sample, max_batch, arrival=None, seed=1, group_small=0):
+def _sampled_case(B, oracle, wl, n_sample, max_batch, arrival=None, seed=1, group_small=0, also=()):
+    """also: further run_chain_gpu keyword sets (other schedules of the same work); every one must reproduce the first
+    run's routes and logits bit for bit.  Their results are returned in got["also"]."""
     from oracle import guard as G
     n = wl.n_requests
     E = wl.graph.n_experts
@@ -68,6 +70,11 @@ def _sampled_case(B, oracle, wl, n_sample, max_batch, arrival=None, seed=1, grou
     assert np.array_equal(alone["path"], got["path"][sample])
     assert np.array_equal(alone["logits"], got["logits"][sample])
     ctx.close()
+    got["also"] = []
+    for kw in also:
+        other = run_chain_gpu(B, wl, blobs, x, wl.first_expert, max_batch=max_batch, arrival=arrival, group_small=group_small, **kw)
+        assert np.array_equal(other["path"], got["path"]) and np.array_equal(other["logits"], got["logits"]), kw
+        got["also"].append(other)
     return got, want, sample, float(err), redraws
 
 
@@ -116,7 +123,8 @@ def test_config3_full_size(B, oracle):
     leaf stage together)."""
     wl = W.config3()
     assert wl.head_bias, "calibration file missing"
-    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=24, max_batch=512, arrival=512, seed=3)
+    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=24, max_batch=512, arrival=512, seed=3,
+                                                    also=[dict(arranging=(0, 43, 8), prefetch_depth=4)])
     stats = [st for rc, st in got["stats"] if rc == B.COE_OK]
     assert len(stats) == 33                                            # 32 arrivals + the last batch's leaf stage
     assert stats[0].n_groups == 1 and stats[0].n_pending == 512 and stats[-1].n_pending == 512
@@ -135,6 +143,18 @@ def test_config3_full_size(B, oracle):
     assert 0.15 < leaves.max() / wl.n_requests < 0.40 and (leaves > 0).sum() >= 40, leaves
     print(f"config3 full size: {len(sample)} sampled, max rel err {err:.2e}, {redraws} re-draws, "
           f"{len(log) - 16} switches, top leaves {np.sort(leaves)[::-1][:6].tolist()}")
+    # the schedule the benchmark times on this workload: an 8-step arranging window for groups of missing experts and
+    # four groups of prefetch.  Same bits (checked above); a consistent switch log with far fewer switches; nobody
+    # waits longer than the window
+    win = got["also"][0]
+    wstats = [st for rc, st in win["stats"] if rc == B.COE_OK]
+    wlog = win["switch_log"]
+    assert len(wlog) == 16 + sum(st.n_misses for st in wstats) and [e for e, v in wlog[:16]] == list(range(16))
+    resident = _replay_switch_log(wlog, 64, 16)
+    assert 0 in resident and all(0 not in v for e, v in wlog)
+    assert len(wlog) - 16 < (len(log) - 16) // 3
+    assert sum(st.n_deferred_groups for st in wstats) > 0 and len(wstats) <= 33 + 8
+    print(f"config3 with the arranging window: {len(wlog) - 16} switches in {len(wstats)} steps")
 
 
 def test_config4_full_size(B, oracle):
@@ -176,7 +196,8 @@ def test_config5_full_size(B, oracle):
     4096 requests: the 3.4 GB/stage of expert switches overlap the forwards of the groups already resident."""
     wl = W.config5()
     assert wl.head_bias, "calibration file missing"
-    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=16, max_batch=512, seed=5)
+    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=16, max_batch=512, seed=5,
+                                                    also=[dict(prefetch_depth=2)])
     stats = [st for rc, st in got["stats"] if rc == B.COE_OK]
     assert len(stats) == 2 and all(st.n_pending == wl.n_requests for st in stats)
     log = got["switch_log"]
@@ -188,5 +209,9 @@ def test_config5_full_size(B, oracle):
     assert leaves.min() > 40 and leaves.max() < 300, leaves              # calibration spreads the 31 routes
     assert stats[1].n_groups == 31 and stats[1].n_misses == 31 - 11      # 11 leaves were resident after the fill
     assert sum(st.bytes_switched for st in stats) == sum(st.n_misses for st in stats) * W.blob_layout(wl.archs[0])[1]
+    # the benchmark's schedule on this workload (two groups of prefetch): same bits (checked above), consistent log
+    plog = got["also"][0]["switch_log"]
+    assert [e for e, v in plog[:12]] == list(range(12)) and len(plog) - 12 >= 20
+    assert 0 in _replay_switch_log(plog, 32, 12) and all(0 not in v for e, v in plog)
     print(f"config5 full size: {len(sample)} sampled, max rel err {err:.2e}, {redraws} re-draws, "
           f"{len(log) - 12} switches, leaves min {leaves.min()} max {leaves.max()}")
