@@ -597,3 +597,42 @@ def test_launch_sequences_respect_the_address_limit(B):
     assert np.isfinite(outs[0]).all() and np.abs(outs[0]).max() > 0
     assert np.array_equal(outs[0], outs[1])
     assert np.array_equal(outs[0][:16], outs[0][16:32])               # repeated images, repeated results
+
+
+def test_arranging_window_on_a_capped_mixed_dag(B, oracle, G):
+    """Three-stage DAG with two architectures, requests arriving in five batches, a cache of 7 of the 18 experts, an
+    arranging window with different thresholds per architecture and two groups of prefetch: results equal the plain
+    schedule's bit for bit and the oracle's within tolerance; which groups run, wait and switch in every step equals
+    the oracle's replay."""
+    from oracle import arrange
+    n, arrival = 150, 30
+    wl = W.config4(n, hw=64, tiers=(3, 6, 9), width=16, fan=(3, 2), calibrated=False)
+    G.calibrate_workload(wl, n_cal=32)
+    E = wl.graph.n_experts
+    blobs = [wl.blob(e) for e in range(E)]
+    x, sub, want, _ = G.guarded_inputs(wl, blobs, range(n))
+    assert not want["ambiguous"].any()
+    plain = run_chain_gpu(B, wl, blobs, x, wl.first_expert, max_batch=32, arrival=arrival)
+    windows = {0: (2, 6, 3), 1: (0, 9, 2)}
+    ctx = B.Context(max_requests=n, max_stages=wl.max_stages, max_batch=32, cache_cap_experts=7, prefetch_depth=2)
+    B.setup_workload(ctx, wl, blobs)
+    for a, w in windows.items():
+        ctx.coe_set_arranging(a, *w)
+    got = run_chain_gpu(B, wl, blobs, x, wl.first_expert, arrival=arrival, ctx=ctx)
+    ctx.close()
+    assert np.array_equal(got["path"], plain["path"]) and np.array_equal(got["logits"], plain["logits"])
+    assert_chain_parity(got, want, REL_TOL_BF16)
+    sim = oracle.CacheSim([b.nbytes for b in blobs], wl.usage_prob, wl.graph.succ_off, wl.graph.succ, cap_experts=7, in_use=2)
+    log = [(e, []) for e in sim.init_fill()]
+    paths = [[int(e) for e in p if e >= 0] for p in want["path"]]
+    submits = [list(range(s, min(s + arrival, n))) for s in range(0, n, arrival)]
+    rec = arrange.replay(submits, paths, wl.expert_arch, windows, sim)
+    stats = [st for rc, st in got["stats"] if rc == B.COE_OK]
+    assert len(stats) == len(rec)
+    for st, r in zip(stats, rec):
+        assert (st.n_pending, st.n_groups, st.n_misses) == (r["n_pending"], len(r["run"]), len(r["switches"]))
+        assert st.n_deferred_groups == len(r["deferred"])
+        assert st.n_deferred_requests == sum(len(m) for m in r["deferred"].values())
+        log += r["switches"]
+    assert got["switch_log"] == log
+    assert sum(st.n_deferred_groups for st in stats) > 0 and len(log) > 7
