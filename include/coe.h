@@ -75,8 +75,10 @@ typedef struct {
 typedef struct {
     int32_t device;            /* HIP device ordinal */
     int32_t max_requests;      /* capacity of the request store (requests submitted and not yet collected) */
-    int32_t max_batch;         /* request splitting: largest batch one expert launch sequence handles (0 = 256);
-                                  paper Section 4.2 "Request splitting" */
+    int32_t max_batch;         /* request splitting (paper Section 4.2 "Request splitting"): largest batch one expert
+                                * launch sequence handles (0 = 256).  Per architecture the library lowers it to what 31-bit
+                                * byte offsets into the largest tensor of a launch allow, and cuts a group into the fewest
+                                * sequences that fit, of equal size.  The activation workspace is sized for it. */
     int32_t max_stages;        /* longest path through the dependency graph that is recorded per request */
     int32_t cache_cap_experts; /* device expert cache: at most this many resident experts (0 = no limit) */
     int32_t profile;           /* k > 0: time every k-th launch of each kernel class with events (1 = all; see
