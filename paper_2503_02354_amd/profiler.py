@@ -6,11 +6,13 @@ microbenchmark over batch sizes,
 and from those the arranging window's thresholds (coe_set_arranging): the group size from which the fixed cost of
 running a group now - B, plus the load when the expert is missing - is a small enough share of the whole.
 
+plus the decay-window search of Section 4.4 for the number of experts to keep on the device.
+
 Experts of one architecture are profiled once (Section 4.5).  The measuring functions drive the library through its
 binding and need a GPU; the fitting functions are plain arithmetic."""
 import math
 import time
-from typing import Dict, Sequence, Tuple
+from typing import Callable, Dict, Sequence, Tuple
 
 import numpy as np
 
@@ -39,6 +41,53 @@ def arranging_window(K_us: float, B_us: float, load_us: float, efficiency: float
     assert K_us > 0 and 0.0 <= efficiency < 1.0 and B_us >= 0 and load_us >= 0 and max_wait_steps >= 0
     r = efficiency / (1.0 - efficiency)
     return int(math.ceil(r * B_us / K_us)), int(math.ceil(r * (B_us + load_us) / K_us)), int(max_wait_steps)
+
+
+def experts_for_usage(usage_prob: Sequence[float], percent: float) -> int:
+    """Experts sorted by descending usage probability: how many of them it takes to cover `percent` of all usage
+    (the CDF of Section 4.4 read from the usage axis to the expert axis); at least one."""
+    p = np.sort(np.asarray(usage_prob, np.float64))[::-1]
+    cdf = np.cumsum(p) / p.sum() * 100.0
+    return int(min(len(p), np.searchsorted(cdf, percent - 1e-9) + 1))
+
+
+def decay_window_search(usage_prob: Sequence[float], throughput_at: Callable[[int], float], initial_window: float = 20.0,
+                        min_points: int = 3, error_margin: float = 0.1, pick: float = 0.5) -> dict:
+    """Section 4.4, "Memory allocation under sufficient computation performance": how many experts to keep on the
+    device when their memory competes with the memory of large batches.  A window slides up the usage CDF; its first
+    size is `initial_window` (percent of all usage) and every slide multiplies the size by the decay factor
+    1 - initial_window / 100.  At every position the experts that cover the window's upper bound are loaded and
+    `throughput_at(n_experts)` measures sample requests.  A line through the throughputs measured so far predicts the
+    next one; the slide stops at the first window whose throughput falls short of the prediction by more than
+    `error_margin` (relative), or when every expert is loaded or the next window is too narrow to add one.  The paper then takes any number of experts inside the last window (it
+    says a random one: differences inside the window are negligible); `pick` in [0, 1] is that choice, passed in.
+
+    Reading of the paper where it leaves room: the line is fitted through all values measured so far, and the test
+    starts once `min_points` values exist.
+
+    Returns dict(n_experts, window=(low %, high %), stopped_by='shortfall' | 'end', trace=[(high %, experts, throughput)])."""
+    assert 0.0 < initial_window < 100.0 and min_points >= 2 and 0.0 <= pick <= 1.0
+    decay = 1.0 - initial_window / 100.0
+    low, size, trace, stopped = 0.0, float(initial_window), [], "end"
+    while True:
+        high = min(low + size, 100.0)
+        n = experts_for_usage(usage_prob, high)
+        t = float(throughput_at(n))
+        if len(trace) >= min_points:
+            K, B0 = fit_latency(range(1, len(trace) + 1), [v[2] for v in trace])      # same least-squares line
+            predicted = K * (len(trace) + 1) + B0
+            if predicted > 0 and (predicted - t) / predicted > error_margin:
+                trace.append((high, n, t))
+                stopped = "shortfall"
+                break
+        trace.append((high, n, t))
+        # the window sizes form a geometric series that sums to exactly 100 %: the slide ends when every expert is
+        # loaded or the next window is too narrow to add one
+        if n >= len(usage_prob) or experts_for_usage(usage_prob, min(high + size * decay, 100.0)) == n:
+            break
+        low, size = high, size * decay
+    return dict(n_experts=experts_for_usage(usage_prob, low + pick * (high - low)), window=(low, high), stopped_by=stopped,
+                trace=trace)
 
 
 def measure_batch_latency(ctx, expert_id: int, in_shape: Tuple[int, int, int], sizes: Sequence[int], repeats: int = 3,

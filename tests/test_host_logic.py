@@ -163,3 +163,29 @@ def test_profiler_arithmetic():
     assert P.arranging_window(10.0, 1000.0, 800.0, 0.5, 8) == (100, 180, 8)
     assert P.arranging_window(10.0, 1000.0, 800.0, 0.2, 3) == (25, 45, 3)
     assert P.arranging_window(10.0, 1000.0, 800.0, 0.0, 3) == (0, 0, 3)
+
+
+def test_decay_window_search_hand_worked():
+    """Section 4.4 on hand-made numbers.  20 experts of equal usage: each covers 5 % of the usage.  Initial window 20 %,
+    decay factor 0.8: upper bounds 20, 36, 48.8, 59.04, 67.23, ... % -> 4, 8, 10, 12, 14 experts.  Throughput rises by 10
+    per window (100, 110, 120, 130) and then falls to 90 at 14 experts: the line through the first four values
+    predicts 140, the shortfall (140 - 90) / 140 = 0.36 exceeds the margin, the search stops in the window 59.04..67.23 %
+    and its middle (63.1 %) is covered by 13 experts."""
+    from paper_2503_02354_amd import profiler as P
+    usage = [1.0] * 20
+    assert [P.experts_for_usage(usage, q) for q in (5, 5.1, 20, 36, 48.8, 59.04, 100)] == [1, 2, 4, 8, 10, 12, 20]
+    curve = {4: 100.0, 8: 110.0, 10: 120.0, 12: 130.0, 14: 90.0}
+    seen = []
+    out = P.decay_window_search(usage, lambda n: (seen.append(n), curve[n])[1], initial_window=20.0, min_points=3,
+                                error_margin=0.1, pick=0.5)
+    assert seen == [4, 8, 10, 12, 14]
+    assert out["stopped_by"] == "shortfall" and out["n_experts"] == 13
+    assert abs(out["window"][0] - 59.04) < 1e-9 and abs(out["window"][1] - 67.232) < 1e-9
+    # a throughput that keeps following the line: the windows (30 %, then x 0.7 each: upper bounds 30, 51, 65.7, 75.99,
+    # 83.19, 88.24, 91.76 %) shrink until the next one (94.24 %) adds no expert to the 19 that cover 91.76 %
+    out = P.decay_window_search(usage, lambda n: 100.0 + 2.0 * n, initial_window=30.0, pick=1.0)
+    assert out["stopped_by"] == "end" and abs(out["window"][1] - 91.76457) < 1e-6 and out["n_experts"] == 19
+    assert [v[1] for v in out["trace"]] == [6, 11, 14, 16, 17, 18, 19]
+    # a skewed CDF: Zipf(1.1) over 63 leaves reaches 74.9 % of the usage with its 15 most used experts
+    z = W.zipf_probs(63, 1.1)
+    assert P.experts_for_usage(z, 74.0) == 15 and P.experts_for_usage(z, 25.0) == 1
