@@ -90,6 +90,11 @@ def main():
                     help="experts of this many groups right before a missing one in the plan count as in use while its copy "
                          "is in flight (0: consecutive misses reuse one slot and each copy waits for the group before it).  "
                          "Default: 4 for config3, 2 for config5 (the workloads with a capped cache), 0 elsewhere")
+    ap.add_argument("--executors", type=int, default=0,
+                    help="executors: launch sequences of different groups run on this many streams (1-3); the kernels of "
+                         "small groups then overlap on the device.  Default: 3 for config3 (many small groups per step), "
+                         "1 elsewhere: per-launch rates in `roofline` drop when kernels share the chip, and the large "
+                         "launches of the other workloads gain 0-3 %%")
     ap.add_argument("--no-profile", action="store_true", help="do not time kernel classes with events")
     ap.add_argument("--profile-every", type=int, default=0,
                     help="time every k-th launch of each kernel class (0 = every launch for config2 / config4, whose steps "
@@ -107,6 +112,8 @@ def main():
         args.arrange = "0,43,8" if args.workload == "config3" else "off"
     if args.arrange == "off":
         args.arrange = ""
+    if args.executors == 0:
+        args.executors = 3 if args.workload == "config3" else 1
     if args.prefetch_depth < 0:
         args.prefetch_depth = {"config3": 4, "config5": 2}.get(args.workload, 0)
     if args.gpus != 1:
@@ -133,8 +140,13 @@ def main():
 
     ctx = B.Context(max_requests=n, max_stages=wl.max_stages, max_batch=args.max_batch,
                     cache_cap_experts=wl.cache_cap_experts, profile=0 if args.no_profile else args.profile_every,
-                    group_small=args.group_small, eviction=["two-stage", "lru", "fifo"].index(args.eviction), prefetch_depth=args.prefetch_depth)
+                    group_small=args.group_small, eviction=["two-stage", "lru", "fifo"].index(args.eviction), prefetch_depth=args.prefetch_depth, executors=args.executors)
     B.setup_workload(ctx, wl, blobs)
+    # latency models from the offline profiler on this GPU (ns per request, ns per launch sequence, ns per expert load)
+    LATENCY = {"resnet18": (3830, 886000, 408000), "resnet50": (14410, 1611000, 846000)}
+    for a, arch_a in enumerate(wl.archs):
+        if arch_a.name in LATENCY:
+            ctx.coe_set_latency_model(a, *LATENCY[arch_a.name])
     window = [int(v) for v in args.arrange.split(",")] if args.arrange else None
     if window:
         assert len(window) == 3, "--arrange takes min_resident,min_missing,max_wait"
@@ -263,7 +275,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": WORKLOAD_TEXT[args.workload], "requests": n, "arrival_batch": arrival,
-                   "arrivals_per_step": args.arrivals_per_step, "max_batch": args.max_batch,
+                   "arrivals_per_step": args.arrivals_per_step, "max_batch": args.max_batch, "executors": args.executors,
                    "arranging_window": None if not window else {"min_group_resident": window[0], "min_group_missing": window[1],
                                                                 "max_wait_steps": window[2]},
                    "stages": wl.max_stages, "gflop_per_request": round(flops_per_step / n / 1e9, 3)},

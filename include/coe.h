@@ -98,6 +98,9 @@ typedef struct {
                                 * missing one in the plan count as in use while its copy is in flight and are not
                                 * evicted for it; 0 = only groups that have not run yet in the stage are protected, and
                                 * consecutive misses then reuse one slot: each copy waits for the group before it. */
+    int32_t executors;         /* executors (paper Section 4.1): launch sequences of different groups run on this many
+                                * streams, each with its own activation workspace, so that small launches overlap on the
+                                * device; 0 or 1 = one (the compute stream), at most 3.  Results do not depend on it. */
 } coe_config;
 
 typedef struct {
@@ -113,6 +116,7 @@ typedef struct {
     int32_t n_group_sets; /* launch sequences those groups were packed into */
     int32_t n_deferred_groups;   /* groups left queued by the arranging window (see coe_set_arranging) */
     int32_t n_deferred_requests; /* their requests; these are counted in n_pending but ran no stage in this step */
+    int32_t n_executors_used;    /* executors that ran at least one launch sequence in this step */
 } coe_step_stats;
 
 /* Create / destroy a context.  coe_create fails with COE_EDEVICE when no GPU is usable. */
@@ -170,6 +174,14 @@ int coe_step(coe_ctx* ctx, coe_step_stats* stats);
 int coe_set_arranging(coe_ctx* ctx, int32_t arch_id, int32_t min_group_resident, int32_t min_group_missing,
                       int32_t max_wait_steps);
 
+/* Latency model of an architecture (paper Section 4.2 "Prediction of additional inference latency"): a batch of n requests
+ * of one expert takes k_ns * n + b_ns, a missing expert adds load_ns; measured offline (Section 4.5).  With several
+ * executors, coe_step gives every launch sequence (a group, or a set of small groups sharing launches) to the executor
+ * whose queue is predicted to finish first ("Request assigning": the assignment that minimises the longest queue; ties go
+ * to the lowest-numbered executor); a group's sequences stay on one executor.  Defaults: k_ns = 1000, b_ns = load_ns = 0
+ * (balance request counts).  Errors: COE_EINVAL (unknown architecture, negative value). */
+int coe_set_latency_model(coe_ctx* ctx, int32_t arch_id, int64_t k_ns, int64_t b_ns, int64_t load_ns);
+
 /* Wait for all enqueued work. */
 int coe_sync(coe_ctx* ctx);
 
@@ -207,6 +219,11 @@ int coe_debug_conv(coe_ctx* ctx, int32_t dtype, const void* x, const void* w, co
 int coe_debug_regroup(coe_ctx* ctx, int32_t n, const int32_t* cur, int32_t n_experts, int32_t* cnt, int32_t* off,
                       int32_t* perm, int32_t* inv);
 
+/* Launch sequences of the last step in launch order: the first expert of each, its predicted cost and the executor it ran
+ * on.  Writes at most cap entries (arrays nullable); *n_units receives the total. */
+int coe_debug_last_assignment(coe_ctx* ctx, int32_t cap, int32_t* first_expert, int64_t* cost_ns, int32_t* executor,
+                              int32_t* n_units);
+
 /* Kernel classes timed when cfg.profile != 0. */
 enum { COE_K_REGROUP_INDEX = 0, COE_K_REGROUP_GATHER = 1, COE_K_CONV_MFMA = 2, COE_K_CONV_DIRECT = 3, COE_K_POOL = 4,
        COE_K_HEAD = 5, COE_K_SWITCH = 6, COE_K_CONV_STEM = 7, COE_K_ATTENTION = 8, COE_K_TOKEN_OPS = 9, COE_K_CONV_SLAB = 10, COE_K_COUNT = 11 };
@@ -226,6 +243,10 @@ int coe_validate_graph(int32_t n_experts, const int32_t* succ_off, const int32_t
 int coe_arrange_defer(int32_t n_experts, const int32_t* count, const int32_t* age, const uint8_t* resident,
                       const int32_t* min_group_resident, const int32_t* min_group_missing, const int32_t* max_wait_steps,
                       uint8_t* defer);
+
+/* The assignment rule on its own: unit u (in order) goes to the executor with the least cost assigned so far, the
+ * lowest-numbered among equals; executor[u] receives it. */
+int coe_assign_executors(int32_t n_units, const int64_t* cost_ns, int32_t n_executors, int32_t* executor);
 
 /* The expert-cache policy on its own (paper Section 4.1 initial fill, Section 4.3 two-stage eviction).
  * coe_policy_stage: has_group[E] marks experts with pending requests; order[E] receives the execution order

@@ -14,9 +14,11 @@ The waiting rule, per queued group of expert e at step k:
 The thresholds come from the latency model of Section 4.2 (a batch of n requests of one expert takes K n + B, a
 missing expert adds its load time): a group is worth running once the fixed part per request is small.
 
+Also here: the rule that gives units of work to parallel executors ("Request assigning").
+
 Pinned by tests/test_oracle_routing.py: a hand-worked schedule, invariants on random arrival sequences (nobody waits
 longer than max_wait, every request runs every stage of its path exactly once and in order), reduction to the
-window-less schedule for max_wait = 0."""
+window-less schedule for max_wait = 0; a hand-worked assignment."""
 from typing import Dict, List, Optional, Sequence, Tuple
 
 
@@ -79,3 +81,23 @@ def replay(submits: Sequence[Sequence[int]], paths: Sequence[Sequence[int]], arc
                     del pos[r]
         step += 1
     return records
+
+
+def assign(costs: Sequence[int], n_executors: int) -> List[int]:
+    """Request assigning (paper Section 4.2): executors work in parallel, the total time is that of the longest queue,
+    and a new unit of work goes where that total stays smallest; among queues that tie, to the one whose own time
+    grows to the smallest value.  For equal executors both criteria pick a queue with the least work so far; the
+    lowest-numbered one is taken.  costs: predicted cost of the units in arrival order.  Returns the executor of each."""
+    assert n_executors >= 1
+    queue_time = [0] * n_executors
+    out = []
+    for cst in costs:
+        totals = []
+        for q in range(n_executors):
+            after = list(queue_time)
+            after[q] += int(cst)
+            totals.append((max(after), after[q], q))        # total time, this queue's time, index
+        q = min(totals)[2]
+        queue_time[q] += int(cst)
+        out.append(q)
+    return out

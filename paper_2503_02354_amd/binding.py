@@ -24,7 +24,7 @@ EXPORTS = [
     "coe_set_dependency_graph", "coe_submit", "coe_step", "coe_sync", "coe_collect", "coe_reset_requests",
     "coe_debug_last_regroup", "coe_debug_switch_log", "coe_debug_resident", "coe_debug_forward", "coe_debug_layer_output", "coe_debug_regroup", "coe_debug_conv",
     "coe_profile_read", "coe_profile_issued", "coe_validate_graph", "coe_policy_create", "coe_policy_destroy", "coe_policy_init_fill",
-    "coe_policy_stage", "coe_policy_resident", "coe_policy_set_eviction", "coe_policy_set_in_use_depth", "coe_set_arranging", "coe_arrange_defer",
+    "coe_policy_stage", "coe_policy_resident", "coe_policy_set_eviction", "coe_policy_set_in_use_depth", "coe_set_arranging", "coe_arrange_defer", "coe_set_latency_model", "coe_assign_executors", "coe_debug_last_assignment",
 ]
 
 
@@ -40,14 +40,14 @@ class coe_arch_desc(C.Structure):
 class coe_config(C.Structure):
     _fields_ = [("device", C.c_int32), ("max_requests", C.c_int32), ("max_batch", C.c_int32), ("max_stages", C.c_int32),
                 ("cache_cap_experts", C.c_int32), ("profile", C.c_int32), ("cache_cap_bytes", C.c_int64),
-                ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p), ("group_small", C.c_int32), ("eviction", C.c_int32), ("prefetch_depth", C.c_int32)]
+                ("compute_stream", C.c_void_p), ("copy_stream", C.c_void_p), ("group_small", C.c_int32), ("eviction", C.c_int32), ("prefetch_depth", C.c_int32), ("executors", C.c_int32)]
 
 
 class coe_step_stats(C.Structure):
     _fields_ = [("n_pending", C.c_int32), ("n_groups", C.c_int32), ("n_chunks", C.c_int32), ("n_hits", C.c_int32),
                 ("n_misses", C.c_int32), ("n_evictions", C.c_int32), ("bytes_switched", C.c_int64),
                 ("host_plan_us", C.c_double), ("n_grouped", C.c_int32), ("n_group_sets", C.c_int32),
-                ("n_deferred_groups", C.c_int32), ("n_deferred_requests", C.c_int32)]
+                ("n_deferred_groups", C.c_int32), ("n_deferred_requests", C.c_int32), ("n_executors_used", C.c_int32)]
 
 
 def _load():
@@ -86,6 +86,9 @@ def _load():
     L.coe_policy_set_eviction.argtypes = [vp, i32]
     L.coe_policy_set_in_use_depth.argtypes = [vp, i32]
     L.coe_set_arranging.argtypes = [vp, i32, i32, i32, i32]
+    L.coe_set_latency_model.argtypes = [vp, i32, C.c_int64, C.c_int64, C.c_int64]
+    L.coe_assign_executors.argtypes = [i32, vp, i32, vp]
+    L.coe_debug_last_assignment.argtypes = [vp, i32, vp, vp, vp, C.POINTER(i32)]
     L.coe_arrange_defer.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp]
     return L
 
@@ -119,6 +122,16 @@ def coe_arrange_defer(count, age, resident, min_group_resident, min_group_missin
     if rc < 0:
         raise CoEError(rc, "coe_arrange_defer")
     return out.astype(bool)
+
+
+def coe_assign_executors(cost_ns, n_executors: int) -> np.ndarray:
+    """The executor assignment rule (host only): which executor every unit goes to, in order."""
+    cost = np.ascontiguousarray(cost_ns, np.int64)
+    out = np.zeros(cost.shape[0], np.int32)
+    rc = lib.coe_assign_executors(cost.shape[0], _ptr(cost), n_executors, _ptr(out))
+    if rc < 0:
+        raise CoEError(rc, "coe_assign_executors")
+    return out
 
 
 def coe_validate_graph(n_experts: int, succ_off, succ, n_classes=None) -> int:
@@ -184,9 +197,9 @@ class Context:
 
     def __init__(self, max_requests: int, max_stages: int = 2, max_batch: int = 0, cache_cap_experts: int = 0,
                  cache_cap_bytes: int = 0, device: int = 0, profile: bool = False, compute_stream: int = 0,
-                 copy_stream: int = 0, group_small: int = 0, eviction: int = 0, prefetch_depth: int = 0):
+                 copy_stream: int = 0, group_small: int = 0, eviction: int = 0, prefetch_depth: int = 0, executors: int = 0):
         cfg = coe_config(device, max_requests, max_batch, max_stages, cache_cap_experts, int(profile), cache_cap_bytes,
-                         compute_stream or None, copy_stream or None, group_small, eviction, prefetch_depth)
+                         compute_stream or None, copy_stream or None, group_small, eviction, prefetch_depth, executors)
         h = C.c_void_p()
         rc = lib.coe_create(C.byref(cfg), C.byref(h))
         if rc != COE_OK:
@@ -257,6 +270,15 @@ class Context:
 
     def coe_set_arranging(self, arch_id: int, min_group_resident: int, min_group_missing: int, max_wait_steps: int):
         self._chk(lib.coe_set_arranging(self._h, arch_id, min_group_resident, min_group_missing, max_wait_steps))
+
+    def coe_set_latency_model(self, arch_id: int, k_ns: int, b_ns: int, load_ns: int):
+        self._chk(lib.coe_set_latency_model(self._h, arch_id, int(k_ns), int(b_ns), int(load_ns)))
+
+    def coe_debug_last_assignment(self, cap: int = 4096):
+        fe = np.zeros(cap, np.int32); cost = np.zeros(cap, np.int64); ex = np.zeros(cap, np.int32); n = C.c_int32(0)
+        self._chk(lib.coe_debug_last_assignment(self._h, cap, _ptr(fe), _ptr(cost), _ptr(ex), C.byref(n)))
+        m = min(n.value, cap)
+        return fe[:m], cost[:m], ex[:m]
 
     def coe_collect(self, cap: int):
         ids = np.zeros(cap, np.int64); logits = np.zeros((cap, max(self.max_classes, 1)), np.float32)

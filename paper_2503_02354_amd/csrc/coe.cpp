@@ -44,6 +44,7 @@ struct ArchPlan {
     int32_t row_cap = INT32_MAX;        // most requests one launch may cover: the kernels address a tensor with 31-bit byte offsets
     int32_t arr_min_res = 0, arr_min_miss = 0, arr_wait = 0;   // arranging window (coe_set_arranging); arr_wait 0 = off
     bool gathers_input = false;         // the only reader of the input is a few-channel conv kernel, which can follow a row table
+    int64_t lat_k_ns = 1000, lat_b_ns = 0, lat_load_ns = 0;   // latency model (coe_set_latency_model): K n + B, expert load
     size_t elem() const { return dtype == COE_DT_BF16 ? 2 : 4; }
     size_t in_bytes() const { return (size_t)in_h * in_w * in_c * elem(); }
 };
@@ -73,6 +74,21 @@ struct ProfClass {
 };
 
 }  // namespace
+
+// One executor (paper Section 4.1: executors run inference in parallel, each on its own queue of requests): a stream and
+// the activation workspace of the launch sequences that run on it.
+constexpr int kMaxLanes = 3;          // with the copy stream: four hardware queues, what a process gets by default
+
+struct Lane {
+    hipStream_t s = nullptr;
+    void* d_buf[kMaxBufs] = {nullptr};
+    size_t buf_bytes[kMaxBufs] = {0};
+    void* d_patch = nullptr;         // GEMM rows of patch-gathered convolutions
+    size_t patch_bytes = 0;
+    hipEvent_t done = nullptr;       // recorded after the lane's last launch of a step
+    bool used = false;               // launched something in the current step
+    int64_t busy_ns = 0;             // predicted work assigned in the current step
+};
 
 struct coe_ctx {
     coe_config cfg;
@@ -110,11 +126,12 @@ struct coe_ctx {
     std::vector<int32_t> submit_step;   // per request slot: number of the first step that sees the request
     int32_t step_no = 0;
 
-    // activation workspace
-    void* d_buf[kMaxBufs] = {nullptr};
-    size_t buf_bytes[kMaxBufs] = {0};
-    void* d_patch = nullptr;         // GEMM rows of patch-gathered convolutions
-    size_t patch_bytes = 0;
+    // executors: lanes[0] runs on the compute stream; further lanes (cfg.executors > 1) have a stream and an activation
+    // workspace of their own, so that launch sequences of different groups overlap on the device
+    std::vector<Lane> lanes;
+    hipEvent_t ev_ready = nullptr;      // recorded on the compute stream when a step's regrouped inputs are ready
+    struct Unit { int32_t expert; int64_t cost_ns; int32_t lane; };
+    std::vector<Unit> last_units;       // launch sequences of the last step: first expert, predicted cost, executor
 
     // profiling
     ProfClass prof[COE_K_COUNT];
@@ -367,25 +384,27 @@ int32_t chunk_rows(const coe_ctx* c, const ArchPlan& a) { return std::min(c->cfg
 
 int ensure_workspace(coe_ctx* c)
 {
-    for (int b = 1; b < kMaxBufs; ++b) {
-        size_t need = 0;
-        for (const ArchPlan& a : c->archs) need = std::max(need, a.buf_elems[b] * a.elem() * (size_t)chunk_rows(c, a));
-        if (need > c->buf_bytes[b]) {
-            HIPCHK(c, hipStreamSynchronize(c->sc));
-            if (c->d_buf[b]) HIPCHK(c, hipFree(c->d_buf[b]));
-            c->d_buf[b] = nullptr;
-            HIPCHK(c, hipMalloc(&c->d_buf[b], need));
-            c->buf_bytes[b] = need;
+    for (Lane& ln : c->lanes) {
+        for (int b = 1; b < kMaxBufs; ++b) {
+            size_t need = 0;
+            for (const ArchPlan& a : c->archs) need = std::max(need, a.buf_elems[b] * a.elem() * (size_t)chunk_rows(c, a));
+            if (need > ln.buf_bytes[b]) {
+                HIPCHK(c, hipStreamSynchronize(ln.s));
+                if (ln.d_buf[b]) HIPCHK(c, hipFree(ln.d_buf[b]));
+                ln.d_buf[b] = nullptr;
+                HIPCHK(c, hipMalloc(&ln.d_buf[b], need));
+                ln.buf_bytes[b] = need;
+            }
         }
-    }
-    size_t need = 0;
-    for (const ArchPlan& a : c->archs) need = std::max(need, a.patch_elems * a.elem() * (size_t)chunk_rows(c, a));
-    if (need > c->patch_bytes) {
-        HIPCHK(c, hipStreamSynchronize(c->sc));
-        if (c->d_patch) HIPCHK(c, hipFree(c->d_patch));
-        c->d_patch = nullptr;
-        HIPCHK(c, hipMalloc(&c->d_patch, need));
-        c->patch_bytes = need;
+        size_t need = 0;
+        for (const ArchPlan& a : c->archs) need = std::max(need, a.patch_elems * a.elem() * (size_t)chunk_rows(c, a));
+        if (need > ln.patch_bytes) {
+            HIPCHK(c, hipStreamSynchronize(ln.s));
+            if (ln.d_patch) HIPCHK(c, hipFree(ln.d_patch));
+            ln.d_patch = nullptr;
+            HIPCHK(c, hipMalloc(&ln.d_patch, need));
+            ln.patch_bytes = need;
+        }
     }
     return COE_OK;
 }
@@ -467,13 +486,13 @@ int issue_load(coe_ctx* c, const coe::Switch& sw, coe_step_stats* st)
 
 // ---- one expert over one batch ---------------------------------------------------------------------------------------
 // rows: the batch is rows[0..n) of the array at `input` (only for architectures whose first kernel follows a row table)
-int run_expert(coe_ctx* c, const Expert& x, const void* weights, const void* input, int32_t n, const coe::k::RouteArgs& route,
-               int32_t last_layer = -1, const int32_t* rows = nullptr)
+int run_expert(coe_ctx* c, Lane& ln, const Expert& x, const void* weights, const void* input, int32_t n,
+               const coe::k::RouteArgs& route, int32_t last_layer = -1, const int32_t* rows = nullptr)
 {
     int32_t li = -1;
     const ArchPlan& a = c->archs[x.arch];
     const uint8_t* wb = (const uint8_t*)weights;
-    auto buf = [&](int id) -> void* { return id == 0 ? const_cast<void*>(input) : c->d_buf[id]; };
+    auto buf = [&](int id) -> void* { return id == 0 ? const_cast<void*>(input) : ln.d_buf[id]; };
     for (const LayerPlan& L : a.layers) {
         const coe_layer& l = L.d;
         if (last_layer >= 0 && ++li > last_layer) break;
@@ -485,67 +504,67 @@ int run_expert(coe_ctx* c, const Expert& x, const void* weights, const void* inp
             if (L.patchify) {
                 {
                     double bytes = 2.0 * n * (double)L.H * L.W * L.C * a.elem();
-                    Span sp(c, COE_K_TOKEN_OPS, bytes, c->sc);
-                    HIPCHK(c, coe::k::patchify(buf(l.src), c->d_patch, n, L.H, L.W, L.C, l.r, l.s, c->sc));
+                    Span sp(c, COE_K_TOKEN_OPS, bytes, ln.s);
+                    HIPCHK(c, coe::k::patchify(buf(l.src), ln.d_patch, n, L.H, L.W, L.C, l.r, l.s, ln.s));
                 }
                 coe::k::ConvShape g{n, L.P, L.Q, l.r * l.s * L.C, L.K, 1, 1, 1, 0, L.P, L.Q, l.act};
-                Span sp(c, COE_K_CONV_MFMA, flops, c->sc);
-                HIPCHK(c, coe::k::conv_mfma(c->d_patch, wb + L.off[0], (const float*)(wb + L.off[1]), nullptr, buf(l.dst), g, c->sc));
+                Span sp(c, COE_K_CONV_MFMA, flops, ln.s);
+                HIPCHK(c, coe::k::conv_mfma(ln.d_patch, wb + L.off[0], (const float*)(wb + L.off[1]), nullptr, buf(l.dst), g, ln.s));
             } else if (L.packed) {
-                Span sp(c, coe::k::conv_mfma_uses_slab(s) ? COE_K_CONV_SLAB : COE_K_CONV_MFMA, flops, c->sc);
-                HIPCHK(c, coe::k::conv_mfma(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), res, buf(l.dst), s, c->sc));
+                Span sp(c, coe::k::conv_mfma_uses_slab(s) ? COE_K_CONV_SLAB : COE_K_CONV_MFMA, flops, ln.s);
+                HIPCHK(c, coe::k::conv_mfma(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), res, buf(l.dst), s, ln.s));
             } else if (L.fuse_pool) {
                 const LayerPlan& pool = *(&L + 1);
-                Span sp(c, COE_K_CONV_STEM, flops, c->sc);
-                HIPCHK(c, coe::k::conv_smallc(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), buf(pool.d.dst), s, true, c->sc,
+                Span sp(c, COE_K_CONV_STEM, flops, ln.s);
+                HIPCHK(c, coe::k::conv_smallc(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), buf(pool.d.dst), s, true, ln.s,
                                               l.src == 0 ? rows : nullptr));
             } else if (a.dtype == COE_DT_BF16 && coe::k::conv_smallc_supported(s, res != nullptr, false)) {
-                Span sp(c, COE_K_CONV_STEM, flops, c->sc);
-                HIPCHK(c, coe::k::conv_smallc(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), buf(l.dst), s, false, c->sc,
+                Span sp(c, COE_K_CONV_STEM, flops, ln.s);
+                HIPCHK(c, coe::k::conv_smallc(buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), buf(l.dst), s, false, ln.s,
                                               l.src == 0 ? rows : nullptr));
             } else {
-                Span sp(c, COE_K_CONV_DIRECT, flops, c->sc);
-                HIPCHK(c, coe::k::conv_direct(a.dtype, buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), res, buf(l.dst), s, c->sc));
+                Span sp(c, COE_K_CONV_DIRECT, flops, ln.s);
+                HIPCHK(c, coe::k::conv_direct(a.dtype, buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), res, buf(l.dst), s, ln.s));
             }
             break;
         }
         case COE_OP_MAXPOOL: {
             if (L.fused_away) break;
             double bytes = (double)n * ((double)L.H * L.W * L.C + (double)L.P * L.Q * L.K) * a.elem();
-            Span sp(c, COE_K_POOL, bytes, c->sc);
-            HIPCHK(c, coe::k::maxpool(a.dtype, buf(l.src), buf(l.dst), n, L.H, L.W, L.C, l.r, l.s, l.stride, l.pad, L.P, L.Q, c->sc));
+            Span sp(c, COE_K_POOL, bytes, ln.s);
+            HIPCHK(c, coe::k::maxpool(a.dtype, buf(l.src), buf(l.dst), n, L.H, L.W, L.C, l.r, l.s, l.stride, l.pad, L.P, L.Q, ln.s));
             break;
         }
         case COE_OP_HEAD: {
             double bytes = (double)n * L.H * L.W * L.C * a.elem();
-            Span sp(c, COE_K_HEAD, bytes, c->sc);
+            Span sp(c, COE_K_HEAD, bytes, ln.s);
             HIPCHK(c, coe::k::head_gap_fc(a.dtype, buf(l.src), wb + L.off[0], (const float*)(wb + L.off[1]), n, L.H * L.W, L.C, L.K,
-                                          route, c->sc));
+                                          route, ln.s));
             break;
         }
         case COE_OP_TOKENS: {
             double bytes = (double)n * ((double)L.H * L.W + L.P) * L.C * a.elem();
-            Span sp(c, COE_K_TOKEN_OPS, bytes, c->sc);
-            HIPCHK(c, coe::k::tokens(buf(l.src), wb + L.off[0], wb + L.off[1], buf(l.dst), n, L.P, L.C, c->sc));
+            Span sp(c, COE_K_TOKEN_OPS, bytes, ln.s);
+            HIPCHK(c, coe::k::tokens(buf(l.src), wb + L.off[0], wb + L.off[1], buf(l.dst), n, L.P, L.C, ln.s));
             break;
         }
         case COE_OP_LAYERNORM: {
             double bytes = 2.0 * n * (double)L.H * L.W * L.C * a.elem();
-            Span sp(c, COE_K_TOKEN_OPS, bytes, c->sc);
+            Span sp(c, COE_K_TOKEN_OPS, bytes, ln.s);
             HIPCHK(c, coe::k::layernorm(buf(l.src), (const float*)(wb + L.off[0]), (const float*)(wb + L.off[1]), buf(l.dst),
-                                        (int64_t)n * L.H * L.W, L.C, c->sc));
+                                        (int64_t)n * L.H * L.W, L.C, ln.s));
             break;
         }
         case COE_OP_ATTENTION: {
-            Span sp(c, COE_K_ATTENTION, 2.0 * L.macs * n, c->sc);
-            HIPCHK(c, coe::k::attention(buf(l.src), buf(l.dst), n, L.H * L.W, L.K, l.aux0, c->sc));
+            Span sp(c, COE_K_ATTENTION, 2.0 * L.macs * n, ln.s);
+            HIPCHK(c, coe::k::attention(buf(l.src), buf(l.dst), n, L.H * L.W, L.K, l.aux0, ln.s));
             break;
         }
         case COE_OP_HEAD_CLS: {
             double bytes = (double)n * L.C * a.elem();
-            Span sp(c, COE_K_HEAD, bytes, c->sc);
+            Span sp(c, COE_K_HEAD, bytes, ln.s);
             HIPCHK(c, coe::k::head_cls(buf(l.src), (const float*)(wb + L.off[0]), (const float*)(wb + L.off[1]), wb + L.off[2],
-                                       (const float*)(wb + L.off[3]), n, L.H * L.W, L.C, L.K, route, c->sc));
+                                       (const float*)(wb + L.off[3]), n, L.H * L.W, L.C, L.K, route, ln.s));
             break;
         }
         default:
@@ -563,7 +582,7 @@ struct SetMember {
 };
 
 // rows: as in run_expert; the members' inputs are rows[first..first+count) of the array at `staged`
-int run_group_set(coe_ctx* c, const std::vector<SetMember>& set, const uint8_t* staged, size_t ib, const int32_t* rows)
+int run_group_set(coe_ctx* c, Lane& ln, const std::vector<SetMember>& set, const uint8_t* staged, size_t ib, const int32_t* rows)
 {
     const ArchPlan& a = c->archs[c->experts[set[0].expert].arch];
     coe::k::GroupTable gt{};
@@ -581,7 +600,7 @@ int run_group_set(coe_ctx* c, const std::vector<SetMember>& set, const uint8_t* 
         n += set[g].count;
     }
     gt.first_row[set.size()] = n;
-    auto buf = [&](int id) -> uint8_t* { return (uint8_t*)c->d_buf[id]; };
+    auto buf = [&](int id) -> uint8_t* { return (uint8_t*)ln.d_buf[id]; };
     for (const LayerPlan& L : a.layers) {
         const coe_layer& l = L.d;
         switch (l.op) {
@@ -591,8 +610,8 @@ int run_group_set(coe_ctx* c, const std::vector<SetMember>& set, const uint8_t* 
             if (L.packed) {
                 if (l.src == 0) return fail(c, COE_ESTATE, "internal: grouped matrix-core conv on the raw input");
                 const void* res = l.res >= 0 ? buf(l.res) : nullptr;
-                Span sp(c, coe::k::conv_mfma_uses_slab(s) ? COE_K_CONV_SLAB : COE_K_CONV_MFMA, flops, c->sc);
-                HIPCHK(c, coe::k::conv_mfma_grouped(buf(l.src), gt, L.off[0], L.off[1], res, buf(l.dst), s, c->sc));
+                Span sp(c, coe::k::conv_mfma_uses_slab(s) ? COE_K_CONV_SLAB : COE_K_CONV_MFMA, flops, ln.s);
+                HIPCHK(c, coe::k::conv_mfma_grouped(buf(l.src), gt, L.off[0], L.off[1], res, buf(l.dst), s, ln.s));
             } else {
                 // few input channels (the stem): the filters live in LDS for a whole launch, so one launch per group,
                 // each writing its rows of the shared activation buffer
@@ -600,7 +619,7 @@ int run_group_set(coe_ctx* c, const std::vector<SetMember>& set, const uint8_t* 
                 const LayerPlan& outL = fused ? *(&L + 1) : L;
                 const size_t in_row = (size_t)L.H * L.W * L.C * a.elem();
                 const size_t out_row = (size_t)outL.P * outL.Q * outL.K * a.elem();
-                Span sp(c, COE_K_CONV_STEM, flops, c->sc);
+                Span sp(c, COE_K_CONV_STEM, flops, ln.s);
                 for (size_t g = 0; g < set.size(); ++g) {
                     coe::k::ConvShape sg = s;
                     sg.N = set[g].count;
@@ -609,7 +628,7 @@ int run_group_set(coe_ctx* c, const std::vector<SetMember>& set, const uint8_t* 
                                       : l.src == 0 ? staged + (size_t)set[g].first * ib : buf(l.src) + (size_t)gt.first_row[g] * in_row;
                     const uint8_t* wb = (const uint8_t*)gt.weights[g];
                     HIPCHK(c, coe::k::conv_smallc(in, wb + L.off[0], (const float*)(wb + L.off[1]),
-                                                  buf(outL.d.dst) + (size_t)gt.first_row[g] * out_row, sg, fused, c->sc,
+                                                  buf(outL.d.dst) + (size_t)gt.first_row[g] * out_row, sg, fused, ln.s,
                                                   via_rows ? rows + set[g].first : nullptr));
                 }
             }
@@ -619,8 +638,8 @@ int run_group_set(coe_ctx* c, const std::vector<SetMember>& set, const uint8_t* 
             if (L.fused_away) break;
             if (l.src == 0) return fail(c, COE_ESTATE, "internal: grouped pool on the raw input");
             double bytes = (double)n * ((double)L.H * L.W * L.C + (double)L.P * L.Q * L.K) * a.elem();
-            Span sp(c, COE_K_POOL, bytes, c->sc);
-            HIPCHK(c, coe::k::maxpool(a.dtype, buf(l.src), buf(l.dst), n, L.H, L.W, L.C, l.r, l.s, l.stride, l.pad, L.P, L.Q, c->sc));
+            Span sp(c, COE_K_POOL, bytes, ln.s);
+            HIPCHK(c, coe::k::maxpool(a.dtype, buf(l.src), buf(l.dst), n, L.H, L.W, L.C, l.r, l.s, l.stride, l.pad, L.P, L.Q, ln.s));
             break;
         }
         case COE_OP_HEAD: {
@@ -628,8 +647,8 @@ int run_group_set(coe_ctx* c, const std::vector<SetMember>& set, const uint8_t* 
             double bytes = (double)n * L.H * L.W * L.C * a.elem();
             coe::k::RouteArgs r{c->d_perm, 0, c->d_succ, 0, c->d_cur, c->d_depth, c->d_path, c->cfg.max_stages, c->d_logits,
                                 c->max_classes};
-            Span sp(c, COE_K_HEAD, bytes, c->sc);
-            HIPCHK(c, coe::k::head_gap_fc_grouped(a.dtype, buf(l.src), gt, L.off[0], L.off[1], n, L.H * L.W, L.C, L.K, r, gr, c->sc));
+            Span sp(c, COE_K_HEAD, bytes, ln.s);
+            HIPCHK(c, coe::k::head_gap_fc_grouped(a.dtype, buf(l.src), gt, L.off[0], L.off[1], n, L.H * L.W, L.C, L.K, r, gr, ln.s));
             break;
         }
         default:
@@ -681,6 +700,14 @@ int coe_create(const coe_config* cfg, coe_ctx** out)
     else { if (hipStreamCreateWithFlags(&c->sc, hipStreamNonBlocking) != hipSuccess) return bail(COE_EDEVICE); c->own_sc = true; }
     if (cfg->copy_stream) c->sx = (hipStream_t)cfg->copy_stream;
     else { if (hipStreamCreateWithFlags(&c->sx, hipStreamNonBlocking) != hipSuccess) return bail(COE_EDEVICE); c->own_sx = true; }
+    if (cfg->executors < 0 || cfg->executors > kMaxLanes) { coe_destroy(c); return COE_EINVAL; }
+    c->lanes.resize(std::max(1, cfg->executors));
+    c->lanes[0].s = c->sc;
+    for (size_t l = 1; l < c->lanes.size(); ++l)
+        if (hipStreamCreateWithFlags(&c->lanes[l].s, hipStreamNonBlocking) != hipSuccess ||
+            hipEventCreateWithFlags(&c->lanes[l].done, hipEventDisableTiming) != hipSuccess)
+            return bail(COE_EDEVICE);
+    if (hipEventCreateWithFlags(&c->ev_ready, hipEventDisableTiming) != hipSuccess) return bail(COE_EDEVICE);
     size_t nreq = (size_t)cfg->max_requests;
     size_t nblocks = (nreq + coe::k::kRegroupTile - 1) / coe::k::kRegroupTile;
     bool ok = hipMalloc((void**)&c->d_cur, nreq * 4) == hipSuccess && hipMalloc((void**)&c->d_depth, nreq * 4) == hipSuccess &&
@@ -716,8 +743,14 @@ void coe_destroy(coe_ctx* c)
     void* ptrs[] = {c->d_inputs, c->d_staged, c->d_cur, c->d_depth, c->d_path, c->d_logits, c->d_cnt, c->d_off,
                     c->d_perm, c->d_inv, c->d_blockhist, c->d_succ};
     for (void* p : ptrs) if (p) hipFree(p);
-    for (int b = 1; b < kMaxBufs; ++b) if (c->d_buf[b]) hipFree(c->d_buf[b]);
-    if (c->d_patch) hipFree(c->d_patch);
+    for (size_t l = 0; l < c->lanes.size(); ++l) {
+        Lane& ln = c->lanes[l];
+        for (int b = 1; b < kMaxBufs; ++b) if (ln.d_buf[b]) hipFree(ln.d_buf[b]);
+        if (ln.d_patch) hipFree(ln.d_patch);
+        if (ln.done) hipEventDestroy(ln.done);
+        if (l > 0 && ln.s) hipStreamDestroy(ln.s);
+    }
+    if (c->ev_ready) hipEventDestroy(c->ev_ready);
     if (c->h_cnt) hipHostFree(c->h_cnt);
     if (c->own_sc && c->sc) hipStreamDestroy(c->sc);
     if (c->own_sx && c->sx) hipStreamDestroy(c->sx);
@@ -963,6 +996,30 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
         }
         return COE_OK;
     };
+    // executors: every launch sequence goes to the executor whose queue is predicted to finish first (paper Section
+    // 4.2 "Request assigning": minimise the total time over all queues, i.e. the longest one; with equal executors that
+    // is the one with the least work so far, the lowest-numbered among equals)
+    std::vector<uint8_t> was_missing(E, 0);
+    for (const coe::Switch& sw : switches) was_missing[sw.expert] = 1;
+    for (Lane& ln : c->lanes) { ln.used = false; ln.busy_ns = 0; }
+    c->last_units.clear();
+    if (c->lanes.size() > 1) HIPCHK(c, hipEventRecord(c->ev_ready, c->sc));
+    auto take_lane = [&](int32_t first_expert, int64_t cost_ns, Lane** out) -> int {
+        size_t best = 0;
+        for (size_t l = 1; l < c->lanes.size(); ++l)
+            if (c->lanes[l].busy_ns < c->lanes[best].busy_ns) best = l;
+        Lane& ln = c->lanes[best];
+        ln.busy_ns += cost_ns;
+        if (best > 0 && !ln.used) HIPCHK(c, hipStreamWaitEvent(ln.s, c->ev_ready, 0));   // inputs regrouped, earlier steps done
+        ln.used = true;
+        c->last_units.push_back({first_expert, cost_ns, (int32_t)best});
+        *out = &ln;
+        return COE_OK;
+    };
+    auto group_cost = [&](int32_t e) {
+        const ArchPlan& a = c->archs[c->experts[e].arch];
+        return a.lat_k_ns * (int64_t)c->h_cnt[e] + (was_missing[e] ? a.lat_load_ns : 0);
+    };
     const int32_t group_small = c->cfg.group_small == 0 ? 64 : c->cfg.group_small;
     auto small = [&](int32_t e) {
         const ArchPlan& a = c->archs[c->experts[e].arch];
@@ -993,19 +1050,24 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
                 rows += c->h_cnt[f];
             }
         }
+        Lane* lane = nullptr;
         if (set.size() >= 2) {
-            for (const SetMember& m : set) {
-                Expert& xm = c->experts[m.expert];
-                if (xm.load_pending) {
-                    HIPCHK(c, hipStreamWaitEvent(c->sc, xm.loaded, 0));
-                    xm.load_pending = false;
-                }
-            }
-            rc = run_group_set(c, set, staged, ib, rows);
+            int64_t cost = c->archs[x.arch].lat_b_ns;                       // one launch sequence for the whole set
+            for (const SetMember& m : set) cost += group_cost(m.expert);
+            rc = take_lane(e, cost, &lane);
             if (rc) return rc;
             for (const SetMember& m : set) {
                 Expert& xm = c->experts[m.expert];
-                HIPCHK(c, hipEventRecord(xm.buf->last_use, c->sc));
+                if (xm.load_pending) {
+                    HIPCHK(c, hipStreamWaitEvent(lane->s, xm.loaded, 0));
+                    xm.load_pending = false;
+                }
+            }
+            rc = run_group_set(c, *lane, set, staged, ib, rows);
+            if (rc) return rc;
+            for (const SetMember& m : set) {
+                Expert& xm = c->experts[m.expert];
+                HIPCHK(c, hipEventRecord(xm.buf->last_use, lane->s));
                 xm.buf->used = true;
                 launched[m.expert] = 1;
                 ++st.n_chunks;
@@ -1015,28 +1077,74 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
             continue;
         }
 
-        if (x.load_pending) {
-            HIPCHK(c, hipStreamWaitEvent(c->sc, x.loaded, 0));
-            x.load_pending = false;
-        }
         const int32_t n_route = c->succ_off[e + 1] - c->succ_off[e];
         // request splitting: as few launch sequences as the cap allows, of equal size (no short last one)
         const int32_t cap_rows = chunk_rows(c, c->archs[x.arch]);
         const int32_t n_seq = (c->h_cnt[e] + cap_rows - 1) / cap_rows;
         const int32_t chunk = (c->h_cnt[e] + n_seq - 1) / n_seq;
+        rc = take_lane(e, group_cost(e) + c->archs[x.arch].lat_b_ns * n_seq, &lane);   // a group stays on one executor
+        if (rc) return rc;
+        if (x.load_pending) {
+            HIPCHK(c, hipStreamWaitEvent(lane->s, x.loaded, 0));
+            x.load_pending = false;
+        }
         for (int32_t s = off[e]; s < off[e + 1]; s += chunk) {
             int32_t cnt = std::min(chunk, off[e + 1] - s);
             coe::k::RouteArgs r{c->d_perm + s, e, c->d_succ + c->succ_off[e], n_route, c->d_cur, c->d_depth, c->d_path,
                                 c->cfg.max_stages, c->d_logits, c->max_classes};
-            rc = run_expert(c, x, x.buf->p, rows ? staged : staged + (size_t)s * ib, cnt, r, -1, rows ? rows + s : nullptr);
+            rc = run_expert(c, *lane, x, x.buf->p, rows ? staged : staged + (size_t)s * ib, cnt, r, -1, rows ? rows + s : nullptr);
             if (rc) return rc;
             ++st.n_chunks;
         }
-        HIPCHK(c, hipEventRecord(x.buf->last_use, c->sc));
+        HIPCHK(c, hipEventRecord(x.buf->last_use, lane->s));
         x.buf->used = true;
         launched[e] = 1;
     }
+    // the step is complete on the compute stream once every executor is
+    for (size_t l = 1; l < c->lanes.size(); ++l) {
+        Lane& ln = c->lanes[l];
+        if (!ln.used) continue;
+        HIPCHK(c, hipEventRecord(ln.done, ln.s));
+        HIPCHK(c, hipStreamWaitEvent(c->sc, ln.done, 0));
+    }
+    for (const Lane& ln : c->lanes) st.n_executors_used += ln.used;
     if (stats) *stats = st;
+    return COE_OK;
+}
+
+int coe_set_latency_model(coe_ctx* c, int32_t arch_id, int64_t k_ns, int64_t b_ns, int64_t load_ns)
+{
+    if (!c) return COE_EINVAL;
+    if (arch_id < 0 || arch_id >= (int32_t)c->archs.size()) return fail(c, COE_EINVAL, "unknown architecture");
+    if (k_ns < 0 || b_ns < 0 || load_ns < 0) return fail(c, COE_EINVAL, "negative latency");
+    ArchPlan& a = c->archs[arch_id];
+    a.lat_k_ns = k_ns; a.lat_b_ns = b_ns; a.lat_load_ns = load_ns;
+    return COE_OK;
+}
+
+int coe_assign_executors(int32_t n_units, const int64_t* cost_ns, int32_t n_executors, int32_t* executor)
+{
+    if (n_units < 0 || n_executors <= 0 || (n_units > 0 && (!cost_ns || !executor))) return COE_EINVAL;
+    std::vector<int64_t> busy(n_executors, 0);
+    for (int32_t u = 0; u < n_units; ++u) {
+        int32_t best = 0;
+        for (int32_t l = 1; l < n_executors; ++l)
+            if (busy[l] < busy[best]) best = l;
+        busy[best] += cost_ns[u];
+        executor[u] = best;
+    }
+    return COE_OK;
+}
+
+int coe_debug_last_assignment(coe_ctx* c, int32_t cap, int32_t* first_expert, int64_t* cost_ns, int32_t* executor, int32_t* n_units)
+{
+    if (!c || !n_units || cap < 0) return COE_EINVAL;
+    *n_units = (int32_t)c->last_units.size();
+    for (int32_t u = 0; u < std::min<int32_t>(cap, *n_units); ++u) {
+        if (first_expert) first_expert[u] = c->last_units[u].expert;
+        if (cost_ns) cost_ns[u] = c->last_units[u].cost_ns;
+        if (executor) executor[u] = c->last_units[u].lane;
+    }
     return COE_OK;
 }
 
@@ -1175,7 +1283,7 @@ int coe_debug_forward(coe_ctx* c, int32_t e, int32_t n, const void* dev_in, floa
     for (int32_t s = 0; s < n && rc == COE_OK; s += chunk) {
         int32_t cnt = std::min(chunk, n - s);
         coe::k::RouteArgs r{nullptr, e, nullptr, 0, nullptr, nullptr, nullptr, 0, d_log + (size_t)s * a.n_classes, a.n_classes};
-        rc = run_expert(c, x, w, (const uint8_t*)dev_in + (size_t)s * ib, cnt, r);
+        rc = run_expert(c, c->lanes[0], x, w, (const uint8_t*)dev_in + (size_t)s * ib, cnt, r);
     }
     hipError_t he = hipStreamSynchronize(c->sc);
     if (rc == COE_OK && he == hipSuccess) he = hipMemcpy(logits_out, d_log, (size_t)n * a.n_classes * 4, hipMemcpyDeviceToHost);
@@ -1205,9 +1313,9 @@ int coe_debug_layer_output(coe_ctx* c, int32_t e, int32_t n, const void* dev_in,
     hipError_t he = hipMemcpy(w, x.host, x.nbytes, hipMemcpyHostToDevice);
     if (he == hipSuccess) {
         coe::k::RouteArgs r{};
-        rc = run_expert(c, x, w, dev_in, n, r, layer);
+        rc = run_expert(c, c->lanes[0], x, w, dev_in, n, r, layer);
         he = hipStreamSynchronize(c->sc);
-        if (rc == COE_OK && he == hipSuccess) he = hipMemcpy(out, c->d_buf[L.d.dst], bytes, hipMemcpyDeviceToHost);
+        if (rc == COE_OK && he == hipSuccess) he = hipMemcpy(out, c->lanes[0].d_buf[L.d.dst], bytes, hipMemcpyDeviceToHost);
     }
     hipFree(w);
     if (rc) return rc;

@@ -13,7 +13,7 @@ def device_tensor(x: np.ndarray):
 
 
 def run_chain_gpu(B, wl, blobs, x, first_expert=None, *, max_batch=0, cap_experts=None, arrival=None, on_device=True,
-                  profile=False, ctx=None, keep=False, group_small=0, arranging=None, eviction=0, prefetch_depth=0):
+                  profile=False, ctx=None, keep=False, group_small=0, arranging=None, eviction=0, prefetch_depth=0, executors=0, latency=None):
     """Submit x in arrival batches, one coe_step after each submit, then step until done; collect everything.
     arranging: (min_group_resident, min_group_missing, max_wait_steps) set for every architecture.
     Returns dict(logits, path, ids, stats, switch_log[, ctx])."""
@@ -23,11 +23,14 @@ def run_chain_gpu(B, wl, blobs, x, first_expert=None, *, max_batch=0, cap_expert
     if own:
         ctx = B.Context(max_requests=max(n, 1), max_stages=wl.max_stages, max_batch=max_batch,
                         cache_cap_experts=wl.cache_cap_experts if cap_experts is None else cap_experts, profile=profile,
-                        group_small=group_small, eviction=eviction, prefetch_depth=prefetch_depth)
+                        group_small=group_small, eviction=eviction, prefetch_depth=prefetch_depth, executors=executors)
         B.setup_workload(ctx, wl, blobs)
     if arranging is not None:
         for a in range(len(wl.archs)):
             ctx.coe_set_arranging(a, *arranging)
+    if latency is not None:                    # (k_ns, b_ns, load_ns) for every architecture
+        for a in range(len(wl.archs)):
+            ctx.coe_set_latency_model(a, *latency)
     arrival = arrival or n or 1
     stats = []
     dev = device_tensor(x) if on_device and n else None

@@ -124,7 +124,8 @@ def test_config3_full_size(B, oracle):
     wl = W.config3()
     assert wl.head_bias, "calibration file missing"
     got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=24, max_batch=512, arrival=512, seed=3,
-                                                    also=[dict(arranging=(0, 43, 8), prefetch_depth=4)])
+                                                    also=[dict(arranging=(0, 43, 8), prefetch_depth=4, executors=3,
+                                                               latency=(14410, 1611000, 846000))])
     stats = [st for rc, st in got["stats"] if rc == B.COE_OK]
     assert len(stats) == 33                                            # 32 arrivals + the last batch's leaf stage
     assert stats[0].n_groups == 1 and stats[0].n_pending == 512 and stats[-1].n_pending == 512
@@ -143,8 +144,8 @@ def test_config3_full_size(B, oracle):
     assert 0.15 < leaves.max() / wl.n_requests < 0.40 and (leaves > 0).sum() >= 40, leaves
     print(f"config3 full size: {len(sample)} sampled, max rel err {err:.2e}, {redraws} re-draws, "
           f"{len(log) - 16} switches, top leaves {np.sort(leaves)[::-1][:6].tolist()}")
-    # the schedule the benchmark times on this workload: an 8-step arranging window for groups of missing experts and
-    # four groups of prefetch.  Same bits (checked above); a consistent switch log with far fewer switches; nobody
+    # the schedule the benchmark times on this workload: an 8-step arranging window for groups of missing experts,
+    # four groups of prefetch and three executors.  Same bits (checked above); a consistent switch log with far fewer switches; nobody
     # waits longer than the window
     win = got["also"][0]
     wstats = [st for rc, st in win["stats"] if rc == B.COE_OK]

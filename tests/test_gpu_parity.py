@@ -636,3 +636,36 @@ def test_arranging_window_on_a_capped_mixed_dag(B, oracle, G):
         log += r["switches"]
     assert got["switch_log"] == log
     assert sum(st.n_deferred_groups for st in stats) > 0 and len(log) > 7
+
+
+@pytest.mark.parametrize("executors,cap,group_small", [(3, 4, -1), (2, 0, 0), (3, 5, 0)])
+def test_executors_give_the_same_bits_and_follow_the_assignment_rule(B, oracle, G, executors, cap, group_small):
+    """Several executors (streams with their own activation workspaces): launch sequences of different groups overlap
+    on the device.  Same routes and logits bit for bit, same switch log as with one executor; the executor of every
+    launch sequence of the last step is what the oracle's assignment rule gives for the library's predicted costs, and
+    those costs are K n + B (+ load for a missing expert) where a launch sequence is one group."""
+    from oracle import arrange
+    n, E, arrival = 160, 16, 40
+    wl = W.config2(n, hw=64, n_experts=E, width=64, calibrated=False)
+    G.calibrate_workload(wl, n_cal=48)
+    blobs = [wl.blob(e) for e in range(E)]
+    x, sub, want, _ = G.guarded_inputs(wl, blobs, range(n))
+    lat = (700, 90000, 50000)
+    one = run_chain_gpu(B, wl, blobs, x, max_batch=64, arrival=arrival, cap_experts=cap, group_small=group_small, latency=lat)
+    got = run_chain_gpu(B, wl, blobs, x, max_batch=64, arrival=arrival, cap_experts=cap, group_small=group_small, latency=lat,
+                        executors=executors, keep=True)
+    ctx = got.pop("ctx")
+    assert np.array_equal(one["path"], got["path"]) and np.array_equal(one["logits"], got["logits"])
+    assert one["switch_log"] == got["switch_log"]
+    assert_chain_parity(got, want, REL_TOL_BF16)
+    assert max(st.n_executors_used for rc, st in got["stats"]) == executors
+    assert all(st.n_executors_used == 1 for rc, st in one["stats"] if rc == B.COE_OK and st.n_groups)
+    fe, cost, ex = ctx.coe_debug_last_assignment()
+    ctx.close()
+    assert len(fe) >= 1 and ex.tolist() == arrange.assign(cost.tolist(), executors)
+    if group_small < 0:                                  # one launch sequence per group: the cost model is checkable
+        last = [st for rc, st in got["stats"] if rc == B.COE_OK][-1]
+        sizes = np.bincount(want["path"][n - arrival:, 1], minlength=E)          # the last step runs the last arrival's leaves
+        misses = {e for e, v in got["switch_log"][-last.n_misses:]} if last.n_misses else set()
+        for e, cst in zip(fe.tolist(), cost.tolist()):
+            assert cst == lat[0] * int(sizes[e]) + lat[1] + (lat[2] if e in misses else 0), (e, cst)

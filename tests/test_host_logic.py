@@ -189,3 +189,14 @@ def test_decay_window_search_hand_worked():
     # a skewed CDF: Zipf(1.1) over 63 leaves reaches 74.9 % of the usage with its 15 most used experts
     z = W.zipf_probs(63, 1.1)
     assert P.experts_for_usage(z, 74.0) == 15 and P.experts_for_usage(z, 25.0) == 1
+
+
+def test_assigning_rule_matches_oracle(B):
+    """The library's executor assignment (least work so far, lowest number among equals) against the oracle's, which
+    evaluates the paper's two criteria (smallest total over all queues, then smallest own queue) literally."""
+    from oracle.arrange import assign
+    rng = np.random.default_rng(11)
+    for _ in range(200):
+        n = int(rng.integers(0, 40)); k = int(rng.integers(1, 5))
+        cost = rng.integers(0, 50, n) if rng.random() < 0.5 else rng.integers(1, 4, n) * 1000
+        assert B.coe_assign_executors(cost, k).tolist() == assign(cost.tolist(), k)

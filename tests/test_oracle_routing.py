@@ -422,3 +422,15 @@ def test_arranging_invariants_random(oracle, seed):
     assert all(not st["deferred"] for st in off)
     plain = arrange.replay(submits, paths, [0] * E, {}, _tree_cache(oracle, probs, cap))
     assert [(st["run"], st["switches"]) for st in off] == [(st["run"], st["switches"]) for st in plain]
+
+
+def test_assigning_hand_worked():
+    """Three executors, units of cost 5 3 3 4 2 6 1 in arrival order.  Queue times after each unit:
+    5|0|0, 5|3|0, 5|3|3, 5|7|3 (the 4: queues 1 and 2 both end at 7, which is also the smallest total; the lower number
+    wins), 5|7|5, 11|7|5 (the 6: queues 0 and 2 both end at 11; the lower number wins), 11|7|6."""
+    from oracle.arrange import assign
+    assert assign([5, 3, 3, 4, 2, 6, 1], 3) == [0, 1, 2, 1, 2, 0, 2]
+    assert assign([7, 7, 7], 1) == [0, 0, 0]
+    assert assign([], 4) == []
+    # equal costs go round the executors in turn
+    assert assign([2] * 7, 3) == [0, 1, 2, 0, 1, 2, 0]
