@@ -45,6 +45,25 @@ def measured_traffic(kernel: str, launch_config=None):
         same = False
     return SLAB_TRAFFIC_BYTES_PER_LAUNCH if same else None
 PEAK_HBM_GBS = 8000.0
+
+
+def arch_macs(arch) -> int:
+    """Multiply-accumulates of one request through the expert (conv, FC and attention contractions)."""
+    import coe_workloads as W
+    total = 0
+    for L, (sshape, dshape) in zip(arch.layers, W.walk(arch)):
+        op, k, r, s = int(L[0]), int(L[4]), int(L[5]), int(L[6])
+        h, w, c = sshape
+        if op == W.OP_CONV:
+            total += dshape[0] * dshape[1] * k * r * s * c
+        elif op in (W.OP_HEAD, W.OP_HEAD_CLS):
+            total += k * c
+        elif op == W.OP_ATTENTION:
+            d = c // 3
+            total += 2 * h * h * d
+    return total
+
+
 WORKLOAD_TEXT = {
     "config2": "config2: 16 ResNet-18-shaped bf16 experts, 4096 requests 3x224x224, 2-stage tree (1 root -> 15 leaves), "
                "all resident",
@@ -125,7 +144,7 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     from paper_2503_02354_amd import binding as B
-    from paper_2503_02354_amd import workloads as W
+    import coe_workloads as W
 
     make = {"config2": W.config2, "config3": W.config3, "config4": W.config4, "config5": W.config5}[args.workload]
     wl = make(args.requests) if args.requests else make()
@@ -207,7 +226,7 @@ def main():
             if launches:
                 prof[name] = {"launches": launches, "ms": round(ms, 3), "work": work, "issued": issued}
     # (FLOPs of the experts every request actually visited, from the collected paths)
-    macs_of = [W.arch_macs(wl.archs[wl.expert_arch[e]]) for e in range(wl.graph.n_experts)]
+    macs_of = [arch_macs(wl.archs[wl.expert_arch[e]]) for e in range(wl.graph.n_experts)]
     # the matrix-core convolution classes; the roofline object is for the one that takes the most time
     mfma_kernels = {"conv_slab": "conv3x3_slab_kernel", "conv_mfma": "conv_igemm_dma_kernel", "attention": "attention_kernel"}
     est_ms = {name: prof[name]["ms"] / prof[name]["launches"] * prof[name]["issued"] for name in mfma_kernels if name in prof}

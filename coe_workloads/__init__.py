@@ -1,11 +1,13 @@
 """Seeded synthetic CoE workloads: architecture descriptors, expert weight blobs,
 dependency graphs and request images.
 
-This module is pure data generation.  It holds no convolution, routing, regroup
-or cache arithmetic: it only describes expert architectures as flat layer lists,
-draws random numbers from counter-based Philox streams and lays tensors out in
-the canonical weight-blob format that both the HIP library and the CPU oracle
-consume.  It imports neither of them.
+This package is pure data generation and belongs to neither the HIP library nor
+the CPU oracle; both are fed from it and it imports neither.  It holds no
+convolution, routing, regroup or cache arithmetic: it only describes expert
+architectures as flat layer lists, draws random numbers from counter-based
+Philox streams and lays tensors out in the canonical weight-blob format that
+both sides consume.  Head-bias calibration files written by the oracle-side
+script live next to it in calib/ and are read by both sides as inputs.
 
 CoE structure follows the paper's Section 2.1: a routing rule picks a first
 expert, an expert's output either selects the next expert or is the final
@@ -317,22 +319,6 @@ def blob_layout(arch: Arch) -> Tuple[List[TensorSpec], int]:
             add(i, "w", (k, c), True)
             add(i, "b", (k,), False)
     return specs, _align(off)
-
-
-def arch_macs(arch: Arch) -> int:
-    """Multiply-accumulates of one request through the expert (conv, FC and attention contractions)."""
-    total = 0
-    for L, (sshape, dshape) in zip(arch.layers, walk(arch)):
-        op, k, r, s = int(L[0]), int(L[4]), int(L[5]), int(L[6])
-        h, w, c = sshape
-        if op == OP_CONV:
-            total += dshape[0] * dshape[1] * k * r * s * c
-        elif op in (OP_HEAD, OP_HEAD_CLS):
-            total += k * c
-        elif op == OP_ATTENTION:
-            d = c // 3
-            total += 2 * h * h * d
-    return total
 
 
 # ----------------------------------------------------------------------------

@@ -17,7 +17,7 @@ import numpy as np
 
 sys.path.insert(0, os.path.dirname(os.path.dirname(os.path.abspath(__file__))))
 from oracle import guard as G  # noqa: E402
-from paper_2503_02354_amd import workloads as W  # noqa: E402
+import coe_workloads as W  # noqa: E402
 
 
 def main():

@@ -31,7 +31,7 @@ def delta_for(wl) -> float:
 def routing_margins(wl, blobs, res) -> np.ndarray:
     """[n][max_stages]: (top1 - top2 over the routed classes) / max_c |logit_c - bias_c| at every routing stage a
     request went through, -1 elsewhere."""
-    from paper_2503_02354_amd import workloads as W
+    import coe_workloads as W
     n, S = res["path"].shape
     out = np.full((n, S), -1.0)
     bias_cache = {}
@@ -102,7 +102,7 @@ def admissible_outcomes_batch(wl, blobs, xs: np.ndarray, first_experts: Sequence
     """For every request: every outcome that is correct up to the routing tolerance.  At each routing stage every class
     whose logit is within delta * (largest computed logit magnitude) of the maximum may be taken.  Returns one list per
     request of (path [max_stages] int32, final logits [max_classes] float32), in no particular order."""
-    from paper_2503_02354_amd import workloads as W
+    import coe_workloads as W
     if delta is None:
         delta = delta_for(wl)
     n = len(xs)

@@ -7,7 +7,7 @@ from concurrent.futures import ThreadPoolExecutor
 import numpy as np
 import pytest
 
-from paper_2503_02354_amd import workloads as W
+import coe_workloads as W
 
 pytestmark = pytest.mark.gpu
 

@@ -6,7 +6,7 @@ import re
 import numpy as np
 import pytest
 
-from paper_2503_02354_amd import workloads as W
+import coe_workloads as W
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 

@@ -5,7 +5,8 @@ import math
 import numpy as np
 import pytest
 
-from paper_2503_02354_amd import workloads as W
+import bench
+import coe_workloads as W
 
 
 # ---------------------------------------------------------------------------------------------
@@ -378,7 +379,7 @@ def test_forward_bf16_close_to_unrounded(oracle):
 
 def test_macs_match_published_tables():
     # standard layer tables: ResNet-18 1.814 GMAC, ResNet-50 (stride on the 3x3) 4.087 GMAC, ViT-B/16 17.56 GMAC
-    assert abs(W.arch_macs(W.resnet18(1000)) / 1e9 - 1.8141) < 2e-3
-    assert abs(W.arch_macs(W.resnet50(1000)) / 1e9 - 4.0891) < 2e-3
-    assert abs(W.arch_macs(W.vit(1000)) / 1e9 - 17.5638) < 2e-3
-    assert W.arch_macs(W.tiny_cnn()) == 64 * 64 * 9 * (3 * 16 + 16 * 32 + 32 * 64) + 64 * 4
+    assert abs(bench.arch_macs(W.resnet18(1000)) / 1e9 - 1.8141) < 2e-3
+    assert abs(bench.arch_macs(W.resnet50(1000)) / 1e9 - 4.0891) < 2e-3
+    assert abs(bench.arch_macs(W.vit(1000)) / 1e9 - 17.5638) < 2e-3
+    assert bench.arch_macs(W.tiny_cnn()) == 64 * 64 * 9 * (3 * 16 + 16 * 32 + 32 * 64) + 64 * 4

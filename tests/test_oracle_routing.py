@@ -4,7 +4,7 @@ import itertools
 import numpy as np
 import pytest
 
-from paper_2503_02354_amd import workloads as W
+import coe_workloads as W
 
 
 # ---------------------------------------------------------------------------------------------
