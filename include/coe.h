@@ -122,7 +122,8 @@ typedef struct {
 /* Create / destroy a context.  coe_create fails with COE_EDEVICE when no GPU is usable. */
 int coe_create(const coe_config* cfg, coe_ctx** out);
 void coe_destroy(coe_ctx* ctx);
-const char* coe_last_error(const coe_ctx* ctx); /* valid until the next call on ctx; "" if none */
+const char* coe_last_error(const coe_ctx* ctx); /* valid until the next call on ctx; "" if none.  ctx == NULL: the message of
+                                                  * the calling thread's last failed call that takes no context */
 
 /* Register an architecture shared by many experts (paper Section 4.5: experts of the same architecture are
  * profiled once).  All architectures of a context take the same input shape and dtype.  The descriptor is copied.
@@ -218,6 +219,21 @@ int coe_debug_conv(coe_ctx* ctx, int32_t dtype, const void* x, const void* w, co
 /* Stand-alone regroup on a host key vector (uploaded, regrouped on the device, read back): same outputs as above. */
 int coe_debug_regroup(coe_ctx* ctx, int32_t n, const int32_t* cur, int32_t n_experts, int32_t* cnt, int32_t* off,
                       int32_t* perm, int32_t* inv);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): the index part of request arranging, as coe_debug_regroup computes it, on DEVICE arrays and without a context.
+ * cur [n] (expert id in [0, n_experts) = queued, anything else = not queued), cnt [n_experts], off [n_experts + 1],
+ * perm [n], inv [n] are device pointers owned by the caller; the kernels are enqueued on `stream` (a hipStream_t, NULL = the
+ * default stream) of the current device and the call returns without waiting.  The per-workgroup histograms, which the other
+ * entry points keep in a buffer the context allocates, live in a static device array of COE_STATIC_SCRATCH_BYTES that every
+ * GPU the library has run this call on holds until the process ends.  The call allocates nothing, frees nothing and
+ * synchronises nothing.  All calls on one GPU share that array: calls that overlap there (two streams, two threads) race;
+ * calls on one stream are ordered and need no clearing in between.
+ * Errors: COE_ERANGE when ceil(n / 256) * n_experts * 4 exceeds COE_STATIC_SCRATCH_BYTES, COE_EINVAL (null pointer, n < 0,
+ * n_experts outside 1..2048), COE_EDEVICE (a HIP call failed); coe_last_error(NULL) holds the message (per thread). */
+#define COE_STATIC_SCRATCH_BYTES (4u << 20)
+int coe_regroup_static(int32_t n, const int32_t* cur, int32_t n_experts, int32_t* cnt, int32_t* off, int32_t* perm,
+                       int32_t* inv, void* stream);
 
 /* Launch sequences of the last step in launch order: the first expert of each, its predicted cost and the executor it ran
  * on.  Writes at most cap entries (arrays nullable); *n_units receives the total. */

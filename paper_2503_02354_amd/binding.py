@@ -25,6 +25,7 @@ EXPORTS = [
     "coe_debug_last_regroup", "coe_debug_switch_log", "coe_debug_resident", "coe_debug_forward", "coe_debug_layer_output", "coe_debug_regroup", "coe_debug_conv",
     "coe_profile_read", "coe_profile_issued", "coe_validate_graph", "coe_policy_create", "coe_policy_destroy", "coe_policy_init_fill",
     "coe_policy_stage", "coe_policy_resident", "coe_policy_set_eviction", "coe_policy_set_in_use_depth", "coe_set_arranging", "coe_arrange_defer", "coe_set_latency_model", "coe_assign_executors", "coe_debug_last_assignment",
+    "coe_regroup_static",
 ]
 
 
@@ -90,6 +91,7 @@ def _load():
     L.coe_assign_executors.argtypes = [i32, vp, i32, vp]
     L.coe_debug_last_assignment.argtypes = [vp, i32, vp, vp, vp, C.POINTER(i32)]
     L.coe_arrange_defer.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp]
+    L.coe_regroup_static.argtypes = [i32, vp, i32, vp, vp, vp, vp, vp]
     return L
 
 
@@ -108,6 +110,14 @@ def _ptr(a):
     if isinstance(a, np.ndarray):
         return a.ctypes.data_as(C.c_void_p)
     return C.c_void_p(int(a))
+
+
+def coe_regroup_static(n: int, cur: int, n_experts: int, cnt: int, off: int, perm: int, inv: int, stream: int = 0) -> None:
+    """Regroup on device arrays (integer device addresses) without any allocation; enqueued on `stream`."""
+    rc = lib.coe_regroup_static(n, _ptr(cur or None), n_experts, _ptr(cnt or None), _ptr(off or None), _ptr(perm or None),
+                                _ptr(inv or None), C.c_void_p(stream or None))
+    if rc < 0:
+        raise CoEError(rc, lib.coe_last_error(None).decode())
 
 
 # ---- host-only functions --------------------------------------------------------------------------------------

@@ -677,7 +677,29 @@ int do_init_fill(coe_ctx* c, coe_step_stats* st)
 // =====================================================================================================================
 extern "C" {
 
-const char* coe_last_error(const coe_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+static_assert(COE_STATIC_SCRATCH_BYTES == sizeof(int32_t) * (size_t)coe::k::kRegroupStaticInts, "header and kernel agree on the scratch size");
+
+// message of the last failed call that takes no context (per thread)
+static thread_local std::string g_err;
+
+const char* coe_last_error(const coe_ctx* ctx) { return ctx ? ctx->err.c_str() : g_err.c_str(); }
+
+int coe_regroup_static(int32_t n, const int32_t* cur, int32_t n_experts, int32_t* cnt, int32_t* off, int32_t* perm, int32_t* inv,
+                       void* stream)
+{
+    auto bad = [](int code, const std::string& msg) { g_err = msg; return code; };
+    if (n < 0 || (n > 0 && (!cur || !perm || !inv)) || !cnt || !off) return bad(COE_EINVAL, "coe_regroup_static: null or negative argument");
+    if (n_experts <= 0 || n_experts > coe::k::kRegroupMaxExperts)
+        return bad(COE_EINVAL, "coe_regroup_static: n_experts must be in 1.." + std::to_string(coe::k::kRegroupMaxExperts));
+    const long long nblocks = ((long long)n + coe::k::kRegroupTile - 1) / coe::k::kRegroupTile;
+    if (nblocks * n_experts > (long long)coe::k::kRegroupStaticInts)
+        return bad(COE_ERANGE, "coe_regroup_static: ceil(n / " + std::to_string(coe::k::kRegroupTile) + ") * n_experts = " +
+                                   std::to_string(nblocks * n_experts) + " exceeds the static scratch of " +
+                                   std::to_string(coe::k::kRegroupStaticInts) + " entries (COE_STATIC_SCRATCH_BYTES)");
+    hipError_t e = coe::k::regroup_index_static(cur, n, n_experts, cnt, off, perm, inv, (hipStream_t)stream);
+    if (e != hipSuccess) return bad(COE_EDEVICE, std::string("coe_regroup_static: ") + hipGetErrorString(e));
+    return COE_OK;
+}
 
 int coe_create(const coe_config* cfg, coe_ctx** out)
 {

@@ -32,6 +32,13 @@ struct RouteArgs {
 hipError_t regroup_index(const int32_t* cur, int32_t n, int32_t E, int32_t* cnt, int32_t* off, int32_t* perm,
                          int32_t* inv, int32_t* blockhist, hipStream_t stream);
 
+// The same with the histogram scratch in a static device array of kRegroupStaticInts int32 (no allocation anywhere on the
+// path): hipErrorInvalidValue when ceil(n / kRegroupTile) * E exceeds it.  Runs on the current device; calls on one device
+// share the array, so calls that overlap there race.
+constexpr int kRegroupStaticInts = 1 << 20;
+hipError_t regroup_index_static(const int32_t* cur, int32_t n, int32_t E, int32_t* cnt, int32_t* off, int32_t* perm,
+                                int32_t* inv, hipStream_t stream);
+
 // Request arranging, activation part: dst row i = src row perm[i]; rows of row_bytes (multiple of 4) bytes.
 // heads[e] = perm[off[e]] (the oldest queued request of expert e: the regroup is stable) or -1 for an empty group
 hipError_t group_heads(const int32_t* perm, const int32_t* off, const int32_t* cnt, int32_t E, int32_t* heads,

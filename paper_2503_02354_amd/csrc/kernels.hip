@@ -2,6 +2,8 @@
 // Wavefronts are 64 lanes wide throughout.
 #include <hip/hip_runtime.h>
 
+#include <mutex>
+
 #include "kernels.h"
 
 namespace coe {
@@ -485,6 +487,47 @@ hipError_t regroup_index(const int32_t* cur, int32_t n, int32_t E, int32_t* cnt,
         hipLaunchKernelGGL(regroup_scatter_kernel, dim3(nblocks), dim3(kRegroupTile),
                            sizeof(int32_t) * E * (kRegroupTile / kWave), stream, cur, n, E, blockhist, off, perm, inv);
     return hipGetLastError();
+}
+
+// -------------------------------------------------------------------------------------------------------------
+// regroup for callers that cannot allocate: the per-workgroup histograms live in a static device array instead of a
+// buffer the caller or a context owns.  Every GPU the library runs on holds its own copy of the array (4 MiB) until the
+// process ends; in host code the array's name is only a handle for hipGetSymbolAddress, the address a kernel can use is
+// looked up once per device and kept.
+// -------------------------------------------------------------------------------------------------------------
+static __device__ __align__(256) int32_t scratch[kRegroupStaticInts];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+int32_t* g_scratch_ptr[kMaxDevices] = {nullptr};
+}  // namespace
+
+hipError_t regroup_index_static(const int32_t* cur, int32_t n, int32_t E, int32_t* cnt, int32_t* off, int32_t* perm,
+                                int32_t* inv, hipStream_t stream)
+{
+    if (n < 0 || E <= 0 || E > kRegroupMaxExperts) return hipErrorInvalidValue;
+    const long long nblocks = ((long long)n + kRegroupTile - 1) / kRegroupTile;
+    if (nblocks * E > (long long)kRegroupStaticInts) return hipErrorInvalidValue;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    int32_t* ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            void* p = nullptr;
+            e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));      // this device's copy of the array
+            if (e != hipSuccess) return e;
+            if (!p) return hipErrorInvalidSymbol;
+            g_scratch_ptr[dev] = (int32_t*)p;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    // every histogram entry the scan and the scatter read is written by the count kernel of the same call: nothing has to
+    // start at zero
+    return regroup_index(cur, n, E, cnt, off, perm, inv, ptr, stream);
 }
 
 __global__ void group_heads_kernel(const int32_t* __restrict__ perm, const int32_t* __restrict__ off,
