@@ -195,8 +195,10 @@ void orc_layernorm(const float* x, int T, int C, const float* gamma, const float
 }
 
 /* qkv[t] = [q(D) | k(D) | v(D)], head h owns channels [h*dh, (h+1)*dh).
- * s_ij = q_i.k_j / sqrt(dh); e_ij = exp(s_ij - max_j s_ij); the weights that multiply v are e_ij in storage
- * precision (they are the matrix-core operand on the GPU); the normaliser is the sum of the unrounded e_ij. */
+ * Scaled dot-product attention as it is defined: s_ij = q_i.k_j / sqrt(dh); p_ij = exp(s_ij - max_j s_ij) / sum_j exp(...)
+ * (the softmax, fp64); the probabilities are a tensor of their own and take the storage precision of the expert like every
+ * other tensor (bf16 experts: one cast to fp32, one round to bf16 per probability); out_i = sum_j p_ij v_j, accumulated in
+ * fp64 over the rounded probabilities and stored in storage precision.  Nothing is divided after the rounding. */
 void orc_attention(const float* qkv, int T, int D, int heads, int dtype, float* y)
 {
     int dh = D / heads;
@@ -214,11 +216,12 @@ void orc_attention(const float* qkv, int T, int D, int heads, int dtype, float* 
                 if (s[j] > m) m = s[j];
             }
             double l = 0.0;
-            for (int j = 0; j < T; ++j) { double e = exp(s[j] - m); l += e; s[j] = (double)store_val(e, dtype); }
+            for (int j = 0; j < T; ++j) { s[j] = exp(s[j] - m); l += s[j]; }
+            for (int j = 0; j < T; ++j) s[j] = (double)store_val(s[j] / l, dtype);
             for (int d = 0; d < dh; ++d) {
                 double a = 0.0;
                 for (int j = 0; j < T; ++j) a += s[j] * (double)qkv[(size_t)j * 3 * D + 2 * D + h * dh + d];
-                y[(size_t)i * D + h * dh + d] = store_val(a / l, dtype);
+                y[(size_t)i * D + h * dh + d] = store_val(a, dtype);
             }
         }
     free(s);
@@ -447,16 +450,24 @@ int orc_regroup(const int32_t* cur, int n, int E, int32_t* cnt, int32_t* off, in
     return m;
 }
 
-/* request splitting: each non-empty group, in the given expert order, is cut into consecutive chunks of at most
- * max_batch requests.  chunks[i] = {expert, start in perm, count}.  Returns the number of chunks (<= cap) or -1. */
+/* Request splitting (Section 4.2): no batch may exceed the maximum executable batch size.  The paper fixes only that bound;
+ * the reading taken here: a group of n requests becomes the FEWEST batches the bound allows, ceil(n / max_batch), and those
+ * are made as even as consecutive cutting allows - every batch holds ceil(n / batches) requests and the last one the rest -
+ * because a short last batch is the least efficient one (latency per request falls with the batch size, Section 4.5).
+ * Groups are taken in the given expert order.  chunks[i] = {expert, start in perm, count}.  Returns the number of chunks
+ * (<= cap) or -1. */
 int orc_split(const int32_t* off, int n_order, const int32_t* order, int max_batch, int32_t* chunks, int cap)
 {
     int n = 0;
     for (int i = 0; i < n_order; ++i) {
         int e = order[i];
-        for (int s = off[e]; s < off[e + 1]; s += max_batch) {
+        int cnt = off[e + 1] - off[e];
+        if (cnt <= 0) continue;
+        int batches = (cnt + max_batch - 1) / max_batch;
+        int size = (cnt + batches - 1) / batches;
+        for (int s = off[e]; s < off[e + 1]; s += size) {
             if (n >= cap) return -1;
-            int c = off[e + 1] - s; if (c > max_batch) c = max_batch;
+            int c = off[e + 1] - s; if (c > size) c = size;
             chunks[3 * n] = e; chunks[3 * n + 1] = s; chunks[3 * n + 2] = c; ++n;
         }
     }

@@ -248,6 +248,28 @@ def test_attention_closed_forms(oracle):
     np.testing.assert_allclose(y2[:, dh:], y[:, dh:], rtol=1e-6)
 
 
+def test_attention_bf16_rounds_the_softmax_probabilities(oracle):
+    """Hand-worked case, bf16 expert, three tokens, one head of width 1 (scores = q k, no scaling).
+    Keys (0, 0, 1), values (1, 3, -2); queries 1, 0, 1.
+    Query 1: scores (0, 0, 1), minus the maximum (-1, -1, 0), exponentials (1/e, 1/e, 1), their sum 1.7357588823...,
+    probabilities (0.2119415576..., 0.2119415576..., 0.5761168847...).  As bf16 (8 significant bits):
+    0.2119415576 = 1.69553 x 2^-3 -> 217/128 x 2^-3 = 0.2119140625; 0.5761168847 = 1.15223 x 2^-1 -> 147/256 = 0.57421875.
+    Output = 0.2119140625 x (1 + 3) + 0.57421875 x (-2) = -0.30078125, which is a bf16 value (-154/512).
+    Rounding the exponentials instead and dividing by their unrounded sum afterwards would give -0.306640625, rounding
+    nothing before the sum -0.3046875: the three readings differ in the stored bits.
+    Query 0: uniform probabilities 1/3 -> bf16 171/512 = 0.333984375; output 0.333984375 x (1 + 3 - 2) = 0.66796875."""
+    qkv = np.array([[1, 0, 1], [0, 0, 3], [1, 1, -2]], np.float32)
+    y = oracle.attention(qkv, 1, dtype=1).reshape(-1)
+    assert y.tolist() == [-0.30078125, 0.66796875, -0.30078125]
+    assert -0.30078125 != -0.306640625 != -0.3046875
+    # the fp32 expert keeps the probabilities unrounded: -0.30466... to fp32 precision
+    y32 = oracle.attention(qkv, 1, dtype=0).reshape(-1)
+    e = math.exp(-1.0)
+    want = (e * 1 + e * 3 - 2.0) / (1 + 2 * e)
+    np.testing.assert_allclose(y32[[0, 2]], want, rtol=1e-6)
+    assert abs(float(y32[0]) - (-0.30078125)) > 1e-3
+
+
 def test_gelu_via_1x1_conv(oracle):
     # act=2 on an identity 1x1 conv exposes the activation: GELU(0)=0, GELU(x)->x for large x, GELU(x)-GELU(-x)=x
     xs = np.array([0.0, 1.0, -1.0, 6.0, -6.0, 0.5, -0.5], np.float32)

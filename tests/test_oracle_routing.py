@@ -43,7 +43,11 @@ def test_regroup_invariants_large(oracle):
 def test_split_covers_groups(oracle):
     off = np.array([0, 5, 5, 12, 13], np.int32)
     ch = oracle.split(off, [2, 0, 3, 1], 4)
-    assert ch.tolist() == [[2, 5, 4], [2, 9, 3], [0, 0, 4], [0, 4, 1], [3, 12, 1]]
+    # by hand: 7 requests, at most 4 per batch -> 2 batches of ceil(7/2) = 4 and the rest; 5 requests -> 2 batches of 3 and 2
+    assert ch.tolist() == [[2, 5, 4], [2, 9, 3], [0, 0, 3], [0, 3, 2], [3, 12, 1]]
+    # fewest batches, as even as consecutive cutting allows: 9 -> 3+3+3 (not 4+4+1), 10 -> 4+4+2, 8 -> 4+4, 4 -> 4, 1 -> 1
+    off2 = np.array([0, 9, 19, 27, 31, 32], np.int32)
+    assert oracle.split(off2, [0, 1, 2, 3, 4], 4)[:, 2].tolist() == [3, 3, 3, 4, 4, 2, 4, 4, 4, 1]
     rng = np.random.default_rng(1)
     cnt = rng.integers(0, 40, 20); off = np.concatenate([[0], np.cumsum(cnt)]).astype(np.int32)
     for mb in (1, 7, 64):
