@@ -116,8 +116,8 @@ __global__ __launch_bounds__(256) void layernorm_kernel(const uint32_t* __restri
 // second operand of the next product O^T = V^T P^T (keys may be visited in any order as long as V^T uses the same
 // one), so the probabilities never leave registers.  A lane ends with 4 consecutive head channels of its query per
 // accumulator quad and stores 8 bytes at a time.
-// Numerics: scores in fp32, e = exp(s - max), normaliser = sum of the unrounded e, weights = bf16(e), output =
-// (sum_j bf16(e_j) v_j) / normaliser, rounded to bf16.
+// Numerics: scores in fp32, e = exp(s - max), probabilities p = e / sum(e) rounded to bf16 (they are a tensor of their
+// own in storage precision), output = sum_j p_j v_j accumulated in fp32 and rounded to bf16.
 constexpr int kDh = 64;
 constexpr int kMaxKeyBlocks = 7;
 constexpr int kKStride = kDh + 8;                 // K tile row stride (elements): conflict-free 16-byte reads
@@ -199,12 +199,20 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
                     // 2^x on the transcendental unit (one instruction; exp(s - max) = 2^((s - max) / ln 2))
                     float e0 = __builtin_amdgcn_exp2f(sc[kb][v] - m), e1 = __builtin_amdgcn_exp2f(sc[kb][v + 1] - m);
                     lsum += e0 + e1;
-                    pw[kb][v >> 1] = pack_bf16(e0, e1);
+                    sc[kb][v] = e0;
+                    sc[kb][v + 1] = e1;
                 }
             }
         }
         lsum += __shfl_xor(lsum, 32, 64);
         const float inv = 1.f / lsum;
+#pragma unroll
+        for (int kb = 0; kb < kMaxKeyBlocks; ++kb) {
+            if (kb < TB) {
+#pragma unroll
+                for (int v = 0; v < 16; v += 2) pw[kb][v >> 1] = pack_bf16(sc[kb][v] * inv, sc[kb][v + 1] * inv);
+            }
+        }
 
         f32x16 oacc[kDh / 32];
 #pragma unroll
@@ -236,8 +244,8 @@ __global__ __launch_bounds__(256) void attention_kernel(const uint16_t* __restri
 #pragma unroll
                 for (int gq = 0; gq < 4; ++gq) {
                     uint2 o;
-                    o.x = pack_bf16(oacc[db][4 * gq] * inv, oacc[db][4 * gq + 1] * inv);
-                    o.y = pack_bf16(oacc[db][4 * gq + 2] * inv, oacc[db][4 * gq + 3] * inv);
+                    o.x = pack_bf16(oacc[db][4 * gq], oacc[db][4 * gq + 1]);
+                    o.y = pack_bf16(oacc[db][4 * gq + 2], oacc[db][4 * gq + 3]);
                     *(uint2*)(op + db * 32 + 8 * gq + 4 * half) = o;
                 }
         }
