@@ -83,7 +83,9 @@ typedef struct {
     int32_t cache_cap_experts; /* device expert cache: at most this many resident experts (0 = no limit) */
     int32_t profile;           /* k > 0: time every k-th launch of each kernel class with events (1 = all; see
                                 * coe_profile_read); 0: no events */
-    int64_t cache_cap_bytes;   /* and at most this many bytes of expert weights (0 = no limit) */
+    int64_t cache_cap_bytes;   /* and at most this many bytes of expert weights (0 = no limit).  The device memory behind the
+                                * cache is one arena, allocated when the dependency graph is set: per distinct blob size as
+                                * many slots as the caps let be resident at once (without caps: one per expert) */
     void* compute_stream;      /* borrowed hipStream_t for kernels, or NULL: the library creates one */
     void* copy_stream;         /* borrowed hipStream_t for expert switches, or NULL: the library creates one */
     int32_t group_small;       /* request arranging leaves many groups of a few requests: groups of at most this many
@@ -117,6 +119,10 @@ typedef struct {
     int32_t n_deferred_groups;   /* groups left queued by the arranging window (see coe_set_arranging) */
     int32_t n_deferred_requests; /* their requests; these are counted in n_pending but ran no stage in this step */
     int32_t n_executors_used;    /* executors that ran at least one launch sequence in this step */
+    int32_t n_device_allocs;     /* device allocations made during this step: 0, because the expert arena (one slot class per
+                                  * blob size), the request store and the activation workspaces are allocated when the
+                                  * dependency graph is set (paper Section 5.5: expert management must stay a negligible
+                                  * share of the time) */
 } coe_step_stats;
 
 /* Create / destroy a context.  coe_create fails with COE_EDEVICE when no GPU is usable. */
@@ -142,13 +148,14 @@ int coe_register_expert(coe_ctx* ctx, int32_t expert_id, int32_t arch_id, const 
 /* Routing rules (paper Sections 2.1, 4.5 "Routing rules"): CSR successor lists.  Expert e routes on the argmax
  * over its first n_route = succ_off[e+1]-succ_off[e] logits (lowest index wins ties); the request goes to
  * succ[succ_off[e]+argmax], or is final when that entry is -1 or n_route is 0.  Every stage's expert consumes the
- * request's original input.  Must be called after all n_experts experts are registered.
- * Errors: COE_EGRAPH (id out of range, cycle, n_route > classes of e), COE_ESTATE (experts missing). */
+ * request's original input.  Must be called after all n_experts experts are registered.  Allocates every device buffer the
+ * step path uses (expert arena, request store, activation workspaces): coe_submit and coe_step allocate nothing.
+ * Errors: COE_EGRAPH (id out of range, cycle, n_route > classes of e), COE_ESTATE (experts missing), COE_ENOMEM. */
 int coe_set_dependency_graph(coe_ctx* ctx, int32_t n_experts, const int32_t* succ_off, const int32_t* succ);
 
 /* Append n requests.  inputs: [n][in_h][in_w][in_c] in the context dtype, a device pointer if on_device != 0,
  * else a host pointer; copied into the request store (stream-ordered; a device source must stay valid until
- * coe_sync or coe_collect).  first_expert: [n] host array of preliminary experts, or NULL = expert 0.
+ * coe_sync or coe_collect, and the call returns without waiting; a host source has been read when the call returns).  first_expert: [n] host array of preliminary experts, or NULL = expert 0.
  * *first_request_id (nullable) receives the id of the first request; ids are consecutive.
  * Errors: COE_ERANGE when the store is full, COE_ESTATE before the graph is set. */
 int coe_submit(coe_ctx* ctx, int32_t n, const void* inputs, int on_device, const int32_t* first_expert,
@@ -220,6 +227,12 @@ int coe_debug_conv(coe_ctx* ctx, int32_t dtype, const void* x, const void* w, co
 int coe_debug_regroup(coe_ctx* ctx, int32_t n, const int32_t* cur, int32_t n_experts, int32_t* cnt, int32_t* off,
                       int32_t* perm, int32_t* inv);
 
+/* Batches of the last step after request splitting (paper Section 4.2 "Request splitting"), in launch order: words
+ * {expert, first row of the batch in the regrouped order, requests} per batch.  A group of n requests whose architecture takes
+ * at most m per launch sequence is cut into ceil(n / m) batches of ceil(n / ceil(n / m)) requests, the last one holding the
+ * rest.  Writes at most cap batches; *n_chunks receives the total. */
+int coe_debug_last_chunks(coe_ctx* ctx, int32_t cap, int32_t* chunks, int32_t* n_chunks);
+
 /* For callers that cannot allocate device memory (code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc): the index part of request arranging, as coe_debug_regroup computes it, on DEVICE arrays and without a context.
  * cur [n] (expert id in [0, n_experts) = queued, anything else = not queued), cnt [n_experts], off [n_experts + 1],
@@ -263,6 +276,43 @@ int coe_arrange_defer(int32_t n_experts, const int32_t* count, const int32_t* ag
 /* The assignment rule on its own: unit u (in order) goes to the executor with the least cost assigned so far, the
  * lowest-numbered among equals; executor[u] receives it. */
 int coe_assign_executors(int32_t n_units, const int64_t* cost_ns, int32_t n_executors, int32_t* executor);
+
+/* ---- offline profiler arithmetic (paper Section 4.5 "Expert performance metrics", Section 4.4 "Efficient Memory Management") ----
+ * The profiler measures through the calls above (coe_debug_forward over batch sizes, switches with cfg.profile) and hands
+ * the numbers to these host-only functions.
+ * coe_profiler_fit_latency: least-squares line latency = K n + B through n >= 2 (batch size, latency) points (Section 4.2:
+ * a batch of one expert scales linearly with the number of requests).  COE_EINVAL when all batch sizes are equal.
+ * coe_profiler_max_batch: the maximum batch size of Section 4.5 (average latency per request stops falling): the smallest
+ * measured batch whose latency per request is within `tol` (relative) of the best one measured.
+ * coe_profiler_arranging_window: thresholds for coe_set_arranging from the model: a group of n requests spends the share
+ * K n / (K n + B [+ load]) on its requests; the smallest n for which that share reaches `efficiency` (in [0, 1)) with the
+ * expert on the device, and with the load of a missing expert added. */
+int coe_profiler_fit_latency(int32_t n, const int32_t* batch, const double* latency_us, double* k_us, double* b_us);
+int coe_profiler_max_batch(int32_t n, const int32_t* batch, const double* latency_us, double tol, int32_t* max_batch);
+int coe_profiler_arranging_window(double k_us, double b_us, double load_us, double efficiency, int32_t* min_group_resident,
+                                  int32_t* min_group_missing);
+
+/* Decay-window search for the number of experts to keep on the device when their memory competes with the memory of large
+ * batches (Section 4.4, "Memory allocation under sufficient computation performance").  The window slides along the number
+ * of experts (sorted by descending usage probability): window k covers [sum of the earlier sizes, + size_k) with
+ * size_k = initial_window * decay^k and decay = 1 - initial_window / 100 (Eq. 1).  For every window the caller loads as many
+ * experts as the window's upper bound (rounded up, at most n_experts_total), runs sample requests and appends the measured
+ * throughput.  Once `fit_points` (>= 2) earlier values exist, a least-squares line through the earlier values over their
+ * index (Eq. 2) predicts the newest one; the search stops at the first window whose value falls short of the prediction by
+ * more than error_margin, relative (Eq. 3), or when a window has loaded every expert.  The number of experts to keep is
+ * then any value in [n_low, n_high] of the final window.  The function is stateless: call it with the throughputs measured
+ * so far (n_measured = 0 first); status says whether to measure again (at n_next experts) or which way the search ended. */
+enum { COE_WINDOW_MEASURE = 0, COE_WINDOW_SHORTFALL = 1, COE_WINDOW_END = 2 };
+typedef struct {
+    int32_t status;        /* COE_WINDOW_* */
+    int32_t n_next;        /* COE_WINDOW_MEASURE: experts to load for the next measurement */
+    double window_low;     /* bounds, on the expert axis, of the window measured last (of the first window when n_measured = 0) */
+    double window_high;
+    int32_t n_low, n_high; /* the same as whole experts (rounded up, clipped to 1..n_experts_total) */
+    double linear_error;   /* Eq. 3's left side for the newest value (0 while fewer than fit_points earlier values exist) */
+} coe_window_state;
+int coe_profiler_window_step(int32_t n_experts_total, double initial_window, double error_margin, int32_t fit_points,
+                             int32_t n_measured, const double* throughput, coe_window_state* out);
 
 /* The expert-cache policy on its own (paper Section 4.1 initial fill, Section 4.3 two-stage eviction).
  * coe_policy_stage: has_group[E] marks experts with pending requests; order[E] receives the execution order

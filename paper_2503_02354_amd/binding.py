@@ -25,7 +25,8 @@ EXPORTS = [
     "coe_debug_last_regroup", "coe_debug_switch_log", "coe_debug_resident", "coe_debug_forward", "coe_debug_layer_output", "coe_debug_regroup", "coe_debug_conv",
     "coe_profile_read", "coe_profile_issued", "coe_validate_graph", "coe_policy_create", "coe_policy_destroy", "coe_policy_init_fill",
     "coe_policy_stage", "coe_policy_resident", "coe_policy_set_eviction", "coe_policy_set_in_use_depth", "coe_set_arranging", "coe_arrange_defer", "coe_set_latency_model", "coe_assign_executors", "coe_debug_last_assignment",
-    "coe_regroup_static",
+    "coe_regroup_static", "coe_debug_last_chunks",
+    "coe_profiler_fit_latency", "coe_profiler_max_batch", "coe_profiler_arranging_window", "coe_profiler_window_step",
 ]
 
 
@@ -48,7 +49,16 @@ class coe_step_stats(C.Structure):
     _fields_ = [("n_pending", C.c_int32), ("n_groups", C.c_int32), ("n_chunks", C.c_int32), ("n_hits", C.c_int32),
                 ("n_misses", C.c_int32), ("n_evictions", C.c_int32), ("bytes_switched", C.c_int64),
                 ("host_plan_us", C.c_double), ("n_grouped", C.c_int32), ("n_group_sets", C.c_int32),
-                ("n_deferred_groups", C.c_int32), ("n_deferred_requests", C.c_int32), ("n_executors_used", C.c_int32)]
+                ("n_deferred_groups", C.c_int32), ("n_deferred_requests", C.c_int32), ("n_executors_used", C.c_int32),
+                ("n_device_allocs", C.c_int32)]
+
+
+class coe_window_state(C.Structure):
+    _fields_ = [("status", C.c_int32), ("n_next", C.c_int32), ("window_low", C.c_double), ("window_high", C.c_double),
+                ("n_low", C.c_int32), ("n_high", C.c_int32), ("linear_error", C.c_double)]
+
+
+COE_WINDOW_MEASURE, COE_WINDOW_SHORTFALL, COE_WINDOW_END = 0, 1, 2
 
 
 def _load():
@@ -91,6 +101,11 @@ def _load():
     L.coe_assign_executors.argtypes = [i32, vp, i32, vp]
     L.coe_debug_last_assignment.argtypes = [vp, i32, vp, vp, vp, C.POINTER(i32)]
     L.coe_arrange_defer.argtypes = [i32, vp, vp, vp, vp, vp, vp, vp]
+    L.coe_debug_last_chunks.argtypes = [vp, i32, vp, C.POINTER(i32)]
+    L.coe_profiler_fit_latency.argtypes = [i32, vp, vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    L.coe_profiler_max_batch.argtypes = [i32, vp, vp, C.c_double, C.POINTER(i32)]
+    L.coe_profiler_arranging_window.argtypes = [C.c_double, C.c_double, C.c_double, C.c_double, C.POINTER(i32), C.POINTER(i32)]
+    L.coe_profiler_window_step.argtypes = [i32, C.c_double, C.c_double, i32, i32, vp, C.POINTER(coe_window_state)]
     L.coe_regroup_static.argtypes = [i32, vp, i32, vp, vp, vp, vp, vp]
     return L
 
@@ -118,6 +133,44 @@ def coe_regroup_static(n: int, cur: int, n_experts: int, cnt: int, off: int, per
                                 _ptr(inv or None), C.c_void_p(stream or None))
     if rc < 0:
         raise CoEError(rc, lib.coe_last_error(None).decode())
+
+
+def coe_profiler_fit_latency(batch, latency_us) -> Tuple[float, float]:
+    b = np.ascontiguousarray(batch, np.int32); t = np.ascontiguousarray(latency_us, np.float64)
+    assert b.shape == t.shape and b.ndim == 1
+    k, c = C.c_double(0), C.c_double(0)
+    rc = lib.coe_profiler_fit_latency(b.shape[0], _ptr(b), _ptr(t), C.byref(k), C.byref(c))
+    if rc < 0:
+        raise CoEError(rc, "coe_profiler_fit_latency")
+    return k.value, c.value
+
+
+def coe_profiler_max_batch(batch, latency_us, tol: float = 0.05) -> int:
+    b = np.ascontiguousarray(batch, np.int32); t = np.ascontiguousarray(latency_us, np.float64)
+    assert b.shape == t.shape and b.ndim == 1
+    out = C.c_int32(0)
+    rc = lib.coe_profiler_max_batch(b.shape[0], _ptr(b), _ptr(t), tol, C.byref(out))
+    if rc < 0:
+        raise CoEError(rc, "coe_profiler_max_batch")
+    return out.value
+
+
+def coe_profiler_arranging_window(k_us: float, b_us: float, load_us: float, efficiency: float) -> Tuple[int, int]:
+    a, b = C.c_int32(0), C.c_int32(0)
+    rc = lib.coe_profiler_arranging_window(k_us, b_us, load_us, efficiency, C.byref(a), C.byref(b))
+    if rc < 0:
+        raise CoEError(rc, "coe_profiler_arranging_window")
+    return a.value, b.value
+
+
+def coe_profiler_window_step(n_experts_total: int, initial_window: float, error_margin: float, fit_points: int, throughput) -> coe_window_state:
+    t = np.ascontiguousarray(throughput, np.float64)
+    st = coe_window_state()
+    rc = lib.coe_profiler_window_step(n_experts_total, initial_window, error_margin, fit_points, t.shape[0],
+                                      _ptr(t) if t.shape[0] else None, C.byref(st))
+    if rc < 0:
+        raise CoEError(rc, "coe_profiler_window_step")
+    return st
 
 
 # ---- host-only functions --------------------------------------------------------------------------------------
@@ -289,6 +342,12 @@ class Context:
         self._chk(lib.coe_debug_last_assignment(self._h, cap, _ptr(fe), _ptr(cost), _ptr(ex), C.byref(n)))
         m = min(n.value, cap)
         return fe[:m], cost[:m], ex[:m]
+
+    def coe_debug_last_chunks(self, cap: int = 65536) -> np.ndarray:
+        """[n][3] int32: {expert, first row in the regrouped order, requests} of every batch of the last step."""
+        out = np.zeros((cap, 3), np.int32); n = C.c_int32(0)
+        self._chk(lib.coe_debug_last_chunks(self._h, cap, _ptr(out), C.byref(n)))
+        return out[:min(n.value, cap)]
 
     def coe_collect(self, cap: int):
         ids = np.zeros(cap, np.int64); logits = np.zeros((cap, max(self.max_classes, 1)), np.float32)

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcoe.so")
-SOURCES = ["kernels.hip", "conv_mfma.hip", "conv_stem.hip", "vit.hip", "coe.cpp", "policy.cpp"]
+SOURCES = ["kernels.hip", "conv_mfma.hip", "conv_stem.hip", "vit.hip", "coe.cpp", "policy.cpp", "profiler.cpp"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 # packed fp32 instructions are kept off for every device compile
 DEVICE_FLAGS = ["--offload-arch=gfx950", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -49,11 +49,15 @@ struct ArchPlan {
     size_t in_bytes() const { return (size_t)in_h * in_w * in_c * elem(); }
 };
 
+// One slot of the expert arena.  The arena is a single device allocation made when the dependency graph is set; it is cut
+// into slots of one size class per distinct blob size (experts of one architecture share a class), as many per class as the
+// cache caps allow to be resident at once, so a switch never allocates, frees or waits for the device.
 struct DevBuf {
     void* p = nullptr;
     size_t bytes = 0;
-    hipEvent_t last_use = nullptr;   // recorded on the compute stream after the last kernel that read p
+    hipEvent_t last_use = nullptr;   // recorded on the stream of the last kernel that read p
     bool used = false;
+    int32_t cls = 0;                 // size class
 };
 
 struct Expert {
@@ -62,7 +66,8 @@ struct Expert {
     float prob = 0.f;
     void* host = nullptr;            // pinned copy of the blob
     size_t nbytes = 0;
-    DevBuf* buf = nullptr;           // device copy when resident
+    int32_t cls = 0;                 // size class of its blob in the expert arena
+    DevBuf* buf = nullptr;           // arena slot that holds the device copy when resident
     hipEvent_t loaded = nullptr;     // recorded on the copy stream after the switch
     bool load_pending = false;       // compute stream has not yet waited for `loaded`
 };
@@ -105,8 +110,10 @@ struct coe_ctx {
     std::unique_ptr<coe::Policy> policy;
     bool filled = false;
     std::vector<int32_t> switch_log;
-    std::vector<DevBuf*> free_bufs;
-    std::vector<DevBuf*> all_bufs;
+    void* arena = nullptr;                          // all expert slots
+    std::vector<DevBuf> slots;
+    std::vector<std::vector<DevBuf*>> free_slots;   // per size class, oldest release first
+    int64_t device_allocs = 0;                      // hipMalloc calls made by this context so far
 
     // request store
     int32_t n_live = 0, n_collected = 0;
@@ -122,6 +129,7 @@ struct coe_ctx {
     // regroup
     int32_t *d_cnt = nullptr, *d_off = nullptr, *d_perm = nullptr, *d_inv = nullptr, *d_blockhist = nullptr;
     int32_t* h_cnt = nullptr;        // pinned
+    int32_t* h_first = nullptr;      // pinned, one entry per request slot: staging of the first experts of a submit
     int32_t last_pending = 0, last_live = 0, last_E = 0;
     std::vector<int32_t> submit_step;   // per request slot: number of the first step that sees the request
     int32_t step_no = 0;
@@ -132,6 +140,7 @@ struct coe_ctx {
     hipEvent_t ev_ready = nullptr;      // recorded on the compute stream when a step's regrouped inputs are ready
     struct Unit { int32_t expert; int64_t cost_ns; int32_t lane; };
     std::vector<Unit> last_units;       // launch sequences of the last step: first expert, predicted cost, executor
+    std::vector<int32_t> last_chunks;   // batches of the last step after request splitting: {expert, first row, count} each
 
     // profiling
     ProfClass prof[COE_K_COUNT];
@@ -360,19 +369,25 @@ int plan_arch(coe_ctx* c, const coe_arch_desc* d, ArchPlan& a)
 }
 
 // ---- device memory helpers -----------------------------------------------------------------------------------------
+hipError_t dev_malloc(coe_ctx* c, void** p, size_t bytes)
+{
+    ++c->device_allocs;
+    return hipMalloc(p, bytes);
+}
+
 int ensure_store(coe_ctx* c)
 {
     if (c->archs.empty()) return fail(c, COE_ESTATE, "no architecture registered");
     size_t nreq = (size_t)c->cfg.max_requests;
     if (!c->d_inputs) {
         size_t ib = c->archs[0].in_bytes();
-        HIPCHK(c, hipMalloc(&c->d_inputs, nreq * ib));
-        HIPCHK(c, hipMalloc(&c->d_staged, nreq * ib));
+        HIPCHK(c, dev_malloc(c, &c->d_inputs, nreq * ib));
+        HIPCHK(c, dev_malloc(c, &c->d_staged, nreq * ib));
     }
     if (c->logits_alloc_classes < c->max_classes) {
         if (c->n_live > 0) return fail(c, COE_ESTATE, "architecture with more classes registered while requests are live");
         if (c->d_logits) HIPCHK(c, hipFree(c->d_logits));
-        HIPCHK(c, hipMalloc((void**)&c->d_logits, nreq * c->max_classes * sizeof(float)));
+        HIPCHK(c, dev_malloc(c, (void**)&c->d_logits, nreq * c->max_classes * sizeof(float)));
         c->logits_alloc_classes = c->max_classes;
     }
     return COE_OK;
@@ -392,7 +407,7 @@ int ensure_workspace(coe_ctx* c)
                 HIPCHK(c, hipStreamSynchronize(ln.s));
                 if (ln.d_buf[b]) HIPCHK(c, hipFree(ln.d_buf[b]));
                 ln.d_buf[b] = nullptr;
-                HIPCHK(c, hipMalloc(&ln.d_buf[b], need));
+                HIPCHK(c, dev_malloc(c, &ln.d_buf[b], need));
                 ln.buf_bytes[b] = need;
             }
         }
@@ -402,46 +417,66 @@ int ensure_workspace(coe_ctx* c)
             HIPCHK(c, hipStreamSynchronize(ln.s));
             if (ln.d_patch) HIPCHK(c, hipFree(ln.d_patch));
             ln.d_patch = nullptr;
-            HIPCHK(c, hipMalloc(&ln.d_patch, need));
+            HIPCHK(c, dev_malloc(c, &ln.d_patch, need));
             ln.patch_bytes = need;
         }
     }
     return COE_OK;
 }
 
-int acquire_buf(coe_ctx* c, size_t bytes, DevBuf** out)
+// The arena: per size class as many slots as the caps let be resident at once (all experts of the class when there is no
+// cap).  Called once, when the dependency graph is set and every expert is known.
+int build_arena(coe_ctx* c)
 {
-    for (size_t i = 0; i < c->free_bufs.size(); ++i)
-        if (c->free_bufs[i]->bytes == bytes) {
-            *out = c->free_bufs[i];
-            c->free_bufs.erase(c->free_bufs.begin() + i);
-            return COE_OK;
-        }
-    // no buffer of that size: give back free buffers of other sizes so the capped footprint holds
-    if (!c->free_bufs.empty()) {
-        HIPCHK(c, hipDeviceSynchronize());
-        for (DevBuf* b : c->free_bufs) {
-            hipFree(b->p);
-            b->p = nullptr;
-            b->bytes = 0;
-        }
-        c->free_bufs.clear();
+    std::vector<size_t> class_bytes;
+    std::vector<int32_t> members;
+    for (Expert& x : c->experts) {
+        size_t k = 0;
+        while (k < class_bytes.size() && class_bytes[k] != x.nbytes) ++k;
+        if (k == class_bytes.size()) { class_bytes.push_back(x.nbytes); members.push_back(0); }
+        x.cls = (int32_t)k;
+        ++members[k];
     }
-    DevBuf* b = new DevBuf();
-    hipError_t e = hipMalloc(&b->p, bytes);
-    if (e != hipSuccess) {
-        delete b;
+    std::vector<int32_t> n_slots(class_bytes.size());
+    size_t total = 0;
+    for (size_t k = 0; k < class_bytes.size(); ++k) {
+        int64_t n = members[k];
+        if (c->cfg.cache_cap_experts > 0) n = std::min<int64_t>(n, c->cfg.cache_cap_experts);
+        if (c->cfg.cache_cap_bytes > 0) n = std::min<int64_t>(n, c->cfg.cache_cap_bytes / (int64_t)class_bytes[k]);
+        n_slots[k] = (int32_t)n;
+        total += (size_t)n * align_up(class_bytes[k]);
+    }
+    if (total > 0 && dev_malloc(c, &c->arena, total) != hipSuccess) {
         (void)hipGetLastError();
-        return fail(c, COE_ENOMEM, "device allocation for an expert failed");
+        c->arena = nullptr;
+        return fail(c, COE_ENOMEM, "device allocation of the expert arena failed");
     }
-    b->bytes = bytes;
-    if (hipEventCreateWithFlags(&b->last_use, hipEventDisableTiming) != hipSuccess) {
-        hipFree(b->p);
-        delete b;
-        return fail(c, COE_EDEVICE, "hipEventCreate failed");
-    }
-    c->all_bufs.push_back(b);
-    *out = b;
+    size_t n_total = 0;
+    for (int32_t n : n_slots) n_total += (size_t)n;
+    c->slots.resize(n_total);
+    c->free_slots.assign(class_bytes.size(), {});
+    size_t off = 0, i = 0;
+    for (size_t k = 0; k < class_bytes.size(); ++k)
+        for (int32_t j = 0; j < n_slots[k]; ++j, ++i) {
+            DevBuf& b = c->slots[i];
+            b.p = (uint8_t*)c->arena + off;
+            b.bytes = class_bytes[k];
+            b.cls = (int32_t)k;
+            off += align_up(class_bytes[k]);
+            HIPCHK(c, hipEventCreateWithFlags(&b.last_use, hipEventDisableTiming));
+            c->free_slots[k].push_back(&b);
+        }
+    return COE_OK;
+}
+
+// A free slot of the class: the one released longest ago (its last reader is the most likely to have finished).  The
+// policy evicts before it loads, so the class always has one.
+int acquire_buf(coe_ctx* c, int32_t cls, DevBuf** out)
+{
+    std::vector<DevBuf*>& fl = c->free_slots[cls];
+    if (fl.empty()) return fail(c, COE_ESTATE, "internal: no free arena slot for an expert the policy admitted");
+    *out = fl.front();
+    fl.erase(fl.begin());
     return COE_OK;
 }
 
@@ -449,7 +484,7 @@ void release_expert(coe_ctx* c, int32_t v)
 {
     Expert& x = c->experts[v];
     if (x.buf) {
-        c->free_bufs.push_back(x.buf);
+        c->free_slots[x.buf->cls].push_back(x.buf);
         x.buf = nullptr;
     }
     x.load_pending = false;
@@ -466,7 +501,7 @@ int issue_load(coe_ctx* c, const coe::Switch& sw, coe_step_stats* st)
     }
     Expert& x = c->experts[sw.expert];
     DevBuf* b = nullptr;
-    int rc = acquire_buf(c, x.nbytes, &b);
+    int rc = acquire_buf(c, x.cls, &b);
     if (rc) return rc;
     // the buffer may still be read by kernels of its previous owner
     if (b->used) HIPCHK(c, hipStreamWaitEvent(c->sx, b->last_use, 0));
@@ -738,7 +773,9 @@ int coe_create(const coe_config* cfg, coe_ctx** out)
               hipMalloc((void**)&c->d_cnt, 2 * coe::k::kRegroupMaxExperts * 4) == hipSuccess &&
               hipMalloc((void**)&c->d_off, (coe::k::kRegroupMaxExperts + 1) * 4) == hipSuccess &&
               hipMalloc((void**)&c->d_blockhist, nblocks * coe::k::kRegroupMaxExperts * 4) == hipSuccess &&
-              hipHostMalloc((void**)&c->h_cnt, 2 * coe::k::kRegroupMaxExperts * 4, hipHostMallocDefault) == hipSuccess;
+              hipHostMalloc((void**)&c->h_cnt, 2 * coe::k::kRegroupMaxExperts * 4, hipHostMallocDefault) == hipSuccess &&
+              hipHostMalloc((void**)&c->h_first, nreq * 4, hipHostMallocDefault) == hipSuccess;
+    c->device_allocs += 7;
     if (!ok) return bail(COE_ENOMEM);
     c->collected.assign(nreq, 0);
     c->submit_step.assign(nreq, 0);
@@ -754,11 +791,9 @@ void coe_destroy(coe_ctx* c)
         if (x.host) hipHostFree(x.host);
         if (x.loaded) hipEventDestroy(x.loaded);
     }
-    for (DevBuf* b : c->all_bufs) {
-        if (b->p) hipFree(b->p);
-        if (b->last_use) hipEventDestroy(b->last_use);
-        delete b;
-    }
+    for (DevBuf& b : c->slots)
+        if (b.last_use) hipEventDestroy(b.last_use);
+    if (c->arena) hipFree(c->arena);
     for (auto& pc : c->prof)
         for (auto& s : pc.spans) { hipEventDestroy(s.first); hipEventDestroy(s.second); }
     for (hipEvent_t e : c->ev_pool) hipEventDestroy(e);
@@ -774,6 +809,7 @@ void coe_destroy(coe_ctx* c)
     }
     if (c->ev_ready) hipEventDestroy(c->ev_ready);
     if (c->h_cnt) hipHostFree(c->h_cnt);
+    if (c->h_first) hipHostFree(c->h_first);
     if (c->own_sc && c->sc) hipStreamDestroy(c->sc);
     if (c->own_sx && c->sx) hipStreamDestroy(c->sx);
     delete c;
@@ -872,7 +908,7 @@ int coe_set_dependency_graph(coe_ctx* c, int32_t n, const int32_t* succ_off, con
     c->succ_off.assign(succ_off, succ_off + n + 1);
     c->succ.assign(succ, succ + succ_off[n]);
     size_t nb = std::max<size_t>(1, c->succ.size()) * 4;
-    HIPCHK(c, hipMalloc((void**)&c->d_succ, nb));
+    HIPCHK(c, dev_malloc(c, (void**)&c->d_succ, nb));
     if (!c->succ.empty()) HIPCHK(c, hipMemcpy(c->d_succ, c->succ.data(), c->succ.size() * 4, hipMemcpyHostToDevice));
     std::vector<int64_t> bytes(n);
     std::vector<float> prob(n);
@@ -881,6 +917,15 @@ int coe_set_dependency_graph(coe_ctx* c, int32_t n, const int32_t* succ_off, con
                                     c->cfg.cache_cap_bytes));
     if (!c->policy->set_eviction(c->cfg.eviction)) return fail(c, COE_EINVAL, "unknown eviction rule");
     if (!c->policy->set_in_use_depth(c->cfg.prefetch_depth)) return fail(c, COE_EINVAL, "negative prefetch depth");
+    // every device buffer the step path needs is allocated here, once: the expert arena, the request store and the
+    // executors' activation workspaces.  coe_submit and coe_step allocate nothing.
+    int rc2 = build_arena(c);
+    if (rc2 == COE_OK) rc2 = ensure_store(c);
+    if (rc2 == COE_OK) rc2 = ensure_workspace(c);
+    if (rc2) {
+        c->policy.reset();
+        return rc2;
+    }
     c->E = n;
     c->graph_set = true;
     return COE_OK;
@@ -902,28 +947,25 @@ int coe_submit(coe_ctx* c, int32_t n, const void* inputs, int on_device, const i
     size_t base = (size_t)c->n_live;
     HIPCHK(c, hipMemcpyAsync((uint8_t*)c->d_inputs + base * ib, inputs, (size_t)n * ib,
                              on_device ? hipMemcpyDeviceToDevice : hipMemcpyHostToDevice, c->sc));
-    std::vector<int32_t> cur(n, 0);
-    if (first) std::copy(first, first + n, cur.begin());
-    HIPCHK(c, hipMemcpyAsync(c->d_cur + base, cur.data(), (size_t)n * 4, hipMemcpyHostToDevice, c->sc));
+    // the first experts travel through pinned staging, one entry per request slot (a slot is reused only after the store
+    // has drained, which synchronises), so the call returns without waiting for the stream
+    if (first) std::copy(first, first + n, c->h_first + base);
+    else std::fill(c->h_first + base, c->h_first + base + n, 0);
+    HIPCHK(c, hipMemcpyAsync(c->d_cur + base, c->h_first + base, (size_t)n * 4, hipMemcpyHostToDevice, c->sc));
     HIPCHK(c, hipMemsetAsync(c->d_depth + base, 0, (size_t)n * 4, c->sc));
     HIPCHK(c, hipMemsetAsync(c->d_path + base * c->cfg.max_stages, 0xFF, (size_t)n * 4 * c->cfg.max_stages, c->sc));
     HIPCHK(c, hipMemsetAsync(c->d_logits + base * c->max_classes, 0, (size_t)n * 4 * c->max_classes, c->sc));
-    // `cur` is pageable host memory: the copy above has been staged by the runtime when the call returns only if we wait
-    HIPCHK(c, hipStreamSynchronize(c->sc));
+    // host inputs are the caller's (possibly pageable) memory and may be freed on return: wait for that copy only
+    if (!on_device) HIPCHK(c, hipStreamSynchronize(c->sc));
     std::fill(c->collected.begin() + base, c->collected.begin() + base + n, 0);
     std::fill(c->submit_step.begin() + base, c->submit_step.begin() + base + n, c->step_no);
     c->n_live += n;
     return COE_OK;
 }
 
-int coe_step(coe_ctx* c, coe_step_stats* stats)
+static int step_body(coe_ctx* c, coe_step_stats& st)
 {
-    if (!c) return COE_EINVAL;
-    coe_step_stats st{};
-    if (stats) *stats = st;
-    if (!c->graph_set) return fail(c, COE_ESTATE, "dependency graph not set");
-    if (c->n_live == 0) return COE_DONE;
-    int rc = ensure_workspace(c);
+    int rc = ensure_workspace(c);       // sized when the graph was set: allocates nothing here
     if (rc) return rc;
     rc = do_init_fill(c, &st);
     if (rc) return rc;
@@ -977,11 +1019,8 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
     // cache plan: execution order and switches
     std::vector<int32_t> order;
     std::vector<coe::Switch> switches;
-    if (!c->policy->plan_stage(has_group.data(), order, switches)) {
-        for (int32_t e = 0; e < E; ++e)
-            if (!c->policy->resident(e)) release_expert(c, e);
+    if (!c->policy->plan_stage(has_group.data(), order, switches))      // (the policy keeps its state: nothing to undo)
         return fail(c, COE_ENOMEM, "an expert does not fit the device cache");
-    }
     st.n_pending = n_pending;
     st.n_groups = (int32_t)order.size();
     st.n_misses = (int32_t)switches.size();
@@ -1025,6 +1064,7 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
     for (const coe::Switch& sw : switches) was_missing[sw.expert] = 1;
     for (Lane& ln : c->lanes) { ln.used = false; ln.busy_ns = 0; }
     c->last_units.clear();
+    c->last_chunks.clear();
     if (c->lanes.size() > 1) HIPCHK(c, hipEventRecord(c->ev_ready, c->sc));
     auto take_lane = [&](int32_t first_expert, int64_t cost_ns, Lane** out) -> int {
         size_t best = 0;
@@ -1093,6 +1133,7 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
                 xm.buf->used = true;
                 launched[m.expert] = 1;
                 ++st.n_chunks;
+                c->last_chunks.insert(c->last_chunks.end(), {m.expert, m.first, m.count});
             }
             st.n_grouped += (int32_t)set.size();
             ++st.n_group_sets;
@@ -1117,21 +1158,38 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
             rc = run_expert(c, *lane, x, x.buf->p, rows ? staged : staged + (size_t)s * ib, cnt, r, -1, rows ? rows + s : nullptr);
             if (rc) return rc;
             ++st.n_chunks;
+            c->last_chunks.insert(c->last_chunks.end(), {e, s, cnt});
         }
         HIPCHK(c, hipEventRecord(x.buf->last_use, lane->s));
         x.buf->used = true;
         launched[e] = 1;
     }
-    // the step is complete on the compute stream once every executor is
+    for (const Lane& ln : c->lanes) st.n_executors_used += ln.used;
+    return COE_OK;
+}
+
+int coe_step(coe_ctx* c, coe_step_stats* stats)
+{
+    if (!c) return COE_EINVAL;
+    coe_step_stats st{};
+    if (stats) *stats = st;
+    if (!c->graph_set) return fail(c, COE_ESTATE, "dependency graph not set");
+    if (c->n_live == 0) return COE_DONE;
+    const int64_t allocs_before = c->device_allocs;
+    for (Lane& ln : c->lanes) ln.used = false;
+    int rc = step_body(c, st);
+    // the step is complete on the compute stream once every executor is - also when the step ended in an error after some
+    // executors had been given work
     for (size_t l = 1; l < c->lanes.size(); ++l) {
         Lane& ln = c->lanes[l];
         if (!ln.used) continue;
-        HIPCHK(c, hipEventRecord(ln.done, ln.s));
-        HIPCHK(c, hipStreamWaitEvent(c->sc, ln.done, 0));
+        hipError_t e1 = hipEventRecord(ln.done, ln.s);
+        hipError_t e2 = e1 == hipSuccess ? hipStreamWaitEvent(c->sc, ln.done, 0) : e1;
+        if (e2 != hipSuccess && rc >= 0) rc = fail(c, COE_EDEVICE, std::string("joining an executor: ") + hipGetErrorString(e2));
     }
-    for (const Lane& ln : c->lanes) st.n_executors_used += ln.used;
-    if (stats) *stats = st;
-    return COE_OK;
+    st.n_device_allocs = (int32_t)(c->device_allocs - allocs_before);
+    if (stats && rc >= 0) *stats = st;
+    return rc;
 }
 
 int coe_set_latency_model(coe_ctx* c, int32_t arch_id, int64_t k_ns, int64_t b_ns, int64_t load_ns)
@@ -1167,6 +1225,15 @@ int coe_debug_last_assignment(coe_ctx* c, int32_t cap, int32_t* first_expert, in
         if (cost_ns) cost_ns[u] = c->last_units[u].cost_ns;
         if (executor) executor[u] = c->last_units[u].lane;
     }
+    return COE_OK;
+}
+
+int coe_debug_last_chunks(coe_ctx* c, int32_t cap, int32_t* chunks, int32_t* n_chunks)
+{
+    if (!c || !n_chunks || cap < 0 || (cap > 0 && !chunks)) return COE_EINVAL;
+    *n_chunks = (int32_t)(c->last_chunks.size() / 3);
+    const size_t words = 3 * (size_t)std::min<int32_t>(cap, *n_chunks);
+    std::copy(c->last_chunks.begin(), c->last_chunks.begin() + words, chunks);
     return COE_OK;
 }
 

@@ -80,6 +80,19 @@ bool Policy::plan_stage(const uint8_t* has_group, std::vector<int32_t>& order, s
     std::vector<uint8_t> waiting(n_, 0);  // group not yet executed in this stage
     for (int32_t e : order) waiting[e] = 1;
 
+    // a stage that cannot be planned leaves the cache as it was: the caller's device state stays the policy's state
+    const std::vector<uint8_t> resident0 = resident_;
+    const std::vector<int64_t> loaded0 = loaded_at_, used0 = used_at_;
+    const int32_t n_res0 = n_res_;
+    const int64_t res_bytes0 = res_bytes_, clock0 = clock_;
+    auto give_up = [&]() {
+        resident_ = resident0; loaded_at_ = loaded0; used_at_ = used0;
+        n_res_ = n_res0; res_bytes_ = res_bytes0; clock_ = clock0;
+        order.clear();
+        switches.clear();
+        return false;
+    };
+
     for (size_t pos = 0; pos < order.size(); ++pos) {
         const int32_t e = order[pos];
         if (!resident_[e]) {
@@ -130,7 +143,7 @@ bool Policy::plan_stage(const uint8_t* has_group, std::vector<int32_t>& order, s
                     sw.victims.push_back(v);
                 }
             }
-            if (!fits(e)) return false;
+            if (!fits(e)) return give_up();
             resident_[e] = 1;
             ++n_res_;
             res_bytes_ += bytes_[e];

@@ -20,7 +20,8 @@ public:
     // Initial fill: descending usage probability (ties: lower id), stopping at the first expert that does not fit.
     std::vector<int32_t> init_fill();
 
-    // Plan one stage.  has_group[e] != 0: some pending request needs e.  Returns false if an expert cannot fit.
+    // Plan one stage.  has_group[e] != 0: some pending request needs e.  Returns false if an expert cannot fit; the cache
+    // state is then what it was before the call.
     // order: resident experts first, then missing ones, each by ascending id.  switches: one per missing expert.
     bool plan_stage(const uint8_t* has_group, std::vector<int32_t>& order, std::vector<Switch>& switches);
 

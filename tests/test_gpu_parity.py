@@ -1,4 +1,6 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs."""
+import time
+
 import numpy as np
 import pytest
 
@@ -186,6 +188,30 @@ def test_regroup_inside_step_matches_oracle(B, oracle, G):
     rc, _ = ctx.coe_step()
     assert rc == B.COE_DONE
     ctx.close()
+
+
+def test_request_splitting_matches_the_oracle_chunk_table(B, oracle, G):
+    """Request splitting (Section 4.2): the batches the library launched in a step, {expert, first row, count} each, against
+    the oracle's split of the same regrouped stage, batch by batch, for several maximum batch sizes."""
+    wl = _config2_small(n=80)
+    G.calibrate_workload(wl, n_cal=48)
+    blobs = [wl.blob(e) for e in range(wl.graph.n_experts)]
+    x, sub, want, _ = G.guarded_inputs(wl, blobs, range(80))
+    dev = device_tensor(x)
+    for max_batch in (1, 3, 7, 16, 33, 80):
+        ctx = B.Context(max_requests=80, max_stages=2, max_batch=max_batch, group_small=-1)
+        B.setup_workload(ctx, wl, blobs)
+        ctx.coe_submit(80, dev.data_ptr(), True)
+        for stage in range(2):
+            rc, st = ctx.coe_step()
+            got = ctx.coe_debug_last_chunks()
+            keys = want["path"][:, stage] if stage else np.zeros(80, np.int32)
+            rg = oracle.regroup(keys, wl.graph.n_experts)
+            order = [e for e in range(wl.graph.n_experts) if rg["cnt"][e] > 0]      # everything resident: ascending id
+            ref = oracle.split(rg["off"], order, max_batch)
+            assert got.tolist() == ref.tolist(), (max_batch, stage)
+            assert st.n_chunks == len(ref)
+        ctx.close()
 
 
 def test_capped_cache_switches_match_policy_and_results_do_not_change(B, oracle, G):
@@ -525,20 +551,66 @@ def test_offline_profiler_measures_a_usable_latency_model(B):
     from paper_2503_02354_amd import profiler as P
     arch = W.resnet50(8, 64, W.DT_BF16, 32)
     blob = W.make_expert_blob(arch, 3, 0)
-    ctx = B.Context(max_requests=4, max_batch=256)
-    aid = ctx.coe_register_arch(arch)
-    ctx.coe_register_expert(0, aid, blob, 1.0)
     sizes = [1, 16, 64, 128, 256]
-    lat = P.measure_batch_latency(ctx, 0, (64, 64, 3), sizes, repeats=5)
-    ctx.close()
-    K, Bc = P.fit_latency(sizes, [lat[n] for n in sizes])
-    assert lat[256] > lat[1] and K > 0 and Bc > 0, (lat, K, Bc)
-    assert P.plateau_batch(sizes, [lat[n] for n in sizes]) in sizes
-    load = P.measure_load_latency(B, arch, blob)
-    assert load["bytes"] == blob.nbytes and load["us"] > 0 and 1.0 < load["GBps"] < 100.0, load
-    lo, hi, wait = P.arranging_window(K, Bc, load["us"], 0.2, 4)
-    assert 0 <= lo <= hi and wait == 4
-    print(f"latency model K {K:.2f} us/request, B {Bc:.0f} us, load {load['us']:.0f} us at {load['GBps']:.1f} GB/s, window {lo, hi, wait}")
+    m = P.profile_arch(arch, blob, sizes, max_batch=256, efficiency=0.2, repeats=5)
+    lat = m["latency_us"]
+    assert lat[256] > lat[1] and m["K_us"] > 0 and m["B_us"] > 0, m
+    assert m["max_batch"] in sizes
+    assert m["load_us"] > 0 and 1.0 < m["load_GBps"] < 100.0, m
+    assert 0 <= m["min_group_resident"] <= m["min_group_missing"]
+    print(f"latency model K {m['K_us']:.2f} us/request, B {m['B_us']:.0f} us, load {m['load_us']:.0f} us at {m['load_GBps']:.1f} GB/s, "
+          f"thresholds {m['min_group_resident'], m['min_group_missing']}, max batch {m['max_batch']}")
+
+
+def test_window_search_on_measured_throughput_with_a_shared_memory_budget(B, oracle, G):
+    """Section 4.4 with measured throughputs.  One memory budget is shared by the expert cache and the activation workspace:
+    keeping n experts on the device leaves budget - n x blob bytes for activations, which bounds the batch size
+    (coe_config.cache_cap_bytes and max_batch are set from the same budget).  Few experts: every group of a missing expert
+    costs a switch; many experts: batches shrink.  The search (library arithmetic, throughputs measured here on the GPU) must
+    visit the windows the decay rule prescribes and stop for the reason its own trace implies; every configuration it visits
+    produces the same routes and logits."""
+    from paper_2503_02354_amd import profiler as P
+    from oracle import profiler_oracle as PO
+    n, E, arrival = 384, 24, 96
+    wl = W.config3(n, hw=64, n_experts=E, width=16, cap=0, arrival_batch=arrival, calibrated=False)
+    G.calibrate_workload(wl, n_cal=64, targets={0: W.zipf_probs(E - 1, 1.1)})
+    blobs = [wl.blob(e) for e in range(E)]
+    x = wl.inputs(range(n))
+    dev = device_tensor(x)
+    blob_bytes = blobs[0].nbytes
+    act_per_request = 64 * 64 * 64 * 2 * 6          # a few activation buffers of the largest tensor, per request
+    budget = E * blob_bytes + 8 * act_per_request   # with every expert resident only 8 requests fit a batch
+    results = {}
+
+    def throughput_at(n_experts):
+        cap_bytes = n_experts * blob_bytes
+        max_batch = max(1, min(256, (budget - cap_bytes) // act_per_request))
+        ctx = B.Context(max_requests=n, max_stages=2, max_batch=int(max_batch), cache_cap_bytes=int(cap_bytes), prefetch_depth=1)
+        B.setup_workload(ctx, wl, blobs)
+        best = 0.0
+        for rep in range(3):
+            t0 = time.perf_counter()
+            for s in range(0, n, arrival):
+                ctx.coe_submit(arrival, dev.data_ptr() + s * x[0].nbytes, True)
+                ctx.coe_step()
+            while ctx.coe_step()[0] != B.COE_DONE:
+                pass
+            ids, logits, path = ctx.coe_collect(n)
+            best = max(best, n / (time.perf_counter() - t0))
+            order = np.argsort(ids)
+            results.setdefault("ref", (path[order], logits[order]))
+            assert np.array_equal(path[order], results["ref"][0]) and np.array_equal(logits[order], results["ref"][1])
+        ctx.close()
+        results[n_experts] = (int(max_batch), best)
+        return best
+
+    # initial window 6, decay factor 0.94: upper bounds 6, 11.64, 16.94, 21.92, 26.6 -> 6, 12, 17, 22 and all 24 experts
+    out = P.search_resident_experts(E, throughput_at, initial_window=6.0, error_margin=0.05, fit_points=2)
+    assert out["loaded"] == [6, 12, 17, 22, 24][:len(out["loaded"])] and len(out["loaded"]) >= 3
+    # the oracle twin, fed the throughputs measured above, takes the same decisions
+    ref = PO.decay_window_search(E, lambda k: results[k][1], 6.0, 0.05, 2)
+    assert out["loaded"] == ref["loaded"] and out["experts"] == ref["experts"] and out["stopped_by"] == ref["stopped_by"]
+    print("window search on measured throughput:", {k: v for k, v in results.items() if k != "ref"}, out)
 
 
 @pytest.mark.parametrize("rule,depth", [(1, 0), (2, 0), (0, 1), (0, 2), (1, 2)])
@@ -597,6 +669,55 @@ def test_launch_sequences_respect_the_address_limit(B):
     assert np.isfinite(outs[0]).all() and np.abs(outs[0]).max() > 0
     assert np.array_equal(outs[0], outs[1])
     assert np.array_equal(outs[0][:16], outs[0][16:32])               # repeated images, repeated results
+
+
+def test_steps_allocate_nothing_on_a_capped_two_architecture_dag(B, oracle, G):
+    """Expert arena: a cache of 5 of 18 experts of two architectures (two slot classes), so consecutive switches alternate
+    between blob sizes.  No step allocates device memory (not even the first), submits of device inputs return without
+    waiting, results equal the oracle's and the switch log equals the policy replay's - also with a byte cap that only the
+    smaller architecture's slots can use up."""
+    n, arrival = 120, 24
+    wl = W.config4(n, hw=64, tiers=(3, 6, 9), width=16, fan=(3, 2), calibrated=False)
+    G.calibrate_workload(wl, n_cal=32)
+    E = wl.graph.n_experts
+    blobs = [wl.blob(e) for e in range(E)]
+    sizes = sorted(set(b.nbytes for b in blobs))
+    assert len(sizes) == 2
+    x, sub, want, _ = G.guarded_inputs(wl, blobs, range(n))
+    assert not want["ambiguous"].any()
+    for caps in (dict(cache_cap_experts=5), dict(cache_cap_experts=6, cache_cap_bytes=2 * sizes[1] + 3 * sizes[0])):
+        ctx = B.Context(max_requests=n, max_stages=wl.max_stages, max_batch=32, prefetch_depth=1, **caps)
+        B.setup_workload(ctx, wl, blobs)
+        got = run_chain_gpu(B, wl, blobs, x, wl.first_expert, arrival=arrival, ctx=ctx)
+        ctx.close()
+        assert_chain_parity(got, want, REL_TOL_BF16)
+        stats = [st for rc, st in got["stats"] if rc == B.COE_OK]
+        assert all(st.n_device_allocs == 0 for st in stats), [st.n_device_allocs for st in stats]
+        assert sum(st.n_misses for st in stats) > 10
+        sim = oracle.CacheSim([b.nbytes for b in blobs], wl.usage_prob, wl.graph.succ_off, wl.graph.succ,
+                              cap_experts=caps["cache_cap_experts"], cap_bytes=caps.get("cache_cap_bytes", 0), in_use=1)
+        fill = sim.init_fill()
+        log = [(e, []) for e in fill]
+        keys = np.full(n, -1, np.int64)
+        depth = np.zeros(n, np.int64)
+        arrived = 0
+        for st in stats:
+            if arrived < n:
+                keys[arrived:arrived + arrival] = want["path"][arrived:arrived + arrival, 0]
+                arrived += arrival
+            has = np.zeros(E, np.uint8)
+            has[keys[keys >= 0]] = 1
+            log += sim.stage(has)[1]
+            live = keys >= 0
+            depth[live] += 1
+            nxt = np.full(n, -1, np.int64)
+            idx = np.nonzero(live)[0]
+            ok = depth[idx] < wl.max_stages
+            nxt[idx[ok]] = want["path"][idx[ok], depth[idx[ok]]]
+            keys = nxt
+        assert got["switch_log"] == log
+        sizes_switched = set(blobs[e].nbytes for e, v in log[len(fill):])
+        assert sizes_switched == set(sizes)                       # switches of both slot classes happened
 
 
 def test_arranging_window_on_a_capped_mixed_dag(B, oracle, G):

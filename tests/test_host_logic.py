@@ -149,46 +149,96 @@ def test_arranging_rule_matches_oracle(B):
         assert got.tolist() == want
 
 
-def test_profiler_arithmetic():
-    """Latency model fit, batch plateau and arranging thresholds (paper Sections 4.2, 4.5) on hand-made numbers."""
-    from paper_2503_02354_amd import profiler as P
-    K, Bc = P.fit_latency([1, 2, 4, 8, 16], [103.0, 106.0, 112.0, 124.0, 148.0])     # exactly 3 n + 100
+def test_profiler_arithmetic(B):
+    """Latency model fit, maximum batch and arranging thresholds (paper Sections 4.2, 4.5) behind the C ABI: hand-made
+    numbers, then random cases against the oracle's twin."""
+    from oracle import profiler_oracle as PO
+    K, Bc = B.coe_profiler_fit_latency([1, 2, 4, 8, 16], [103.0, 106.0, 112.0, 124.0, 148.0])     # exactly 3 n + 100
     assert abs(K - 3.0) < 1e-9 and abs(Bc - 100.0) < 1e-9
-    K, Bc = P.fit_latency([10, 20, 30], [25.0, 45.0, 59.0])                           # textbook least squares: 1.7 n + 9
+    K, Bc = B.coe_profiler_fit_latency([10, 20, 30], [25.0, 45.0, 59.0])                          # textbook least squares: 1.7 n + 9
     assert abs(K - 1.7) < 1e-9 and abs(Bc - 9.0) < 1e-9
+    with pytest.raises(B.CoEError):
+        B.coe_profiler_fit_latency([4, 4, 4], [1.0, 2.0, 3.0])
     # per-request latency 110, 60, 35, 22.5, 21.2, 21.0: within 5 % of the best from n = 16 on
-    assert P.plateau_batch([1, 2, 4, 8, 16, 32], [110, 120, 140, 180, 339.2, 672], tol=0.05) == 16
-    assert P.plateau_batch([1, 2, 4], [10, 20, 40]) == 1
+    assert B.coe_profiler_max_batch([1, 2, 4, 8, 16, 32], [110, 120, 140, 180, 339.2, 672], 0.05) == 16
+    assert B.coe_profiler_max_batch([1, 2, 4], [10, 20, 40]) == 1
     # K = 10, B = 1000, load = 800; half of the time useful: n >= 100 resident, 180 missing; a fifth: 25 and 45
-    assert P.arranging_window(10.0, 1000.0, 800.0, 0.5, 8) == (100, 180, 8)
-    assert P.arranging_window(10.0, 1000.0, 800.0, 0.2, 3) == (25, 45, 3)
-    assert P.arranging_window(10.0, 1000.0, 800.0, 0.0, 3) == (0, 0, 3)
+    assert B.coe_profiler_arranging_window(10.0, 1000.0, 800.0, 0.5) == (100, 180)
+    assert B.coe_profiler_arranging_window(10.0, 1000.0, 800.0, 0.2) == (25, 45)
+    assert B.coe_profiler_arranging_window(10.0, 1000.0, 800.0, 0.0) == (0, 0)
+    rng = np.random.default_rng(3)
+    for _ in range(100):
+        n = int(rng.integers(2, 9))
+        ns = np.sort(rng.choice(np.arange(1, 600), size=n, replace=False))
+        ts = rng.uniform(2, 20) * ns + rng.uniform(0, 2000) + rng.normal(0, 5, n)
+        ts = np.maximum(ts, 1.0)
+        k, b = B.coe_profiler_fit_latency(ns, ts)
+        k2, b2 = PO.line_through(ns.tolist(), ts.tolist())
+        assert abs(k - k2) <= 1e-9 * max(1, abs(k2)) and abs(b - b2) <= 1e-7 * max(1, abs(b2))
+        tol = float(rng.choice([0.0, 0.05, 0.3]))
+        assert B.coe_profiler_max_batch(ns, ts, tol) == PO.max_batch(ns.tolist(), ts.tolist(), tol)
+        kk, bb, ld, eff = rng.uniform(1, 30), rng.uniform(0, 3000), rng.uniform(0, 2000), float(rng.choice([0.1, 0.2, 0.5, 0.8]))
+        assert B.coe_profiler_arranging_window(kk, bb, ld, eff) == PO.arranging_thresholds(kk, bb, ld, eff)
 
 
-def test_decay_window_search_hand_worked():
-    """Section 4.4 on hand-made numbers.  20 experts of equal usage: each covers 5 % of the usage.  Initial window 20 %,
-    decay factor 0.8: upper bounds 20, 36, 48.8, 59.04, 67.23, ... % -> 4, 8, 10, 12, 14 experts.  Throughput rises by 10
-    per window (100, 110, 120, 130) and then falls to 90 at 14 experts: the line through the first four values
-    predicts 140, the shortfall (140 - 90) / 140 = 0.36 exceeds the margin, the search stops in the window 59.04..67.23 %
-    and its middle (63.1 %) is covered by 13 experts."""
-    from paper_2503_02354_amd import profiler as P
-    usage = [1.0] * 20
-    assert [P.experts_for_usage(usage, q) for q in (5, 5.1, 20, 36, 48.8, 59.04, 100)] == [1, 2, 4, 8, 10, 12, 20]
-    curve = {4: 100.0, 8: 110.0, 10: 120.0, 12: 130.0, 14: 90.0}
-    seen = []
-    out = P.decay_window_search(usage, lambda n: (seen.append(n), curve[n])[1], initial_window=20.0, min_points=3,
-                                error_margin=0.1, pick=0.5)
-    assert seen == [4, 8, 10, 12, 14]
-    assert out["stopped_by"] == "shortfall" and out["n_experts"] == 13
-    assert abs(out["window"][0] - 59.04) < 1e-9 and abs(out["window"][1] - 67.232) < 1e-9
-    # a throughput that keeps following the line: the windows (30 %, then x 0.7 each: upper bounds 30, 51, 65.7, 75.99,
-    # 83.19, 88.24, 91.76 %) shrink until the next one (94.24 %) adds no expert to the 19 that cover 91.76 %
-    out = P.decay_window_search(usage, lambda n: 100.0 + 2.0 * n, initial_window=30.0, pick=1.0)
-    assert out["stopped_by"] == "end" and abs(out["window"][1] - 91.76457) < 1e-6 and out["n_experts"] == 19
-    assert [v[1] for v in out["trace"]] == [6, 11, 14, 16, 17, 18, 19]
-    # a skewed CDF: Zipf(1.1) over 63 leaves reaches 74.9 % of the usage with its 15 most used experts
-    z = W.zipf_probs(63, 1.1)
-    assert P.experts_for_usage(z, 74.0) == 15 and P.experts_for_usage(z, 25.0) == 1
+def _run_window_search(B, total, curve, initial, margin, fit_points=2):
+    ts, loaded = [], []
+    st = B.coe_profiler_window_step(total, initial, margin, fit_points, ts)
+    while st.status == B.COE_WINDOW_MEASURE:
+        loaded.append(st.n_next)
+        ts.append(curve(st.n_next))
+        st = B.coe_profiler_window_step(total, initial, margin, fit_points, ts)
+    return st, loaded, ts
+
+
+def test_decay_window_search_reproduces_the_printed_case(B):
+    """Section 5.4 prints one run of the search of Section 4.4: initial window size 15, error margin 5 %, final window
+    "loading 28 to 39 experts" with a linear error of 7.7 % (Task A, 352 experts).  Eq. 1 gives the decay factor 0.85, so the
+    window sizes are 15, 12.75, 10.8375 and the upper bounds 15, 27.75, 38.5875: the third window is 27.75..38.5875 = experts
+    28 to 39, reached when the third throughput falls 7.7 % short of the line through the first two.  Oracle twin and
+    library both have to land there."""
+    from oracle import profiler_oracle as PO
+    assert [round(v, 4) for k in range(3) for v in PO.window_bounds(15.0, k)] == [0, 15, 15, 27.75, 27.75, 38.5875]
+    # throughputs 20 and 24 at 15 and 28 experts: the line predicts 28 at the third point; 7.7 % short of that is 25.844
+    curve = {15: 20.0, 28: 24.0, 39: 28.0 * (1 - 0.077)}
+    ref = PO.decay_window_search(352, lambda n: curve[n], 15.0, 0.05)
+    assert ref["loaded"] == [15, 28, 39] and ref["experts"] == (28, 39) and ref["stopped_by"] == "shortfall"
+    assert abs(ref["linear_error"] - 0.077) < 1e-12
+    st, loaded, ts = _run_window_search(B, 352, lambda n: curve[n], 15.0, 0.05)
+    assert loaded == [15, 28, 39] and (st.n_low, st.n_high) == (28, 39) and st.status == B.COE_WINDOW_SHORTFALL
+    assert abs(st.window_low - 27.75) < 1e-9 and abs(st.window_high - 38.5875) < 1e-9 and abs(st.linear_error - 0.077) < 1e-9
+    # a shortfall inside the margin (4 %) does not stop the slide: the fourth window is 38.5875..47.799 = experts 39 to 48
+    curve = {15: 20.0, 28: 24.0, 39: 28.0 * 0.96, 48: 10.0}
+    st, loaded, ts = _run_window_search(B, 352, lambda n: curve[n], 15.0, 0.05)
+    assert loaded == [15, 28, 39, 48] and (st.n_low, st.n_high) == (39, 48)
+    assert PO.decay_window_search(352, lambda n: curve[n], 15.0, 0.05)["experts"] == (39, 48)
+
+
+def test_decay_window_search_matches_the_oracle_twin(B):
+    """Random throughput curves (rise, then fall somewhere), several initial windows, margins and expert counts: library and
+    oracle twin measure at the same expert counts, stop at the same window for the same reason.  A curve that keeps rising
+    ends when a window has loaded every expert (window sizes sum to 100, so totals below 100 are always reached)."""
+    from oracle import profiler_oracle as PO
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        total = int(rng.integers(3, 99))
+        initial = float(rng.choice([5.0, 10.0, 15.0, 20.0, 30.0, 50.0]))
+        margin = float(rng.choice([0.0, 0.05, 0.1, 0.3]))
+        fit_points = int(rng.integers(2, 5))
+        peak = rng.uniform(0, 1.5) * total
+        noise = rng.normal(0, 0.02, total + 1)
+        curve = lambda n: 100.0 + 10.0 * min(n, peak) - 25.0 * max(0.0, n - peak) + noise[n]
+        ref = PO.decay_window_search(total, curve, initial, margin, fit_points)
+        st, loaded, ts = _run_window_search(B, total, curve, initial, margin, fit_points)
+        assert loaded == ref["loaded"], (total, initial, margin, fit_points)
+        assert (st.n_low, st.n_high) == ref["experts"]
+        assert ("shortfall" if st.status == B.COE_WINDOW_SHORTFALL else "end") == ref["stopped_by"]
+        assert abs(st.linear_error - ref["linear_error"]) < 1e-9
+        assert abs(st.window_low - ref["window"][0]) < 1e-9 and abs(st.window_high - ref["window"][1]) < 1e-9
+    with pytest.raises(B.CoEError):
+        B.coe_profiler_window_step(10, 0.0, 0.05, 2, [])
+    with pytest.raises(B.CoEError):
+        B.coe_profiler_window_step(10, 15.0, 0.05, 1, [])
 
 
 def test_assigning_rule_matches_oracle(B):
