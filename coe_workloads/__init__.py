@@ -382,19 +382,39 @@ def blob_tensor(arch: Arch, blob: np.ndarray, layer: int, name: str) -> np.ndarr
 # ----------------------------------------------------------------------------
 # request inputs
 # ----------------------------------------------------------------------------
-def make_inputs(arch: Arch, seed: int, request_ids: Sequence[int], subseeds: Optional[Sequence[int]] = None) -> np.ndarray:
-    """Images ~ N(0,1), NHWC, one independent Philox stream per (request id, sub-seed).
+STRUCT_GRID = 2           # a structured image's coarse pattern has STRUCT_GRID x STRUCT_GRID cells per channel
+STRUCT_NOISE_STD = 0.5    # and pixel noise of this standard deviation on top
+
+
+def make_inputs(arch: Arch, seed: int, request_ids: Sequence[int], subseeds: Optional[Sequence[int]] = None,
+                kind: str = "noise") -> np.ndarray:
+    """Request images, NHWC, one independent Philox stream per (request id, sub-seed).
+
+    kind "noise": every element ~ N(0,1).  kind "structured": a per-request coarse pattern (a STRUCT_GRID x STRUCT_GRID
+    grid of N(0,1) values per channel, each cell covering a block of pixels) plus N(0, STRUCT_NOISE_STD^2) pixel noise.
+    Pure-noise images all look alike to an expert after its global pooling (every request gets nearly the same logits);
+    the coarse pattern gives each request features of its own, as the images of a real workload have.
 
     Returns uint16 bf16 bit patterns [n][H][W][C] for bf16 architectures, float32 otherwise.  A request whose
     routing margin is too small for a well-posed argmax is re-drawn by bumping its sub-seed."""
+    assert kind in ("noise", "structured")
     n = len(request_ids)
     elems = arch.input_elems
     out = np.empty((n, elems), dtype=np.uint16 if arch.dtype == DT_BF16 else np.float32)
     ids = [int(r) for r in request_ids]
+    # pixel row / column -> cell of the coarse grid
+    cell_h = (np.arange(arch.in_h) * STRUCT_GRID) // arch.in_h
+    cell_w = (np.arange(arch.in_w) * STRUCT_GRID) // arch.in_w
 
     def draw(i):
         ss = 0 if subseeds is None else int(subseeds[i])
-        v = _stream(seed, _KIND_INPUT, ids[i], ss).standard_normal(elems, dtype=np.float32)
+        g = _stream(seed, _KIND_INPUT, ids[i], ss)
+        if kind == "structured":
+            coarse = g.standard_normal((STRUCT_GRID, STRUCT_GRID, arch.in_c), dtype=np.float32)
+            v = g.standard_normal(elems, dtype=np.float32) * np.float32(STRUCT_NOISE_STD)
+            v = (v.reshape(arch.in_h, arch.in_w, arch.in_c) + coarse[cell_h][:, cell_w]).reshape(elems)
+        else:
+            v = g.standard_normal(elems, dtype=np.float32)
         out[i] = f32_to_bf16_bits(v) if arch.dtype == DT_BF16 else v
 
     if n * elems > (1 << 24):      # large batches: numpy releases the GIL inside the generator
@@ -455,12 +475,13 @@ class Workload:
     arrival_batch: int                # requests per coe_submit
     head_bias: Dict[int, np.ndarray]  # expert id -> calibrated head bias
     max_stages: int
+    input_kind: str = "noise"         # see make_inputs
 
     def blob(self, e: int) -> np.ndarray:
         return make_expert_blob(self.archs[self.expert_arch[e]], self.seed, e, self.head_bias.get(e))
 
     def inputs(self, request_ids, subseeds=None) -> np.ndarray:
-        return make_inputs(self.archs[0], self.seed, request_ids, subseeds)
+        return make_inputs(self.archs[0], self.seed, request_ids, subseeds, self.input_kind)
 
     @property
     def max_classes(self) -> int:
@@ -508,7 +529,7 @@ def config3(n_requests: int = 16384, hw: int = 224, n_experts: int = 64, width: 
     g = tree_graph(n_experts)
     p = [1.0] + list(zipf_probs(n_experts - 1, 1.1))
     return Workload(name, 0xC0E3, [a], [0] * n_experts, p, g, n_requests, None, cap, arrival_batch,
-                    load_calibration(name) if calibrated else {}, 2)
+                    load_calibration(name) if calibrated else {}, 2, "structured")
 
 
 def config4(n_requests: int = 8192, hw: int = 224, tiers: Tuple[int, int, int] = (8, 32, 80), width: int = 64,
@@ -545,7 +566,7 @@ def config4(n_requests: int = 8192, hw: int = 224, tiers: Tuple[int, int, int] =
         for s in lists[e]:
             prob[s] += prob[e] / len(lists[e])
     return Workload(name, seed, [a18, a50], [e % 2 for e in range(e_total)], list(prob), graph, n_requests, first,
-                    0, n_requests, load_calibration(name) if calibrated else {}, 3)
+                    0, n_requests, load_calibration(name) if calibrated else {}, 3, "structured")
 
 
 def config5(n_requests: int = 4096, hw: int = 224, n_experts: int = 32, cap: int = 12, dim: int = 768,
@@ -557,4 +578,4 @@ def config5(n_requests: int = 4096, hw: int = 224, n_experts: int = 32, cap: int
     g = tree_graph(n_experts)
     p = [1.0] + [1.0 / (n_experts - 1)] * (n_experts - 1)
     return Workload(name, 0xC0E5, [a], [0] * n_experts, p, g, n_requests, None, cap, n_requests,
-                    load_calibration(name) if calibrated else {}, 2)
+                    load_calibration(name) if calibrated else {}, 2, "structured")

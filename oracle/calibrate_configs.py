@@ -24,8 +24,9 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("configs", nargs="+")
     ap.add_argument("--n-cal", type=int, default=256)
+    ap.add_argument("--out-dir", default=W._CALIB_DIR, help="where the .json files go (default: next to the generators)")
     args = ap.parse_args()
-    os.makedirs(W._CALIB_DIR, exist_ok=True)
+    os.makedirs(args.out_dir, exist_ok=True)
     for name in args.configs:
         t0 = time.time()
         if name == "config2":
@@ -39,10 +40,11 @@ def main():
             wl, targets = W.config5(calibrated=False), None
         else:
             raise SystemExit(f"unknown config {name}")
-        hb = G.calibrate_workload(wl, n_cal=args.n_cal, targets=targets)
-        out = {"workload": wl.name, "seed": wl.seed, "n_cal": args.n_cal,
+        hb = G.calibrate_workload(wl, n_cal=args.n_cal, targets=targets,
+                                  progress=lambda e: print(f"  {name}: expert {e} calibrated ({time.time() - t0:.0f}s)", flush=True))
+        out = {"workload": wl.name, "seed": wl.seed, "n_cal": args.n_cal, "input_kind": wl.input_kind,
                "head_bias": {str(e): [float(v) for v in b] for e, b in hb.items()}}
-        path = os.path.join(W._CALIB_DIR, wl.name + ".json")
+        path = os.path.join(args.out_dir, wl.name + ".json")
         with open(path, "w") as f:
             json.dump(out, f, indent=0)
         print(f"{name}: {len(hb)} routing experts calibrated on {args.n_cal} images in {time.time() - t0:.1f}s -> {path}", flush=True)

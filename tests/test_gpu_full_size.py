@@ -32,23 +32,122 @@ def _valid_paths(path, wl):
         assert len(succ) == 0 or -1 in succ, "request stopped at an expert that still routes"
 
 
-def _sampled_case(B, oracle, wl, n_sample, max_batch, arrival=None, seed=1, group_small=0, also=()):
-    """also: further run_chain_gpu keyword sets (other schedules of the same work); every one must reproduce the first
-    run's routes and logits bit for bit.  Their results are returned in got["also"]."""
+N_SAMPLE = 512           # requests per full-size workload that the oracle checks one by one
+MAX_AMBIGUOUS = 0.05     # share of them the margin guard may leave undecided after its re-draws
+
+
+def _routing_census(B, wl, blobs, x0, first):
+    """GPU against oracle at every routing expert, on the UNFILTERED first draw of the sampled requests: the largest
+    logit difference as a share of the computed logit magnitude (what the guard's delta is derived from) and how often
+    the two argmaxes agree without any guard.  Stage s is evaluated on the requests the oracle sent through stage s."""
+    from oracle import guard as G
+    path, all_logits = first["path"], first["all_logits"]
+    n, S = path.shape
+    ctx = B.Context(max_requests=1, max_stages=wl.max_stages, max_batch=256)
+    B.setup_workload(ctx, wl, blobs)
+    dev = device_tensor(x0)
+    import torch
+    out = []
+    bias_cache = {}
+    for s in range(S):
+        eps, agree, n_eval = [], 0, 0
+        for e in sorted(set(int(v) for v in path[:, s] if v >= 0)):
+            k = len(wl.graph.successors(e))
+            if k < 2:
+                continue
+            rows = np.nonzero(path[:, s] == e)[0]
+            xin = dev[torch.from_numpy(rows).cuda()].contiguous()
+            g = ctx.coe_debug_forward(e, len(rows), xin.data_ptr()).astype(np.float64)
+            b = G._head_bias(wl, blobs, e, bias_cache).astype(np.float64)
+            o = all_logits[rows, s, :len(b)].astype(np.float64)
+            scale = np.maximum(np.abs(o - b).max(axis=1), 1e-30)
+            eps.append(np.abs(g[:, :len(b)] - o).max(axis=1) / scale / G.delta_for_arch(wl.archs[wl.expert_arch[e]]))
+            agree += int((np.argmax(g[:, :k], axis=1) == np.argmax(o[:, :k], axis=1)).sum())
+            n_eval += len(rows)
+        if n_eval:
+            eps = np.concatenate(eps)
+            out.append(dict(stage=s, n=n_eval, eps_over_delta_med=float(np.median(eps)), eps_over_delta_max=float(eps.max()),
+                            unguarded_agreement=agree / n_eval))
+    ctx.close()
+    return out
+
+
+def _merge_guarded(a, b):
+    """Two guarded_inputs results (inputs, subseeds, oracle result, re-draws) over disjoint request sets, concatenated."""
+    xa, sa, wa, ra = a
+    xb, sb, wb, rb = b
+    want = {k: np.concatenate([wa[k], wb[k]]) for k in wa if k != "first_draw"}
+    want["first_draw"] = {k: np.concatenate([wa["first_draw"][k], wb["first_draw"][k]]) for k in wa["first_draw"]}
+    return np.concatenate([xa, xb]), np.concatenate([sa, sb]), want, ra + rb
+
+
+_ORACLE_SIDE = {}        # what the oracle says about a workload's sample, shared by the launch configurations of one workload
+
+
+def _oracle_side(B, wl, n_sample, seed, cover_candidates):
+    """Sample, guarded inputs, oracle results, admissible outcomes of the ambiguous rest and the routing census.
+    cover_candidates > 0 (two-stage trees): that many further requests go through the oracle's root only, and one request per
+    leaf that no sampled request reaches joins the sample."""
+    key = (wl.name, n_sample, seed, cover_candidates)
+    if key in _ORACLE_SIDE:
+        return _ORACLE_SIDE[key]
     from oracle import guard as G
     n = wl.n_requests
-    E = wl.graph.n_experts
     with ThreadPoolExecutor(8) as ex:
-        blobs = list(ex.map(wl.blob, range(E)))
+        blobs = list(ex.map(wl.blob, range(wl.graph.n_experts)))
     rng = np.random.default_rng(seed)
     sample = np.sort(rng.choice(n, size=n_sample, replace=False))
     print(f"{wl.name}: blobs ready", flush=True)
-    xs, sub, want, redraws = G.guarded_inputs(wl, blobs, sample)
-    print(f"{wl.name}: guard done, {redraws} re-draws, {int(want['ambiguous'].sum())} ambiguous", flush=True)
-    fe_s = np.zeros(n_sample, np.int32) if wl.first_expert is None else wl.first_expert[sample]
+    guarded = G.guarded_inputs(wl, blobs, sample)
+    if cover_candidates:
+        k = len(wl.graph.successors(0))
+        reached = set(int(v) for v in guarded[2]["path"][:, 1])
+        rest = np.setdiff1d(np.arange(n), sample)
+        cand = np.sort(rng.choice(rest, size=min(cover_candidates, len(rest)), replace=False))
+        lg = G.evaluate_pairs(wl, blobs, wl.inputs(cand), np.zeros(len(cand), np.int32))
+        extra = []
+        for i, c in enumerate(np.argmax(lg[:, :k], axis=1).tolist()):
+            leaf = int(wl.graph.successors(0)[c])
+            if leaf not in reached:
+                reached.add(leaf)
+                extra.append(int(cand[i]))
+        print(f"{wl.name}: {len(extra)} requests added so that {len(reached)} of {k} leaves are sampled", flush=True)
+        if extra:
+            extra = np.array(sorted(extra), np.int64)
+            guarded = _merge_guarded(guarded, G.guarded_inputs(wl, blobs, extra))
+            sample = np.concatenate([sample, extra])
+            order = np.argsort(sample)
+            sample = sample[order]
+            xs, sub, want, redraws = guarded
+            want = {k: (v[order] if k != "first_draw" else {kk: vv[order] for kk, vv in v.items()}) for k, v in want.items()}
+            guarded = (xs[order], sub[order], want, redraws)
+    xs, sub, want, redraws = guarded
+    n_amb = int(want["ambiguous"].sum())
+    print(f"{wl.name}: guard done on {len(sample)} requests: {int(want['first_draw']['undecidable'].sum())} undecidable at the "
+          f"first draw, {redraws} re-draws, {n_amb} still ambiguous", flush=True)
+    assert n_amb <= MAX_AMBIGUOUS * len(sample), f"{n_amb} of {len(sample)} sampled requests stay ambiguous"
+    census = _routing_census(B, wl, blobs, wl.inputs(sample), want["first_draw"])
+    for c in census:
+        print(f"{wl.name}: routing census stage {c['stage']}: {c['n']} unfiltered requests, GPU-oracle logit difference / delta "
+              f"median {c['eps_over_delta_med']:.3f} max {c['eps_over_delta_max']:.3f}, unguarded route agreement "
+              f"{c['unguarded_agreement']:.4f}", flush=True)
+        # delta must cover two logits moving towards each other
+        assert c["eps_over_delta_max"] <= 0.5, "the guard's delta no longer covers the measured GPU-oracle noise"
+    fe_s = np.zeros(len(sample), np.int32) if wl.first_expert is None else wl.first_expert[sample]
     amb_idx = np.nonzero(want["ambiguous"])[0]
     adm = dict(zip(amb_idx.tolist(), G.admissible_outcomes_batch(wl, blobs, xs[amb_idx], fe_s[amb_idx]))) if len(amb_idx) else {}
-    print(f"{wl.name}: admissible outcomes enumerated", flush=True)
+    _ORACLE_SIDE.clear()                                   # one workload's blobs and inputs at a time
+    _ORACLE_SIDE[key] = (blobs, sample, xs, sub, want, redraws, adm)
+    return _ORACLE_SIDE[key]
+
+
+def _sampled_case(B, oracle, wl, n_sample, max_batch, arrival=None, seed=1, group_small=0, also=(), cover_candidates=0,
+                  min_cover=0.8):
+    """also: further run_chain_gpu keyword sets (other schedules of the same work); every one must reproduce the first
+    run's routes and logits bit for bit.  Their results are returned in got["also"]."""
+    n = wl.n_requests
+    blobs, sample, xs, sub, want, redraws, adm = _oracle_side(B, wl, n_sample, seed, cover_candidates)
+    n_amb = int(want["ambiguous"].sum())
     subseeds = np.zeros(n, np.int32)
     subseeds[sample] = sub
     x = wl.inputs(range(n), subseeds)
@@ -61,7 +160,13 @@ def _sampled_case(B, oracle, wl, n_sample, max_batch, arrival=None, seed=1, grou
     print(f"{wl.name}: GPU chain done", flush=True)
     sub_got = dict(path=got["path"][sample], logits=got["logits"][sample])
     err = assert_chain_parity(sub_got, want, REL_TOL_BF16, admissible=lambda i: adm[i])
-    print(f"{wl.name}: {int(want['ambiguous'].sum())} of {len(sample)} sampled requests ambiguous after the guard")
+    visited = set(int(v) for v in got["path"].ravel() if v >= 0)
+    checked = set(int(v) for v in want["path"][~want["ambiguous"]].ravel() if v >= 0)
+    print(f"{wl.name}: {len(sample) - n_amb} of {len(sample)} sampled requests bit-exact in route, {n_amb} ambiguous; "
+          f"{len(checked & visited)} of the {len(visited)} experts the full run visits are covered by a bit-exact sample; "
+          f"max rel logit err {err:.2e}", flush=True)
+    got["experts_visited"], got["experts_checked"] = visited, checked
+    assert len(checked & visited) >= min_cover * len(visited), "too few of the visited experts are oracle-checked"
     # every request: valid path
     _valid_paths(got["path"], wl)
     # the sampled requests alone give the same bits: results do not depend on grouping or batch composition
@@ -85,7 +190,7 @@ def test_config2_full_size(B, oracle, max_batch, group_small):
     leaf groups sharing one), then with 512-request launch sequences and the library's default grouping."""
     wl = W.config2()
     assert wl.head_bias, "calibration file missing"
-    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=48, max_batch=max_batch, group_small=group_small)
+    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=N_SAMPLE, max_batch=max_batch, group_small=group_small)
     # the regroup of the second stage is the stable sort of the routed ids (all 4096 requests, bit exact):
     # replay stage 2's keys through the library's regroup and the oracle's
     keys = got["path"][:, 1].astype(np.int32)
@@ -123,7 +228,7 @@ def test_config3_full_size(B, oracle):
     leaf stage together)."""
     wl = W.config3()
     assert wl.head_bias, "calibration file missing"
-    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=24, max_batch=512, arrival=512, seed=3,
+    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=N_SAMPLE, max_batch=512, arrival=512, seed=3, cover_candidates=1024, min_cover=0.9,
                                                     also=[dict(arranging=(0, 43, 8), prefetch_depth=4, executors=3,
                                                                latency=(14410, 1611000, 846000))])
     stats = [st for rc, st in got["stats"] if rc == B.COE_OK]
@@ -163,7 +268,7 @@ def test_config4_full_size(B, oracle):
     8192 requests, everything resident."""
     wl = W.config4()
     assert wl.head_bias, "calibration file missing"
-    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=24, max_batch=4096, seed=4, group_small=512)
+    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=N_SAMPLE, max_batch=4096, seed=4, group_small=512)
     stats = [st for rc, st in got["stats"] if rc == B.COE_OK]
     assert len(stats) == 3 and all(st.n_pending == wl.n_requests for st in stats)
     assert np.all(got["path"][:, 2] >= 0)
@@ -197,7 +302,7 @@ def test_config5_full_size(B, oracle):
     4096 requests: the 3.4 GB/stage of expert switches overlap the forwards of the groups already resident."""
     wl = W.config5()
     assert wl.head_bias, "calibration file missing"
-    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=16, max_batch=512, seed=5,
+    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=N_SAMPLE, max_batch=512, seed=5,
                                                     also=[dict(prefetch_depth=2)])
     stats = [st for rc, st in got["stats"] if rc == B.COE_OK]
     assert len(stats) == 2 and all(st.n_pending == wl.n_requests for st in stats)
