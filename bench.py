@@ -33,9 +33,15 @@ SLAB_TRAFFIC_SOURCE = ("paper_2503_02354_amd/csrc/conv_mfma.hip",
 SLAB_TRAFFIC_LAUNCH_CONFIG = ("config2", 0, 4096, 512, 1, "")   # workload, requests, max_batch, group_small, arrivals per step, window
 
 
+SLAB_TRAFFIC_PROFILE = "profiles/conv3x3_slab_config2_hbm_counters.md"
+
+
 def measured_traffic(kernel: str, launch_config=None):
-    if kernel != "conv3x3_slab_kernel" or launch_config != SLAB_TRAFFIC_LAUNCH_CONFIG:
-        return None
+    """(bytes per launch or None, where the figure comes from or why there is none)."""
+    if kernel != "conv3x3_slab_kernel":
+        return None, f"no HBM counters were taken for {kernel}"
+    if launch_config != SLAB_TRAFFIC_LAUNCH_CONFIG:
+        return None, f"the counters in {SLAB_TRAFFIC_PROFILE} were taken on another workload or launch configuration"
     import hashlib
     path = os.path.join(os.path.dirname(os.path.abspath(__file__)), SLAB_TRAFFIC_SOURCE[0])
     try:
@@ -43,7 +49,9 @@ def measured_traffic(kernel: str, launch_config=None):
             same = hashlib.sha256(f.read()).hexdigest() == SLAB_TRAFFIC_SOURCE[1]
     except OSError:
         same = False
-    return SLAB_TRAFFIC_BYTES_PER_LAUNCH if same else None
+    if not same:
+        return None, f"{SLAB_TRAFFIC_SOURCE[0]} has changed since the counters in {SLAB_TRAFFIC_PROFILE} were taken"
+    return SLAB_TRAFFIC_BYTES_PER_LAUNCH, f"{SLAB_TRAFFIC_PROFILE} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by a copy of known size)"
 PEAK_HBM_GBS = 8000.0
 
 
@@ -76,6 +84,204 @@ WORKLOAD_TEXT = {
 }
 
 
+DEFAULTS = {   # per workload: launch sequence cap, grouping threshold, every k-th launch timed, arranging window, executors, prefetch
+    "config2": dict(max_batch=4096, group_small=512, profile_every=1, arrange="", executors=1, prefetch_depth=0),
+    "config3": dict(max_batch=512, group_small=0, profile_every=7, arrange="0,43,8", executors=3, prefetch_depth=4),
+    "config4": dict(max_batch=4096, group_small=512, profile_every=7, arrange="", executors=1, prefetch_depth=0),
+    "config5": dict(max_batch=512, group_small=0, profile_every=7, arrange="", executors=1, prefetch_depth=2),
+}
+
+
+def make_workload(name: str, requests: int = 0):
+    import coe_workloads as W
+    from concurrent.futures import ThreadPoolExecutor
+    make = {"config2": W.config2, "config3": W.config3, "config4": W.config4, "config5": W.config5}[name]
+    wl = make(requests) if requests else make()
+    t0 = time.time()
+    with ThreadPoolExecutor(8) as ex:
+        blobs = list(ex.map(wl.blob, range(wl.graph.n_experts)))
+    x = wl.inputs(range(wl.n_requests))
+    return wl, blobs, x, time.time() - t0
+
+
+def measure_latency_models(wl, blobs):
+    """The offline profiler (paper Section 4.5) on this GPU, once per architecture: K, B of latency = K n + B per launch
+    sequence, the load latency of one expert and the arranging thresholds at 20 % efficiency."""
+    from paper_2503_02354_amd import profiler as P
+    out = {}
+    for a, arch in enumerate(wl.archs):
+        e = wl.expert_arch.index(a)
+        m = P.profile_arch(arch, blobs[e], [1, 32, 128, 512], max_batch=512, efficiency=0.2, repeats=3)
+        out[arch.name] = {k: (round(v, 2) if isinstance(v, float) else v) for k, v in m.items() if k != "latency_us"}
+    return out
+
+
+def run_workload(name, wl, blobs, x, opt, steps, warmup, latency, cache_cap=None):
+    """Warm-up passes, then `steps` timed passes of the whole hot path.  Returns the measurements as a dict."""
+    import torch
+    from paper_2503_02354_amd import binding as B
+    n = wl.n_requests
+    cap = wl.cache_cap_experts if cache_cap is None else cache_cap
+    ctx = B.Context(max_requests=n, max_stages=wl.max_stages, max_batch=opt["max_batch"], cache_cap_experts=cap,
+                    profile=opt["profile_every"], group_small=opt["group_small"],
+                    eviction=["two-stage", "lru", "fifo"].index(opt.get("eviction", "two-stage")),
+                    prefetch_depth=opt["prefetch_depth"], executors=opt["executors"])
+    B.setup_workload(ctx, wl, blobs)
+    for a, arch_a in enumerate(wl.archs):
+        if latency and arch_a.name in latency:
+            m = latency[arch_a.name]
+            ctx.coe_set_latency_model(a, int(max(m["K_us"], 0) * 1e3), int(max(m["B_us"], 0) * 1e3), int(m["load_us"] * 1e3))
+    window = [int(v) for v in opt["arrange"].split(",")] if opt["arrange"] else None
+    if window:
+        assert len(window) == 3, "--arrange takes min_resident,min_missing,max_wait"
+        for a in range(len(wl.archs)):
+            ctx.coe_set_arranging(a, *window)
+    dev = torch.from_numpy(x.view(np.int16)).cuda()
+    torch.cuda.synchronize()
+    per = x[0].nbytes
+    arrival = wl.arrival_batch or n
+    aps = max(opt.get("arrivals_per_step", 1), 1)
+    step_stats = []
+
+    def one_pass():
+        # requests arrive in batches of `arrival`; every arrival is followed by one stage over everything pending
+        for k, s0 in enumerate(range(0, n, arrival)):
+            m = min(arrival, n - s0)
+            ctx.coe_submit(m, dev.data_ptr() + s0 * per, True, None if wl.first_expert is None else wl.first_expert[s0:s0 + m])
+            if (k + 1) % aps and s0 + arrival < n:
+                continue
+            rc, st = ctx.coe_step()
+            step_stats.append(st)
+        # without a window the graph's depth bounds the steps left (no empty probing step after them); with one, groups
+        # may still be waiting: step until the queue is empty
+        for _ in range(wl.max_stages - 1 if not window else 10 ** 6):
+            rc, st = ctx.coe_step()
+            if rc == B.COE_DONE:
+                break
+            step_stats.append(st)
+        ids, logits, path = ctx.coe_collect(n)
+        assert len(ids) == n, f"only {len(ids)} of {n} requests finished"
+        return path[np.argsort(ids)]
+
+    for _ in range(warmup):
+        path = one_pass()
+    ctx.coe_sync()
+    for k in range(len(B.KERNEL_CLASS_NAMES)):
+        ctx.coe_profile_read(k)            # drop warm-up spans
+        ctx.coe_profile_issued(k)
+    torch.cuda.synchronize()
+    step_stats.clear()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        path = one_pass()
+    ctx.coe_sync()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / max(steps, 1)
+
+    prof = {}
+    if opt["profile_every"]:
+        for k, kname in enumerate(B.KERNEL_CLASS_NAMES):
+            launches, ms, work = ctx.coe_profile_read(k)
+            issued = ctx.coe_profile_issued(k)
+            if launches:
+                prof[kname] = {"launches": launches, "ms": round(ms, 3), "work": work, "issued": issued}
+    ctx.close()
+    del dev
+    torch.cuda.empty_cache()
+
+    # (FLOPs of the experts every request actually visited, from the collected paths)
+    macs_of = [arch_macs(wl.archs[wl.expert_arch[e]]) for e in range(wl.graph.n_experts)]
+    visits = np.bincount(path[path >= 0].ravel(), minlength=wl.graph.n_experts)
+    flops_per_step = 2.0 * float(np.dot(visits, macs_of))
+    # the matrix-core convolution classes; the roofline object is for the one that takes the most time
+    mfma_kernels = {"conv_slab": "conv3x3_slab_kernel", "conv_mfma": "conv_igemm_dma_kernel", "attention": "attention_kernel"}
+    est_ms = {k: prof[k]["ms"] / prof[k]["launches"] * prof[k]["issued"] for k in mfma_kernels if k in prof}
+    roofline = None
+    if est_ms:
+        dom = max(est_ms, key=est_ms.get)
+        p = prof[dom]
+        achieved = p["work"] / (p["ms"] * 1e-3) / 1e12
+        traffic, traffic_source = measured_traffic(mfma_kernels[dom], (name, opt.get("requests", 0), opt["max_batch"], opt["group_small"],
+                                                                       aps, opt["arrange"]))
+        roofline = {"bound": "mfma", "kernel": mfma_kernels[dom], "achieved": round(achieved, 2),
+                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                    "traffic": traffic, "traffic_unit": "HBM bytes per launch", "traffic_source": traffic_source,
+                    "launches_timed": p["launches"], "launches": p["issued"],
+                    "avg_launch_us": round(p["ms"] * 1e3 / p["launches"], 2),
+                    "share_of_step": round(est_ms[dom] / steps / ms_per_step, 3)}
+    classes = {}
+    for kname in ("conv_slab", "conv_mfma", "attention", "token_ops", "regroup_gather", "switch", "pool", "conv_stem",
+                  "conv_direct", "head", "regroup_index"):
+        if kname in prof:
+            p = prof[kname]
+            # timed launches are every k-th of the class: scale their mean to all launches
+            entry = {"ms_per_step": round(p["ms"] / p["launches"] * p["issued"] / steps, 3),
+                     "launches_per_step": p["issued"] // max(steps, 1)}
+            if kname in ("regroup_gather", "pool", "switch", "token_ops"):
+                entry["GB/s"] = round(p["work"] / (p["ms"] * 1e-3) / 1e9, 1) if p["ms"] > 0 else None
+            if kname in ("conv_direct", "conv_stem", "conv_slab", "conv_mfma", "attention"):
+                entry["TFLOP/s"] = round(p["work"] / (p["ms"] * 1e-3) / 1e12, 2)
+            classes[kname] = entry
+    # expert cache: switches of the timed region (copy-stream events bracket every H2D copy) and the host planning time
+    misses = sum(st.n_misses for st in step_stats)
+    cache = {"cap_experts": cap, "replacement": opt.get("eviction", "two-stage"), "prefetch_depth": opt["prefetch_depth"],
+             "switches_per_pass": misses // max(steps, 1),
+             "evictions_per_pass": sum(st.n_evictions for st in step_stats) // max(steps, 1),
+             "bytes_switched_per_pass": sum(st.bytes_switched for st in step_stats) // max(steps, 1),
+             "host_plan_us_per_step": round(float(np.mean([st.host_plan_us for st in step_stats])), 1),
+             "device_allocations_in_steps": int(sum(st.n_device_allocs for st in step_stats))}
+    if "switch" in prof:
+        sw = prof["switch"]
+        copy_ms = sw["ms"] / sw["launches"] * sw["issued"] / steps
+        cache["switch_GB/s"] = round(sw["work"] / (sw["ms"] * 1e-3) / 1e9, 1)
+        cache["copy_ms_per_pass"] = round(copy_ms, 2)
+        cache["copy_share_of_pass"] = round(copy_ms / ms_per_step, 3)
+    leaves = np.bincount(path[:, 1][path[:, 1] >= 0], minlength=wl.graph.n_experts)[1:]
+    return {
+        "value": n * steps / elapsed, "ms_per_step": ms_per_step, "path": path, "flops_per_step": flops_per_step,
+        "roofline": roofline, "kernel_classes": classes, "expert_cache": cache, "window": window, "arrival": arrival,
+        "grouped_launches": {
+            "groups_per_pass": sum(st.n_groups for st in step_stats) // max(steps, 1),
+            "of_them_in_shared_launches": sum(st.n_grouped for st in step_stats) // max(steps, 1),
+            "shared_launch_sequences": sum(st.n_group_sets for st in step_stats) // max(steps, 1)},
+        "arranging": None if not window else {
+            "steps_per_pass": len(step_stats) // max(steps, 1),
+            "group_waits_per_pass": sum(st.n_deferred_groups for st in step_stats) // max(steps, 1),
+            "request_waits_per_pass": sum(st.n_deferred_requests for st in step_stats) // max(steps, 1)},
+        "leaf_group_sizes": {"min": int(leaves.min()), "max": int(leaves.max())},
+    }
+
+
+def capped_leg(name, steps, warmup):
+    """One of the workloads with a capped expert cache, at its full shape, outside the timed region of the benchmark line:
+    throughput, expert-switch bandwidth from pinned host memory, how much of the copy time hides under compute (the same
+    pass with every expert resident has no switches: whatever the capped pass takes longer is the exposed part of the copy
+    time), switches per pass, and the regroup gather's bandwidth where the gather is a copy."""
+    wl, blobs, x, t_gen = make_workload(name)
+    latency = measure_latency_models(wl, blobs)
+    opt = dict(DEFAULTS[name])
+    r = run_workload(name, wl, blobs, x, opt, steps, warmup, latency)
+    free = run_workload(name, wl, blobs, x, dict(opt, profile_every=0), steps, warmup, latency, cache_cap=0)
+    c = r["expert_cache"]
+    copy_ms = c.get("copy_ms_per_pass", 0.0)
+    exposed = max(0.0, r["ms_per_step"] - free["ms_per_step"])
+    out = {"workload": WORKLOAD_TEXT[name], "requests_per_s": round(r["value"], 1), "ms_per_pass": round(r["ms_per_step"], 2),
+           "ms_per_pass_all_experts_resident": round(free["ms_per_step"], 2),
+           "switches_per_pass": c["switches_per_pass"], "bytes_switched_per_pass": c["bytes_switched_per_pass"],
+           "switch_GB/s": c.get("switch_GB/s"), "copy_ms_per_pass": copy_ms,
+           "copy_hidden_under_compute": None if copy_ms <= 0 else round(max(0.0, 1.0 - exposed / copy_ms), 3),
+           "host_plan_us_per_step": c["host_plan_us_per_step"], "device_allocations_in_steps": c["device_allocations_in_steps"],
+           "regroup_gather_GB/s": r["kernel_classes"].get("regroup_gather", {}).get("GB/s"),
+           "regroup_gather": "inside the first convolution kernel (row table): no bytes of its own" if "regroup_gather" not in r["kernel_classes"] else "copy kernel",
+           "end_to_end_tflops": round(r["flops_per_step"] / (r["ms_per_step"] * 1e-3) / 1e12, 2),
+           "dominant_kernel": None if not r["roofline"] else {k: r["roofline"][k] for k in ("kernel", "achieved", "frac", "share_of_step")},
+           "schedule": {"arranging_window": r["window"], "prefetch_depth": opt["prefetch_depth"], "executors": opt["executors"],
+                        "max_batch": opt["max_batch"]},
+           "latency_model": latency, "input_generation_s": round(t_gen, 1)}
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -96,7 +302,7 @@ def main():
     ap.add_argument("--group-small", type=int, default=None,
                     help="groups of at most this many requests share launches (default: 512 for config2 / config4, so the "
                          "leaf groups of a stage run as one launch per layer; otherwise 0 = the library's default; -1 = never)")
-    ap.add_argument("--arrange", default="",
+    ap.add_argument("--arrange", default=None,
                     help="arranging window 'min_resident,min_missing,max_wait' for every architecture: a queued group "
                          "smaller than min_resident (expert on the device) or min_missing (expert missing) waits up to "
                          "max_wait steps for later arrivals to join it.  Default: '0,43,8' for config3 (requests arrive in "
@@ -116,206 +322,93 @@ def main():
                          "launches of the other workloads gain 0-3 %%")
     ap.add_argument("--no-profile", action="store_true", help="do not time kernel classes with events")
     ap.add_argument("--profile-every", type=int, default=0,
-                    help="time every k-th launch of each kernel class (0 = every launch for config2 / config4, whose steps "
+                    help="time every k-th launch of each kernel class (0 = every launch for config2, whose steps "
                          "are a few dozen large launches; 7 otherwise: an event pair costs a pipeline bubble, and 7 is "
                          "coprime to the launches per forward, so every layer shape is sampled)")
+    ap.add_argument("--capped-legs", default=None,
+                    help="comma-separated workloads with a capped expert cache that run after the timed region, one warm-up "
+                         "and one timed pass each, and ride in the same JSON line (expert-switch GB/s, share of the copy time "
+                         "hidden under compute, switches per pass, regroup gather GB/s).  Default: 'config3,config5' when the "
+                         "benchmark line is config2 at its full size, else none; 'none' switches them off")
     args = ap.parse_args()
-    big = args.workload in ("config2", "config4")
-    if args.max_batch == 0:
-        args.max_batch = 4096 if big else 512
-    if args.group_small is None:
-        args.group_small = 512 if big else 0
-    if args.profile_every == 0:
-        args.profile_every = 1 if args.workload == "config2" else 7
-    if args.arrange == "":
-        args.arrange = "0,43,8" if args.workload == "config3" else "off"
-    if args.arrange == "off":
-        args.arrange = ""
-    if args.executors == 0:
-        args.executors = 3 if args.workload == "config3" else 1
-    if args.prefetch_depth < 0:
-        args.prefetch_depth = {"config3": 4, "config5": 2}.get(args.workload, 0)
     if args.gpus != 1:
         print("bench.py runs on exactly one GPU: the library has no multi-GPU path (--gpus 1 only)", file=sys.stderr)
         sys.exit(2)
+    opt = dict(DEFAULTS[args.workload])
+    if args.max_batch:
+        opt["max_batch"] = args.max_batch
+    if args.group_small is not None:
+        opt["group_small"] = args.group_small
+    if args.profile_every:
+        opt["profile_every"] = args.profile_every
+    if args.no_profile:
+        opt["profile_every"] = 0
+    if args.arrange is not None:
+        opt["arrange"] = "" if args.arrange == "off" else args.arrange
+    if args.executors:
+        opt["executors"] = args.executors
+    if args.prefetch_depth >= 0:
+        opt["prefetch_depth"] = args.prefetch_depth
+    opt["eviction"] = args.eviction
+    opt["arrivals_per_step"] = args.arrivals_per_step
+    opt["requests"] = args.requests
+    if args.capped_legs is None:
+        args.capped_legs = "config3,config5" if (args.workload == "config2" and not args.requests) else "none"
+    legs = [] if args.capped_legs in ("none", "") else args.capped_legs.split(",")
 
     import torch
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
-    from paper_2503_02354_amd import binding as B
-    import coe_workloads as W
 
-    make = {"config2": W.config2, "config3": W.config3, "config4": W.config4, "config5": W.config5}[args.workload]
-    wl = make(args.requests) if args.requests else make()
+    wl, blobs, x, t_gen = make_workload(args.workload, args.requests)
     n = wl.n_requests
-    arch = wl.archs[0]
-    t0 = time.time()
-    from concurrent.futures import ThreadPoolExecutor
-    with ThreadPoolExecutor(8) as ex:
-        blobs = list(ex.map(wl.blob, range(wl.graph.n_experts)))
-    x = wl.inputs(range(n))
-    t_gen = time.time() - t0
-
-    ctx = B.Context(max_requests=n, max_stages=wl.max_stages, max_batch=args.max_batch,
-                    cache_cap_experts=wl.cache_cap_experts, profile=0 if args.no_profile else args.profile_every,
-                    group_small=args.group_small, eviction=["two-stage", "lru", "fifo"].index(args.eviction), prefetch_depth=args.prefetch_depth, executors=args.executors)
-    B.setup_workload(ctx, wl, blobs)
-    # latency models from the offline profiler on this GPU (ns per request, ns per launch sequence, ns per expert load)
-    LATENCY = {"resnet18": (3830, 886000, 408000), "resnet50": (14410, 1611000, 846000)}
-    for a, arch_a in enumerate(wl.archs):
-        if arch_a.name in LATENCY:
-            ctx.coe_set_latency_model(a, *LATENCY[arch_a.name])
-    window = [int(v) for v in args.arrange.split(",")] if args.arrange else None
-    if window:
-        assert len(window) == 3, "--arrange takes min_resident,min_missing,max_wait"
-        for a in range(len(wl.archs)):
-            ctx.coe_set_arranging(a, *window)
-    dev = torch.from_numpy(x.view(np.int16)).cuda()
-    torch.cuda.synchronize()
-
-    per = x[0].nbytes
-    arrival = wl.arrival_batch or n
-    step_stats = []
-
-    def one_step():
-        # requests arrive in batches of `arrival`; every arrival is followed by one stage over everything pending
-        steps_run = 0
-        for k, s0 in enumerate(range(0, n, arrival)):
-            m = min(arrival, n - s0)
-            ctx.coe_submit(m, dev.data_ptr() + s0 * per, True, None if wl.first_expert is None else wl.first_expert[s0:s0 + m])
-            if (k + 1) % max(args.arrivals_per_step, 1) and s0 + arrival < n:
-                continue
-            rc, st = ctx.coe_step()
-            step_stats.append(st)
-            steps_run += 1
-        # without a window the graph's depth bounds the steps left (no empty probing step after them); with one, groups
-        # may still be waiting: step until the queue is empty
-        for _ in range(wl.max_stages - 1 if not window else 10 ** 6):
-            rc, st = ctx.coe_step()
-            if rc == B.COE_DONE:
-                break
-            step_stats.append(st)
-        ids, logits, path = ctx.coe_collect(n)
-        assert len(ids) == n, f"only {len(ids)} of {n} requests finished"
-        order = np.argsort(ids)
-        return path[order]
-
-    for _ in range(args.warmup):
-        path = one_step()
-    ctx.coe_sync()
-    for k in range(len(B.KERNEL_CLASS_NAMES)):
-        ctx.coe_profile_read(k)            # drop warm-up spans
-        ctx.coe_profile_issued(k)
-    torch.cuda.synchronize()
-    step_stats.clear()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        path = one_step()
-    ctx.coe_sync()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / max(args.steps, 1)
-    value = n * args.steps / elapsed
-
-    prof = {}
-    if not args.no_profile:
-        for k, name in enumerate(B.KERNEL_CLASS_NAMES):
-            launches, ms, work = ctx.coe_profile_read(k)
-            issued = ctx.coe_profile_issued(k)
-            if launches:
-                prof[name] = {"launches": launches, "ms": round(ms, 3), "work": work, "issued": issued}
-    # (FLOPs of the experts every request actually visited, from the collected paths)
-    macs_of = [arch_macs(wl.archs[wl.expert_arch[e]]) for e in range(wl.graph.n_experts)]
-    # the matrix-core convolution classes; the roofline object is for the one that takes the most time
-    mfma_kernels = {"conv_slab": "conv3x3_slab_kernel", "conv_mfma": "conv_igemm_dma_kernel", "attention": "attention_kernel"}
-    est_ms = {name: prof[name]["ms"] / prof[name]["launches"] * prof[name]["issued"] for name in mfma_kernels if name in prof}
-    roofline = None
-    if est_ms:
-        dom = max(est_ms, key=est_ms.get)
-        p = prof[dom]
-        achieved = p["work"] / (p["ms"] * 1e-3) / 1e12
-        roofline = {"bound": "mfma", "kernel": mfma_kernels[dom], "achieved": round(achieved, 2),
-                    "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "traffic": measured_traffic(mfma_kernels[dom], (args.workload, args.requests, args.max_batch, args.group_small,
-                                                                              args.arrivals_per_step, args.arrange)),
-                    "traffic_unit": "HBM bytes per launch",
-                    "launches_timed": p["launches"], "launches": p["issued"],
-                    "avg_launch_us": round(p["ms"] * 1e3 / p["launches"], 2),
-                    "share_of_step": round(est_ms[dom] / args.steps / ms_per_step, 3)}
-    other = {}
-    for name in ("conv_slab", "conv_mfma", "attention", "token_ops", "regroup_gather", "switch", "pool", "conv_stem",
-                 "conv_direct", "head", "regroup_index"):
-        if name in prof:
-            p = prof[name]
-            # timed launches are every k-th of the class: scale their mean to all launches
-            entry = {"ms_per_step": round(p["ms"] / p["launches"] * p["issued"] / args.steps, 3),
-                     "launches_per_step": p["issued"] // max(args.steps, 1)}
-            if name in ("regroup_gather", "pool", "switch", "token_ops"):
-                entry["GB/s"] = round(p["work"] / (p["ms"] * 1e-3) / 1e9, 1) if p["ms"] > 0 else None
-            if name in ("conv_direct", "conv_stem", "conv_slab", "conv_mfma", "attention"):
-                entry["TFLOP/s"] = round(p["work"] / (p["ms"] * 1e-3) / 1e12, 2)
-            other[name] = entry
-
-    leaves = np.bincount(path[:, 1][path[:, 1] >= 0], minlength=wl.graph.n_experts)[1:]
-    visits = np.bincount(path[path >= 0].ravel(), minlength=wl.graph.n_experts)
-    flops_per_step = 2.0 * float(np.dot(visits, macs_of))
-
-    # expert cache: switches of the timed region (copy-stream events bracket every H2D copy) and the host planning time
-    cache = None
-    if step_stats:
-        misses = sum(st.n_misses for st in step_stats)
-        cache = {"cap_experts": wl.cache_cap_experts, "replacement": args.eviction, "prefetch_depth": args.prefetch_depth, "switches_per_pass": misses // max(args.steps, 1),
-                 "evictions_per_pass": sum(st.n_evictions for st in step_stats) // max(args.steps, 1),
-                 "bytes_switched_per_pass": sum(st.bytes_switched for st in step_stats) // max(args.steps, 1),
-                 "host_plan_us_per_step": round(float(np.mean([st.host_plan_us for st in step_stats])), 1)}
-        if "switch" in prof:
-            sw = prof["switch"]
-            copy_ms = sw["ms"] / sw["launches"] * sw["issued"] / args.steps
-            cache["switch_GB/s"] = round(sw["work"] / (sw["ms"] * 1e-3) / 1e9, 1)
-            cache["copy_ms_per_pass"] = round(copy_ms, 2)
-            cache["copy_share_of_pass"] = round(copy_ms / ms_per_step, 3)
+    latency = measure_latency_models(wl, blobs)        # the offline profiler, in this run, on this GPU
+    r = run_workload(args.workload, wl, blobs, x, opt, args.steps, args.warmup, latency)
+    path, ms_per_step, flops_per_step = r["path"], r["ms_per_step"], r["flops_per_step"]
 
     cpu = None
     if args.cpu_sample > 0:
         from oracle import oracle as O
         m = min(args.cpu_sample, n)
         t0 = time.perf_counter()
-        ref = O.run_chain(wl.archs, wl.expert_arch, blobs, wl.graph.succ_off, wl.graph.succ, x[:m], None, wl.max_stages,
-                          wl.max_classes)
+        ref = O.run_chain(wl.archs, wl.expert_arch, blobs, wl.graph.succ_off, wl.graph.succ, x[:m],
+                          None if wl.first_expert is None else wl.first_expert[:m], wl.max_stages, wl.max_classes)
         dt = time.perf_counter() - t0
         agree = float(np.mean((ref["path"] == path[:m]).all(axis=1)))
         cpu = {"value": round(m / dt, 3), "unit": "requests/s", "cores": O.threads(), "kind": "oracle",
                "sample": f"first {m} requests of the same workload, full {wl.max_stages}-stage chain, {dt:.1f}s",
                "route_agreement_unguarded": round(agree, 4)}
+    del x, blobs
+    capped = {}
+    for leg in legs:
+        capped[leg] = capped_leg(leg, 1, 1)
 
+    window = r["window"]
     out = {
-        "metric": "requests/s through a multi-stage CoE chain (1 GPU)", "value": round(value, 1), "unit": "requests/s",
+        "metric": "requests/s through a multi-stage CoE chain (1 GPU); MFMA util; expert-switch GB/s", "value": round(r["value"], 1),
+        "unit": "requests/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 3),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": WORKLOAD_TEXT[args.workload], "requests": n, "arrival_batch": arrival,
-                   "arrivals_per_step": args.arrivals_per_step, "max_batch": args.max_batch, "executors": args.executors,
+        "config": {"workload": WORKLOAD_TEXT[args.workload], "requests": n, "arrival_batch": r["arrival"],
+                   "arrivals_per_step": args.arrivals_per_step, "max_batch": opt["max_batch"], "executors": opt["executors"],
                    "arranging_window": None if not window else {"min_group_resident": window[0], "min_group_missing": window[1],
                                                                 "max_wait_steps": window[2]},
                    "stages": wl.max_stages, "gflop_per_request": round(flops_per_step / n / 1e9, 3)},
         "end_to_end_tflops": round(flops_per_step / (ms_per_step * 1e-3) / 1e12, 2),
         "end_to_end_frac_of_bf16_peak": round(flops_per_step / (ms_per_step * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
-        "roofline": roofline, "kernel_classes": other, "expert_cache": cache,
-        "grouped_launches": None if not step_stats else {
-            "groups_per_pass": sum(st.n_groups for st in step_stats) // max(args.steps, 1),
-            "of_them_in_shared_launches": sum(st.n_grouped for st in step_stats) // max(args.steps, 1),
-            "shared_launch_sequences": sum(st.n_group_sets for st in step_stats) // max(args.steps, 1)},
-        "arranging": None if not (step_stats and window) else {
-            "steps_per_pass": len(step_stats) // max(args.steps, 1),
-            "group_waits_per_pass": sum(st.n_deferred_groups for st in step_stats) // max(args.steps, 1),
-            "request_waits_per_pass": sum(st.n_deferred_requests for st in step_stats) // max(args.steps, 1)},
+        "mfma_util": None if not r["roofline"] else r["roofline"]["frac"],
+        "expert_switch_GB/s": {k: v["switch_GB/s"] for k, v in capped.items()} or r["expert_cache"].get("switch_GB/s"),
+        "roofline": r["roofline"], "kernel_classes": r["kernel_classes"], "expert_cache": r["expert_cache"],
+        "latency_model": latency,
+        "grouped_launches": r["grouped_launches"], "arranging": r["arranging"],
+        "capped_cache_legs": capped or None,
         "cpu_baseline": cpu,
-        "leaf_group_sizes": {"min": int(leaves.min()), "max": int(leaves.max())},
+        "leaf_group_sizes": r["leaf_group_sizes"],
         "input_generation_s": round(t_gen, 1),
         "paper_context": "the paper reports 4.5x-12x throughput over prior systems (Samba-CoE variants) on an RTX 3080Ti/"
                          "Xeon Silver 4214R box and an Apple M2 - context only",
     }
-    ctx.close()
     print(json.dumps(out))
 
 
