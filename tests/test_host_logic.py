@@ -198,15 +198,23 @@ def test_decay_window_search_reproduces_the_printed_case(B):
     28 to 39, reached when the third throughput falls 7.7 % short of the line through the first two.  Oracle twin and
     library both have to land there."""
     from oracle import profiler_oracle as PO
-    assert [round(v, 4) for k in range(3) for v in PO.window_bounds(15.0, k)] == [0, 15, 15, 27.75, 27.75, 38.5875]
+    gold = {}
+    for line in open(os.path.join(ROOT, "tests", "golden", "section_5_4_memory_window.txt")):
+        if "=" in line and not line.startswith("#"):
+            k, v = line.split("=")
+            gold[k.strip()] = float(v)
+    w0, margin, total = gold["initial_window"], gold["error_margin"], int(gold["n_experts"])
+    lo, hi, lin = int(gold["final_window_low_experts"]), int(gold["final_window_high_experts"]), gold["linear_error"]
+    assert (w0, margin, total, lo, hi, lin) == (15, 0.05, 352, 28, 39, 0.077)
+    assert [round(v, 4) for k in range(3) for v in PO.window_bounds(w0, k)] == [0, 15, 15, 27.75, 27.75, 38.5875]
     # throughputs 20 and 24 at 15 and 28 experts: the line predicts 28 at the third point; 7.7 % short of that is 25.844
-    curve = {15: 20.0, 28: 24.0, 39: 28.0 * (1 - 0.077)}
-    ref = PO.decay_window_search(352, lambda n: curve[n], 15.0, 0.05)
-    assert ref["loaded"] == [15, 28, 39] and ref["experts"] == (28, 39) and ref["stopped_by"] == "shortfall"
-    assert abs(ref["linear_error"] - 0.077) < 1e-12
-    st, loaded, ts = _run_window_search(B, 352, lambda n: curve[n], 15.0, 0.05)
-    assert loaded == [15, 28, 39] and (st.n_low, st.n_high) == (28, 39) and st.status == B.COE_WINDOW_SHORTFALL
-    assert abs(st.window_low - 27.75) < 1e-9 and abs(st.window_high - 38.5875) < 1e-9 and abs(st.linear_error - 0.077) < 1e-9
+    curve = {15: 20.0, 28: 24.0, 39: 28.0 * (1 - lin)}
+    ref = PO.decay_window_search(total, lambda n: curve[n], w0, margin)
+    assert ref["loaded"] == [15, lo, hi] and ref["experts"] == (lo, hi) and ref["stopped_by"] == "shortfall"
+    assert abs(ref["linear_error"] - lin) < 1e-12
+    st, loaded, ts = _run_window_search(B, total, lambda n: curve[n], w0, margin)
+    assert loaded == [15, lo, hi] and (st.n_low, st.n_high) == (lo, hi) and st.status == B.COE_WINDOW_SHORTFALL
+    assert abs(st.window_low - 27.75) < 1e-9 and abs(st.window_high - 38.5875) < 1e-9 and abs(st.linear_error - lin) < 1e-9
     # a shortfall inside the margin (4 %) does not stop the slide: the fourth window is 38.5875..47.799 = experts 39 to 48
     curve = {15: 20.0, 28: 24.0, 39: 28.0 * 0.96, 48: 10.0}
     st, loaded, ts = _run_window_search(B, 352, lambda n: curve[n], 15.0, 0.05)
