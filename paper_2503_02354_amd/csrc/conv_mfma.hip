@@ -691,8 +691,15 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_slab_kernel
     constexpr int B_STAGE = FB * FRAG;
     constexpr int SPARE = 2 * SLAB;                                       // 1 KiB that absorbs the padding loads
     constexpr int B_BASE = SPARE + FRAG;
+    // 64-row wave tiles have registers for two sets of operands: ALL operands of step u + 1 (filters too) are read while
+    // step u is multiplied, so after a step's barrier the matrix cores start at once instead of waiting for the filter
+    // reads.  A wave then keeps its SIMD's matrix core busy on its own, which matters whenever the other workgroup of the
+    // compute unit is in its epilogue.  The filters then have to be in LDS one step earlier: four stages, loads three
+    // steps ahead.
+    constexpr bool kDeep = MB <= 2;
+    constexpr int kStagesB = kDeep ? 4 : 3;
 
-    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // 2 slabs | spare block | 3 filter stages
+    extern __shared__ __attribute__((aligned(16))) uint16_t lds[];   // 2 slabs | spare block | 3 or 4 filter stages
 
     int tile;
     {
@@ -745,6 +752,7 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_slab_kernel
         b_off[j] = (uint32_t)((((n0 / 32 + fb / KS) * ks16_total + fb % KS) * FRAG + lane * 8) * 2);
     }
     auto issue_b = [&](int cb, int tap, int stage) {
+        if (tap >= kTaps) { tap -= kTaps; ++cb; }
         if (cb >= cblocks) { cb = cblocks - 1; tap = kTaps - 1; }          // past the end: re-read the last step
         const uint32_t wstep = (uint32_t)((tap * cblocks + cb) * KS) * (FRAG * 2);
 #pragma unroll
@@ -761,13 +769,17 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_slab_kernel
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
-    // prologue: the whole first slab, then filters of steps 0 and 1 with one padding load between them so that the
-    // order of outstanding loads is the steady-state one (slab piece, filters, slab piece, filters)
+    // prologue: the whole first slab, then filters of steps 0 and 1 (and 2) with one padding load between them so that
+    // the order of outstanding loads is the steady-state one (slab piece, filters, slab piece, filters)
 #pragma unroll
     for (int t = 0; t < (SB_CAP + NW - 1) / NW; ++t) issue_slab(0, t, 0);
     issue_b(0, 0, 0);
     issue_slab(cblocks, 8, 0);                                              // lands in the spare block
     issue_b(0, 1, 1);
+    if (kDeep) {
+        issue_slab(cblocks, 8, 0);
+        issue_b(0, 2, 2);
+    }
 
     // (built while the first loads are in flight)
     // operand addresses (elements, relative to a slab buffer) of this lane's pixel rows for the nine positions.
@@ -807,6 +819,83 @@ __global__ __launch_bounds__(64 * WAVES_M * WAVES_N, 2) void conv3x3_slab_kernel
     // tiles there are no registers left for that; there the reads of the second 16-channel half are slipped between
     // the matrix-core instructions of the first.)
     constexpr bool kAhead = MB <= 2;
+    if constexpr (kDeep) {
+        bf16x8 af[2][KS][MB], bfr[2][KS][NB];   // [step parity]
+        auto read_a = [&](int par, const uint16_t* slab, int tap) {
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int i = 0; i < MB; ++i) af[par][ks][i] = *(const bf16x8*)(slab + (a_addr[i][tap] ^ (ks * 16)));
+        };
+        auto read_b = [&](int par, int stage) {
+            const uint16_t* b_lds = lds + B_BASE + stage * B_STAGE + (wn * NB * KS) * FRAG + lane * 8;
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int j = 0; j < NB; ++j) bfr[par][ks][j] = *(const bf16x8*)(b_lds + (j * KS + ks) * FRAG);
+        };
+        // operands of step 0: its filters and the first slab have landed when all but the newest two steps' loads have
+        wait_before_barrier<2 * (1 + B_PER_WAVE)>();
+        __builtin_amdgcn_s_barrier();
+        read_a(0, lds, 0);
+        read_b(0, 0);
+        static_assert(SB_CAP <= 7 * NW, "the next slab is complete one step before its first operands are read ahead");
+        int stage_rd = 1, stage_ld = 3;          // stage of the NEXT step's filters; stage the loads three steps ahead go to
+        // one step; TAP and the register set CUR of its operands are compile-time (a channel block has nine positions, so
+        // the sets swap roles from one block to the next: blocks are walked in pairs)
+        auto step = [&](auto tap_c, auto cur_c, int cb) {
+            constexpr int tap = decltype(tap_c)::value, cur = decltype(cur_c)::value, nxt = cur ^ 1;
+            constexpr int kReads = KS * MB + KS * NB, kMfma = KS * MB * NB;
+            const bool more = cb + 1 < cblocks;
+            // the filters of the next step (and, at a channel block's last position, the whole next slab: its last piece
+            // was issued at least two steps ago) have landed; only this wave's newest loads may still be in flight
+            wait_before_barrier<1 + B_PER_WAVE>();
+            __builtin_amdgcn_s_barrier();
+            issue_slab(cb + 1, tap, (cb + 1) & 1);
+            issue_b(cb, tap + 3, stage_ld);
+            // operands of the next step: next position of this channel block, or position 0 of the next block
+            if (tap + 1 < kTaps) { read_a(nxt, lds + (cb & 1) * SLAB, tap + 1); read_b(nxt, stage_rd); }
+            else if (more) { read_a(nxt, lds + ((cb + 1) & 1) * SLAB, 0); read_b(nxt, stage_rd); }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+                for (int i = 0; i < MB; ++i)
+#pragma unroll
+                    for (int j = 0; j < NB; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(bfr[cur][ks][j], af[cur][ks][i], acc[i][j], 0, 0, 0);
+            // issue order inside the step (0x100 = LDS read, 0x008 = matrix core): matrix-core instructions from the start,
+            // the next step's operand reads slipped in between them one by one
+            if (tap + 1 < kTaps || more) {
+#pragma unroll
+                for (int t = 0; t < (kReads < kMfma ? kReads : kMfma); ++t) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                if (kReads > kMfma) __builtin_amdgcn_sched_group_barrier(0x100, kReads - kMfma, 0);
+                if (kReads < kMfma) __builtin_amdgcn_sched_group_barrier(0x008, kMfma - kReads, 0);
+            } else {
+                __builtin_amdgcn_sched_group_barrier(0x008, kMfma, 0);
+            }
+            stage_rd = (stage_rd + 1) & 3;
+            stage_ld = (stage_ld + 1) & 3;
+        };
+        auto block = [&](auto first_c, int cb) {        // the nine positions of channel block cb, starting in register set FIRST
+            constexpr int f = decltype(first_c)::value;
+            step(std::integral_constant<int, 0>{}, std::integral_constant<int, f>{}, cb);
+            step(std::integral_constant<int, 1>{}, std::integral_constant<int, f ^ 1>{}, cb);
+            step(std::integral_constant<int, 2>{}, std::integral_constant<int, f>{}, cb);
+            step(std::integral_constant<int, 3>{}, std::integral_constant<int, f ^ 1>{}, cb);
+            step(std::integral_constant<int, 4>{}, std::integral_constant<int, f>{}, cb);
+            step(std::integral_constant<int, 5>{}, std::integral_constant<int, f ^ 1>{}, cb);
+            step(std::integral_constant<int, 6>{}, std::integral_constant<int, f>{}, cb);
+            step(std::integral_constant<int, 7>{}, std::integral_constant<int, f ^ 1>{}, cb);
+            step(std::integral_constant<int, 8>{}, std::integral_constant<int, f>{}, cb);
+        };
+        for (int cb = 0; cb < cblocks; cb += 2) {
+            block(std::integral_constant<int, 0>{}, cb);
+            if (cb + 1 < cblocks) block(std::integral_constant<int, 1>{}, cb + 1);
+        }
+    } else
     for (int cb = 0; cb < cblocks; ++cb) {
         const uint16_t* slab = lds + (cb & 1) * SLAB;
         bf16x8 af[2][KS][MB];               // [tap parity]
@@ -887,7 +976,8 @@ hipError_t launch_slab(const void* x, const void* wp, const float* bias, const v
     if (total > 0x7FFFFFFFll) return hipErrorInvalidValue;
     if (total == 0) return hipSuccess;
     constexpr int kSbCap = (BM + 2 * kSlabMaxW + 2 + 15) / 16;
-    constexpr size_t kLdsBytes = (2 * (size_t)(kSbCap * 512 + 64) + 512 + 3 * (size_t)BN * 32) * sizeof(uint16_t);
+    constexpr int kStagesB = (BM / WAVES_M) / 32 <= 2 ? 4 : 3;             // as in the kernel: 64-row wave tiles read one step ahead
+    constexpr size_t kLdsBytes = (2 * (size_t)(kSbCap * 512 + 64) + 512 + kStagesB * (size_t)BN * 32) * sizeof(uint16_t);
     constexpr int kThreads = 64 * WAVES_M * WAVES_N;
     static bool configured = false;
     if (!configured) {

@@ -33,6 +33,7 @@ def _valid_paths(path, wl):
 
 
 N_SAMPLE = 512           # requests per full-size workload that the oracle checks one by one
+N_SAMPLE_VIT = 256       # (a ViT-B/16-shaped forward costs the oracle ten times a ResNet-18-shaped one)
 MAX_AMBIGUOUS = 0.05     # share of them the margin guard may leave undecided after its re-draws
 
 
@@ -92,6 +93,7 @@ def _oracle_side(B, wl, n_sample, seed, cover_candidates):
     if key in _ORACLE_SIDE:
         return _ORACLE_SIDE[key]
     from oracle import guard as G
+    G.PROGRESS = lambda done, total: print(f"{wl.name}: oracle {done}/{total}", flush=True)
     n = wl.n_requests
     with ThreadPoolExecutor(8) as ex:
         blobs = list(ex.map(wl.blob, range(wl.graph.n_experts)))
@@ -302,7 +304,7 @@ def test_config5_full_size(B, oracle):
     4096 requests: the 3.4 GB/stage of expert switches overlap the forwards of the groups already resident."""
     wl = W.config5()
     assert wl.head_bias, "calibration file missing"
-    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=N_SAMPLE, max_batch=512, seed=5,
+    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=N_SAMPLE_VIT, max_batch=512, seed=5,
                                                     also=[dict(prefetch_depth=2)])
     stats = [st for rc, st in got["stats"] if rc == B.COE_OK]
     assert len(stats) == 2 and all(st.n_pending == wl.n_requests for st in stats)
