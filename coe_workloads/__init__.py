@@ -28,8 +28,12 @@ Layer descriptor: 12 int32 words
          5 = LAYERNORM over channels; weights gamma[C], beta[C] (fp32), eps 1e-6
          6 = ATTENTION src holds [T][3*D] (q | k | v), aux0 = heads; softmax(q k^T / sqrt(dh)) v
          7 = HEAD_CLS  layer norm of token 0 then FC to k logits
+         8 = CONCAT    dst = [src | res] along channels (same height and width)
+         9 = UPSAMPLE  nearest neighbour, factor 2
+        10 = HEAD_DET  src (and res, if >= 0) are detection maps with aux0 anchors x (5 + k) channels per position:
+                       logits[c] = max over maps, positions, anchors of sigmoid(objectness) * sigmoid(class c); no weights
     src/dst/res are activation buffer ids (0 = the request's input, res -1 = none)
-    act  0 none, 1 ReLU, 2 GELU (erf form)
+    act  0 none, 1 ReLU, 2 GELU (erf form), 3 SiLU
 Architecture header: dtype (0 fp32, 1 bf16), in_h, in_w, in_c, n_classes.
 Weight blob: tensors in layer order, every tensor at a 256-byte aligned offset.
     CONV   W[K][R][S][C] in the arch dtype, then bias[K] fp32
@@ -49,7 +53,8 @@ from typing import Dict, List, Optional, Sequence, Tuple
 import numpy as np
 
 OP_CONV, OP_MAXPOOL, OP_HEAD, OP_TOKENS, OP_LAYERNORM, OP_ATTENTION, OP_HEAD_CLS = 1, 2, 3, 4, 5, 6, 7
-ACT_NONE, ACT_RELU, ACT_GELU = 0, 1, 2
+OP_CONCAT, OP_UPSAMPLE, OP_HEAD_DET = 8, 9, 10
+ACT_NONE, ACT_RELU, ACT_GELU, ACT_SILU = 0, 1, 2, 3
 DT_F32, DT_BF16 = 0, 1
 LAYER_WORDS = 12
 BLOB_ALIGN = 256
@@ -143,6 +148,24 @@ class _Prog:
 
     def head(self, src, n_classes):
         self.layers.append([OP_HEAD, src, -1, -1, n_classes, 0, 0, 0, 0, 0, 0, 0])
+        self.gains.append(1.0)
+
+    def concat(self, a, b, dst):
+        ha, wa, ca = self.shape[a]
+        hb, wb, cb = self.shape[b]
+        assert (ha, wa) == (hb, wb)
+        self.shape[dst] = (ha, wa, ca + cb)
+        self.layers.append([OP_CONCAT, a, dst, b, ca + cb, 0, 0, 0, 0, 0, 0, 0])
+        self.gains.append(1.0)
+
+    def upsample(self, src, dst):
+        h, w, c = self.shape[src]
+        self.shape[dst] = (2 * h, 2 * w, c)
+        self.layers.append([OP_UPSAMPLE, src, dst, -1, c, 0, 0, 0, 0, 0, 0, 0])
+        self.gains.append(1.0)
+
+    def det_head(self, a, b, n_classes, anchors):
+        self.layers.append([OP_HEAD_DET, a, -1, b, n_classes, 0, 0, 0, 0, 0, anchors, 0])
         self.gains.append(1.0)
 
     def raw(self, words, gain=1.0):
@@ -246,6 +269,55 @@ def vit(n_classes: int, hw: int = 224, patch: int = 16, dim: int = 768, depth: i
     return Arch("vit", dtype, hw, hw, 3, n_classes, np.array(p.layers, dtype=np.int32), p.gains)
 
 
+def detector(n_classes: int = 27, hw: int = 224, width: int = 64, anchors: int = 3, dtype: int = DT_BF16) -> Arch:
+    """Detector-shaped expert in the style of the one-stage detectors the paper uses downstream of its classifiers (Section
+    5.1): strided conv stem, cross-stage blocks (two 1x1 branches, a residual bottleneck on one, concatenation, 1x1 fusion),
+    a pooling pyramid (three chained 5x5 max pools, concatenated), a top-down neck (upsample + concatenate with the
+    finer map), 1x1 detection outputs on two scales with `anchors` x (5 + n_classes) channels, SiLU activations.  The
+    expert's logits are its best detection score per class (HEAD_DET).  anchors * (5 + n_classes) must be a multiple of 32."""
+    assert (anchors * (5 + n_classes)) % 32 == 0
+    S = ACT_SILU
+    p = _Prog(hw, hw, 3, n_scratch=7)
+
+    def csp(x, c, keep=()):
+        """cross-stage block on buffer x with c channels; returns the output buffer (x is free afterwards)"""
+        a = p.free_buf([x, *keep]); p.conv(x, a, c // 2, 1, 1, 0, S)
+        b = p.free_buf([x, a, *keep]); p.conv(x, b, c // 2, 1, 1, 0, S)
+        t = p.free_buf([a, b, *keep]); p.conv(a, t, c // 2, 1, 1, 0, S)
+        a2 = p.free_buf([a, b, t, *keep]); p.conv(t, a2, c // 2, 3, 1, 1, S, res=a, gain=RES_BRANCH_GAIN)
+        cat = p.free_buf([a2, b, *keep]); p.concat(a2, b, cat)
+        y = p.free_buf([cat, *keep]); p.conv(cat, y, c, 1, 1, 0, S)
+        return y
+
+    p.conv(0, 1, width, 6, 2, 2, S)                                   # hw/2
+    p.conv(1, 2, 2 * width, 3, 2, 1, S)                               # hw/4
+    x = csp(2, 2 * width)
+    d = p.free_buf([x]); p.conv(x, d, 4 * width, 3, 2, 1, S)          # hw/8
+    p4 = csp(d, 4 * width)                                            # kept for the neck
+    d = p.free_buf([p4]); p.conv(p4, d, 8 * width, 3, 2, 1, S)        # hw/16
+    x = csp(d, 8 * width, keep=(p4,))
+    # pooling pyramid
+    q = p.free_buf([x, p4]); p.conv(x, q, 4 * width, 1, 1, 0, S)
+    m1 = p.free_buf([q, p4]); p.maxpool(q, m1, 5, 1, 2)
+    c1 = p.free_buf([q, m1, p4]); p.concat(q, m1, c1)
+    m2 = p.free_buf([m1, c1, p4]); p.maxpool(m1, m2, 5, 1, 2)
+    c2 = p.free_buf([c1, m2, p4]); p.concat(c1, m2, c2)
+    m3 = p.free_buf([m2, c2, p4]); p.maxpool(m2, m3, 5, 1, 2)
+    c3 = p.free_buf([c2, m3, p4]); p.concat(c2, m3, c3)               # 16 * width channels
+    p5 = p.free_buf([c3, p4]); p.conv(c3, p5, 8 * width, 1, 1, 0, S)
+    # neck: coarse map reduced, upsampled, concatenated with the finer one
+    r = p.free_buf([p5, p4]); p.conv(p5, r, 4 * width, 1, 1, 0, S)
+    u = p.free_buf([r, p5, p4]); p.upsample(r, u)
+    cat = p.free_buf([u, p5, p4]); p.concat(u, p4, cat)               # 8 * width channels at hw/8
+    f = p.free_buf([cat, p5]); p.conv(cat, f, 4 * width, 1, 1, 0, S)
+    g = p.free_buf([f, p5]); p.conv(f, g, 4 * width, 3, 1, 1, S)
+    det_c = anchors * (5 + n_classes)
+    d4 = p.free_buf([g, p5]); p.conv(g, d4, det_c, 1, 1, 0, ACT_NONE)
+    d5 = p.free_buf([d4, p5]); p.conv(p5, d5, det_c, 1, 1, 0, ACT_NONE)
+    p.det_head(d4, d5, n_classes, anchors)
+    return Arch("detector", dtype, hw, hw, 3, n_classes, np.array(p.layers, dtype=np.int32), p.gains)
+
+
 # ----------------------------------------------------------------------------
 # shape walk and blob layout
 # ----------------------------------------------------------------------------
@@ -278,6 +350,10 @@ def walk(arch: Arch):
             d = (h, w, c)
         elif op == OP_ATTENTION:
             d = (h, w, c // 3)
+        elif op == OP_CONCAT:
+            d = (h, w, c + shp[res][2])
+        elif op == OP_UPSAMPLE:
+            d = (2 * h, 2 * w, c)
         else:
             d = None
         if d is not None:
@@ -341,7 +417,7 @@ def make_expert_blob(arch: Arch, seed: int, expert_id: int, head_bias: Optional[
             fan_in = n // sp.shape[0]
             if op == OP_CONV:
                 act = int(arch.layers[sp.layer][9])
-                std = math.sqrt((2.0 if act == ACT_RELU or int(arch.layers[sp.layer][3]) >= 0 else 1.0) / fan_in)
+                std = math.sqrt((2.0 if act in (ACT_RELU, ACT_SILU) or int(arch.layers[sp.layer][3]) >= 0 else 1.0) / fan_in)
                 if arch.name == "vit":
                     std = math.sqrt(1.0 / fan_in)
                 std *= arch.gains[sp.layer]
@@ -579,3 +655,35 @@ def config5(n_requests: int = 4096, hw: int = 224, n_experts: int = 32, cap: int
     p = [1.0] + [1.0 / (n_experts - 1)] * (n_experts - 1)
     return Workload(name, 0xC0E5, [a], [0] * n_experts, p, g, n_requests, None, cap, n_requests,
                     load_calibration(name) if calibrated else {}, 2, "structured")
+
+
+def config6(n_requests: int = 4096, hw: int = 224, n_classifiers: int = 4, n_detectors: int = 8, fan: int = 6, width: int = 64,
+            det_width: int = 64, det_classes: int = 27, calibrated: bool = True) -> Workload:
+    """Classifier -> detector DAG in the shape of the paper's own workload (Section 5.1: classification experts decide what a
+    component is, object-detection experts inspect it; several upstream experts share one downstream expert).  Stage 1:
+    `n_classifiers` ResNet-18-shaped classifiers (the first expert of a request follows Zipf(1.2)); each routes `fan` ways to
+    detector-shaped experts drawn from seeded, overlapping windows of the `n_detectors` detectors, which are final: a request's
+    result is its detector's best detection score per class."""
+    e_total = n_classifiers + n_detectors
+    a_cls = resnet18(fan + 2, hw, DT_BF16, width)
+    a_det = detector(det_classes, hw, det_width, 3, DT_BF16)
+    name = "config6" if (hw, n_classifiers, n_detectors, fan, width, det_width) == (224, 4, 8, 6, 64, 64) else \
+        f"config6_hw{hw}_c{n_classifiers}_d{n_detectors}_f{fan}_w{width}_{det_width}"
+    seed = 0xC0E6
+    g = _stream(seed, _KIND_MISC, 1)
+    lists: List[List[int]] = []
+    for i in range(n_classifiers):
+        start = (i * n_detectors) // n_classifiers
+        lists.append([n_classifiers + (start + d + int(g.integers(0, 2))) % n_detectors for d in range(fan)])
+    for _ in range(n_detectors):
+        lists.append([])
+    graph = graph_from_lists(lists)
+    first = _stream(seed, _KIND_MISC, 2).choice(n_classifiers, size=n_requests, p=zipf_probs(n_classifiers, 1.2)).astype(np.int32)
+    prob = np.zeros(e_total)
+    prob[:n_classifiers] = zipf_probs(n_classifiers, 1.2)
+    for e in range(n_classifiers):
+        for s_ in lists[e]:
+            prob[s_] += prob[e] / len(lists[e])
+    return Workload(name, seed, [a_cls, a_det], [0] * n_classifiers + [1] * n_detectors, list(prob), graph, n_requests, first,
+                    0, n_requests, load_calibration(name) if calibrated else {}, 2, "structured")
+

@@ -39,8 +39,9 @@
 #include <omp.h>
 #endif
 
-enum { OP_CONV = 1, OP_MAXPOOL = 2, OP_HEAD = 3, OP_TOKENS = 4, OP_LAYERNORM = 5, OP_ATTENTION = 6, OP_HEAD_CLS = 7 };
-enum { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2 };
+enum { OP_CONV = 1, OP_MAXPOOL = 2, OP_HEAD = 3, OP_TOKENS = 4, OP_LAYERNORM = 5, OP_ATTENTION = 6, OP_HEAD_CLS = 7,
+       OP_CONCAT = 8, OP_UPSAMPLE = 9, OP_HEAD_DET = 10 };
+enum { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU = 2, ACT_SILU = 3 };
 enum { DT_F32 = 0, DT_BF16 = 1 };
 #define LAYER_WORDS 12
 #define BLOB_ALIGN 256
@@ -85,6 +86,7 @@ static double apply_act(double v, int act)
 {
     if (act == ACT_RELU) return v > 0.0 ? v : 0.0;
     if (act == ACT_GELU) return 0.5 * v * (1.0 + erf(v * 0.70710678118654752440));
+    if (act == ACT_SILU) return v / (1.0 + exp(-v));
     return v;
 }
 
@@ -227,6 +229,45 @@ void orc_attention(const float* qkv, int T, int D, int heads, int dtype, float* 
     free(s);
 }
 
+/* ---- detector-shaped experts (the paper's object-detection experts, Section 5.1: a multi-scale backbone whose feature maps
+ * are concatenated, upsampled and read out by per-position detection outputs) ---- */
+/* y[h][w] = [a[h][w] (Ca channels) | b[h][w] (Cb channels)] */
+void orc_concat(const float* a, const float* b, int HW, int Ca, int Cb, float* y)
+{
+    for (int i = 0; i < HW; ++i) {
+        for (int c = 0; c < Ca; ++c) y[(size_t)i * (Ca + Cb) + c] = a[(size_t)i * Ca + c];
+        for (int c = 0; c < Cb; ++c) y[(size_t)i * (Ca + Cb) + Ca + c] = b[(size_t)i * Cb + c];
+    }
+}
+
+/* nearest-neighbour upsampling by two: y[h][w] = x[h / 2][w / 2] */
+void orc_upsample2(const float* x, int H, int W, int C, float* y)
+{
+    for (int h = 0; h < 2 * H; ++h)
+        for (int w = 0; w < 2 * W; ++w)
+            for (int c = 0; c < C; ++c) y[((size_t)h * 2 * W + w) * C + c] = x[((size_t)(h / 2) * W + w / 2) * C + c];
+}
+
+/* Detection read-out.  A detection map holds, per position, `anchors` boxes of (5 + ncls) values: 4 box terms, one
+ * objectness logit, ncls class logits.  The expert's output for class c is its best detection of that class anywhere:
+ * logits[c] = max over maps, positions and anchors of sigmoid(objectness) * sigmoid(class c), computed in fp64 from the
+ * stored map values and cast to fp32 once.  (A maximum has no accumulation order: the value is exact on any device.) */
+void orc_det_head(const float* const* maps, const int* map_hw, int n_maps, int anchors, int ncls, float* logits)
+{
+    int stride = anchors * (5 + ncls);
+    for (int c = 0; c < ncls; ++c) {
+        double best = 0.0;
+        for (int m = 0; m < n_maps; ++m)
+            for (int i = 0; i < map_hw[m]; ++i)
+                for (int a = 0; a < anchors; ++a) {
+                    const float* box = maps[m] + (size_t)i * stride + (size_t)a * (5 + ncls);
+                    double sc = 1.0 / (1.0 + exp(-(double)box[4])) * (1.0 / (1.0 + exp(-(double)box[5 + c])));
+                    if (sc > best) best = sc;
+                }
+        logits[c] = (float)best;
+    }
+}
+
 /* ------------------------------------------------------------------------------------------
  * expert forward from an architecture descriptor and a weight blob
  * ---------------------------------------------------------------------------------------- */
@@ -322,6 +363,29 @@ int orc_forward(int dtype, int in_h, int in_w, int in_c, int n_layers, const int
             ensure(&buf[dst], (size_t)x->h * x->w * D);
             orc_attention(x->data, x->h * x->w, D, heads, dtype, buf[dst].data);
             buf[dst].h = x->h; buf[dst].w = x->w; buf[dst].c = D;
+        } else if (op == OP_CONCAT) {
+            if (dst <= 0 || dst >= MAX_BUFS || dst == src || dst == res) { rc = -2; break; }
+            if (res < 0 || res >= MAX_BUFS || !buf[res].data || buf[res].h != x->h || buf[res].w != x->w) { rc = -3; break; }
+            int Cc = x->c + buf[res].c;
+            ensure(&buf[dst], (size_t)x->h * x->w * Cc);
+            orc_concat(x->data, buf[res].data, x->h * x->w, x->c, buf[res].c, buf[dst].data);
+            buf[dst].h = x->h; buf[dst].w = x->w; buf[dst].c = Cc;
+        } else if (op == OP_UPSAMPLE) {
+            if (dst <= 0 || dst >= MAX_BUFS || dst == src) { rc = -2; break; }
+            ensure(&buf[dst], (size_t)4 * x->h * x->w * x->c);
+            orc_upsample2(x->data, x->h, x->w, x->c, buf[dst].data);
+            buf[dst].h = 2 * x->h; buf[dst].w = 2 * x->w; buf[dst].c = x->c;
+        } else if (op == OP_HEAD_DET) {
+            /* src (and res, if >= 0) are detection maps; K classes; aux0 anchors */
+            int anchors = L[10];
+            const float* maps[2]; int hw[2]; int nm = 0;
+            if (anchors <= 0 || x->c != anchors * (5 + K)) { rc = -6; break; }
+            maps[nm] = x->data; hw[nm] = x->h * x->w; ++nm;
+            if (res >= 0) {
+                if (res >= MAX_BUFS || !buf[res].data || buf[res].c != x->c) { rc = -3; break; }
+                maps[nm] = buf[res].data; hw[nm] = buf[res].h * buf[res].w; ++nm;
+            }
+            orc_det_head(maps, hw, nm, anchors, K, logits);
         } else if (op == OP_HEAD_CLS) {
             float* g = take(blob, &off, (size_t)x->c, DT_F32);
             float* b = take(blob, &off, (size_t)x->c, DT_F32);

@@ -118,6 +118,33 @@ def attention(qkv, heads, dtype=0) -> np.ndarray:
     return y
 
 
+def concat(a, b) -> np.ndarray:
+    a = np.ascontiguousarray(a, np.float32); b = np.ascontiguousarray(b, np.float32)
+    H, W_, Ca = a.shape; Cb = b.shape[2]
+    assert b.shape[:2] == (H, W_)
+    y = np.empty((H, W_, Ca + Cb), np.float32)
+    lib().orc_concat(_p(a), _p(b), H * W_, Ca, Cb, _p(y))
+    return y
+
+
+def upsample2(x) -> np.ndarray:
+    x = np.ascontiguousarray(x, np.float32)
+    H, W_, Cc = x.shape
+    y = np.empty((2 * H, 2 * W_, Cc), np.float32)
+    lib().orc_upsample2(_p(x), H, W_, Cc, _p(y))
+    return y
+
+
+def det_head(maps, anchors: int, ncls: int) -> np.ndarray:
+    """maps: list of [H][W][anchors * (5 + ncls)] arrays -> [ncls] best detection score per class."""
+    ms = [np.ascontiguousarray(m, np.float32) for m in maps]
+    ptrs = (C.c_void_p * len(ms))(*[m.ctypes.data for m in ms])
+    hw = (C.c_int * len(ms))(*[m.shape[0] * m.shape[1] for m in ms])
+    out = np.empty(ncls, np.float32)
+    lib().orc_det_head(ptrs, hw, len(ms), anchors, ncls, _p(out))
+    return out
+
+
 def forward(arch, blob: np.ndarray, x: np.ndarray) -> np.ndarray:
     """One request through one expert.  arch: object with dtype/in_h/in_w/in_c/n_classes/layers; returns fp32 logits."""
     layers = np.ascontiguousarray(arch.layers, np.int32)

@@ -283,6 +283,61 @@ def test_gelu_via_1x1_conv(oracle):
     np.testing.assert_allclose(y[5] - y[6], 0.5, rtol=1e-6)
 
 
+def test_detector_ops(oracle):
+    """Concatenation, upsampling, SiLU and the detection read-out of detector-shaped experts against closed forms."""
+    rng = np.random.default_rng(23)
+    a = rng.standard_normal((3, 5, 8)).astype(np.float32); b = rng.standard_normal((3, 5, 16)).astype(np.float32)
+    assert np.array_equal(oracle.concat(a, b), np.concatenate([a, b], axis=2))
+    up = oracle.upsample2(a)
+    assert up.shape == (6, 10, 8) and np.array_equal(up[::2, ::2], a) and np.array_equal(up[1::2, 1::2], a)
+    assert np.array_equal(up[::2, 1::2], a) and np.array_equal(up[1::2, ::2], a)
+    # SiLU through an identity 1x1 conv: SiLU(0) = 0, SiLU(1) = 1 / (1 + 1/e), SiLU(x) -> x for large x, SiLU(x) - SiLU(-x) = x
+    xs = np.array([0.0, 1.0, -1.0, 20.0, -20.0, 0.5, -0.5], np.float32).reshape(1, -1, 1)
+    y = oracle.conv2d(xs, np.ones((1, 1, 1, 1), np.float32), np.zeros(1, np.float32), act=3).reshape(-1)
+    assert y[0] == 0
+    np.testing.assert_allclose(y[1], 1.0 / (1.0 + math.exp(-1.0)), rtol=1e-6)
+    np.testing.assert_allclose(y[3], 20.0, rtol=1e-6)
+    assert abs(y[4]) < 1e-6
+    np.testing.assert_allclose(y[1] - y[2], 1.0, rtol=1e-6)
+    np.testing.assert_allclose(y[5] - y[6], 0.5, rtol=1e-6)
+    # detection read-out by hand: one anchor, two classes, boxes (x, y, w, h, objectness, class 0, class 1).
+    # All-zero logits: sigmoid(0)^2 = 0.25 for both classes.  One confident box (objectness 30, class 1 logit 30): class 1 -> 1,
+    # class 0 stays 0.25 unless a box beats it; a box with objectness ln 3 (sigmoid 0.75) and class 0 logit ln 3: 0.5625.
+    m = np.zeros((2, 2, 7), np.float32)
+    assert oracle.det_head([m], 1, 2).tolist() == [0.25, 0.25]
+    m[0, 1, 4] = 30.0; m[0, 1, 6] = 30.0
+    m[1, 0, 4] = math.log(3.0); m[1, 0, 5] = math.log(3.0)
+    got = oracle.det_head([m], 1, 2)
+    np.testing.assert_allclose(got, [0.5625, 1.0], rtol=1e-6)
+    # a second map can only raise the scores; the order of positions does not matter; two anchors per position
+    m2 = np.zeros((1, 1, 7), np.float32); m2[0, 0, 4] = 30.0; m2[0, 0, 5] = 30.0
+    np.testing.assert_allclose(oracle.det_head([m, m2], 1, 2), [1.0, 1.0], rtol=1e-6)
+    assert np.array_equal(oracle.det_head([m[::-1, ::-1].copy()], 1, 2), got)
+    two = np.concatenate([m, m[::-1]], axis=2)                       # anchors side by side in the channel dimension
+    np.testing.assert_allclose(oracle.det_head([two], 2, 2), got, rtol=1e-6)
+
+
+def test_forward_detector_fp32_matches_numpy(oracle):
+    # detector-shaped expert at 64x64 input, width 16: wiring of the cross-stage blocks, the pooling pyramid, the neck
+    # (upsample + concatenation with the finer map) and the two-scale detection read-out against the independent walk
+    a = W.detector(n_classes=3, hw=64, width=16, anchors=4, dtype=W.DT_F32)
+    blob = W.make_expert_blob(a, 31, 0)
+    x = W.make_inputs(a, 31, [4])[0]
+    got = oracle.forward(a, blob, x)
+    want = _np_forward_f64(a, blob, x)
+    assert got.shape == (3,) and 0 < got.min() and got.max() < 1
+    np.testing.assert_allclose(got, want, rtol=1e-4, atol=1e-6)
+
+
+def test_forward_detector_bf16_close_to_unrounded(oracle):
+    a = W.detector(n_classes=3, hw=64, width=16, anchors=4, dtype=W.DT_BF16)
+    blob = W.make_expert_blob(a, 31, 0)
+    xb = W.make_inputs(a, 31, [4])[0]
+    got = oracle.forward(a, blob, xb)
+    want = _np_forward_f64(a, blob, W.bf16_bits_to_f32(xb).reshape(xb.shape))
+    assert np.max(np.abs(got - want)) / np.max(np.abs(want)) < 3e-2
+
+
 def test_tokens(oracle):
     x = np.arange(6, dtype=np.float32).reshape(3, 2)
     cls = np.array([10, 20], np.float32)
@@ -307,7 +362,19 @@ def _np_forward_f64(arch, blob, x):
                 y = np.maximum(y, 0)
             elif act == 2:
                 y = 0.5 * y * (1.0 + np.vectorize(math.erf)(y / math.sqrt(2.0)))
+            elif act == 3:
+                y = y * (0.5 * (1.0 + np.tanh(0.5 * y)))          # x sigmoid(x), the logistic function written through tanh
             bufs[dst] = y
+        elif op == W.OP_CONCAT:
+            bufs[dst] = np.concatenate([bufs[src], bufs[res]], axis=2)
+        elif op == W.OP_UPSAMPLE:
+            bufs[dst] = np.repeat(np.repeat(bufs[src], 2, axis=0), 2, axis=1)
+        elif op == W.OP_HEAD_DET:
+            anchors = int(L[10])
+            maps = [bufs[src]] + ([bufs[res]] if res >= 0 else [])
+            boxes = np.concatenate([m.reshape(-1, 5 + k) for m in maps])          # [positions * anchors][5 + k]
+            sig = lambda v: 0.5 * (1.0 + np.tanh(0.5 * v))
+            return (sig(boxes[:, 4:5]) * sig(boxes[:, 5:])).max(axis=0)
         elif op == W.OP_TOKENS:
             t = bufs[src].reshape(-1, bufs[src].shape[2])
             t = np.concatenate([W.blob_tensor(arch, blob, li, "cls")[None].astype(np.float64), t], 0)
