@@ -47,11 +47,18 @@ typedef struct coe_ctx coe_ctx;
  *   op COE_OP_LAYERNORM dst = layer norm of src over channels, eps 1e-6
  *   op COE_OP_ATTENTION src = [T][3D] (q|k|v), aux0 = heads; dst = softmax(q k^T / sqrt(D/heads)) v
  *   op COE_OP_HEAD_CLS logits[k] = FC(layer norm(token 0 of src)); ends the program
- * act: 0 none, 1 ReLU, 2 GELU (erf form).  res = -1 for none; res must have dst's shape.
+ *   op COE_OP_CONCAT   dst = [src | res] along channels (same height and width; k = channels of dst)
+ *   op COE_OP_UPSAMPLE dst = src upsampled by two, nearest neighbour (k = channels)
+ *   op COE_OP_HEAD_DET src (and res, if >= 0) are detection maps with aux0 anchors x (5 + k) channels per position (4 box
+ *                      terms, objectness, k class logits): logits[c] = max over maps, positions and anchors of
+ *                      sigmoid(objectness) * sigmoid(class c); no weights; ends the program
+ * (the last three serve detector-shaped experts, the paper's object-detection experts downstream of its classifiers,
+ * Section 5.1; bf16 only, channel counts multiples of 8)
+ * act: 0 none, 1 ReLU, 2 GELU (erf form), 3 SiLU.  res = -1 for none; for a CONV, res must have dst's shape.
  * dtype: 0 = fp32 everywhere; 1 = bf16 weights and stored activations, fp32 accumulation, bias, residual add
  * and activation in fp32, one round-to-nearest-even to bf16 per stored activation, fp32 logits. */
 enum { COE_OP_CONV = 1, COE_OP_MAXPOOL = 2, COE_OP_HEAD = 3, COE_OP_TOKENS = 4, COE_OP_LAYERNORM = 5,
-       COE_OP_ATTENTION = 6, COE_OP_HEAD_CLS = 7 };
+       COE_OP_ATTENTION = 6, COE_OP_HEAD_CLS = 7, COE_OP_CONCAT = 8, COE_OP_UPSAMPLE = 9, COE_OP_HEAD_DET = 10 };
 enum { COE_DT_F32 = 0, COE_DT_BF16 = 1 };
 
 typedef struct {

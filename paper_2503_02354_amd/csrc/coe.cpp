@@ -221,7 +221,7 @@ int plan_arch(coe_ctx* c, const coe_arch_desc* d, ArchPlan& a)
         const coe_layer& l = L.d;
         if (l.src < 0 || l.src >= kMaxBufs || !shp[l.src].set) return fail(c, COE_EINVAL, "arch: layer reads an unset buffer");
         L.H = shp[l.src].h; L.W = shp[l.src].w; L.C = shp[l.src].c;
-        bool is_head = l.op == COE_OP_HEAD || l.op == COE_OP_HEAD_CLS;
+        bool is_head = l.op == COE_OP_HEAD || l.op == COE_OP_HEAD_CLS || l.op == COE_OP_HEAD_DET;
         if (!is_head && (l.dst <= 0 || l.dst >= kMaxBufs || l.dst == l.src))
             return fail(c, COE_EINVAL, "arch: bad destination buffer");
         if (is_head && i != d->n_layers - 1) return fail(c, COE_EINVAL, "arch: head must be the last layer");
@@ -259,7 +259,7 @@ int plan_arch(coe_ctx* c, const coe_arch_desc* d, ArchPlan& a)
                         shp[l.res].c != L.K)
                         return fail(c, COE_EINVAL, "arch: residual shape mismatch");
                 }
-                if (l.act < 0 || l.act > 2) return fail(c, COE_EINVAL, "arch: unknown activation");
+                if (l.act < 0 || l.act > 3) return fail(c, COE_EINVAL, "arch: unknown activation");
             }
             break;
         }
@@ -300,6 +300,27 @@ int plan_arch(coe_ctx* c, const coe_arch_desc* d, ArchPlan& a)
             L.off[3] = take((size_t)l.k, false);
             L.macs = (double)l.k * L.C;
             break;
+        case COE_OP_CONCAT:
+            if (d->dtype != COE_DT_BF16) return fail(c, COE_EINVAL, "arch: concatenation needs bf16");
+            if (l.res < 0 || l.res >= kMaxBufs || !shp[l.res].set || l.res == l.dst || shp[l.res].h != L.H || shp[l.res].w != L.W)
+                return fail(c, COE_EINVAL, "arch: concatenation of different sizes");
+            if (L.C % 8 || shp[l.res].c % 8) return fail(c, COE_EINVAL, "arch: concatenated channel counts must be multiples of 8");
+            L.P = L.H; L.Q = L.W; L.K = L.C + shp[l.res].c;
+            if (l.k != L.K) return fail(c, COE_EINVAL, "arch: concatenation width differs from the sum of its inputs");
+            break;
+        case COE_OP_UPSAMPLE:
+            if (d->dtype != COE_DT_BF16 || L.C % 8) return fail(c, COE_EINVAL, "arch: upsampling needs bf16 and channels % 8 == 0");
+            L.P = 2 * L.H; L.Q = 2 * L.W; L.K = L.C;
+            break;
+        case COE_OP_HEAD_DET:
+            if (l.k != d->n_classes) return fail(c, COE_EINVAL, "arch: head width differs from n_classes");
+            if (d->dtype != COE_DT_BF16 || l.aux0 <= 0 || L.C != l.aux0 * (5 + l.k) || l.k > 256)
+                return fail(c, COE_EINVAL, "arch: detection head needs bf16 maps of anchors x (5 + classes) channels, at most 256 classes");
+            if (l.res >= 0 && (l.res >= kMaxBufs || !shp[l.res].set || shp[l.res].c != L.C))
+                return fail(c, COE_EINVAL, "arch: second detection map has another layout");
+            L.K = l.k;
+            L.P = l.res >= 0 ? shp[l.res].h * shp[l.res].w : 0;        // positions of the second map
+            break;
         default:
             return fail(c, COE_EINVAL, "arch: unknown op");
         }
@@ -307,7 +328,8 @@ int plan_arch(coe_ctx* c, const coe_arch_desc* d, ArchPlan& a)
         a.layers.push_back(L);
     }
     int last = a.layers.back().d.op;
-    if (last != COE_OP_HEAD && last != COE_OP_HEAD_CLS) return fail(c, COE_EINVAL, "arch: program must end in a head");
+    if (last != COE_OP_HEAD && last != COE_OP_HEAD_CLS && last != COE_OP_HEAD_DET)
+        return fail(c, COE_EINVAL, "arch: program must end in a head");
     // few-channel conv followed by a 3x3/2 pad-1 max pool of its output, which nobody else reads: one fused kernel
     for (size_t i = 0; i + 1 < a.layers.size(); ++i) {
         LayerPlan& cv = a.layers[i];
@@ -328,7 +350,7 @@ int plan_arch(coe_ctx* c, const coe_arch_desc* d, ArchPlan& a)
     // activation buffers per request: what the launched kernels write (a conv fused with its pool writes the pool's output)
     for (const LayerPlan& L : a.layers) {
         const int op = L.d.op;
-        if (op == COE_OP_HEAD || op == COE_OP_HEAD_CLS || L.fuse_pool) continue;
+        if (op == COE_OP_HEAD || op == COE_OP_HEAD_CLS || op == COE_OP_HEAD_DET || L.fuse_pool) continue;
         a.buf_elems[L.d.dst] = std::max(a.buf_elems[L.d.dst], (size_t)L.P * L.Q * L.K);
     }
     a.blob_bytes = align_up(off);
@@ -593,6 +615,25 @@ int run_expert(coe_ctx* c, Lane& ln, const Expert& x, const void* weights, const
         case COE_OP_ATTENTION: {
             Span sp(c, COE_K_ATTENTION, 2.0 * L.macs * n, ln.s);
             HIPCHK(c, coe::k::attention(buf(l.src), buf(l.dst), n, L.H * L.W, L.K, l.aux0, ln.s));
+            break;
+        }
+        case COE_OP_CONCAT: {
+            const int32_t cb = L.K - L.C;
+            double bytes = 2.0 * n * (double)L.H * L.W * L.K * a.elem();
+            Span sp(c, COE_K_TOKEN_OPS, bytes, ln.s);
+            HIPCHK(c, coe::k::concat_channels(buf(l.src), buf(l.res), buf(l.dst), (int64_t)n * L.H * L.W, L.C, cb, ln.s));
+            break;
+        }
+        case COE_OP_UPSAMPLE: {
+            double bytes = 5.0 * n * (double)L.H * L.W * L.C * a.elem();
+            Span sp(c, COE_K_TOKEN_OPS, bytes, ln.s);
+            HIPCHK(c, coe::k::upsample2(buf(l.src), buf(l.dst), n, L.H, L.W, L.C, ln.s));
+            break;
+        }
+        case COE_OP_HEAD_DET: {
+            double bytes = (double)n * ((double)L.H * L.W + L.P) * L.C * a.elem();
+            Span sp(c, COE_K_HEAD, bytes, ln.s);
+            HIPCHK(c, coe::k::head_det(buf(l.src), L.H * L.W, l.res >= 0 ? buf(l.res) : nullptr, L.P, n, l.aux0, L.K, route, ln.s));
             break;
         }
         case COE_OP_HEAD_CLS: {
@@ -1436,7 +1477,7 @@ int coe_debug_conv(coe_ctx* c, int32_t dtype, const void* x, const void* w, cons
 {
     if (!c || !x || !w || !bias || !y) return fail(c, COE_EINVAL, "null argument");
     if ((dtype != COE_DT_F32 && dtype != COE_DT_BF16) || n <= 0 || h <= 0 || wd <= 0 || ch <= 0 || k <= 0 || r <= 0 || s <= 0 ||
-        stride <= 0 || pad < 0 || act < 0 || act > 2 || repeat <= 0)
+        stride <= 0 || pad < 0 || act < 0 || act > 3 || repeat <= 0)
         return fail(c, COE_EINVAL, "bad convolution parameters");
     const int P = (h + 2 * pad - r) / stride + 1, Q = (wd + 2 * pad - s) / stride + 1;
     if (P <= 0 || Q <= 0) return fail(c, COE_EINVAL, "empty output");

@@ -57,6 +57,7 @@ __device__ __forceinline__ float act_fn(float v, int act)
 {
     if (act == 1) return v > 0.f ? v : 0.f;
     if (act == 2) return 0.5f * v * erfcf(-v * 0.70710678118654752440f);
+    if (act == 3) return v / (1.f + expf(-v));
     return v;
 }
 // The activation is a launch parameter, but an epilogue that tests it per element compiles into hundreds of
@@ -65,6 +66,7 @@ template <typename F> __device__ __forceinline__ void with_activation(int act, F
 {
     if (act == 1) body(std::integral_constant<int, 1>{});
     else if (act == 2) body(std::integral_constant<int, 2>{});
+    else if (act == 3) body(std::integral_constant<int, 3>{});
     else body(std::integral_constant<int, 0>{});
 }
 // raw buffer descriptor over [p, p + bytes): offsets at or beyond `bytes` read as zero

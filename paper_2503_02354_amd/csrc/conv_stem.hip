@@ -52,12 +52,14 @@ __device__ __forceinline__ float act_fn(float v, int act)
 {
     if (act == 1) return v > 0.f ? v : 0.f;
     if (act == 2) return 0.5f * v * erfcf(-v * 0.70710678118654752440f);
+    if (act == 3) return v / (1.f + expf(-v));
     return v;
 }
 template <typename F> __device__ __forceinline__ void with_activation(int act, F&& body)
 {
     if (act == 1) body(std::integral_constant<int, 1>{});
     else if (act == 2) body(std::integral_constant<int, 2>{});
+    else if (act == 3) body(std::integral_constant<int, 3>{});
     else body(std::integral_constant<int, 0>{});
 }
 
@@ -326,6 +328,12 @@ bool geometry(const ConvShape& s, bool pool, StemGeom& g, size_t& smem)
     int furthest = (kTile - 1) * s.stride * s.C + g.cpr * 8;       // one past the last element any chunk read touches
     int ps = g.patch_cols > furthest ? g.patch_cols : furthest;
     g.patch_stride = (ps + 7) / 8 * 8 + 8;                         // multiple of 8: the regions after it stay 16-byte aligned
+    // The 32 lanes of an operand read cover two rows of the conv tile, 16 pixels each, stride * C elements apart inside a row:
+    // dword 3 l for lane l of a row with the 7x7x3 stem's 6 elements per pixel.  Two tile rows are stride * patch_stride
+    // elements apart; when that is a multiple of 32 dwords both rows hit the same 16 banks.  Shift it to 16 dwords mod 32:
+    // the second row's banks (3 l + 16 mod 32) then fall between the first row's.
+    for (int extra = 0; extra < 64; extra += 8)
+        if ((s.stride * (g.patch_stride + extra) / 2) % 32 == 16) { g.patch_stride += extra; break; }
     if ((long long)s.H * s.W * s.C * 2 >= 0x7FFFFFFFll) return false;    // byte offsets inside one image are 31-bit
     if (g.patch_rows > kMaxRowsPerWave * (kThreads / 64) || g.patch_cols + 1 > kMaxDwordsPerLane * 128) return false;
     if ((s.W * s.C) % 2) return false;                             // aligned dwords must not straddle the end of an image row

@@ -108,6 +108,16 @@ hipError_t head_gap_fc_grouped(int dtype, const void* x, const GroupTable& group
                                int32_t HW, int32_t C, int32_t ncls, const RouteArgs& r, const GroupRoutes& routes,
                                hipStream_t stream);
 
+// ---- detector-shaped experts (bf16 only) -----------------------------------------------------------------------
+// out[n][i] = [a[n][i] (Ca channels) | b[n][i] (Cb channels)] for the HW positions of every image; Ca, Cb multiples of 8.
+hipError_t concat_channels(const void* a, const void* b, void* out, int64_t rows, int32_t Ca, int32_t Cb, hipStream_t stream);
+// nearest-neighbour upsampling by two: out[n][h][w] = x[n][h/2][w/2]; C a multiple of 8.
+hipError_t upsample2(const void* x, void* out, int32_t N, int32_t H, int32_t W, int32_t C, hipStream_t stream);
+// Detection read-out: maps m0 [N][hw0][anchors*(5+ncls)] and (optional) m1 [N][hw1][...]; logits[c] = max over maps, positions
+// and anchors of sigmoid(objectness) * sigmoid(class c); then routing like head_gap_fc.  ncls <= 256.
+hipError_t head_det(const void* m0, int32_t hw0, const void* m1, int32_t hw1, int32_t N, int32_t anchors, int32_t ncls,
+                    const RouteArgs& r, hipStream_t stream);
+
 // ---- transformer-shaped experts (bf16 only) --------------------------------------------------------------------
 // Patches of a non-overlapping convolution (stride == window, no padding) as GEMM rows:
 // x [N][H][W][C] -> out [N * (H/R) * (W/S)][R*S*C].  S*C*2 bytes must be a multiple of 16.

@@ -38,6 +38,7 @@ __device__ __forceinline__ float apply_act(float v, int act)
 {
     if (act == 1) return v > 0.f ? v : 0.f;
     if (act == 2) return 0.5f * v * erfcf(-v * 0.70710678118654752440f);
+    if (act == 3) return v / (1.f + expf(-v));
     return v;
 }
 
@@ -469,6 +470,67 @@ __global__ __launch_bounds__(kHeadThreads) void head_cls_kernel(const uint16_t* 
     route_tail(logit, ncls, row, r);
 }
 
+// -------------------------------------------------------------------------------------------------------------
+// detector-shaped experts: channel concatenation, nearest-neighbour upsampling, detection read-out
+// -------------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void concat_kernel(const uint4* __restrict__ a, const uint4* __restrict__ b, uint4* __restrict__ out,
+                                                     size_t rows, int A8, int B8)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const int C8 = A8 + B8;
+    if (idx >= rows * C8) return;
+    const size_t r = idx / C8;
+    const int c = (int)(idx % C8);
+    out[idx] = c < A8 ? a[r * A8 + c] : b[r * B8 + (c - A8)];
+}
+
+__global__ __launch_bounds__(256) void upsample2_kernel(const uint4* __restrict__ x, uint4* __restrict__ out, int N, int H, int W, int C8)
+{
+    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t total = (size_t)N * 4 * H * W * C8;
+    if (idx >= total) return;
+    const int c = (int)(idx % C8);
+    size_t m = idx / C8;
+    const int w = (int)(m % (2 * W)); m /= 2 * W;
+    const int h = (int)(m % (2 * H));
+    const int n = (int)(m / (2 * H));
+    out[idx] = x[(((size_t)n * H + h / 2) * W + w / 2) * C8 + c];
+}
+
+__device__ __forceinline__ float sigmoid_f(float v) { return 1.f / (1.f + expf(-v)); }
+
+// one workgroup per request: every thread walks (position, anchor) boxes of both maps and keeps the best score of each class
+// in LDS with an integer max (scores are positive floats, which order like their bit patterns)
+constexpr int kDetMaxClasses = 256;
+__global__ __launch_bounds__(kHeadThreads) void head_det_kernel(const uint16_t* __restrict__ m0, int hw0, const uint16_t* __restrict__ m1,
+                                                                int hw1, int anchors, int ncls, RouteArgs r)
+{
+    __shared__ uint32_t best[kDetMaxClasses];
+    __shared__ float logit[kDetMaxClasses];
+    const int row = blockIdx.x;
+    for (int c = threadIdx.x; c < ncls; c += kHeadThreads) best[c] = 0u;
+    __syncthreads();
+    const int box_len = 5 + ncls, stride = anchors * box_len;
+    for (int map = 0; map < 2; ++map) {
+        const uint16_t* mp = map == 0 ? m0 : m1;
+        const int hw = map == 0 ? hw0 : hw1;
+        if (!mp) continue;
+        const uint16_t* base = mp + (size_t)row * hw * stride;
+        for (int bx = threadIdx.x; bx < hw * anchors; bx += kHeadThreads) {
+            const uint16_t* box = base + (size_t)bx * box_len;       // boxes of one position are consecutive
+            const float obj = sigmoid_f(bf16_to_f32(box[4]));
+            for (int c = 0; c < ncls; ++c) {
+                const float sc = obj * sigmoid_f(bf16_to_f32(box[5 + c]));
+                atomicMax(&best[c], __float_as_uint(sc));
+            }
+        }
+    }
+    __syncthreads();
+    for (int c = threadIdx.x; c < ncls; c += kHeadThreads) logit[c] = __uint_as_float(best[c]);
+    __syncthreads();
+    route_tail(logit, ncls, row, r);
+}
+
 }  // namespace
 
 // -------------------------------------------------------------------------------------------------------------
@@ -646,6 +708,39 @@ hipError_t head_gap_fc_grouped(int dtype, const void* x, const GroupTable& group
         hipLaunchKernelGGL(head_gap_fc_kernel<float>, dim3(N), dim3(kHeadThreads), smem, stream, (const float*)x,
                            (const float*)nullptr, (const float*)nullptr, HW, C, ncls, r, groups, routes, (uint32_t)off_w,
                            (uint32_t)off_b);
+    return hipGetLastError();
+}
+
+hipError_t concat_channels(const void* a, const void* b, void* out, int64_t rows, int32_t Ca, int32_t Cb, hipStream_t stream)
+{
+    if (Ca <= 0 || Cb <= 0 || Ca % 8 || Cb % 8 || rows < 0) return hipErrorInvalidValue;
+    const size_t total = (size_t)rows * ((Ca + Cb) / 8);
+    if (total == 0) return hipSuccess;
+    const size_t blocks = (total + 255) / 256;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(concat_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (const uint4*)a, (const uint4*)b, (uint4*)out,
+                       (size_t)rows, Ca / 8, Cb / 8);
+    return hipGetLastError();
+}
+
+hipError_t upsample2(const void* x, void* out, int32_t N, int32_t H, int32_t W, int32_t C, hipStream_t stream)
+{
+    if (C <= 0 || C % 8 || H <= 0 || W <= 0 || N < 0) return hipErrorInvalidValue;
+    const size_t total = (size_t)N * 4 * H * W * (C / 8);
+    if (total == 0) return hipSuccess;
+    const size_t blocks = (total + 255) / 256;
+    if (blocks > 0x7FFFFFFFull) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(upsample2_kernel, dim3((unsigned)blocks), dim3(256), 0, stream, (const uint4*)x, (uint4*)out, N, H, W, C / 8);
+    return hipGetLastError();
+}
+
+hipError_t head_det(const void* m0, int32_t hw0, const void* m1, int32_t hw1, int32_t N, int32_t anchors, int32_t ncls,
+                    const RouteArgs& r, hipStream_t stream)
+{
+    if (N <= 0) return hipSuccess;
+    if (!m0 || hw0 <= 0 || anchors <= 0 || ncls <= 0 || ncls > kDetMaxClasses || (m1 && hw1 <= 0)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(head_det_kernel, dim3(N), dim3(kHeadThreads), 0, stream, (const uint16_t*)m0, hw0, (const uint16_t*)m1, hw1,
+                       anchors, ncls, r);
     return hipGetLastError();
 }
 
