@@ -298,8 +298,28 @@ static void ensure(obuf* b, size_t n)
 
 /* One request through one expert.  input: in_h*in_w*in_c elements in the expert's dtype (bf16 bits or fp32).
  * Returns 0, or a negative number for a malformed descriptor. */
+static int forward_impl(int dtype, int in_h, int in_w, int in_c, int n_layers, const int32_t* layers, const uint8_t* blob,
+                        const void* input, float* logits, int stop_after, float* layer_out, int64_t layer_cap, int32_t* layer_shape);
+
 int orc_forward(int dtype, int in_h, int in_w, int in_c, int n_layers, const int32_t* layers, const uint8_t* blob,
                 const void* input, float* logits)
+{
+    return forward_impl(dtype, in_h, in_w, in_c, n_layers, layers, blob, input, logits, -1, 0, 0, 0);
+}
+
+/* The same program stopped after layer `stop_after` (not a head): that layer's output tensor [h][w][c], as fp32 values in
+ * storage precision, goes to layer_out (at most layer_cap elements) and its shape to layer_shape[3].  For looking at where two
+ * implementations of an expert drift apart.  Returns 0, a negative error, or -20 when layer_cap is too small. */
+int orc_forward_layer(int dtype, int in_h, int in_w, int in_c, int n_layers, const int32_t* layers, const uint8_t* blob,
+                      const void* input, int stop_after, float* layer_out, int64_t layer_cap, int32_t* layer_shape)
+{
+    float dummy[1024];
+    if (stop_after < 0 || stop_after >= n_layers) return -21;
+    return forward_impl(dtype, in_h, in_w, in_c, n_layers, layers, blob, input, dummy, stop_after, layer_out, layer_cap, layer_shape);
+}
+
+static int forward_impl(int dtype, int in_h, int in_w, int in_c, int n_layers, const int32_t* layers, const uint8_t* blob,
+                        const void* input, float* logits, int stop_after, float* layer_out, int64_t layer_cap, int32_t* layer_shape)
 {
     obuf buf[MAX_BUFS];
     memset(buf, 0, sizeof(buf));
@@ -400,6 +420,18 @@ int orc_forward(int dtype, int in_h, int in_w, int in_c, int n_layers, const int
             }
             free(g); free(b); free(w); free(fb); free(n);
         } else rc = -9;
+        if (rc == 0 && li == stop_after) {
+            if (op == OP_HEAD || op == OP_HEAD_CLS || op == OP_HEAD_DET) rc = -22;
+            else {
+                int64_t n = (int64_t)buf[dst].h * buf[dst].w * buf[dst].c;
+                if (n > layer_cap) rc = -20;
+                else {
+                    memcpy(layer_out, buf[dst].data, sizeof(float) * (size_t)n);
+                    layer_shape[0] = buf[dst].h; layer_shape[1] = buf[dst].w; layer_shape[2] = buf[dst].c;
+                }
+            }
+            break;
+        }
     }
     for (int i = 0; i < MAX_BUFS; ++i) free(buf[i].data);
     return rc;

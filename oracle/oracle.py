@@ -157,6 +157,24 @@ def forward(arch, blob: np.ndarray, x: np.ndarray) -> np.ndarray:
     return out
 
 
+def forward_layer(arch, blob: np.ndarray, x: np.ndarray, layer: int) -> np.ndarray:
+    """Output tensor [h][w][c] of layer `layer` (not a head) of one request's forward, fp32 values in storage precision."""
+    layers = np.ascontiguousarray(arch.layers, np.int32)
+    blob = np.ascontiguousarray(blob, np.uint8)
+    x = np.ascontiguousarray(x)
+    cap = 1 << 24
+    out = np.zeros(cap, np.float32)
+    shape = np.zeros(3, np.int32)
+    L = lib()
+    L.orc_forward_layer.argtypes = [C.c_int] * 5 + [C.c_void_p] * 3 + [C.c_int, C.c_void_p, C.c_int64, C.c_void_p]
+    rc = L.orc_forward_layer(arch.dtype, arch.in_h, arch.in_w, arch.in_c, layers.shape[0], _p(layers), _p(blob), _p(x), layer,
+                             _p(out), cap, _p(shape))
+    if rc:
+        raise RuntimeError(f"orc_forward_layer failed: {rc}")
+    h, w, c = (int(v) for v in shape)
+    return out[:h * w * c].reshape(h, w, c).copy()
+
+
 def run_chain(archs: Sequence, expert_arch: Sequence[int], blobs: Sequence[np.ndarray], succ_off, succ, inputs: np.ndarray,
               first_expert: Optional[np.ndarray], max_stages: int, max_classes: int, threads: int = 0):
     """Every request through its whole chain.  Returns dict(logits, path, all_logits, margin)."""

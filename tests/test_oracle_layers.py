@@ -349,11 +349,14 @@ def test_tokens(oracle):
 # ---------------------------------------------------------------------------------------------
 # whole-expert forward from descriptor + blob
 # ---------------------------------------------------------------------------------------------
-def _np_forward_f64(arch, blob, x):
-    """Independent float64 walk of a conv/pool/head program using numpy matmul convolution, no rounding."""
+def _np_forward_f64(arch, blob, x, stop_at=-1):
+    """Independent float64 walk of a conv/pool/head program using numpy matmul convolution, no rounding.
+    stop_at >= 0: the tensor that layer wrote instead of the head's output."""
     bufs = {0: x.astype(np.float64)}
     for li, L in enumerate(arch.layers):
         op, src, dst, res, k, r, s, stride, pad, act = [int(v) for v in L[:10]]
+        if li == stop_at + 1 and stop_at >= 0:
+            return bufs[int(arch.layers[stop_at][2])]
         if op == W.OP_CONV:
             y = _conv_im2col(bufs[src], W.blob_tensor(arch, blob, li, "w"), W.blob_tensor(arch, blob, li, "b"), stride, pad)
             if res >= 0:
@@ -444,6 +447,22 @@ def test_forward_vit_fp32_matches_numpy(oracle):
     blob = W.make_expert_blob(a, 21, 0)
     x = W.make_inputs(a, 21, [3])[0]
     np.testing.assert_allclose(oracle.forward(a, blob, x), _np_forward_f64(a, blob, x), rtol=1e-4, atol=1e-5)
+
+
+@pytest.mark.parametrize("make", [lambda: W.resnet18(5, 32, W.DT_F32, 8),
+                                  lambda: W.vit(5, hw=32, patch=8, dim=32, depth=2, heads=2, mlp=64, dtype=W.DT_F32),
+                                  lambda: W.detector(3, hw=32, width=8, anchors=4, dtype=W.DT_F32)])
+def test_forward_layer_matches_numpy_at_every_layer(oracle, make):
+    # the per-layer read-out used for the layer-wise error budget: every intermediate tensor of a forward against the
+    # independent walk stopped at the same layer
+    a = make()
+    blob = W.make_expert_blob(a, 31, 1)
+    x = W.make_inputs(a, 31, [4])[0]
+    for li in range(a.n_layers - 1):
+        got = oracle.forward_layer(a, blob, x, li)
+        want = _np_forward_f64(a, blob, x, stop_at=li)
+        assert got.shape == want.shape, li
+        np.testing.assert_allclose(got, want, rtol=2e-4, atol=2e-5, err_msg=f"layer {li}")
 
 
 def test_forward_vit_bf16_close_to_unrounded(oracle):
