@@ -27,9 +27,9 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA
 # scaled by what the same counters read for the gather kernel's plain copy (profiles/conv3x3_slab_config2_hbm_counters.md).
 # Tied to the kernel source and the launch configuration it was measured on: an edit of that file, another workload,
 # batch cap or grouping threshold make bench.py report null again.
-SLAB_TRAFFIC_BYTES_PER_LAUNCH = 2329.8e6
+SLAB_TRAFFIC_BYTES_PER_LAUNCH = 2332.7e6
 SLAB_TRAFFIC_SOURCE = ("paper_2503_02354_amd/csrc/conv_mfma.hip",
-                       "da23a53c7c541e6dd6397032f79f58e0a921a3f097e18b8be3344e87c0625597")
+                       "7752fcdddb0d2eb49fa2ced5bfc67a721b140ad46ce3e1f2c6ebbd121817c217")
 SLAB_TRAFFIC_LAUNCH_CONFIG = ("config2", 0, 4096, 512, 1, "")   # workload, requests, max_batch, group_small, arrivals per step, window
 
 
@@ -211,7 +211,7 @@ def run_workload(name, wl, blobs, x, opt, steps, warmup, latency, cache_cap=None
                     "avg_launch_us": round(p["ms"] * 1e3 / p["launches"], 2),
                     "share_of_step": round(est_ms[dom] / steps / ms_per_step, 3)}
     classes = {}
-    for kname in ("conv_slab", "conv_mfma", "attention", "token_ops", "regroup_gather", "switch", "pool", "conv_stem",
+    for kname in ("conv_slab", "conv_mfma", "attention", "token_ops", "regroup_gather", "switch", "switch_wait", "pool", "conv_stem",
                   "conv_direct", "head", "regroup_index"):
         if kname in prof:
             p = prof[kname]
@@ -237,6 +237,12 @@ def run_workload(name, wl, blobs, x, opt, steps, warmup, latency, cache_cap=None
         cache["switch_GB/s"] = round(sw["work"] / (sw["ms"] * 1e-3) / 1e9, 1)
         cache["copy_ms_per_pass"] = round(copy_ms, 2)
         cache["copy_share_of_pass"] = round(copy_ms / ms_per_step, 3)
+        # what the executors' streams actually stood still for, waiting for a copy to land (from the end of their previous
+        # work to the end of the copy): the part of the switch time that compute did not hide
+        wt = prof.get("switch_wait")
+        wait_ms = 0.0 if not wt else wt["ms"] / wt["launches"] * wt["issued"] / steps
+        cache["copy_wait_ms_per_pass"] = round(wait_ms, 2)
+        cache["copy_hidden_under_compute"] = round(max(0.0, 1.0 - wait_ms / copy_ms), 3) if copy_ms > 0 else None
     leaves = np.bincount(path[:, 1][path[:, 1] >= 0], minlength=wl.graph.n_experts)[1:]
     return {
         "value": n * steps / elapsed, "ms_per_step": ms_per_step, "path": path, "flops_per_step": flops_per_step,
@@ -255,22 +261,20 @@ def run_workload(name, wl, blobs, x, opt, steps, warmup, latency, cache_cap=None
 
 def capped_leg(name, steps, warmup):
     """One of the workloads with a capped expert cache, at its full shape, outside the timed region of the benchmark line:
-    throughput, expert-switch bandwidth from pinned host memory, how much of the copy time hides under compute (the same
-    pass with every expert resident has no switches: whatever the capped pass takes longer is the exposed part of the copy
-    time), switches per pass, and the regroup gather's bandwidth where the gather is a copy."""
+    throughput, expert-switch bandwidth from pinned host memory, how much of the copy time hides under compute (1 - the time
+    the executors' streams stood still waiting for copies / the copy time, both from events), switches per pass, the same
+    pass with every expert resident for comparison, and the regroup gather's bandwidth where the gather is a copy."""
     wl, blobs, x, t_gen = make_workload(name)
     latency = measure_latency_models(wl, blobs)
     opt = dict(DEFAULTS[name])
     r = run_workload(name, wl, blobs, x, opt, steps, warmup, latency)
     free = run_workload(name, wl, blobs, x, dict(opt, profile_every=0), steps, warmup, latency, cache_cap=0)
     c = r["expert_cache"]
-    copy_ms = c.get("copy_ms_per_pass", 0.0)
-    exposed = max(0.0, r["ms_per_step"] - free["ms_per_step"])
     out = {"workload": WORKLOAD_TEXT[name], "requests_per_s": round(r["value"], 1), "ms_per_pass": round(r["ms_per_step"], 2),
            "ms_per_pass_all_experts_resident": round(free["ms_per_step"], 2),
            "switches_per_pass": c["switches_per_pass"], "bytes_switched_per_pass": c["bytes_switched_per_pass"],
-           "switch_GB/s": c.get("switch_GB/s"), "copy_ms_per_pass": copy_ms,
-           "copy_hidden_under_compute": None if copy_ms <= 0 else round(max(0.0, 1.0 - exposed / copy_ms), 3),
+           "switch_GB/s": c.get("switch_GB/s"), "copy_ms_per_pass": c.get("copy_ms_per_pass"),
+           "copy_wait_ms_per_pass": c.get("copy_wait_ms_per_pass"), "copy_hidden_under_compute": c.get("copy_hidden_under_compute"),
            "host_plan_us_per_step": c["host_plan_us_per_step"], "device_allocations_in_steps": c["device_allocations_in_steps"],
            "regroup_gather_GB/s": r["kernel_classes"].get("regroup_gather", {}).get("GB/s"),
            "regroup_gather": "inside the first convolution kernel (row table): no bytes of its own" if "regroup_gather" not in r["kernel_classes"] else "copy kernel",
@@ -330,6 +334,10 @@ def main():
                          "and one timed pass each, and ride in the same JSON line (expert-switch GB/s, share of the copy time "
                          "hidden under compute, switches per pass, regroup gather GB/s).  Default: 'config3,config5' when the "
                          "benchmark line is config2 at its full size, else none; 'none' switches them off")
+    ap.add_argument("--latency-model", default="measure", choices=["measure", "off"],
+                    help="measure: run the offline profiler's microbenchmark (forwards over batch sizes, switches) on this GPU "
+                         "before the timed region and hand its K, B and load latency to the library; off: skip it (library "
+                         "defaults; for rocprofv3 runs whose per-kernel averages should cover the benchmark's launches only)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py runs on exactly one GPU: the library has no multi-GPU path (--gpus 1 only)", file=sys.stderr)
@@ -363,7 +371,7 @@ def main():
 
     wl, blobs, x, t_gen = make_workload(args.workload, args.requests)
     n = wl.n_requests
-    latency = measure_latency_models(wl, blobs)        # the offline profiler, in this run, on this GPU
+    latency = measure_latency_models(wl, blobs) if args.latency_model == "measure" else None   # the offline profiler, in this run
     r = run_workload(args.workload, wl, blobs, x, opt, args.steps, args.warmup, latency)
     path, ms_per_step, flops_per_step = r["path"], r["ms_per_step"], r["flops_per_step"]
 

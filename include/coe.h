@@ -262,7 +262,11 @@ int coe_debug_last_assignment(coe_ctx* ctx, int32_t cap, int32_t* first_expert, 
 
 /* Kernel classes timed when cfg.profile != 0. */
 enum { COE_K_REGROUP_INDEX = 0, COE_K_REGROUP_GATHER = 1, COE_K_CONV_MFMA = 2, COE_K_CONV_DIRECT = 3, COE_K_POOL = 4,
-       COE_K_HEAD = 5, COE_K_SWITCH = 6, COE_K_CONV_STEM = 7, COE_K_ATTENTION = 8, COE_K_TOKEN_OPS = 9, COE_K_CONV_SLAB = 10, COE_K_COUNT = 11 };
+       COE_K_HEAD = 5, COE_K_SWITCH = 6, COE_K_CONV_STEM = 7, COE_K_ATTENTION = 8, COE_K_TOKEN_OPS = 9, COE_K_CONV_SLAB = 10,
+       COE_K_SWITCH_WAIT = 11, /* not a kernel: the time an executor's stream stood still waiting for an expert's copy to land
+                                * (from the end of its previous work to the end of the copy); what is left of the switch time
+                                * after the overlap with compute */
+       COE_K_COUNT = 12 };
 /* Synchronises, then returns and clears the accumulated TIMED launches, their milliseconds and algorithmic work of a class
  * (flops for the conv and attention classes, bytes for the others). */
 int coe_profile_read(coe_ctx* ctx, int32_t kernel_class, int64_t* launches, double* ms, double* work);

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libcoe.so")
 COE_OK, COE_DONE = 0, 1
 COE_EINVAL, COE_ENOMEM, COE_ESTATE, COE_EGRAPH, COE_EDEVICE, COE_ERANGE = -1, -2, -3, -4, -5, -6
 K_REGROUP_INDEX, K_REGROUP_GATHER, K_CONV_MFMA, K_CONV_DIRECT, K_POOL, K_HEAD, K_SWITCH, K_CONV_STEM = range(8)
-KERNEL_CLASS_NAMES = ["regroup_index", "regroup_gather", "conv_mfma", "conv_direct", "pool", "head", "switch", "conv_stem", "attention", "token_ops", "conv_slab"]
+KERNEL_CLASS_NAMES = ["regroup_index", "regroup_gather", "conv_mfma", "conv_direct", "pool", "head", "switch", "conv_stem", "attention", "token_ops", "conv_slab", "switch_wait"]
 
 EXPORTS = [
     "coe_create", "coe_destroy", "coe_last_error", "coe_register_arch", "coe_arch_blob_bytes", "coe_register_expert",

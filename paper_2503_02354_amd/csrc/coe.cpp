@@ -1162,6 +1162,7 @@ static int step_body(coe_ctx* c, coe_step_stats& st)
             for (const SetMember& m : set) {
                 Expert& xm = c->experts[m.expert];
                 if (xm.load_pending) {
+                    Span sp(c, COE_K_SWITCH_WAIT, (double)xm.nbytes, lane->s);
                     HIPCHK(c, hipStreamWaitEvent(lane->s, xm.loaded, 0));
                     xm.load_pending = false;
                 }
@@ -1189,6 +1190,7 @@ static int step_body(coe_ctx* c, coe_step_stats& st)
         rc = take_lane(e, group_cost(e) + c->archs[x.arch].lat_b_ns * n_seq, &lane);   // a group stays on one executor
         if (rc) return rc;
         if (x.load_pending) {
+            Span sp(c, COE_K_SWITCH_WAIT, (double)x.nbytes, lane->s);
             HIPCHK(c, hipStreamWaitEvent(lane->s, x.loaded, 0));
             x.load_pending = false;
         }
