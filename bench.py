@@ -81,6 +81,8 @@ WORKLOAD_TEXT = {
                "8192 requests 3x224x224 with skewed group sizes, all resident",
     "config5": "config5: 32 ViT-B/16-shaped bf16 experts, 4096 requests 3x224x224, 2-stage tree (1 root -> 31 leaves, uniform "
                "usage), device cache capped at 12 experts",
+    "config6": "config6: 4 ResNet-18-shaped bf16 classifiers routing 6 ways each to 8 shared detector-shaped bf16 experts (cross-"
+               "stage blocks, pooling pyramid, two-scale read-out), 4096 requests 3x224x224, all resident",
 }
 
 
@@ -89,13 +91,14 @@ DEFAULTS = {   # per workload: launch sequence cap, grouping threshold, every k-
     "config3": dict(max_batch=512, group_small=0, profile_every=7, arrange="0,43,8", executors=3, prefetch_depth=4),
     "config4": dict(max_batch=4096, group_small=512, profile_every=7, arrange="", executors=1, prefetch_depth=0),
     "config5": dict(max_batch=512, group_small=0, profile_every=7, arrange="", executors=1, prefetch_depth=2),
+    "config6": dict(max_batch=4096, group_small=512, profile_every=1, arrange="", executors=1, prefetch_depth=0),
 }
 
 
 def make_workload(name: str, requests: int = 0):
     import coe_workloads as W
     from concurrent.futures import ThreadPoolExecutor
-    make = {"config2": W.config2, "config3": W.config3, "config4": W.config4, "config5": W.config5}[name]
+    make = {"config2": W.config2, "config3": W.config3, "config4": W.config4, "config5": W.config5, "config6": W.config6}[name]
     wl = make(requests) if requests else make()
     t0 = time.time()
     with ThreadPoolExecutor(8) as ex:
@@ -291,7 +294,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=3)
     ap.add_argument("--warmup", type=int, default=1)
-    ap.add_argument("--workload", default="config2", choices=["config2", "config3", "config4", "config5"],
+    ap.add_argument("--workload", default="config2", choices=["config2", "config3", "config4", "config5", "config6"],
                     help="config2 (default) is the benchmark line; config3 / config5 have a capped expert cache and report "
                          "switch bandwidth, overlap and host planning time next to their throughput")
     ap.add_argument("--requests", type=int, default=0, help="0 = the workload's own request count")

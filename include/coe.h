@@ -51,7 +51,7 @@ typedef struct coe_ctx coe_ctx;
  *   op COE_OP_UPSAMPLE dst = src upsampled by two, nearest neighbour (k = channels)
  *   op COE_OP_HEAD_DET src (and res, if >= 0) are detection maps with aux0 anchors x (5 + k) channels per position (4 box
  *                      terms, objectness, k class logits): logits[c] = max over maps, positions and anchors of
- *                      sigmoid(objectness) * sigmoid(class c); no weights; ends the program
+ *                      sigmoid(objectness) * sigmoid(class c); k <= 251; no weights; ends the program
  * (the last three serve detector-shaped experts, the paper's object-detection experts downstream of its classifiers,
  * Section 5.1; bf16 only, channel counts multiples of 8)
  * act: 0 none, 1 ReLU, 2 GELU (erf form), 3 SiLU.  res = -1 for none; for a CONV, res must have dst's shape.

@@ -38,6 +38,8 @@ def main():
             wl, targets = W.config4(calibrated=False), None
         elif name == "config5":
             wl, targets = W.config5(calibrated=False), None
+        elif name == "config6":
+            wl, targets = W.config6(calibrated=False), None
         else:
             raise SystemExit(f"unknown config {name}")
         hb = G.calibrate_workload(wl, n_cal=args.n_cal, targets=targets,

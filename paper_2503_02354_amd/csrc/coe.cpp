@@ -314,8 +314,8 @@ int plan_arch(coe_ctx* c, const coe_arch_desc* d, ArchPlan& a)
             break;
         case COE_OP_HEAD_DET:
             if (l.k != d->n_classes) return fail(c, COE_EINVAL, "arch: head width differs from n_classes");
-            if (d->dtype != COE_DT_BF16 || l.aux0 <= 0 || L.C != l.aux0 * (5 + l.k) || l.k > 256)
-                return fail(c, COE_EINVAL, "arch: detection head needs bf16 maps of anchors x (5 + classes) channels, at most 256 classes");
+            if (d->dtype != COE_DT_BF16 || l.aux0 <= 0 || L.C != l.aux0 * (5 + l.k) || l.k > 251)
+                return fail(c, COE_EINVAL, "arch: detection head needs bf16 maps of anchors x (5 + classes) channels, at most 251 classes");
             if (l.res >= 0 && (l.res >= kMaxBufs || !shp[l.res].set || shp[l.res].c != L.C))
                 return fail(c, COE_EINVAL, "arch: second detection map has another layout");
             L.K = l.k;

@@ -499,34 +499,55 @@ __global__ __launch_bounds__(256) void upsample2_kernel(const uint4* __restrict_
 
 __device__ __forceinline__ float sigmoid_f(float v) { return 1.f / (1.f + expf(-v)); }
 
-// one workgroup per request: every thread walks (position, anchor) boxes of both maps and keeps the best score of each class
-// in LDS with an integer max (scores are positive floats, which order like their bit patterns)
-constexpr int kDetMaxClasses = 256;
+// one workgroup per request.  A box is box_len = 5 + classes consecutive elements; thread t owns element t % box_len of
+// boxes t / box_len, + per_iter, ... (per_iter = boxes the workgroup covers at once), so consecutive threads read consecutive
+// elements and a thread's class never changes: it keeps its best score in a register.  The per_iter partial maxima of a
+// class meet in LDS at the end.  Scores are products of two sigmoids, hence positive, and the maximum does not depend on
+// the order it is taken in.
+constexpr int kDetMaxClasses = 251;            // box_len <= kHeadThreads
 __global__ __launch_bounds__(kHeadThreads) void head_det_kernel(const uint16_t* __restrict__ m0, int hw0, const uint16_t* __restrict__ m1,
                                                                 int hw1, int anchors, int ncls, RouteArgs r)
 {
-    __shared__ uint32_t best[kDetMaxClasses];
-    __shared__ float logit[kDetMaxClasses];
+    __shared__ float part[kHeadThreads];
+    __shared__ float logit[kHeadThreads];
     const int row = blockIdx.x;
-    for (int c = threadIdx.x; c < ncls; c += kHeadThreads) best[c] = 0u;
-    __syncthreads();
     const int box_len = 5 + ncls, stride = anchors * box_len;
-    for (int map = 0; map < 2; ++map) {
-        const uint16_t* mp = map == 0 ? m0 : m1;
-        const int hw = map == 0 ? hw0 : hw1;
-        if (!mp) continue;
-        const uint16_t* base = mp + (size_t)row * hw * stride;
-        for (int bx = threadIdx.x; bx < hw * anchors; bx += kHeadThreads) {
-            const uint16_t* box = base + (size_t)bx * box_len;       // boxes of one position are consecutive
-            const float obj = sigmoid_f(bf16_to_f32(box[4]));
-            for (int c = 0; c < ncls; ++c) {
-                const float sc = obj * sigmoid_f(bf16_to_f32(box[5 + c]));
-                atomicMax(&best[c], __float_as_uint(sc));
+    const int per_iter = kHeadThreads / box_len;
+    const int j = threadIdx.x % box_len, b0 = threadIdx.x / box_len;
+    float best = 0.f;
+    if (b0 < per_iter && j >= 5) {
+        for (int map = 0; map < 2; ++map) {
+            const uint16_t* mp = map == 0 ? m0 : m1;
+            const int hw = map == 0 ? hw0 : hw1;
+            if (!mp) continue;
+            const uint16_t* base = mp + (size_t)row * hw * stride;
+            const int nbox = hw * anchors;                           // boxes of one position are consecutive
+            // four boxes per trip: eight loads in flight per thread (a launch may hold only a few workgroups per compute unit)
+            int bx = b0;
+            for (; bx + 3 * per_iter < nbox; bx += 4 * per_iter) {
+                uint16_t o[4], v[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const uint16_t* box = base + (size_t)(bx + u * per_iter) * box_len;
+                    o[u] = box[4];
+                    v[u] = box[j];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) best = fmaxf(best, sigmoid_f(bf16_to_f32(o[u])) * sigmoid_f(bf16_to_f32(v[u])));
+            }
+            for (; bx < nbox; bx += per_iter) {
+                const uint16_t* box = base + (size_t)bx * box_len;
+                best = fmaxf(best, sigmoid_f(bf16_to_f32(box[4])) * sigmoid_f(bf16_to_f32(box[j])));
             }
         }
     }
+    part[threadIdx.x] = best;
     __syncthreads();
-    for (int c = threadIdx.x; c < ncls; c += kHeadThreads) logit[c] = __uint_as_float(best[c]);
+    for (int c = threadIdx.x; c < ncls; c += kHeadThreads) {
+        float m = 0.f;
+        for (int b = 0; b < per_iter; ++b) m = fmaxf(m, part[b * box_len + 5 + c]);
+        logit[c] = m;
+    }
     __syncthreads();
     route_tail(logit, ncls, row, r);
 }

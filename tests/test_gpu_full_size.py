@@ -330,6 +330,27 @@ def test_config5_full_size(B, oracle):
           f"{len(log) - 12} switches, leaves min {leaves.min()} max {leaves.max()}")
 
 
+def test_config6_full_size(B, oracle):
+    """The paper's own workload shape (Section 5.1): 4 ResNet-18-shaped classifiers (first expert ~ Zipf(1.2)) route 6 ways
+    each to 8 detector-shaped experts that several classifiers share; 4096 requests, all resident, launch configuration of
+    the benchmark.  A request's result is its detector's best detection score per class."""
+    wl = W.config6()
+    assert wl.head_bias, "calibration file missing"
+    got, want, sample, err, redraws = _sampled_case(B, oracle, wl, n_sample=N_SAMPLE, max_batch=4096, group_small=512, seed=6,
+                                                    also=[dict(cap_experts=6, prefetch_depth=1)])
+    stats = [st for rc, st in got["stats"] if rc == B.COE_OK]
+    assert len(stats) == 2 and all(st.n_pending == wl.n_requests for st in stats)
+    firsts = np.bincount(got["path"][:, 0], minlength=12)
+    assert np.array_equal(firsts[:4], np.bincount(wl.first_expert, minlength=4)) and firsts[4:].sum() == 0
+    dets = np.bincount(got["path"][:, 1], minlength=12)
+    assert dets[:4].sum() == 0 and (dets[4:] > 0).all(), dets              # every request ends in a detector, all 8 are used
+    assert got["experts_checked"] >= set(range(12))
+    assert (got["logits"][:, :27] >= 0).all() and (got["logits"][:, :27] <= 1).all()     # scores are products of two sigmoids
+    capped = got["also"][0]
+    assert sum(st.n_misses for rc, st in capped["stats"] if rc == B.COE_OK) > 0          # two slot classes in the arena
+    print(f"config6 full size: {len(sample)} sampled, max rel err {err:.2e}, {redraws} re-draws, detectors {dets[4:].tolist()}")
+
+
 def test_vit_layerwise_error_budget(B, oracle):
     """Where the 2e-2 logit tolerance of the ViT-B/16-shaped experts comes from: the GPU's stored activations against
     the oracle's, layer by layer, on two requests.  Both sides round every stored tensor to bf16 (Section 5.1's
