@@ -129,6 +129,12 @@ def run_workload(name, wl, blobs, x, opt, steps, warmup, latency, cache_cap=None
                     profile=opt["profile_every"], group_small=opt["group_small"],
                     eviction=["two-stage", "lru", "fifo"].index(opt.get("eviction", "two-stage")),
                     prefetch_depth=opt["prefetch_depth"], executors=opt["executors"])
+    backing = None
+    if opt.get("host_cap", 0) > 0:
+        # third storage level: the experts live in a file, at most host_cap of them in pinned host memory
+        import tempfile
+        backing = os.path.join(opt.get("backing_dir") or tempfile.gettempdir(), f"coe_bench_experts_{os.getpid()}.bin")
+        ctx.coe_set_host_tier(opt["host_cap"], backing)
     B.setup_workload(ctx, wl, blobs)
     for a, arch_a in enumerate(wl.archs):
         if latency and arch_a.name in latency:
@@ -246,6 +252,15 @@ def run_workload(name, wl, blobs, x, opt, steps, warmup, latency, cache_cap=None
         wait_ms = 0.0 if not wt else wt["ms"] / wt["launches"] * wt["issued"] / steps
         cache["copy_wait_ms_per_pass"] = round(wait_ms, 2)
         cache["copy_hidden_under_compute"] = round(max(0.0, 1.0 - wait_ms / copy_ms), 3) if copy_ms > 0 else None
+    if backing:
+        reads = sum(st.n_host_misses for st in step_stats)
+        read_bytes = sum(st.bytes_read for st in step_stats)
+        read_us = sum(st.read_us for st in step_stats)
+        cache["host_tier"] = {"cap_experts": opt["host_cap"], "reads_per_pass": reads // max(steps, 1),
+                              "bytes_read_per_pass": read_bytes // max(steps, 1),
+                              "read_ms_per_pass": round(read_us / 1e3 / max(steps, 1), 2),
+                              "file_read_GB/s": round(read_bytes / (read_us * 1e-6) / 1e9, 2) if read_us > 0 else None,
+                              "backing_file": backing}
     leaves = np.bincount(path[:, 1][path[:, 1] >= 0], minlength=wl.graph.n_experts)[1:]
     return {
         "value": n * steps / elapsed, "ms_per_step": ms_per_step, "path": path, "flops_per_step": flops_per_step,
@@ -286,6 +301,12 @@ def capped_leg(name, steps, warmup):
            "schedule": {"arranging_window": r["window"], "prefetch_depth": opt["prefetch_depth"], "executors": opt["executors"],
                         "max_batch": opt["max_batch"]},
            "latency_model": latency, "input_generation_s": round(t_gen, 1)}
+    if name == "config3":
+        # the same pass with a third storage level: the 64 experts in a file, half of them at a time in pinned host memory
+        h = run_workload(name, wl, blobs, x, dict(opt, profile_every=0, host_cap=wl.graph.n_experts // 2), steps, warmup, latency)
+        out["host_tier"] = dict(h["expert_cache"]["host_tier"], requests_per_s=round(h["value"], 1),
+                                ms_per_pass=round(h["ms_per_step"], 2), switches_per_pass=h["expert_cache"]["switches_per_pass"])
+        del out["host_tier"]["backing_file"]
     return out
 
 
@@ -327,6 +348,10 @@ def main():
                          "small groups then overlap on the device.  Default: 3 for config3 (many small groups per step), "
                          "1 elsewhere: per-launch rates in `roofline` drop when kernels share the chip, and the large "
                          "launches of the other workloads gain 0-3 %%")
+    ap.add_argument("--host-cap", type=int, default=0,
+                    help="third storage level: experts live in a backing file and at most this many in pinned host memory "
+                         "(0 = every expert keeps a pinned host copy)")
+    ap.add_argument("--backing-dir", default="", help="directory of the backing file (default: the system's temporary directory)")
     ap.add_argument("--no-profile", action="store_true", help="do not time kernel classes with events")
     ap.add_argument("--profile-every", type=int, default=0,
                     help="time every k-th launch of each kernel class (0 = every launch for config2, whose steps "
@@ -361,6 +386,8 @@ def main():
     if args.prefetch_depth >= 0:
         opt["prefetch_depth"] = args.prefetch_depth
     opt["eviction"] = args.eviction
+    opt["host_cap"] = args.host_cap
+    opt["backing_dir"] = args.backing_dir
     opt["arrivals_per_step"] = args.arrivals_per_step
     opt["requests"] = args.requests
     if args.capped_legs is None:

@@ -34,6 +34,7 @@ extern "C" {
 #define COE_EGRAPH (-4) /* dependency graph invalid: id out of range, cycle, more routes than classes */
 #define COE_EDEVICE (-5)/* a HIP runtime call failed */
 #define COE_ERANGE (-6) /* a caller buffer or a configured capacity is too small */
+#define COE_EIO (-7)    /* the backing file of the host tier could not be created, written or read */
 
 typedef struct coe_ctx coe_ctx;
 
@@ -130,6 +131,10 @@ typedef struct {
                                   * blob size), the request store and the activation workspaces are allocated when the
                                   * dependency graph is set (paper Section 5.5: expert management must stay a negligible
                                   * share of the time) */
+    int32_t n_host_misses;       /* with a host tier (coe_set_host_tier): switches whose expert had to be read from the backing
+                                  * file first */
+    int64_t bytes_read;          /* bytes read from the backing file */
+    double read_us;              /* host time spent in those reads */
 } coe_step_stats;
 
 /* Create / destroy a context.  coe_create fails with COE_EDEVICE when no GPU is usable. */
@@ -151,6 +156,20 @@ int64_t coe_arch_blob_bytes(const coe_ctx* ctx, int32_t arch_id);
  * the initial cache fill and for eviction. */
 int coe_register_expert(coe_ctx* ctx, int32_t expert_id, int32_t arch_id, const void* host_weights, size_t nbytes,
                         float usage_prob);
+
+/* Third storage tier (paper Section 1: experts are offloaded to CPU memory or SSD; Section 5.1: where CPU memory cannot
+ * hold every expert either, it serves as a cache in front of the SSD).  Without this call every expert keeps a pinned host
+ * copy.  With it, host memory holds at most host_cap_experts experts in pinned slots (a slot class per blob size, allocated
+ * when the dependency graph is set) and every expert's blob lives in the file at backing_path, which the library creates,
+ * truncates, fills at registration, and removes in coe_destroy.  A device switch whose expert has no host slot reads the
+ * blob from the file into one first (a synchronous read on the calling thread; switches are issued prefetch_depth groups
+ * ahead, so the device keeps computing meanwhile).  The host tier is a cache of the same kind one level down: its requests
+ * are the device tier's switches, one at a time in the order they are issued; replacement by the same rule as the device
+ * tier (coe_config.eviction), applied to host residency; its initial fill is by descending usage probability (Section 4.1)
+ * and precedes the device's.  Must be called before the first coe_register_expert.  coe_debug_forward then serves
+ * device-resident experts only and coe_debug_layer_output is not available (COE_ESTATE).
+ * Errors: COE_EINVAL (cap <= 0, null or overlong path), COE_ESTATE (experts already registered), COE_EIO (file). */
+int coe_set_host_tier(coe_ctx* ctx, int32_t host_cap_experts, const char* backing_path);
 
 /* Routing rules (paper Sections 2.1, 4.5 "Routing rules"): CSR successor lists.  Expert e routes on the argmax
  * over its first n_route = succ_off[e+1]-succ_off[e] logits (lowest index wins ties); the request goes to
@@ -216,6 +235,8 @@ int coe_debug_last_regroup(coe_ctx* ctx, int32_t* n_pending, int32_t* n_live, in
 /* Switch log since creation: flat words {expert, n_victims, victims...} per switch, initial fill included.
  * Writes at most cap words; *n_words receives the total. */
 int coe_debug_switch_log(coe_ctx* ctx, int32_t cap, int32_t* log, int32_t* n_words);
+/* The same for the host tier (empty without one): {expert, n_victims, victims...} per read from the backing file. */
+int coe_debug_host_log(coe_ctx* ctx, int32_t cap, int32_t* log, int32_t* n_words);
 /* Which experts are resident: out[E] bytes (0/1). */
 int coe_debug_resident(coe_ctx* ctx, uint8_t* out);
 /* Run one expert on n inputs (device pointer, context dtype) without routing: logits_out [n][n_classes] fp32 (host). */

@@ -272,3 +272,36 @@ class CacheSim:
             e, nv = int(log[i]), int(log[i + 1])
             sw.append((e, [int(v) for v in log[i + 2:i + 2 + nv]])); i += 2 + nv
         return [int(v) for v in order[:n_order.value]], sw
+
+
+class TieredCacheSim:
+    """Replay of two cache levels (Section 1: experts are offloaded to CPU memory or SSD; Section 5.1: CPU memory as a cache in
+    front of the SSD).  The reading: the lower level is a cache of the same kind whose requests are the upper level's loads,
+    one at a time in the order they are issued; each level applies the replacement rule to its own residency; the lower
+    level's initial fill (Section 4.1, descending usage probability) precedes the upper one's."""
+
+    def __init__(self, nbytes, prob, succ_off, succ, cap_device: int, cap_host: int, rule: int = 0, in_use: int = 0):
+        self.E = len(nbytes)
+        self.dev = CacheSim(nbytes, prob, succ_off, succ, cap_experts=cap_device, rule=rule, in_use=in_use)
+        self.host = CacheSim(nbytes, prob, succ_off, succ, cap_experts=cap_host, rule=rule)
+
+    def _serve(self, e: int):
+        need = np.zeros(self.E, np.uint8)
+        need[e] = 1
+        return self.host.stage(need)[1]
+
+    def init_fill(self):
+        """Returns (experts loaded to the device, reads of the lower level as [(expert, victims)])."""
+        reads = [(e, []) for e in self.host.init_fill()]
+        loaded = self.dev.init_fill()
+        for e in loaded:
+            reads += self._serve(e)
+        return loaded, reads
+
+    def stage(self, has_group):
+        """Returns (order, device switches, reads of the lower level)."""
+        order, sw = self.dev.stage(has_group)
+        reads = []
+        for e, _ in sw:
+            reads += self._serve(e)
+        return order, sw, reads

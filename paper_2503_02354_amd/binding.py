@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcoe.so")
 
 COE_OK, COE_DONE = 0, 1
-COE_EINVAL, COE_ENOMEM, COE_ESTATE, COE_EGRAPH, COE_EDEVICE, COE_ERANGE = -1, -2, -3, -4, -5, -6
+COE_EINVAL, COE_ENOMEM, COE_ESTATE, COE_EGRAPH, COE_EDEVICE, COE_ERANGE, COE_EIO = -1, -2, -3, -4, -5, -6, -7
 K_REGROUP_INDEX, K_REGROUP_GATHER, K_CONV_MFMA, K_CONV_DIRECT, K_POOL, K_HEAD, K_SWITCH, K_CONV_STEM = range(8)
 KERNEL_CLASS_NAMES = ["regroup_index", "regroup_gather", "conv_mfma", "conv_direct", "pool", "head", "switch", "conv_stem", "attention", "token_ops", "conv_slab", "switch_wait"]
 
@@ -25,7 +25,7 @@ EXPORTS = [
     "coe_debug_last_regroup", "coe_debug_switch_log", "coe_debug_resident", "coe_debug_forward", "coe_debug_layer_output", "coe_debug_regroup", "coe_debug_conv",
     "coe_profile_read", "coe_profile_issued", "coe_validate_graph", "coe_policy_create", "coe_policy_destroy", "coe_policy_init_fill",
     "coe_policy_stage", "coe_policy_resident", "coe_policy_set_eviction", "coe_policy_set_in_use_depth", "coe_set_arranging", "coe_arrange_defer", "coe_set_latency_model", "coe_assign_executors", "coe_debug_last_assignment",
-    "coe_regroup_static", "coe_debug_last_chunks",
+    "coe_regroup_static", "coe_debug_last_chunks", "coe_set_host_tier", "coe_debug_host_log",
     "coe_profiler_fit_latency", "coe_profiler_max_batch", "coe_profiler_arranging_window", "coe_profiler_window_step",
 ]
 
@@ -50,7 +50,8 @@ class coe_step_stats(C.Structure):
                 ("n_misses", C.c_int32), ("n_evictions", C.c_int32), ("bytes_switched", C.c_int64),
                 ("host_plan_us", C.c_double), ("n_grouped", C.c_int32), ("n_group_sets", C.c_int32),
                 ("n_deferred_groups", C.c_int32), ("n_deferred_requests", C.c_int32), ("n_executors_used", C.c_int32),
-                ("n_device_allocs", C.c_int32)]
+                ("n_device_allocs", C.c_int32), ("n_host_misses", C.c_int32), ("bytes_read", C.c_int64),
+                ("read_us", C.c_double)]
 
 
 class coe_window_state(C.Structure):
@@ -82,6 +83,8 @@ def _load():
     L.coe_debug_last_regroup.argtypes = [vp, C.POINTER(i32), C.POINTER(i32), vp, vp, vp, vp, i32]
     L.coe_debug_switch_log.argtypes = [vp, i32, vp, C.POINTER(i32)]
     L.coe_debug_resident.argtypes = [vp, vp]
+    L.coe_set_host_tier.argtypes = [vp, i32, C.c_char_p]
+    L.coe_debug_host_log.argtypes = [vp, i32, vp, C.POINTER(i32)]
     L.coe_debug_forward.argtypes = [vp, i32, i32, vp, vp]
     L.coe_debug_layer_output.argtypes = [vp, i32, i32, vp, i32, vp, C.c_size_t]
     L.coe_debug_regroup.argtypes = [vp, i32, vp, i32, vp, vp, vp, vp]
@@ -372,6 +375,16 @@ class Context:
         self._chk(lib.coe_debug_switch_log(self._h, 0, None, C.byref(n)))
         log = np.zeros(max(n.value, 1), np.int32)
         self._chk(lib.coe_debug_switch_log(self._h, n.value, _ptr(log), C.byref(n)))
+        return parse_switch_log(log[:n.value])
+
+    def coe_set_host_tier(self, host_cap_experts: int, backing_path: str):
+        self._chk(lib.coe_set_host_tier(self._h, host_cap_experts, os.fsencode(backing_path)))
+
+    def coe_debug_host_log(self):
+        n = C.c_int32(0)
+        self._chk(lib.coe_debug_host_log(self._h, 0, None, C.byref(n)))
+        log = np.zeros(max(n.value, 1), np.int32)
+        self._chk(lib.coe_debug_host_log(self._h, n.value, _ptr(log), C.byref(n)))
         return parse_switch_log(log[:n.value])
 
     def coe_debug_resident(self) -> np.ndarray:

@@ -4,6 +4,9 @@
 
 #include <hip/hip_runtime_api.h>
 
+#include <fcntl.h>
+#include <unistd.h>
+
 #include <algorithm>
 #include <chrono>
 #include <cstdio>
@@ -60,6 +63,14 @@ struct DevBuf {
     int32_t cls = 0;                 // size class
 };
 
+// A pinned host buffer of the host tier (only with coe_set_host_tier): holds the blob of one expert at a time.
+struct HostSlot {
+    void* p = nullptr;
+    int32_t cls = 0;
+    hipEvent_t copied = nullptr;     // recorded on the copy stream after the last host-to-device copy out of p
+    bool used = false;
+};
+
 struct Expert {
     bool registered = false;
     int32_t arch = -1;
@@ -70,6 +81,8 @@ struct Expert {
     DevBuf* buf = nullptr;           // arena slot that holds the device copy when resident
     hipEvent_t loaded = nullptr;     // recorded on the copy stream after the switch
     bool load_pending = false;       // compute stream has not yet waited for `loaded`
+    int64_t file_off = -1;           // host tier: where the blob sits in the backing file
+    HostSlot* hslot = nullptr;       // host tier: the pinned slot that holds it, if any
 };
 
 struct ProfClass {
@@ -114,6 +127,16 @@ struct coe_ctx {
     std::vector<DevBuf> slots;
     std::vector<std::vector<DevBuf*>> free_slots;   // per size class, oldest release first
     int64_t device_allocs = 0;                      // hipMalloc calls made by this context so far
+
+    // host tier (third storage level): blobs live in a file, at most host_cap of them in pinned slots
+    int32_t host_cap = 0;
+    int fd = -1;
+    std::string backing_path;
+    int64_t file_bytes = 0;
+    std::unique_ptr<coe::Policy> host_policy;
+    std::vector<HostSlot> hslots;
+    std::vector<std::vector<HostSlot*>> free_hslots;
+    std::vector<int32_t> host_log;
 
     // request store
     int32_t n_live = 0, n_collected = 0;
@@ -512,8 +535,90 @@ void release_expert(coe_ctx* c, int32_t v)
     x.load_pending = false;
 }
 
+// ---- host tier --------------------------------------------------------------------------------------------------------
+int build_host_arena(coe_ctx* c)
+{
+    // size classes are the device arena's (build_arena ran first)
+    std::vector<size_t> class_bytes(c->free_slots.size(), 0);
+    std::vector<int32_t> members(c->free_slots.size(), 0);
+    for (const Expert& x : c->experts) { class_bytes[x.cls] = x.nbytes; ++members[x.cls]; }
+    size_t n_total = 0;
+    for (int32_t m : members) n_total += (size_t)std::min(m, c->host_cap);
+    c->hslots.resize(n_total);
+    c->free_hslots.assign(class_bytes.size(), {});
+    size_t i = 0;
+    for (size_t k = 0; k < class_bytes.size(); ++k)
+        for (int32_t j = 0; j < std::min(members[k], c->host_cap); ++j, ++i) {
+            HostSlot& h = c->hslots[i];
+            h.cls = (int32_t)k;
+            if (hipHostMalloc(&h.p, class_bytes[k], hipHostMallocDefault) != hipSuccess) {
+                (void)hipGetLastError();
+                h.p = nullptr;
+                return fail(c, COE_ENOMEM, "pinned host allocation of the host tier failed");
+            }
+            HIPCHK(c, hipEventCreateWithFlags(&h.copied, hipEventDisableTiming));
+            c->free_hslots[k].push_back(&h);
+        }
+    return COE_OK;
+}
+
+// One read from the backing file: victims leave their host slots, the blob of `sw.expert` is read into a free one.
+int host_read(coe_ctx* c, const coe::Switch& sw, coe_step_stats* st)
+{
+    c->host_log.push_back(sw.expert);
+    c->host_log.push_back((int32_t)sw.victims.size());
+    for (int32_t v : sw.victims) {
+        c->host_log.push_back(v);
+        Expert& xv = c->experts[v];
+        if (xv.hslot) {
+            c->free_hslots[xv.hslot->cls].push_back(xv.hslot);
+            xv.hslot = nullptr;
+        }
+    }
+    Expert& x = c->experts[sw.expert];
+    std::vector<HostSlot*>& fl = c->free_hslots[x.cls];
+    if (fl.empty()) return fail(c, COE_ESTATE, "internal: no free host slot for an expert the host policy admitted");
+    HostSlot* h = fl.front();
+    fl.erase(fl.begin());
+    // the slot may still be the source of a copy that was enqueued earlier
+    if (h->used) HIPCHK(c, hipEventSynchronize(h->copied));
+    auto t0 = std::chrono::steady_clock::now();
+    size_t done = 0;
+    while (done < x.nbytes) {
+        ssize_t got = pread(c->fd, (uint8_t*)h->p + done, x.nbytes - done, (off_t)(x.file_off + (int64_t)done));
+        if (got <= 0) {
+            fl.push_back(h);
+            return fail(c, COE_EIO, "reading an expert from the backing file failed");
+        }
+        done += (size_t)got;
+    }
+    x.hslot = h;
+    if (st) {
+        ++st->n_host_misses;
+        st->bytes_read += (int64_t)x.nbytes;
+        st->read_us += std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
+    }
+    return COE_OK;
+}
+
+// The host tier serves one device switch: a hit needs nothing, a miss evicts by the tier's own policy and reads.
+int host_fetch(coe_ctx* c, int32_t e, coe_step_stats* st)
+{
+    std::vector<uint8_t> need((size_t)c->experts.size(), 0);
+    need[e] = 1;
+    std::vector<int32_t> order;
+    std::vector<coe::Switch> sws;
+    if (!c->host_policy->plan_stage(need.data(), order, sws)) return fail(c, COE_ENOMEM, "an expert does not fit the host tier");
+    for (const coe::Switch& sw : sws) {
+        int rc = host_read(c, sw, st);
+        if (rc) return rc;
+    }
+    return COE_OK;
+}
+
 // Enqueue one expert switch on the copy stream: victims leave, the expert's blob is copied into a device buffer.
-int issue_load(coe_ctx* c, const coe::Switch& sw, coe_step_stats* st)
+// st counts the switch; read_st (if the host tier has to read the blob first) counts the read.
+int issue_load(coe_ctx* c, const coe::Switch& sw, coe_step_stats* st, coe_step_stats* read_st)
 {
     c->switch_log.push_back(sw.expert);
     c->switch_log.push_back((int32_t)sw.victims.size());
@@ -525,13 +630,23 @@ int issue_load(coe_ctx* c, const coe::Switch& sw, coe_step_stats* st)
     DevBuf* b = nullptr;
     int rc = acquire_buf(c, x.cls, &b);
     if (rc) return rc;
+    const void* src = x.host;
+    if (c->host_cap > 0) {
+        rc = host_fetch(c, sw.expert, read_st);
+        if (rc) { c->free_slots[x.cls].insert(c->free_slots[x.cls].begin(), b); return rc; }
+        src = x.hslot->p;
+    }
     // the buffer may still be read by kernels of its previous owner
     if (b->used) HIPCHK(c, hipStreamWaitEvent(c->sx, b->last_use, 0));
     {
         Span sp(c, COE_K_SWITCH, (double)x.nbytes, c->sx);
-        HIPCHK(c, hipMemcpyAsync(b->p, x.host, x.nbytes, hipMemcpyHostToDevice, c->sx));
+        HIPCHK(c, hipMemcpyAsync(b->p, src, x.nbytes, hipMemcpyHostToDevice, c->sx));
     }
     HIPCHK(c, hipEventRecord(x.loaded, c->sx));
+    if (c->host_cap > 0) {
+        HIPCHK(c, hipEventRecord(x.hslot->copied, c->sx));
+        x.hslot->used = true;
+    }
     x.buf = b;
     x.load_pending = true;
     if (st) {
@@ -737,13 +852,20 @@ int run_group_set(coe_ctx* c, Lane& ln, const std::vector<SetMember>& set, const
 int do_init_fill(coe_ctx* c, coe_step_stats* st)
 {
     if (c->filled) return COE_OK;
+    if (c->host_cap > 0) {
+        // the host tier fills first (descending usage probability), then serves the device's fill
+        for (int32_t e : c->host_policy->init_fill()) {
+            coe::Switch sw{e, {}};
+            int rc = host_read(c, sw, st);
+            if (rc) return rc;
+        }
+    }
     std::vector<int32_t> loaded = c->policy->init_fill();
     for (int32_t e : loaded) {
         coe::Switch sw{e, {}};
-        int rc = issue_load(c, sw, nullptr);
+        int rc = issue_load(c, sw, nullptr, st);
         if (rc) return rc;
     }
-    (void)st;
     c->filled = true;
     return COE_OK;
 }
@@ -835,6 +957,14 @@ void coe_destroy(coe_ctx* c)
     for (DevBuf& b : c->slots)
         if (b.last_use) hipEventDestroy(b.last_use);
     if (c->arena) hipFree(c->arena);
+    for (HostSlot& h : c->hslots) {
+        if (h.p) hipHostFree(h.p);
+        if (h.copied) hipEventDestroy(h.copied);
+    }
+    if (c->fd >= 0) {
+        close(c->fd);
+        unlink(c->backing_path.c_str());
+    }
     for (auto& pc : c->prof)
         for (auto& s : pc.spans) { hipEventDestroy(s.first); hipEventDestroy(s.second); }
     for (hipEvent_t e : c->ev_pool) hipEventDestroy(e);
@@ -890,7 +1020,11 @@ int coe_register_expert(coe_ctx* c, int32_t id, int32_t arch_id, const void* w, 
     if ((size_t)id >= c->experts.size()) c->experts.resize((size_t)id + 1);
     Expert& x = c->experts[id];
     if (x.registered) return fail(c, COE_EINVAL, "expert id registered twice");
-    if (hipHostMalloc(&x.host, nbytes, hipHostMallocDefault) != hipSuccess) {
+    std::vector<uint8_t> image;          // host tier: the blob is prepared here and goes to the backing file
+    if (c->host_cap > 0) {
+        image.resize(nbytes);
+        x.host = image.data();
+    } else if (hipHostMalloc(&x.host, nbytes, hipHostMallocDefault) != hipSuccess) {
         (void)hipGetLastError();
         x.host = nullptr;
         return fail(c, COE_ENOMEM, "pinned host allocation failed");
@@ -909,11 +1043,46 @@ int coe_register_expert(coe_ctx* c, int32_t id, int32_t arch_id, const void* w, 
             std::memcpy(t, tmp.data(), n * sizeof(uint16_t));
         }
     }
+    if (c->host_cap > 0) {
+        x.host = nullptr;
+        size_t done = 0;
+        while (done < nbytes) {
+            ssize_t put = pwrite(c->fd, image.data() + done, nbytes - done, (off_t)(c->file_bytes + (int64_t)done));
+            if (put <= 0) return fail(c, COE_EIO, "writing an expert to the backing file failed");
+            done += (size_t)put;
+        }
+        x.file_off = c->file_bytes;
+        c->file_bytes += (int64_t)((nbytes + 4095) / 4096 * 4096);
+    }
     HIPCHK(c, hipEventCreateWithFlags(&x.loaded, hipEventDisableTiming));
     x.registered = true;
     x.arch = arch_id;
     x.prob = prob;
     x.nbytes = nbytes;
+    return COE_OK;
+}
+
+int coe_set_host_tier(coe_ctx* c, int32_t host_cap_experts, const char* backing_path)
+{
+    if (!c) return COE_EINVAL;
+    if (host_cap_experts <= 0 || !backing_path || !backing_path[0] || std::strlen(backing_path) >= 4096)
+        return fail(c, COE_EINVAL, "host tier needs a positive cap and a path");
+    if (!c->experts.empty() || c->graph_set) return fail(c, COE_ESTATE, "the host tier must be set before experts are registered");
+    if (c->fd >= 0) return fail(c, COE_ESTATE, "host tier already set");
+    int fd = open(backing_path, O_CREAT | O_RDWR | O_TRUNC | O_CLOEXEC, 0600);
+    if (fd < 0) return fail(c, COE_EIO, std::string("cannot create the backing file ") + backing_path);
+    c->fd = fd;
+    c->backing_path = backing_path;
+    c->host_cap = host_cap_experts;
+    c->file_bytes = 0;
+    return COE_OK;
+}
+
+int coe_debug_host_log(coe_ctx* c, int32_t cap, int32_t* log, int32_t* n_words)
+{
+    if (!c || !n_words || (cap > 0 && !log) || cap < 0) return fail(c, COE_EINVAL, "bad argument");
+    *n_words = (int32_t)c->host_log.size();
+    for (int32_t i = 0; i < std::min<int32_t>(cap, *n_words); ++i) log[i] = c->host_log[i];
     return COE_OK;
 }
 
@@ -961,10 +1130,18 @@ int coe_set_dependency_graph(coe_ctx* c, int32_t n, const int32_t* succ_off, con
     // every device buffer the step path needs is allocated here, once: the expert arena, the request store and the
     // executors' activation workspaces.  coe_submit and coe_step allocate nothing.
     int rc2 = build_arena(c);
+    if (rc2 == COE_OK && c->host_cap > 0) {
+        c->host_policy.reset(new coe::Policy(n, bytes.data(), prob.data(), c->succ_off.data(), c->succ.data(), c->host_cap, 0));
+        c->host_policy->set_eviction(c->cfg.eviction);
+        rc2 = build_host_arena(c);
+        // the file's pages leave the page cache where the file system allows it, so that reads come from the device below
+        if (rc2 == COE_OK && fsync(c->fd) == 0) (void)posix_fadvise(c->fd, 0, 0, POSIX_FADV_DONTNEED);
+    }
     if (rc2 == COE_OK) rc2 = ensure_store(c);
     if (rc2 == COE_OK) rc2 = ensure_workspace(c);
     if (rc2) {
         c->policy.reset();
+        c->host_policy.reset();
         return rc2;
     }
     c->E = n;
@@ -1092,7 +1269,7 @@ static int step_body(coe_ctx* c, coe_step_stats& st)
             bool ready = true;
             for (int32_t v : sw.victims) ready = ready && !(has_group[v] && !launched[v]);
             if (!ready) break;
-            int r2 = issue_load(c, sw, &st);
+            int r2 = issue_load(c, sw, &st, &st);
             if (r2) return r2;
             ++next_load;
         }
@@ -1405,6 +1582,7 @@ int coe_debug_forward(coe_ctx* c, int32_t e, int32_t n, const void* dev_in, floa
         if (x.load_pending) { HIPCHK(c, hipStreamWaitEvent(c->sc, x.loaded, 0)); x.load_pending = false; }
         w = x.buf->p;
     } else {
+        if (!x.host) return fail(c, COE_ESTATE, "with a host tier only resident experts can be run directly");
         HIPCHK(c, hipMalloc(&w, x.nbytes));
         temp = true;
         HIPCHK(c, hipMemcpy(w, x.host, x.nbytes, hipMemcpyHostToDevice));
@@ -1438,6 +1616,7 @@ int coe_debug_layer_output(coe_ctx* c, int32_t e, int32_t n, const void* dev_in,
     if (L.fuse_pool || L.fused_away) return fail(c, COE_EINVAL, "layer is fused with its neighbour");
     const size_t bytes = (size_t)n * L.P * L.Q * L.K * a.elem();
     if (out_bytes != bytes) return fail(c, COE_EINVAL, "output size does not match the layer");
+    if (!x.host) return fail(c, COE_ESTATE, "not available with a host tier");
     int rc = ensure_workspace(c);
     if (rc) return rc;
     void* w = nullptr;

@@ -13,10 +13,12 @@ def device_tensor(x: np.ndarray):
 
 
 def run_chain_gpu(B, wl, blobs, x, first_expert=None, *, max_batch=0, cap_experts=None, arrival=None, on_device=True,
-                  profile=False, ctx=None, keep=False, group_small=0, arranging=None, eviction=0, prefetch_depth=0, executors=0, latency=None):
+                  profile=False, ctx=None, keep=False, group_small=0, arranging=None, eviction=0, prefetch_depth=0, executors=0, latency=None,
+                  host_tier=None):
     """Submit x in arrival batches, one coe_step after each submit, then step until done; collect everything.
     arranging: (min_group_resident, min_group_missing, max_wait_steps) set for every architecture.
-    Returns dict(logits, path, ids, stats, switch_log[, ctx])."""
+    host_tier: (host_cap_experts, backing_path): experts live in that file, at most so many of them in pinned host memory.
+    Returns dict(logits, path, ids, stats, switch_log, host_log[, ctx])."""
     import torch
     n = x.shape[0]
     own = ctx is None
@@ -24,6 +26,8 @@ def run_chain_gpu(B, wl, blobs, x, first_expert=None, *, max_batch=0, cap_expert
         ctx = B.Context(max_requests=max(n, 1), max_stages=wl.max_stages, max_batch=max_batch,
                         cache_cap_experts=wl.cache_cap_experts if cap_experts is None else cap_experts, profile=profile,
                         group_small=group_small, eviction=eviction, prefetch_depth=prefetch_depth, executors=executors)
+        if host_tier is not None:
+            ctx.coe_set_host_tier(*host_tier)
         B.setup_workload(ctx, wl, blobs)
     if arranging is not None:
         for a in range(len(wl.archs)):
@@ -53,7 +57,8 @@ def run_chain_gpu(B, wl, blobs, x, first_expert=None, *, max_batch=0, cap_expert
         raise AssertionError("chain did not finish")
     ids, logits, path = ctx.coe_collect(max(n, 1))
     order = np.argsort(ids)
-    out = dict(ids=ids[order], logits=logits[order], path=path[order], stats=stats, switch_log=ctx.coe_debug_switch_log())
+    out = dict(ids=ids[order], logits=logits[order], path=path[order], stats=stats, switch_log=ctx.coe_debug_switch_log(),
+               host_log=ctx.coe_debug_host_log())
     if keep:
         out["ctx"] = ctx
     elif own:

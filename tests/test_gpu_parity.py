@@ -1,4 +1,5 @@
 """GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same seeded inputs."""
+import os
 import time
 
 import numpy as np
@@ -252,6 +253,75 @@ def test_capped_cache_switches_match_policy_and_results_do_not_change(B, oracle,
         g2 = run_chain_gpu(B, wl, blobs, x, max_batch=16, arrival=30, cap_experts=cap)
         assert np.array_equal(g2["path"], got["path"])
         assert rel_err(g2["logits"], got["logits"]).max() <= 1e-6
+
+
+@pytest.mark.parametrize("rule,depth,host_cap", [(0, 0, 6), (0, 2, 5), (1, 1, 4)])
+def test_host_tier_serves_switches_from_a_file(B, oracle, G, tmp_path, rule, depth, host_cap):
+    """Third storage level (Section 5.1: CPU memory as a cache in front of the SSD): every expert lives in a backing file, at
+    most host_cap of them in pinned host memory, four on the device.  Results and the device's switch log equal those of the
+    run that keeps every expert in host memory, the reads from the file equal the oracle's two-level replay, and the file is
+    gone after the context."""
+    wl = W.config3(120, hw=64, n_experts=10, width=16, cap=4, arrival_batch=30, calibrated=False)
+    G.calibrate_workload(wl, n_cal=64, targets={0: W.zipf_probs(9, 1.1)})
+    blobs = [wl.blob(e) for e in range(10)]
+    x, sub, want, _ = G.guarded_inputs(wl, blobs, range(120))
+    plain = run_chain_gpu(B, wl, blobs, x, max_batch=16, arrival=30, eviction=rule, prefetch_depth=depth)
+    assert_chain_parity(plain, want, REL_TOL_BF16)
+    assert plain["host_log"] == []
+    path = str(tmp_path / "experts.bin")
+    got = run_chain_gpu(B, wl, blobs, x, max_batch=16, arrival=30, eviction=rule, prefetch_depth=depth, host_tier=(host_cap, path),
+                        keep=True)
+    ctx = got.pop("ctx")
+    assert os.path.getsize(path) >= sum(b.nbytes for b in blobs)
+    assert np.array_equal(got["path"], plain["path"]) and np.array_equal(got["logits"], plain["logits"])
+    assert got["switch_log"] == plain["switch_log"]
+    # the oracle's replay of both levels over the same per-step group sets
+    sim = oracle.TieredCacheSim([b.nbytes for b in blobs], wl.usage_prob, wl.graph.succ_off, wl.graph.succ, cap_device=4,
+                                cap_host=host_cap, rule=rule, in_use=depth)
+    loaded, reads = sim.init_fill()
+    log = [(e, []) for e in loaded]
+    n_init = len(reads)
+    pend, nxt, per_step = {}, 0, []
+    for rc, st in got["stats"]:
+        if nxt < 120:
+            for r in range(nxt, nxt + 30):
+                pend[r] = 0
+            nxt += 30
+        if not pend:
+            break
+        hg = np.zeros(10, np.uint8); hg[list(set(pend.values()))] = 1
+        order, sw, rd = sim.stage(hg)
+        log += sw
+        reads += rd
+        per_step.append(len(rd))
+        assert st.n_misses == len(sw) and st.n_host_misses == len(rd) + (n_init if len(per_step) == 1 else 0)
+        assert st.bytes_read == st.n_host_misses * blobs[0].nbytes
+        new = {}
+        for r, e in pend.items():
+            stage = want["path"][r].tolist().index(e)
+            if stage + 1 < want["path"].shape[1] and want["path"][r, stage + 1] >= 0:
+                new[r] = int(want["path"][r, stage + 1])
+        pend = new
+    assert got["switch_log"] == log and got["host_log"] == reads
+    assert sum(per_step) > 0 and len(reads) < n_init + len(log)        # the host level both misses and hits
+    with pytest.raises(B.CoEError):                                   # direct forwards are served from the device only
+        missing = int(np.nonzero(~ctx.coe_debug_resident())[0][0])
+        ctx.coe_debug_forward(missing, 1, device_tensor(x[:1]).data_ptr())
+    ctx.close()
+    assert not os.path.exists(path)
+
+
+def test_host_tier_argument_checks(B, tmp_path):
+    ctx = B.Context(max_requests=4)
+    for cap, path in ((0, str(tmp_path / "a")), (2, ""), (2, str(tmp_path / "no_such_dir" / "a"))):
+        with pytest.raises(B.CoEError):
+            ctx.coe_set_host_tier(cap, path)
+    ctx.coe_set_host_tier(2, str(tmp_path / "b"))
+    with pytest.raises(B.CoEError) as ei:
+        ctx.coe_set_host_tier(2, str(tmp_path / "c"))
+    assert ei.value.code == B.COE_ESTATE
+    ctx.close()
+    assert not os.path.exists(tmp_path / "b")
 
 
 def test_config4_small_dag(B, oracle, G):

@@ -120,6 +120,38 @@ def test_in_use_depth_matches_oracle_random(B, oracle, seed, depth):
     _compare_policy(B, oracle, nbytes, wl.usage_prob, wl.graph, 0 if seed % 2 else 8, 130 if seed % 2 else 0, stages, depth=depth)
 
 
+@pytest.mark.parametrize("seed", range(4))
+def test_two_level_policy_matches_oracle_random(B, oracle, seed):
+    """The host tier's arrangement (Section 5.1: CPU memory as a cache in front of the SSD): the library's policy, once per
+    level with the lower level asked once per device switch, against the oracle's two-level replay."""
+    rng = np.random.default_rng(200 + seed)
+    wl = W.config4(8, hw=32, tiers=(4, 8, 12), width=8, fan=(3, 2), calibrated=False)
+    E = wl.graph.n_experts
+    nbytes = [10] * E
+    rule = seed % 3
+    sim = oracle.TieredCacheSim(nbytes, wl.usage_prob, wl.graph.succ_off, wl.graph.succ, cap_device=5, cap_host=9 + seed, rule=rule,
+                                in_use=seed % 2)
+    dev = B.Policy(nbytes, wl.usage_prob, wl.graph.succ_off, wl.graph.succ, 5, 0, eviction=rule, in_use_depth=seed % 2)
+    host = B.Policy(nbytes, wl.usage_prob, wl.graph.succ_off, wl.graph.succ, 9 + seed, 0, eviction=rule)
+
+    def serve(e):
+        need = np.zeros(E, np.uint8); need[e] = 1
+        return host.stage(need)[1]
+
+    reads = [(e, []) for e in host.init_fill()]
+    loaded = dev.init_fill()
+    for e in loaded:
+        reads += serve(e)
+    assert (loaded, reads) == sim.init_fill()
+    for _ in range(40):
+        hg = (rng.random(E) < rng.choice([0.1, 0.3, 0.5])).astype(np.uint8)
+        order, sw = dev.stage(hg)
+        reads = []
+        for e, _ in sw:
+            reads += serve(e)
+        assert (order, sw, reads) == sim.stage(hg)
+
+
 def test_policy_zipf_tree_keeps_hot_experts(B, oracle):
     # config-3 structure at small scale: root + Zipf leaves, cap 5: after many stages the hottest leaves stay resident
     wl = W.config3(64, hw=32, n_experts=12, width=8, cap=5, arrival_batch=16, calibrated=False)

@@ -259,6 +259,57 @@ def test_cache_invariants_random(oracle):
         assert all(before[e] for e in order[:n_hit])                              # hits run first
 
 
+def test_two_level_cache_hand_worked(oracle):
+    """Root 0 -> leaves 1..5 with usage probabilities 1.0, .30, .25, .20, .15, .10; two experts fit the device, four the host
+    level.  Worked by hand from the reading: the host level fills first ([0, 1, 2, 3]), serves the device's fill ([0, 1]) without
+    a read, and afterwards every device switch is one request to it."""
+    g = W.tree_graph(6)
+    sim = oracle.TieredCacheSim([10] * 6, [1.0, 0.30, 0.25, 0.20, 0.15, 0.10], g.succ_off, g.succ, cap_device=2, cap_host=4)
+    loaded, reads = sim.init_fill()
+    assert loaded == [0, 1] and reads == [(0, []), (1, []), (2, []), (3, [])]
+    # a group for leaf 4: the device evicts its least probable expert (1); the host level misses and evicts ITS least probable (3)
+    order, sw, reads = sim.stage([False, False, False, False, True, False])
+    assert order == [4] and sw == [(4, [1])] and reads == [(4, [3])]
+    assert sim.host.resident().tolist() == [True, True, True, False, True, False]
+    # groups for 3 and 5, both missing on the device.  Device: 3 replaces 4; 3 has run when 5 is loaded and is the least
+    # probable again.  Host level: 3 is read back (4 leaves), then 5 replaces 3: each level thrashes its own coldest slot
+    order, sw, reads = sim.stage([False, False, False, True, False, True])
+    assert order == [3, 5] and sw == [(3, [4]), (5, [3])] and reads == [(3, [4]), (5, [3])]
+    assert sim.dev.resident().tolist() == [True, False, False, False, False, True]
+    assert sim.host.resident().tolist() == [True, True, True, False, False, True]
+    # leaf 2 is on the host level: a device switch without a read
+    order, sw, reads = sim.stage([False, False, True, False, False, False])
+    assert sw == [(2, [5])] and reads == []
+
+
+def test_two_level_cache_invariants_random(oracle):
+    rng = np.random.default_rng(11)
+    wl = W.config4(16, hw=32, tiers=(4, 8, 12), width=8, fan=(3, 2), calibrated=False)
+    E = wl.graph.n_experts
+    for cap_host in (8, 12, E):
+        sim = oracle.TieredCacheSim([10] * E, wl.usage_prob, wl.graph.succ_off, wl.graph.succ, cap_device=5, cap_host=cap_host)
+        loaded, reads = sim.init_fill()
+        assert [e for e, _ in reads[:cap_host]] == sorted(range(E), key=lambda e: (-wl.usage_prob[e], e))[:cap_host]
+        seen = {e for e, _ in reads}
+        n_sw = n_rd = 0
+        for _ in range(40):
+            hg = rng.random(E) < 0.25
+            on_host = sim.host.resident()
+            order, sw, reads = sim.stage(hg)
+            assert all(sim.host.resident()[e] for e, _ in sw[-1:])               # the newest load's source is still there
+            assert [e for e, _ in reads] == [e for e in dict.fromkeys(e for e, _ in reads)]     # never read twice in a stage...
+            assert set(e for e, _ in reads) <= set(e for e, _ in sw)             # ... and only for device switches
+            assert int(sim.host.resident().sum()) <= cap_host
+            if cap_host == E:
+                assert all(v == [] for _, v in reads) and not (set(e for e, _ in reads) & seen)   # everything fits: one read each
+            seen |= {e for e, _ in reads}
+            n_sw += len(sw); n_rd += len(reads)
+            del on_host
+        assert n_rd <= n_sw
+        if cap_host < E:
+            assert 0 < n_rd
+
+
 # ---------------------------------------------------------------------------------------------
 # margin guard: admissible outcomes at near-ties
 # ---------------------------------------------------------------------------------------------
