@@ -293,6 +293,9 @@ def capped_leg(name, steps, warmup):
            "switches_per_pass": c["switches_per_pass"], "bytes_switched_per_pass": c["bytes_switched_per_pass"],
            "switch_GB/s": c.get("switch_GB/s"), "copy_ms_per_pass": c.get("copy_ms_per_pass"),
            "copy_wait_ms_per_pass": c.get("copy_wait_ms_per_pass"), "copy_hidden_under_compute": c.get("copy_hidden_under_compute"),
+           # the other way to ask the same question: how much of the copy time shows up as extra time of the pass
+           "pass_slowdown_over_copy_time": None if not c.get("copy_ms_per_pass") else
+           round((r["ms_per_step"] - free["ms_per_step"]) / c["copy_ms_per_pass"], 3),
            "host_plan_us_per_step": c["host_plan_us_per_step"], "device_allocations_in_steps": c["device_allocations_in_steps"],
            "regroup_gather_GB/s": r["kernel_classes"].get("regroup_gather", {}).get("GB/s"),
            "regroup_gather": "inside the first convolution kernel (row table): no bytes of its own" if "regroup_gather" not in r["kernel_classes"] else "copy kernel",
