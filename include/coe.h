@@ -161,9 +161,9 @@ int coe_register_expert(coe_ctx* ctx, int32_t expert_id, int32_t arch_id, const 
  * hold every expert either, it serves as a cache in front of the SSD).  Without this call every expert keeps a pinned host
  * copy.  With it, host memory holds at most host_cap_experts experts in pinned slots (a slot class per blob size, allocated
  * when the dependency graph is set) and every expert's blob lives in the file at backing_path, which the library creates,
- * truncates, fills at registration, and removes in coe_destroy.  A device switch whose expert has no host slot reads the
- * blob from the file into one first (a synchronous read on the calling thread; switches are issued prefetch_depth groups
- * ahead, so the device keeps computing meanwhile).  The host tier is a cache of the same kind one level down: its requests
+ * truncates, fills at registration, and removes in coe_destroy.  A device switch whose expert has no host slot has the
+ * blob read from the file into one first: the reads of a step are queued, in switch order, on a loader thread of the context
+ * when the step is planned, and coe_step waits for one only when the next group cannot be launched without it.  The host tier is a cache of the same kind one level down: its requests
  * are the device tier's switches, one at a time in the order they are issued; replacement by the same rule as the device
  * tier (coe_config.eviction), applied to host residency; its initial fill is by descending usage probability (Section 4.1)
  * and precedes the device's.  Must be called before the first coe_register_expert.  coe_debug_forward then serves

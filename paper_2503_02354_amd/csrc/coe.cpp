@@ -9,6 +9,10 @@
 
 #include <algorithm>
 #include <chrono>
+#include <condition_variable>
+#include <deque>
+#include <mutex>
+#include <thread>
 #include <cstdio>
 #include <cstring>
 #include <memory>
@@ -68,7 +72,19 @@ struct HostSlot {
     void* p = nullptr;
     int32_t cls = 0;
     hipEvent_t copied = nullptr;     // recorded on the copy stream after the last host-to-device copy out of p
-    bool used = false;
+    uint64_t planned = 0;            // copies out of p that steps have planned so far (stepping thread only)
+    uint64_t issued = 0;             // ... and enqueued so far (guarded by the loader's mutex)
+};
+
+// One read from the backing file, carried out by the loader thread while the stepping thread goes on launching.
+struct ReadJob {
+    HostSlot* slot = nullptr;
+    int64_t file_off = 0;
+    size_t nbytes = 0;
+    uint64_t need_issued = 0;        // copies out of the slot that must be enqueued (and complete) before it is overwritten
+    bool done = false;
+    int rc = COE_OK;
+    double read_us = 0.0;
 };
 
 struct Expert {
@@ -137,6 +153,12 @@ struct coe_ctx {
     std::vector<HostSlot> hslots;
     std::vector<std::vector<HostSlot*>> free_hslots;
     std::vector<int32_t> host_log;
+    std::thread loader;                             // started with the host tier's slots, joined in coe_destroy
+    std::mutex ld_mutex;
+    std::condition_variable ld_cv;
+    std::deque<ReadJob*> ld_queue;                  // jobs in the order of the switches they serve
+    std::deque<ReadJob> ld_jobs;                    // storage of the current step's jobs
+    bool ld_stop = false;
 
     // request store
     int32_t n_live = 0, n_collected = 0;
@@ -562,63 +584,120 @@ int build_host_arena(coe_ctx* c)
     return COE_OK;
 }
 
-// One read from the backing file: victims leave their host slots, the blob of `sw.expert` is read into a free one.
-int host_read(coe_ctx* c, const coe::Switch& sw, coe_step_stats* st)
+// The loader thread: reads in the order the jobs were queued.  A slot is overwritten only after every copy out of it that
+// was planned before the read has been enqueued by the stepping thread and has completed on the copy stream.
+void loader_main(coe_ctx* c)
 {
-    c->host_log.push_back(sw.expert);
-    c->host_log.push_back((int32_t)sw.victims.size());
-    for (int32_t v : sw.victims) {
-        c->host_log.push_back(v);
-        Expert& xv = c->experts[v];
-        if (xv.hslot) {
-            c->free_hslots[xv.hslot->cls].push_back(xv.hslot);
-            xv.hslot = nullptr;
+    (void)hipSetDevice(c->cfg.device);
+    for (;;) {
+        ReadJob* j = nullptr;
+        {
+            std::unique_lock<std::mutex> lk(c->ld_mutex);
+            c->ld_cv.wait(lk, [&] { return c->ld_stop || !c->ld_queue.empty(); });
+            if (c->ld_queue.empty()) return;             // stop requested and nothing left to do
+            j = c->ld_queue.front();
+            c->ld_cv.wait(lk, [&] { return c->ld_stop || j->slot->issued >= j->need_issued; });
+            if (j->slot->issued < j->need_issued) { j->rc = COE_ESTATE; j->done = true; c->ld_queue.pop_front(); c->ld_cv.notify_all(); continue; }
         }
+        int rc = COE_OK;
+        if (j->need_issued > 0 && hipEventSynchronize(j->slot->copied) != hipSuccess) rc = COE_EDEVICE;
+        auto t0 = std::chrono::steady_clock::now();
+        size_t done = 0;
+        while (rc == COE_OK && done < j->nbytes) {
+            ssize_t got = pread(c->fd, (uint8_t*)j->slot->p + done, j->nbytes - done, (off_t)(j->file_off + (int64_t)done));
+            if (got <= 0) rc = COE_EIO;
+            else done += (size_t)got;
+        }
+        const double us = std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
+        {
+            std::lock_guard<std::mutex> lk(c->ld_mutex);
+            j->rc = rc;
+            j->read_us = us;
+            j->done = true;
+            c->ld_queue.pop_front();
+        }
+        c->ld_cv.notify_all();
     }
-    Expert& x = c->experts[sw.expert];
+}
+
+// Give expert x the oldest free host slot of its class and queue the read of its blob into it.
+int queue_read(coe_ctx* c, Expert& x, coe_step_stats* st, ReadJob** job)
+{
     std::vector<HostSlot*>& fl = c->free_hslots[x.cls];
     if (fl.empty()) return fail(c, COE_ESTATE, "internal: no free host slot for an expert the host policy admitted");
     HostSlot* h = fl.front();
     fl.erase(fl.begin());
-    // the slot may still be the source of a copy that was enqueued earlier
-    if (h->used) HIPCHK(c, hipEventSynchronize(h->copied));
-    auto t0 = std::chrono::steady_clock::now();
-    size_t done = 0;
-    while (done < x.nbytes) {
-        ssize_t got = pread(c->fd, (uint8_t*)h->p + done, x.nbytes - done, (off_t)(x.file_off + (int64_t)done));
-        if (got <= 0) {
-            fl.push_back(h);
-            return fail(c, COE_EIO, "reading an expert from the backing file failed");
-        }
-        done += (size_t)got;
-    }
     x.hslot = h;
+    c->ld_jobs.emplace_back();
+    ReadJob& j = c->ld_jobs.back();
+    j.slot = h;
+    j.file_off = x.file_off;
+    j.nbytes = x.nbytes;
+    j.need_issued = h->planned;
+    {
+        std::lock_guard<std::mutex> lk(c->ld_mutex);
+        c->ld_queue.push_back(&j);
+    }
+    c->ld_cv.notify_all();
+    *job = &j;
     if (st) {
         ++st->n_host_misses;
         st->bytes_read += (int64_t)x.nbytes;
-        st->read_us += std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
     }
     return COE_OK;
 }
 
-// The host tier serves one device switch: a hit needs nothing, a miss evicts by the tier's own policy and reads.
-int host_fetch(coe_ctx* c, int32_t e, coe_step_stats* st)
+// The host tier serves one device switch (a request to the level below): a hit needs nothing; a miss evicts by the tier's
+// own policy, takes a free slot and queues the read.  *job receives the read the switch has to wait for (null on a hit),
+// *src the slot the switch copies from (a later switch of the same step may take the expert out of the host tier again, so
+// the expert itself does not remember it).  Policy, log and slot lists change here, on the stepping thread, in switch
+// order; only the bytes move on the loader thread.
+int host_plan(coe_ctx* c, int32_t e, coe_step_stats* st, ReadJob** job, HostSlot** src)
 {
-    std::vector<uint8_t> need((size_t)c->experts.size(), 0);
+    *job = nullptr;
+    *src = nullptr;
+    Expert& x = c->experts[e];
+    std::vector<uint8_t> need(c->experts.size(), 0);
     need[e] = 1;
     std::vector<int32_t> order;
     std::vector<coe::Switch> sws;
     if (!c->host_policy->plan_stage(need.data(), order, sws)) return fail(c, COE_ENOMEM, "an expert does not fit the host tier");
-    for (const coe::Switch& sw : sws) {
-        int rc = host_read(c, sw, st);
+    for (const coe::Switch& sw : sws) {          // none (hit) or one (miss)
+        c->host_log.push_back(sw.expert);
+        c->host_log.push_back((int32_t)sw.victims.size());
+        for (int32_t v : sw.victims) {
+            c->host_log.push_back(v);
+            Expert& xv = c->experts[v];
+            if (xv.hslot) {
+                c->free_hslots[xv.hslot->cls].push_back(xv.hslot);
+                xv.hslot = nullptr;
+            }
+        }
+        int rc = queue_read(c, x, st, job);
         if (rc) return rc;
     }
+    if (!x.hslot) return fail(c, COE_ESTATE, "internal: the host tier lost an expert it reported resident");
+    ++x.hslot->planned;
+    *src = x.hslot;
+    return COE_OK;
+}
+
+// Block until a queued read has finished; its time goes into the step's statistics.
+int host_wait(coe_ctx* c, ReadJob* j, coe_step_stats* st)
+{
+    std::unique_lock<std::mutex> lk(c->ld_mutex);
+    c->ld_cv.wait(lk, [&] { return j->done; });
+    if (st) st->read_us += j->read_us;
+    if (j->rc == COE_EIO) return fail(c, COE_EIO, "reading an expert from the backing file failed");
+    if (j->rc) return fail(c, j->rc, "the loader thread could not serve a read");
     return COE_OK;
 }
 
 // Enqueue one expert switch on the copy stream: victims leave, the expert's blob is copied into a device buffer.
-// st counts the switch; read_st (if the host tier has to read the blob first) counts the read.
-int issue_load(coe_ctx* c, const coe::Switch& sw, coe_step_stats* st, coe_step_stats* read_st)
+// st counts the switch; read_st (if the host tier has to read the blob first) counts the read.  planned: the host tier has
+// already been asked for this switch (host_plan) and `job` is the read to wait for, if any.
+int issue_load(coe_ctx* c, const coe::Switch& sw, coe_step_stats* st, coe_step_stats* read_st, bool planned = false,
+               ReadJob* job = nullptr, HostSlot* hs = nullptr)
 {
     c->switch_log.push_back(sw.expert);
     c->switch_log.push_back((int32_t)sw.victims.size());
@@ -632,9 +711,10 @@ int issue_load(coe_ctx* c, const coe::Switch& sw, coe_step_stats* st, coe_step_s
     if (rc) return rc;
     const void* src = x.host;
     if (c->host_cap > 0) {
-        rc = host_fetch(c, sw.expert, read_st);
+        if (!planned) rc = host_plan(c, sw.expert, read_st, &job, &hs);
+        if (rc == COE_OK && job) rc = host_wait(c, job, read_st);
         if (rc) { c->free_slots[x.cls].insert(c->free_slots[x.cls].begin(), b); return rc; }
-        src = x.hslot->p;
+        src = hs->p;
     }
     // the buffer may still be read by kernels of its previous owner
     if (b->used) HIPCHK(c, hipStreamWaitEvent(c->sx, b->last_use, 0));
@@ -643,9 +723,13 @@ int issue_load(coe_ctx* c, const coe::Switch& sw, coe_step_stats* st, coe_step_s
         HIPCHK(c, hipMemcpyAsync(b->p, src, x.nbytes, hipMemcpyHostToDevice, c->sx));
     }
     HIPCHK(c, hipEventRecord(x.loaded, c->sx));
-    if (c->host_cap > 0) {
-        HIPCHK(c, hipEventRecord(x.hslot->copied, c->sx));
-        x.hslot->used = true;
+    if (hs) {
+        HIPCHK(c, hipEventRecord(hs->copied, c->sx));
+        {
+            std::lock_guard<std::mutex> lk(c->ld_mutex);
+            ++hs->issued;
+        }
+        c->ld_cv.notify_all();
     }
     x.buf = b;
     x.load_pending = true;
@@ -855,8 +939,11 @@ int do_init_fill(coe_ctx* c, coe_step_stats* st)
     if (c->host_cap > 0) {
         // the host tier fills first (descending usage probability), then serves the device's fill
         for (int32_t e : c->host_policy->init_fill()) {
-            coe::Switch sw{e, {}};
-            int rc = host_read(c, sw, st);
+            c->host_log.push_back(e);
+            c->host_log.push_back(0);
+            ReadJob* job = nullptr;
+            int rc = queue_read(c, c->experts[e], st, &job);
+            if (rc == COE_OK) rc = host_wait(c, job, st);
             if (rc) return rc;
         }
     }
@@ -957,6 +1044,14 @@ void coe_destroy(coe_ctx* c)
     for (DevBuf& b : c->slots)
         if (b.last_use) hipEventDestroy(b.last_use);
     if (c->arena) hipFree(c->arena);
+    if (c->loader.joinable()) {
+        {
+            std::lock_guard<std::mutex> lk(c->ld_mutex);
+            c->ld_stop = true;
+        }
+        c->ld_cv.notify_all();
+        c->loader.join();
+    }
     for (HostSlot& h : c->hslots) {
         if (h.p) hipHostFree(h.p);
         if (h.copied) hipEventDestroy(h.copied);
@@ -1134,6 +1229,7 @@ int coe_set_dependency_graph(coe_ctx* c, int32_t n, const int32_t* succ_off, con
         c->host_policy.reset(new coe::Policy(n, bytes.data(), prob.data(), c->succ_off.data(), c->succ.data(), c->host_cap, 0));
         c->host_policy->set_eviction(c->cfg.eviction);
         rc2 = build_host_arena(c);
+        if (rc2 == COE_OK) c->loader = std::thread(loader_main, c);
         // the file's pages leave the page cache where the file system allows it, so that reads come from the device below
         if (rc2 == COE_OK && fsync(c->fd) == 0) (void)posix_fadvise(c->fd, 0, 0, POSIX_FADV_DONTNEED);
     }
@@ -1259,17 +1355,33 @@ static int step_body(coe_ctx* c, coe_step_stats& st)
         HIPCHK(c, coe::k::gather_rows(c->d_inputs, c->d_perm, n_pending, ib, c->d_staged, c->sc));
     }
 
+    // host tier: every switch of the step is a request to it, in switch order; the reads start now, on the loader thread,
+    // while the groups whose experts are resident are launched
+    std::vector<ReadJob*> read_job(switches.size(), nullptr);
+    std::vector<HostSlot*> read_src(switches.size(), nullptr);
+    if (c->host_cap > 0)
+        for (size_t k = 0; k < switches.size(); ++k) {
+            int r2 = host_plan(c, switches[k].expert, &st, &read_job[k], &read_src[k]);
+            if (r2) return r2;
+        }
+
     std::vector<uint8_t> launched(E, 0);
     size_t next_load = 0;
     // enqueue every switch whose victims are no longer needed by a group that has not been launched yet; the copies
     // run on the copy stream while earlier groups compute
-    auto issue_ready_loads = [&]() -> int {
+    // (need: the expert of the group about to be launched.  A switch whose blob is still being read from the backing file
+    // is waited for only when that group cannot start without it; otherwise the launches go on and the read catches up.)
+    auto issue_ready_loads = [&](int32_t need) -> int {
         while (next_load < switches.size()) {
             const coe::Switch& sw = switches[next_load];
             bool ready = true;
             for (int32_t v : sw.victims) ready = ready && !(has_group[v] && !launched[v]);
             if (!ready) break;
-            int r2 = issue_load(c, sw, &st, &st);
+            if (read_job[next_load] && c->experts[need].buf) {
+                std::lock_guard<std::mutex> lk(c->ld_mutex);
+                if (!read_job[next_load]->done) break;
+            }
+            int r2 = issue_load(c, sw, &st, &st, c->host_cap > 0, read_job[next_load], read_src[next_load]);
             if (r2) return r2;
             ++next_load;
         }
@@ -1308,7 +1420,7 @@ static int step_body(coe_ctx* c, coe_step_stats& st)
     for (size_t i = 0; i < order.size(); ++i) {
         const int32_t e = order[i];
         if (launched[e]) continue;                             // ran earlier, in a set with other small groups
-        rc = issue_ready_loads();
+        rc = issue_ready_loads(e);
         if (rc) return rc;
         Expert& x = c->experts[e];
         if (!x.buf) return fail(c, COE_ESTATE, "internal: expert not loaded at launch time");
@@ -1406,6 +1518,15 @@ int coe_step(coe_ctx* c, coe_step_stats* stats)
         hipError_t e1 = hipEventRecord(ln.done, ln.s);
         hipError_t e2 = e1 == hipSuccess ? hipStreamWaitEvent(c->sc, ln.done, 0) : e1;
         if (e2 != hipSuccess && rc >= 0) rc = fail(c, COE_EDEVICE, std::string("joining an executor: ") + hipGetErrorString(e2));
+    }
+    if (c->host_cap > 0) {
+        // reads of a step that ended early are still on the loader's queue: they finish before their storage goes
+        std::unique_lock<std::mutex> lk(c->ld_mutex);
+        if (rc < 0)      // their copies will not be enqueued any more: let the loader through
+            for (HostSlot& h : c->hslots) h.issued = h.planned;
+        c->ld_cv.notify_all();
+        c->ld_cv.wait(lk, [&] { return c->ld_queue.empty(); });
+        c->ld_jobs.clear();
     }
     st.n_device_allocs = (int32_t)(c->device_allocs - allocs_before);
     if (stats && rc >= 0) *stats = st;
@@ -1582,7 +1703,7 @@ int coe_debug_forward(coe_ctx* c, int32_t e, int32_t n, const void* dev_in, floa
         if (x.load_pending) { HIPCHK(c, hipStreamWaitEvent(c->sc, x.loaded, 0)); x.load_pending = false; }
         w = x.buf->p;
     } else {
-        if (!x.host) return fail(c, COE_ESTATE, "with a host tier only resident experts can be run directly");
+        if (c->host_cap > 0) return fail(c, COE_ESTATE, "with a host tier only resident experts can be run directly");
         HIPCHK(c, hipMalloc(&w, x.nbytes));
         temp = true;
         HIPCHK(c, hipMemcpy(w, x.host, x.nbytes, hipMemcpyHostToDevice));
@@ -1616,7 +1737,7 @@ int coe_debug_layer_output(coe_ctx* c, int32_t e, int32_t n, const void* dev_in,
     if (L.fuse_pool || L.fused_away) return fail(c, COE_EINVAL, "layer is fused with its neighbour");
     const size_t bytes = (size_t)n * L.P * L.Q * L.K * a.elem();
     if (out_bytes != bytes) return fail(c, COE_EINVAL, "output size does not match the layer");
-    if (!x.host) return fail(c, COE_ESTATE, "not available with a host tier");
+    if (c->host_cap > 0) return fail(c, COE_ESTATE, "not available with a host tier");
     int rc = ensure_workspace(c);
     if (rc) return rc;
     void* w = nullptr;

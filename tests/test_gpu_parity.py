@@ -311,6 +311,25 @@ def test_host_tier_serves_switches_from_a_file(B, oracle, G, tmp_path, rule, dep
     assert not os.path.exists(path)
 
 
+def test_host_tier_read_failure_is_an_error_not_a_hang(B, tmp_path):
+    """A backing file that has lost its contents: the step that needs a read from it fails with COE_EIO, the loader thread's
+    queue drains, and the context can still be destroyed."""
+    wl = W.config3(40, hw=64, n_experts=8, width=16, cap=3, arrival_batch=40, calibrated=False)
+    blobs = [wl.blob(e) for e in range(8)]
+    x = wl.inputs(range(40))
+    path = str(tmp_path / "experts.bin")
+    ctx = B.Context(max_requests=40, max_stages=wl.max_stages, max_batch=16, cache_cap_experts=3)
+    ctx.coe_set_host_tier(4, path)
+    B.setup_workload(ctx, wl, blobs)
+    os.truncate(path, 0)
+    ctx.coe_submit(40, x, False, None)
+    with pytest.raises(B.CoEError) as ei:
+        ctx.coe_step()
+    assert ei.value.code == B.COE_EIO
+    ctx.close()
+    assert not os.path.exists(path)
+
+
 def test_host_tier_argument_checks(B, tmp_path):
     ctx = B.Context(max_requests=4)
     for cap, path in ((0, str(tmp_path / "a")), (2, ""), (2, str(tmp_path / "no_such_dir" / "a"))):
