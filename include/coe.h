@@ -324,6 +324,18 @@ int coe_profiler_max_batch(int32_t n, const int32_t* batch, const double* latenc
 int coe_profiler_arranging_window(double k_us, double b_us, double load_us, double efficiency, int32_t* min_group_resident,
                                   int32_t* min_group_missing);
 
+/* Memory scores (Section 4.5: an expert's memory footprint is normalised to its memory score; Section 4.3's eviction figure
+ * and the user-configurable memory allocation are stated in them).  The unit is the smallest footprint among the experts, so
+ * score[e] = nbytes[e] / unit >= 1; *unit_bytes receives it.  A memory allocation of s scores is cache_cap_bytes =
+ * floor(s * unit).  COE_EINVAL for n <= 0, a null pointer or a footprint <= 0.
+ * coe_profiler_expert_budget: memory allocation under limited computation performance (Section 4.4): inference runs at the
+ * maximum batch size and everything else goes to experts: total_bytes - reserve_bytes - max_batch * bytes_per_request
+ * (activation workspace of one request), never below 0.  *budget_scores (nullable) receives it in memory scores of
+ * unit_bytes.  COE_EINVAL for negative sizes or unit_bytes <= 0. */
+int coe_profiler_memory_scores(int32_t n, const int64_t* nbytes, double* score, int64_t* unit_bytes);
+int coe_profiler_expert_budget(int64_t total_bytes, int64_t reserve_bytes, int64_t bytes_per_request, int32_t max_batch,
+                               int64_t unit_bytes, int64_t* budget_bytes, double* budget_scores);
+
 /* Decay-window search for the number of experts to keep on the device when their memory competes with the memory of large
  * batches (Section 4.4, "Memory allocation under sufficient computation performance").  The window slides along the number
  * of experts (sorted by descending usage probability): window k covers [sum of the earlier sizes, + size_k) with

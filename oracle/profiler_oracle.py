@@ -90,3 +90,14 @@ def decay_window_search(total: int, throughput_at: Callable[[int], float], initi
         k += 1
     return dict(window=(low, high), experts=(whole(low, total), whole(high, total)), stopped_by=stopped, linear_error=err,
                 loaded=loaded, throughputs=ts)
+
+
+def memory_scores(nbytes: Sequence[int]) -> Tuple[list, int]:
+    """Section 4.5: memory footprints normalised to memory scores; the unit is the smallest footprint."""
+    unit = min(nbytes)
+    return [b / unit for b in nbytes], unit
+
+
+def expert_budget(total_bytes: int, reserve_bytes: int, bytes_per_request: int, max_batch: int) -> int:
+    """Section 4.4, limited computation performance: inference gets the memory of the maximum batch, experts the rest."""
+    return max(0, total_bytes - reserve_bytes - bytes_per_request * max_batch)

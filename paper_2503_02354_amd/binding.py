@@ -25,7 +25,7 @@ EXPORTS = [
     "coe_debug_last_regroup", "coe_debug_switch_log", "coe_debug_resident", "coe_debug_forward", "coe_debug_layer_output", "coe_debug_regroup", "coe_debug_conv",
     "coe_profile_read", "coe_profile_issued", "coe_validate_graph", "coe_policy_create", "coe_policy_destroy", "coe_policy_init_fill",
     "coe_policy_stage", "coe_policy_resident", "coe_policy_set_eviction", "coe_policy_set_in_use_depth", "coe_set_arranging", "coe_arrange_defer", "coe_set_latency_model", "coe_assign_executors", "coe_debug_last_assignment",
-    "coe_regroup_static", "coe_debug_last_chunks", "coe_set_host_tier", "coe_debug_host_log",
+    "coe_regroup_static", "coe_debug_last_chunks", "coe_set_host_tier", "coe_debug_host_log", "coe_profiler_memory_scores", "coe_profiler_expert_budget",
     "coe_profiler_fit_latency", "coe_profiler_max_batch", "coe_profiler_arranging_window", "coe_profiler_window_step",
 ]
 
@@ -108,6 +108,8 @@ def _load():
     L.coe_profiler_fit_latency.argtypes = [i32, vp, vp, C.POINTER(C.c_double), C.POINTER(C.c_double)]
     L.coe_profiler_max_batch.argtypes = [i32, vp, vp, C.c_double, C.POINTER(i32)]
     L.coe_profiler_arranging_window.argtypes = [C.c_double, C.c_double, C.c_double, C.c_double, C.POINTER(i32), C.POINTER(i32)]
+    L.coe_profiler_memory_scores.argtypes = [i32, vp, vp, C.POINTER(i64)]
+    L.coe_profiler_expert_budget.argtypes = [i64, i64, i64, i32, i64, C.POINTER(i64), C.POINTER(C.c_double)]
     L.coe_profiler_window_step.argtypes = [i32, C.c_double, C.c_double, i32, i32, vp, C.POINTER(coe_window_state)]
     L.coe_regroup_static.argtypes = [i32, vp, i32, vp, vp, vp, vp, vp]
     return L
@@ -164,6 +166,24 @@ def coe_profiler_arranging_window(k_us: float, b_us: float, load_us: float, effi
     if rc < 0:
         raise CoEError(rc, "coe_profiler_arranging_window")
     return a.value, b.value
+
+
+def coe_profiler_memory_scores(nbytes) -> Tuple[np.ndarray, int]:
+    b = np.ascontiguousarray(nbytes, np.int64)
+    score = np.zeros(b.shape[0], np.float64)
+    unit = C.c_int64(0)
+    rc = lib.coe_profiler_memory_scores(b.shape[0], _ptr(b) if b.shape[0] else None, _ptr(score) if b.shape[0] else None, C.byref(unit))
+    if rc < 0:
+        raise CoEError(rc, "coe_profiler_memory_scores")
+    return score, unit.value
+
+
+def coe_profiler_expert_budget(total_bytes: int, reserve_bytes: int, bytes_per_request: int, max_batch: int, unit_bytes: int) -> Tuple[int, float]:
+    left, scores = C.c_int64(0), C.c_double(0.0)
+    rc = lib.coe_profiler_expert_budget(total_bytes, reserve_bytes, bytes_per_request, max_batch, unit_bytes, C.byref(left), C.byref(scores))
+    if rc < 0:
+        raise CoEError(rc, "coe_profiler_expert_budget")
+    return left.value, scores.value
 
 
 def coe_profiler_window_step(n_experts_total: int, initial_window: float, error_margin: float, fit_points: int, throughput) -> coe_window_state:

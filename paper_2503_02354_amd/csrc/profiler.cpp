@@ -56,6 +56,32 @@ int coe_profiler_arranging_window(double k_us, double b_us, double load_us, doub
     return COE_OK;
 }
 
+int coe_profiler_memory_scores(int32_t n, const int64_t* nbytes, double* score, int64_t* unit_bytes)
+{
+    if (n <= 0 || !nbytes || !score || !unit_bytes) return COE_EINVAL;
+    int64_t unit = nbytes[0];
+    for (int32_t e = 0; e < n; ++e) {
+        if (nbytes[e] <= 0) return COE_EINVAL;
+        if (nbytes[e] < unit) unit = nbytes[e];
+    }
+    for (int32_t e = 0; e < n; ++e) score[e] = (double)nbytes[e] / (double)unit;
+    *unit_bytes = unit;
+    return COE_OK;
+}
+
+int coe_profiler_expert_budget(int64_t total_bytes, int64_t reserve_bytes, int64_t bytes_per_request, int32_t max_batch,
+                               int64_t unit_bytes, int64_t* budget_bytes, double* budget_scores)
+{
+    if (total_bytes < 0 || reserve_bytes < 0 || bytes_per_request < 0 || max_batch < 0 || unit_bytes <= 0 || !budget_bytes)
+        return COE_EINVAL;
+    // (compared before subtracting: the workspace of a large batch may exceed any memory)
+    const long double need = (long double)reserve_bytes + (long double)bytes_per_request * (long double)max_batch;
+    const int64_t left = need >= (long double)total_bytes ? 0 : total_bytes - reserve_bytes - bytes_per_request * (int64_t)max_batch;
+    *budget_bytes = left;
+    if (budget_scores) *budget_scores = (double)left / (double)unit_bytes;
+    return COE_OK;
+}
+
 int coe_profiler_window_step(int32_t n_experts_total, double initial_window, double error_margin, int32_t fit_points,
                              int32_t n_measured, const double* throughput, coe_window_state* out)
 {

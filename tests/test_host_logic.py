@@ -290,3 +290,24 @@ def test_assigning_rule_matches_oracle(B):
         n = int(rng.integers(0, 40)); k = int(rng.integers(1, 5))
         cost = rng.integers(0, 50, n) if rng.random() < 0.5 else rng.integers(1, 4, n) * 1000
         assert B.coe_assign_executors(cost, k).tolist() == assign(cost.tolist(), k)
+
+
+def test_memory_scores_and_expert_budget(B):
+    """Section 4.5: footprints normalised to memory scores; Section 4.4: with inference at the maximum batch, experts get the
+    rest of the memory.  Library against the oracle's twin and against hand values."""
+    from oracle import profiler_oracle as PO
+    nbytes = [46_900_000, 22_300_000, 171_400_000, 22_300_000]          # ResNet-50-, ResNet-18-, ViT-B/16-shaped blobs
+    score, unit = B.coe_profiler_memory_scores(nbytes)
+    want, wunit = PO.memory_scores(nbytes)
+    assert unit == wunit == 22_300_000 and np.allclose(score, want, rtol=0, atol=1e-12)
+    assert score[1] == score[3] == 1.0 and abs(score[2] - 7.686098654708520) < 1e-12
+    # 12 GB of device memory (the paper's RTX 3080Ti), 1 GB reserved, 9.5 MB of activations per request, maximum batch 64
+    left, scores = B.coe_profiler_expert_budget(12 * 10**9, 10**9, 9_500_000, 64, unit)
+    assert left == PO.expert_budget(12 * 10**9, 10**9, 9_500_000, 64) == 10_392_000_000
+    assert abs(scores - left / unit) < 1e-9
+    assert B.coe_profiler_expert_budget(10**9, 0, 10**9, 4096, unit) == (0, 0.0)        # the batch alone exceeds the memory
+    for bad in ([], [5, 0], [-1]):
+        with pytest.raises(B.CoEError):
+            B.coe_profiler_memory_scores(bad)
+    with pytest.raises(B.CoEError):
+        B.coe_profiler_expert_budget(10, 0, 1, 1, 0)
