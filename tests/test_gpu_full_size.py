@@ -22,6 +22,27 @@ def B():
     return binding
 
 
+_CAPSYS = None
+
+
+@pytest.fixture(autouse=True)
+def _uncaptured_progress(capsys):
+    """The oracle needs minutes per workload here: progress lines go to the terminal even when pytest captures output, so
+    that whoever runs the suite can tell a long test from a hung one."""
+    global _CAPSYS
+    _CAPSYS = capsys
+    yield
+    _CAPSYS = None
+
+
+def say(msg):
+    if _CAPSYS is None:
+        print(msg, flush=True)
+    else:
+        with _CAPSYS.disabled():
+            print(msg, flush=True)
+
+
 def _valid_paths(path, wl):
     for r, p in enumerate(path):
         p = [int(v) for v in p if v >= 0]
@@ -93,13 +114,13 @@ def _oracle_side(B, wl, n_sample, seed, cover_candidates):
     if key in _ORACLE_SIDE:
         return _ORACLE_SIDE[key]
     from oracle import guard as G
-    G.PROGRESS = lambda done, total: print(f"{wl.name}: oracle {done}/{total}", flush=True)
+    G.PROGRESS = lambda done, total: say(f"{wl.name}: oracle {done}/{total}")
     n = wl.n_requests
     with ThreadPoolExecutor(8) as ex:
         blobs = list(ex.map(wl.blob, range(wl.graph.n_experts)))
     rng = np.random.default_rng(seed)
     sample = np.sort(rng.choice(n, size=n_sample, replace=False))
-    print(f"{wl.name}: blobs ready", flush=True)
+    say(f"{wl.name}: blobs ready")
     guarded = G.guarded_inputs(wl, blobs, sample)
     if cover_candidates:
         k = len(wl.graph.successors(0))
@@ -118,7 +139,7 @@ def _oracle_side(B, wl, n_sample, seed, cover_candidates):
             if clear[i] and leaf not in reached:
                 reached.add(leaf)
                 extra.append(int(cand[i]))
-        print(f"{wl.name}: {len(extra)} requests added so that {len(reached)} of {k} leaves are sampled", flush=True)
+        say(f"{wl.name}: {len(extra)} requests added so that {len(reached)} of {k} leaves are sampled")
         if extra:
             extra = np.array(sorted(extra), np.int64)
             guarded = _merge_guarded(guarded, G.guarded_inputs(wl, blobs, extra))
@@ -130,14 +151,14 @@ def _oracle_side(B, wl, n_sample, seed, cover_candidates):
             guarded = (xs[order], sub[order], want, redraws)
     xs, sub, want, redraws = guarded
     n_amb = int(want["ambiguous"].sum())
-    print(f"{wl.name}: guard done on {len(sample)} requests: {int(want['first_draw']['undecidable'].sum())} undecidable at the "
-          f"first draw, {redraws} re-draws, {n_amb} still ambiguous", flush=True)
+    say(f"{wl.name}: guard done on {len(sample)} requests: {int(want['first_draw']['undecidable'].sum())} undecidable at the "
+          f"first draw, {redraws} re-draws, {n_amb} still ambiguous")
     assert n_amb <= MAX_AMBIGUOUS * len(sample), f"{n_amb} of {len(sample)} sampled requests stay ambiguous"
     census = _routing_census(B, wl, blobs, wl.inputs(sample), want["first_draw"])
     for c in census:
-        print(f"{wl.name}: routing census stage {c['stage']}: {c['n']} unfiltered requests, GPU-oracle logit difference / delta "
+        say(f"{wl.name}: routing census stage {c['stage']}: {c['n']} unfiltered requests, GPU-oracle logit difference / delta "
               f"median {c['eps_over_delta_med']:.3f} max {c['eps_over_delta_max']:.3f}, unguarded route agreement "
-              f"{c['unguarded_agreement']:.4f}", flush=True)
+              f"{c['unguarded_agreement']:.4f}")
         # delta must cover two logits moving towards each other
         assert c["eps_over_delta_max"] <= 0.5, "the guard's delta no longer covers the measured GPU-oracle noise"
     fe_s = np.zeros(len(sample), np.int32) if wl.first_expert is None else wl.first_expert[sample]
@@ -159,19 +180,19 @@ def _sampled_case(B, oracle, wl, n_sample, max_batch, arrival=None, seed=1, grou
     subseeds[sample] = sub
     x = wl.inputs(range(n), subseeds)
     assert np.array_equal(x[sample], xs)
-    print(f"{wl.name}: inputs ready", flush=True)
+    say(f"{wl.name}: inputs ready")
     got = run_chain_gpu(B, wl, blobs, x, wl.first_expert, max_batch=max_batch, arrival=arrival, keep=True,
                         group_small=group_small)
     ctx = got.pop("ctx")
     # sampled requests against the oracle (requests the guard left ambiguous: any admissible outcome)
-    print(f"{wl.name}: GPU chain done", flush=True)
+    say(f"{wl.name}: GPU chain done")
     sub_got = dict(path=got["path"][sample], logits=got["logits"][sample])
     err = assert_chain_parity(sub_got, want, REL_TOL_BF16, admissible=lambda i: adm[i])
     visited = set(int(v) for v in got["path"].ravel() if v >= 0)
     checked = set(int(v) for v in want["path"][~want["ambiguous"]].ravel() if v >= 0)
-    print(f"{wl.name}: {len(sample) - n_amb} of {len(sample)} sampled requests bit-exact in route, {n_amb} ambiguous; "
+    say(f"{wl.name}: {len(sample) - n_amb} of {len(sample)} sampled requests bit-exact in route, {n_amb} ambiguous; "
           f"{len(checked & visited)} of the {len(visited)} experts the full run visits are covered by a bit-exact sample; "
-          f"max rel logit err {err:.2e}", flush=True)
+          f"max rel logit err {err:.2e}")
     got["experts_visited"], got["experts_checked"] = visited, checked
     assert len(checked & visited) >= min_cover * len(visited), "too few of the visited experts are oracle-checked"
     # every request: valid path
@@ -213,7 +234,7 @@ def test_config2_full_size(B, oracle, max_batch, group_small):
         assert st.n_grouped == int((ref["cnt"][1:] <= 512).sum()) >= 13 and st.n_group_sets == 1
     leaves = ref["cnt"][1:]
     assert leaves.min() > 100 and leaves.max() < 600, leaves          # calibration spreads the 15 routes
-    print(f"config2 full size: {len(sample)} sampled requests, max rel err {err:.2e}, {redraws} re-draws, leaves {leaves.tolist()}")
+    say(f"config2 full size: {len(sample)} sampled requests, max rel err {err:.2e}, {redraws} re-draws, leaves {leaves.tolist()}")
 
 
 def _replay_switch_log(log, n_experts, cap):
@@ -254,7 +275,7 @@ def test_config3_full_size(B, oracle):
     # leaf usage follows the calibrated Zipf target roughly: the hottest leaf takes a fifth to a third of the requests
     leaves = np.bincount(got["path"][:, 1], minlength=64)[1:]
     assert 0.15 < leaves.max() / wl.n_requests < 0.40 and (leaves > 0).sum() >= 40, leaves
-    print(f"config3 full size: {len(sample)} sampled, max rel err {err:.2e}, {redraws} re-draws, "
+    say(f"config3 full size: {len(sample)} sampled, max rel err {err:.2e}, {redraws} re-draws, "
           f"{len(log) - 16} switches, top leaves {np.sort(leaves)[::-1][:6].tolist()}")
     # the schedule the benchmark times on this workload: an 8-step arranging window for groups of missing experts,
     # four groups of prefetch and three executors.  Same bits (checked above); a consistent switch log with far fewer switches; nobody
@@ -267,7 +288,7 @@ def test_config3_full_size(B, oracle):
     assert 0 in resident and all(0 not in v for e, v in wlog)
     assert len(wlog) - 16 < (len(log) - 16) // 3
     assert sum(st.n_deferred_groups for st in wstats) > 0 and len(wstats) <= 33 + 8
-    print(f"config3 with the arranging window: {len(wlog) - 16} switches in {len(wstats)} steps")
+    say(f"config3 with the arranging window: {len(wlog) - 16} switches in {len(wstats)} steps")
 
 
 def test_config4_full_size(B, oracle):
@@ -299,7 +320,7 @@ def test_config4_full_size(B, oracle):
     assert [st.n_chunks for st in stats] == want_chunks
     assert sum(st.n_grouped for st in stats) >= 90
     allsz = np.concatenate(sizes)
-    print(f"config4 full size: {len(sample)} sampled, max rel err {err:.2e}, {redraws} re-draws, groups per stage "
+    say(f"config4 full size: {len(sample)} sampled, max rel err {err:.2e}, {redraws} re-draws, groups per stage "
           f"{[len(s) for s in sizes]}, sizes min {allsz.min()} median {int(np.median(allsz))} max {allsz.max()}")
     assert allsz.max() >= 1000 and (allsz <= 64).sum() >= 5        # skew: a few huge groups, several small ones
 
@@ -326,7 +347,7 @@ def test_config5_full_size(B, oracle):
     plog = got["also"][0]["switch_log"]
     assert [e for e, v in plog[:12]] == list(range(12)) and len(plog) - 12 >= 20
     assert 0 in _replay_switch_log(plog, 32, 12) and all(0 not in v for e, v in plog)
-    print(f"config5 full size: {len(sample)} sampled, max rel err {err:.2e}, {redraws} re-draws, "
+    say(f"config5 full size: {len(sample)} sampled, max rel err {err:.2e}, {redraws} re-draws, "
           f"{len(log) - 12} switches, leaves min {leaves.min()} max {leaves.max()}")
 
 
@@ -348,7 +369,7 @@ def test_config6_full_size(B, oracle):
     assert (got["logits"][:, :27] >= 0).all() and (got["logits"][:, :27] <= 1).all()     # scores are products of two sigmoids
     capped = got["also"][0]
     assert sum(st.n_misses for rc, st in capped["stats"] if rc == B.COE_OK) > 0          # two slot classes in the arena
-    print(f"config6 full size: {len(sample)} sampled, max rel err {err:.2e}, {redraws} re-draws, detectors {dets[4:].tolist()}")
+    say(f"config6 full size: {len(sample)} sampled, max rel err {err:.2e}, {redraws} re-draws, detectors {dets[4:].tolist()}")
 
 
 def test_vit_layerwise_error_budget(B, oracle):
@@ -390,7 +411,7 @@ def test_vit_layerwise_error_budget(B, oracle):
         ulp = np.maximum(np.abs(o), 2.0 ** -120) * 2.0 ** -7
         assert (np.abs(d) <= 4 * ulp + 2e-2 * np.abs(o).max()).all(), li
     ctx.close()
-    print("ViT-B/16-shaped expert, layer: share of differing elements, relative RMS difference: "
+    say("ViT-B/16-shaped expert, layer: share of differing elements, relative RMS difference: "
           + ", ".join(f"{li}: {s:.4f} {r:.1e}" for li, s, r in rows))
     assert rows[0][2] < 1e-4                       # patch embedding: one GEMM from the same inputs
     assert rows[-1][2] < 1.2e-2

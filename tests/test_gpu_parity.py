@@ -311,6 +311,36 @@ def test_host_tier_serves_switches_from_a_file(B, oracle, G, tmp_path, rule, dep
     assert not os.path.exists(path)
 
 
+def test_host_tier_with_two_architectures(B, oracle, G, tmp_path):
+    """Two blob sizes, so two slot classes on both levels: 18 experts in the file, 8 in host memory, 5 on the device, requests
+    arriving in five batches.  Same bits and the same device switches as without the file; the reads are what the lower level's
+    policy does when it is asked for every device switch in turn."""
+    n, arrival = 120, 24
+    wl = W.config4(n, hw=64, tiers=(3, 6, 9), width=16, fan=(3, 2), calibrated=False)
+    G.calibrate_workload(wl, n_cal=32)
+    E = wl.graph.n_experts
+    blobs = [wl.blob(e) for e in range(E)]
+    assert len(set(b.nbytes for b in blobs)) == 2
+    x = wl.inputs(range(n))
+    kw = dict(max_batch=32, arrival=arrival, cap_experts=5, prefetch_depth=1)
+    plain = run_chain_gpu(B, wl, blobs, x, wl.first_expert, **kw)
+    path = str(tmp_path / "experts.bin")
+    got = run_chain_gpu(B, wl, blobs, x, wl.first_expert, host_tier=(8, path), **kw)
+    assert np.array_equal(got["path"], plain["path"]) and np.array_equal(got["logits"], plain["logits"])
+    assert got["switch_log"] == plain["switch_log"] and len(got["switch_log"]) > 15
+    host = oracle.CacheSim([b.nbytes for b in blobs], wl.usage_prob, wl.graph.succ_off, wl.graph.succ, cap_experts=8)
+    reads = [(e, []) for e in host.init_fill()]
+    for e, _ in got["switch_log"]:
+        need = np.zeros(E, np.uint8); need[e] = 1
+        reads += host.stage(need)[1]
+    assert got["host_log"] == reads and len(reads) > 8 + 5
+    stats = [st for rc, st in got["stats"] if rc == B.COE_OK]
+    assert sum(st.n_host_misses for st in stats) == len(reads)
+    assert sum(st.bytes_read for st in stats) == sum(blobs[e].nbytes for e, _ in reads)
+    assert all(st.n_device_allocs == 0 for st in stats)
+    assert not os.path.exists(path)
+
+
 def test_host_tier_read_failure_is_an_error_not_a_hang(B, tmp_path):
     """A backing file that has lost its contents: the step that needs a read from it fails with COE_EIO, the loader thread's
     queue drains, and the context can still be destroyed."""
