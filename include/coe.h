@@ -333,6 +333,10 @@ int coe_profiler_arranging_window(double k_us, double b_us, double load_us, doub
  * (activation workspace of one request), never below 0.  *budget_scores (nullable) receives it in memory scores of
  * unit_bytes.  COE_EINVAL for negative sizes or unit_bytes <= 0. */
 int coe_profiler_memory_scores(int32_t n, const int64_t* nbytes, double* score, int64_t* unit_bytes);
+/* The current maximum executable batch size (Section 4.2 "Request splitting"): the smaller of the largest batch the
+ * available memory holds (free_bytes / bytes_per_request, rounded down) and the maximum batch size the profiler measured;
+ * at least 0.  This is the value for coe_config.max_batch.  COE_EINVAL for negative sizes or bytes_per_request <= 0. */
+int coe_profiler_executable_batch(int64_t free_bytes, int64_t bytes_per_request, int32_t profiled_max_batch, int32_t* batch);
 int coe_profiler_expert_budget(int64_t total_bytes, int64_t reserve_bytes, int64_t bytes_per_request, int32_t max_batch,
                                int64_t unit_bytes, int64_t* budget_bytes, double* budget_scores);
 

@@ -101,3 +101,8 @@ def memory_scores(nbytes: Sequence[int]) -> Tuple[list, int]:
 def expert_budget(total_bytes: int, reserve_bytes: int, bytes_per_request: int, max_batch: int) -> int:
     """Section 4.4, limited computation performance: inference gets the memory of the maximum batch, experts the rest."""
     return max(0, total_bytes - reserve_bytes - bytes_per_request * max_batch)
+
+
+def executable_batch(free_bytes: int, bytes_per_request: int, profiled_max_batch: int) -> int:
+    """Section 4.2 "Request splitting": the smaller of what memory holds and what the profiler measured."""
+    return min(free_bytes // bytes_per_request, profiled_max_batch)

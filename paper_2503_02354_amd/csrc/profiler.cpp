@@ -69,6 +69,14 @@ int coe_profiler_memory_scores(int32_t n, const int64_t* nbytes, double* score, 
     return COE_OK;
 }
 
+int coe_profiler_executable_batch(int64_t free_bytes, int64_t bytes_per_request, int32_t profiled_max_batch, int32_t* batch)
+{
+    if (free_bytes < 0 || bytes_per_request <= 0 || profiled_max_batch < 0 || !batch) return COE_EINVAL;
+    const int64_t fits = free_bytes / bytes_per_request;
+    *batch = (int32_t)(fits < (int64_t)profiled_max_batch ? fits : (int64_t)profiled_max_batch);
+    return COE_OK;
+}
+
 int coe_profiler_expert_budget(int64_t total_bytes, int64_t reserve_bytes, int64_t bytes_per_request, int32_t max_batch,
                                int64_t unit_bytes, int64_t* budget_bytes, double* budget_scores)
 {

@@ -311,3 +311,17 @@ def test_memory_scores_and_expert_budget(B):
             B.coe_profiler_memory_scores(bad)
     with pytest.raises(B.CoEError):
         B.coe_profiler_expert_budget(10, 0, 1, 1, 0)
+
+
+def test_executable_batch_is_the_smaller_of_memory_and_profile(B):
+    """Section 4.2 "Request splitting": hand values, the oracle's twin, and the consistency with the expert budget: what is
+    left after the experts' share holds exactly the batch the budget was computed for."""
+    from oracle import profiler_oracle as PO
+    assert B.coe_profiler_executable_batch(10**9, 9_500_000, 512) == PO.executable_batch(10**9, 9_500_000, 512) == 105
+    assert B.coe_profiler_executable_batch(10**10, 9_500_000, 512) == 512
+    assert B.coe_profiler_executable_batch(9_499_999, 9_500_000, 512) == 0
+    total, reserve, per_req, mb = 12 * 10**9, 10**9, 9_500_000, 64
+    experts, _ = B.coe_profiler_expert_budget(total, reserve, per_req, mb, 1)
+    assert B.coe_profiler_executable_batch(total - reserve - experts, per_req, 10**6) == mb
+    with pytest.raises(B.CoEError):
+        B.coe_profiler_executable_batch(1, 0, 1)
