@@ -340,6 +340,12 @@ int coe_profiler_executable_batch(int64_t free_bytes, int64_t bytes_per_request,
 int coe_profiler_expert_budget(int64_t total_bytes, int64_t reserve_bytes, int64_t bytes_per_request, int32_t max_batch,
                                int64_t unit_bytes, int64_t* budget_bytes, double* budget_scores);
 
+/* Expert usage probabilities from a sample run (Section 4.5 "Expert information": where the routing rules do not give the
+ * probabilities in closed form, the CoE is run on a small sample and each expert's use is recorded).  path: [n_requests]
+ * [max_stages] expert ids as coe_collect returns them (-1 padded); prob[e] = share of the sampled requests whose path
+ * visits expert e.  COE_EINVAL for a null pointer, non-positive sizes or an id outside [-1, n_experts). */
+int coe_profiler_usage_probabilities(int32_t n_requests, int32_t max_stages, const int32_t* path, int32_t n_experts, float* prob);
+
 /* Decay-window search for the number of experts to keep on the device when their memory competes with the memory of large
  * batches (Section 4.4, "Memory allocation under sufficient computation performance").  The window slides along the number
  * of experts (sorted by descending usage probability): window k covers [sum of the earlier sizes, + size_k) with

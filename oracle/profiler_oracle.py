@@ -106,3 +106,14 @@ def expert_budget(total_bytes: int, reserve_bytes: int, bytes_per_request: int, 
 def executable_batch(free_bytes: int, bytes_per_request: int, profiled_max_batch: int) -> int:
     """Section 4.2 "Request splitting": the smaller of what memory holds and what the profiler measured."""
     return min(free_bytes // bytes_per_request, profiled_max_batch)
+
+
+def usage_probabilities(paths, n_experts: int):
+    """Section 4.5 "Expert information": share of the sampled requests whose path visits each expert (paths: rows of
+    expert ids, -1 padded)."""
+    n = len(paths)
+    visits = [0] * n_experts
+    for p in paths:
+        for e in set(int(v) for v in p if v >= 0):
+            visits[e] += 1
+    return [v / n for v in visits]

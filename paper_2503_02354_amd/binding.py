@@ -25,7 +25,7 @@ EXPORTS = [
     "coe_debug_last_regroup", "coe_debug_switch_log", "coe_debug_resident", "coe_debug_forward", "coe_debug_layer_output", "coe_debug_regroup", "coe_debug_conv",
     "coe_profile_read", "coe_profile_issued", "coe_validate_graph", "coe_policy_create", "coe_policy_destroy", "coe_policy_init_fill",
     "coe_policy_stage", "coe_policy_resident", "coe_policy_set_eviction", "coe_policy_set_in_use_depth", "coe_set_arranging", "coe_arrange_defer", "coe_set_latency_model", "coe_assign_executors", "coe_debug_last_assignment",
-    "coe_regroup_static", "coe_debug_last_chunks", "coe_set_host_tier", "coe_debug_host_log", "coe_profiler_memory_scores", "coe_profiler_expert_budget", "coe_profiler_executable_batch",
+    "coe_regroup_static", "coe_debug_last_chunks", "coe_set_host_tier", "coe_debug_host_log", "coe_profiler_memory_scores", "coe_profiler_expert_budget", "coe_profiler_executable_batch", "coe_profiler_usage_probabilities",
     "coe_profiler_fit_latency", "coe_profiler_max_batch", "coe_profiler_arranging_window", "coe_profiler_window_step",
 ]
 
@@ -111,6 +111,7 @@ def _load():
     L.coe_profiler_memory_scores.argtypes = [i32, vp, vp, C.POINTER(i64)]
     L.coe_profiler_expert_budget.argtypes = [i64, i64, i64, i32, i64, C.POINTER(i64), C.POINTER(C.c_double)]
     L.coe_profiler_executable_batch.argtypes = [i64, i64, i32, C.POINTER(i32)]
+    L.coe_profiler_usage_probabilities.argtypes = [i32, i32, vp, i32, vp]
     L.coe_profiler_window_step.argtypes = [i32, C.c_double, C.c_double, i32, i32, vp, C.POINTER(coe_window_state)]
     L.coe_regroup_static.argtypes = [i32, vp, i32, vp, vp, vp, vp, vp]
     return L
@@ -185,6 +186,16 @@ def coe_profiler_expert_budget(total_bytes: int, reserve_bytes: int, bytes_per_r
     if rc < 0:
         raise CoEError(rc, "coe_profiler_expert_budget")
     return left.value, scores.value
+
+
+def coe_profiler_usage_probabilities(path, n_experts: int) -> np.ndarray:
+    p = np.ascontiguousarray(path, np.int32)
+    assert p.ndim == 2
+    prob = np.zeros(max(n_experts, 1), np.float32)
+    rc = lib.coe_profiler_usage_probabilities(p.shape[0], p.shape[1], _ptr(p) if p.size else None, n_experts, _ptr(prob))
+    if rc < 0:
+        raise CoEError(rc, "coe_profiler_usage_probabilities")
+    return prob[:n_experts]
 
 
 def coe_profiler_executable_batch(free_bytes: int, bytes_per_request: int, profiled_max_batch: int) -> int:

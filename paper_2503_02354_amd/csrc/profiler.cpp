@@ -3,6 +3,7 @@
 // window's thresholds derived from that model, and the decay-window search for the number of experts to keep on the
 // device (Section 4.4, Eq. 1-3).  The measurements themselves are taken by the caller through the library's other calls.
 #include <cmath>
+#include <vector>
 #include <cstdint>
 
 #include "../../include/coe.h"
@@ -53,6 +54,22 @@ int coe_profiler_arranging_window(double k_us, double b_us, double load_us, doub
     if (b > 2147483647.0) return COE_ERANGE;
     *min_group_resident = (int32_t)a;
     *min_group_missing = (int32_t)b;
+    return COE_OK;
+}
+
+int coe_profiler_usage_probabilities(int32_t n_requests, int32_t max_stages, const int32_t* path, int32_t n_experts, float* prob)
+{
+    if (n_requests <= 0 || max_stages <= 0 || n_experts <= 0 || !path || !prob) return COE_EINVAL;
+    std::vector<int64_t> visits((size_t)n_experts, 0);
+    std::vector<int32_t> seen((size_t)n_experts, -1);          // last request that counted the expert (a path visits it once)
+    for (int32_t r = 0; r < n_requests; ++r)
+        for (int32_t s = 0; s < max_stages; ++s) {
+            const int32_t e = path[(size_t)r * max_stages + s];
+            if (e == -1) continue;
+            if (e < 0 || e >= n_experts) return COE_EINVAL;
+            if (seen[e] != r) { seen[e] = r; ++visits[e]; }
+        }
+    for (int32_t e = 0; e < n_experts; ++e) prob[e] = (float)((double)visits[e] / (double)n_requests);
     return COE_OK;
 }
 

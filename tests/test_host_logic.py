@@ -325,3 +325,33 @@ def test_executable_batch_is_the_smaller_of_memory_and_profile(B):
     assert B.coe_profiler_executable_batch(total - reserve - experts, per_req, 10**6) == mb
     with pytest.raises(B.CoEError):
         B.coe_profiler_executable_batch(1, 0, 1)
+
+
+def test_usage_probabilities_from_sample_paths(B, oracle):
+    """Section 4.5 "Expert information": probabilities recorded from a sample run.  Hand case, the oracle's twin on random
+    paths through a DAG, and the closed form of a workload whose routes are drawn with known probabilities."""
+    from oracle import profiler_oracle as PO
+    paths = np.array([[0, 2, -1], [0, 3, 5], [1, 3, 5], [0, 2, -1]], np.int32)
+    got = B.coe_profiler_usage_probabilities(paths, 6)
+    assert got.tolist() == [0.75, 0.25, 0.5, 0.5, 0.0, 0.5] == PO.usage_probabilities(paths, 6)
+    rng = np.random.default_rng(4)
+    wl = W.config4(2000, hw=32, tiers=(4, 8, 12), width=8, fan=(3, 2), calibrated=False)
+    E = wl.graph.n_experts
+    rnd = np.full((2000, 3), -1, np.int32)
+    for r in range(2000):
+        e = int(wl.first_expert[r])
+        for s_ in range(3):
+            rnd[r, s_] = e
+            succ = wl.graph.successors(e)
+            if len(succ) == 0:
+                break
+            e = int(succ[rng.integers(len(succ))])
+            if e < 0:
+                break
+    got = B.coe_profiler_usage_probabilities(rnd, E)
+    assert np.allclose(got, PO.usage_probabilities(rnd, E), rtol=0, atol=1e-7)
+    assert abs(got[:4].sum() - 1.0) < 1e-6                                  # every request starts at one first-tier expert
+    assert np.abs(got - np.asarray(wl.usage_prob)).max() < 0.05            # uniform random routes: the workload's own probabilities
+    for bad in (np.array([[7]], np.int32), np.array([[-2]], np.int32)):
+        with pytest.raises(B.CoEError):
+            B.coe_profiler_usage_probabilities(bad, 6)
